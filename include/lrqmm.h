@@ -1,0 +1,138 @@
+/*
+ * lrqmm.h -- C ABI of the MI355X (gfx950) LRQMM library.
+ *
+ * LRQMM = low-rank residual quantized matrix multiplication: C ~ A.B with A, B
+ * float32, computed as an N-bit integer GEMM plus a rank-r correction obtained
+ * from a randomized SVD of the quantization residuals (paper: Methodology,
+ * Algorithm 2).
+ *
+ * Conventions for every entry point
+ *  - All matrix/vector pointers are DEVICE pointers owned by the caller (e.g. a
+ *    torch tensor's data_ptr()); the library never allocates or frees memory and
+ *    writes only the declared outputs and the caller's workspace.
+ *  - `stream` is a hipStream_t passed as void* (NULL = default stream).  Calls
+ *    only enqueue work on that stream; they do not synchronise with the host.
+ *  - Matrices are dense row-major float32 unless stated.  Inputs must be finite.
+ *  - Return value: LRQMM_OK or a negative LRQMM_ERR_* code (no exceptions, no
+ *    errno).  Zero-sized problems return LRQMM_OK and do nothing.
+ *  - bits N in [2, 8]; qmax = 2^(N-1)-1; codes are sign-extended int8 in
+ *    [-qmax-1, qmax] (int4 codes live in int8 operands).
+ *  - A scale group is a row (axis LRQMM_AXIS_ROW, operand A) or a column (axis
+ *    LRQMM_AXIS_COL, operand B) -- vector-wise quantization, Background 2.2.  The
+ *    `amax` arrays hold the raw absolute maxima; every kernel re-derives
+ *    lambda = fl32(qmax/amax) and the step s = fl32(amax/qmax) by one IEEE
+ *    division each (Eq. (quantA)); amax < 1e-30 means lambda = s = 0.
+ */
+#ifndef LRQMM_H
+#define LRQMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LRQMM_API __attribute__((visibility("default")))
+
+#define LRQMM_OK                 0
+#define LRQMM_ERR_INVALID_ARG   -1   /* null pointer, negative size, rank out of range */
+#define LRQMM_ERR_UNSUPPORTED   -2   /* bits outside [2,8], K too large for int32, l > LRQMM_MAX_SKETCH */
+#define LRQMM_ERR_WORKSPACE     -3   /* workspace missing, misaligned or too small */
+#define LRQMM_ERR_HIP           -4   /* a HIP launch failed */
+
+#define LRQMM_AXIS_ROW  0
+#define LRQMM_AXIS_COL  1
+
+#define LRQMM_ROUND_FLOOR    0   /* round down: residual entries in [0, s)  (Eq. (get_ra2)) */
+#define LRQMM_ROUND_NEAREST  1   /* round to nearest, ties to even          (Eq. (quantAB)) */
+
+#define LRQMM_MAX_SKETCH  80     /* largest supported sketch width l = rank + oversample */
+
+/* Human-readable text for a status code (static storage). */
+LRQMM_API const char* lrqmm_status_string(int status);
+
+/* Bytes of device workspace that lrqmm_rsvd / lrqmm_gemm / lrqmm_matmul need for
+ * a problem of this size (the maximum over the three).  The workspace must be
+ * 256-byte aligned.  Returns 0 for invalid arguments. */
+LRQMM_API size_t lrqmm_workspace_bytes(int M, int N, int K, int rank, int oversample);
+
+/*
+ * Symmetric data-free quantization (Background 2.2, Eq. (quantA); floor variant
+ * Methodology Eq. (get_ra2); Algorithm 2 line 1).
+ *   X      rows x cols float32, row-major (device, read only)
+ *   axis   LRQMM_AXIS_ROW: one scale per row,  amax[rows],
+ *                          codes rows x cols row-major;
+ *          LRQMM_AXIS_COL: one scale per column, amax[cols],
+ *                          codes stored TRANSPOSED, cols x rows row-major
+ *                          (so both GEMM operands are contiguous along K).
+ *   code = clamp(floor_or_rint(fl32(lambda * x)), -qmax-1, qmax)
+ * Outputs: codes (int8), amax (float32).  Bit-exact and order-independent.
+ */
+LRQMM_API int lrqmm_quantize(const float* X, int rows, int cols, int axis, int bits, int round_mode,
+                   int8_t* codes, float* amax, void* stream);
+
+/*
+ * Gaussian test matrix of the randomized range finder (Background 2.1, stage 1).
+ * omega is rows x cols float32 row-major; element (i, j) is a function of
+ * (seed, stream_id, i, j) only: splitmix64 counter hash -> two 24-bit uniforms ->
+ * Box-Muller, evaluated in float64 with a fixed operation order and rounded to
+ * float32.  stream_id 0 is used for R_A, 1 for R_B.
+ */
+LRQMM_API int lrqmm_fill_sketch(uint64_t seed, int stream_id, int rows, int cols, float* omega,
+                      void* stream);
+
+/*
+ * Rank-`rank` randomized SVD of the quantization residual
+ *     R = X - Dequant(Quant(X))          (Algorithm 2 lines 4-7; Algorithm 1)
+ * R is never stored: it is regenerated from X and amax inside every pass.
+ *   X, amax, rows, cols, axis, bits, round_mode   as for lrqmm_quantize
+ *   rank r >= 1, oversample p >= 0, l = r + p <= min(rows, cols, LRQMM_MAX_SKETCH)
+ *   power_iters q >= 0: Y = R.Omega, Q = orth(Y); q times Z = orth(R^T Q),
+ *          Q = orth(R Z); B = Q^T R; SVD of B truncated to r (Eq. (k-svd)); U = Q U'.
+ *   omega_or_null  optional cols x l sketch (row-major) replacing the internal
+ *          generator (which uses lrqmm_fill_sketch(seed, axis, cols, l)).
+ * Outputs: U rows x rank, Sigma[rank] (descending), Vt rank x cols, row-major.
+ * Singular vectors are defined up to sign; only U.diag(Sigma).Vt is unique.
+ */
+LRQMM_API int lrqmm_rsvd(const float* X, const float* amax, int rows, int cols, int axis, int bits,
+               int round_mode, int rank, int oversample, int power_iters, uint64_t seed,
+               const float* omega_or_null, float* U, float* Sigma, float* Vt,
+               void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Quantized GEMM with fused dequantization and rank-2r compensation
+ * (Eq. (INTGEMM), Eq. (QUANTGEMM); Algorithm 2 lines 2-3 and 8-12):
+ *   C[i,j] = sA[i] sB[j] sum_k Aq[i,k] BqT[j,k]
+ *            + (U Sig)(Vt B~) + (A~ W)(Gam Zt) + (U Sig)(Vt W)(Gam Zt)
+ * with A~ = diag(sA) Aq, B~ = Bq diag(sB).
+ *   Aq   M x K int8 row-major;  BqT  N x K int8 row-major (B's codes transposed)
+ *   amaxA[M], amaxB[N]          raw absolute maxima (steps are re-derived)
+ *   U M x rank, Sig[rank], Vt rank x K     factors of R_A
+ *   W K x rank, Gam[rank], Zt rank x N     factors of R_B
+ *   rank == 0: factor pointers are ignored; plain direct-quantization product.
+ *   C    M x N float32 row-major (output)
+ *   Cint_or_null  optional M x N int32 output of the raw integer accumulators.
+ * K must satisfy K * (qmax+1)^2 < 2^31.
+ */
+LRQMM_API int lrqmm_gemm(int M, int N, int K, int bits, int rank,
+               const int8_t* Aq, const float* amaxA, const int8_t* BqT, const float* amaxB,
+               const float* U, const float* Sig, const float* Vt,
+               const float* W, const float* Gam, const float* Zt,
+               float* C, int32_t* Cint_or_null,
+               void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The whole hot path, Algorithm 2 lines 1-12, from float32 A (M x K) and
+ * B (K x N) to float32 C (M x N): quantize both operands, factor both residuals
+ * (sketch seeds (seed, 0) and (seed, 1)), integer GEMM, fused compensation.
+ * rank == 0 runs the direct-quantization pipeline only.
+ */
+LRQMM_API int lrqmm_matmul(int M, int N, int K, int bits, int rank, int oversample, int power_iters,
+                 uint64_t seed, int round_mode, const float* A, const float* B, float* C,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LRQMM_H */

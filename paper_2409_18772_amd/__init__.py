@@ -1,0 +1,11 @@
+"""MI355X-native LRQMM hot path: thin Python binding over the C-ABI library.
+
+The binding only marshals arguments (torch tensors -> device pointers); every
+step of the path runs in the HIP kernels of liblrqmm.so.  There is no CPU
+fallback: importing the binding without the built library raises.
+"""
+from .binding import (  # noqa: F401
+    AXIS_COL, AXIS_ROW, ROUND_FLOOR, ROUND_NEAREST, MAX_SKETCH, LrqmmError,
+    lib_path, load_library, lrqmm_fill_sketch, lrqmm_gemm, lrqmm_matmul, lrqmm_quantize,
+    lrqmm_rsvd, lrqmm_workspace_bytes, lrqmm_status_string, Workspace,
+)

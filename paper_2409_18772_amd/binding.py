@@ -1,0 +1,208 @@
+"""ctypes binding of include/lrqmm.h.  Same names as the C entry points.
+
+torch is used for device memory and the current stream only.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+AXIS_ROW, AXIS_COL = 0, 1
+ROUND_FLOOR, ROUND_NEAREST = 0, 1
+MAX_SKETCH = 80
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+EXPORTS = ("lrqmm_status_string", "lrqmm_workspace_bytes", "lrqmm_quantize", "lrqmm_fill_sketch",
+           "lrqmm_rsvd", "lrqmm_gemm", "lrqmm_matmul")
+
+
+class LrqmmError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {lrqmm_status_string(status)} ({status})")
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "liblrqmm.so")
+
+
+def load_library() -> ctypes.CDLL:
+    """Load liblrqmm.so (built in-tree by paper_2409_18772_amd/build.py); never falls back."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: run `python -m paper_2409_18772_amd.build` "
+                          "(or __graft_entry__.build()) first; there is no CPU fallback")
+    lib = ctypes.CDLL(path)
+    c_int, c_vp, c_sz, c_u64 = ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_uint64
+    lib.lrqmm_status_string.restype = ctypes.c_char_p
+    lib.lrqmm_status_string.argtypes = [c_int]
+    lib.lrqmm_workspace_bytes.restype = c_sz
+    lib.lrqmm_workspace_bytes.argtypes = [c_int] * 5
+    lib.lrqmm_quantize.restype = c_int
+    lib.lrqmm_quantize.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp]
+    lib.lrqmm_fill_sketch.restype = c_int
+    lib.lrqmm_fill_sketch.argtypes = [c_u64, c_int, c_int, c_int, c_vp, c_vp]
+    lib.lrqmm_rsvd.restype = c_int
+    lib.lrqmm_rsvd.argtypes = [c_vp, c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_int,
+                               c_u64, c_vp, c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
+    lib.lrqmm_gemm.restype = c_int
+    lib.lrqmm_gemm.argtypes = [c_int] * 5 + [c_vp] * 12 + [c_vp, c_sz, c_vp]
+    lib.lrqmm_matmul.restype = c_int
+    lib.lrqmm_matmul.argtypes = [c_int] * 7 + [c_u64, c_int, c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
+    _LIB = lib
+    return lib
+
+
+def lrqmm_status_string(status: int) -> str:
+    return load_library().lrqmm_status_string(int(status)).decode()
+
+
+def lrqmm_workspace_bytes(M: int, N: int, K: int, rank: int, oversample: int) -> int:
+    return int(load_library().lrqmm_workspace_bytes(M, N, K, rank, oversample))
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise LrqmmError(status, where)
+
+
+def _dev(t, dtype, name):
+    import torch
+    if t is None:
+        return
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"{name}: expected a contiguous CUDA tensor of dtype {dtype}")
+
+
+class Workspace:
+    """A 256-byte aligned device buffer (a torch uint8 tensor) handed to the library."""
+
+    def __init__(self, nbytes: int, device="cuda"):
+        import torch
+        self.nbytes = int(nbytes)
+        self._buf = torch.empty(self.nbytes + 256, dtype=torch.uint8, device=device)
+        base = self._buf.data_ptr()
+        self.ptr = (base + 255) // 256 * 256
+
+    @classmethod
+    def for_problem(cls, M, N, K, rank, oversample, device="cuda"):
+        return cls(lrqmm_workspace_bytes(M, N, K, rank, oversample), device)
+
+
+def lrqmm_quantize(X, axis: int, bits: int, round_mode: int = ROUND_FLOOR, codes=None, amax=None):
+    """codes (int8; transposed for AXIS_COL) and amax (float32) of X (rows x cols float32)."""
+    import torch
+    _dev(X, torch.float32, "X")
+    rows, cols = X.shape
+    if codes is None:
+        shape = (rows, cols) if axis == AXIS_ROW else (cols, rows)
+        codes = torch.empty(shape, dtype=torch.int8, device=X.device)
+    if amax is None:
+        amax = torch.empty(rows if axis == AXIS_ROW else cols, dtype=torch.float32, device=X.device)
+    _dev(codes, torch.int8, "codes")
+    _dev(amax, torch.float32, "amax")
+    st = load_library().lrqmm_quantize(_ptr(X), rows, cols, axis, bits, round_mode, _ptr(codes),
+                                       _ptr(amax), _stream())
+    _check(st, "lrqmm_quantize")
+    return codes, amax
+
+
+def lrqmm_fill_sketch(seed: int, stream_id: int, rows: int, cols: int, device="cuda"):
+    import torch
+    omega = torch.empty((rows, cols), dtype=torch.float32, device=device)
+    st = load_library().lrqmm_fill_sketch(seed & 0xFFFFFFFFFFFFFFFF, stream_id, rows, cols, _ptr(omega),
+                                          _stream())
+    _check(st, "lrqmm_fill_sketch")
+    return omega
+
+
+def lrqmm_rsvd(X, amax, axis: int, bits: int, rank: int, oversample: int = 0, power_iters: int = 0,
+               seed: int = 0, round_mode: int = ROUND_FLOOR, omega=None, workspace: Workspace | None = None):
+    """U (rows x rank), Sigma (rank), Vt (rank x cols) of the residual of X."""
+    import torch
+    _dev(X, torch.float32, "X")
+    _dev(amax, torch.float32, "amax")
+    _dev(omega, torch.float32, "omega")
+    rows, cols = X.shape
+    if omega is not None and tuple(omega.shape) != (cols, rank + oversample):
+        raise ValueError("omega must be cols x (rank + oversample)")
+    U = torch.empty((rows, rank), dtype=torch.float32, device=X.device)
+    Sigma = torch.empty((rank,), dtype=torch.float32, device=X.device)
+    Vt = torch.empty((rank, cols), dtype=torch.float32, device=X.device)
+    if workspace is None:
+        workspace = Workspace.for_problem(max(rows, cols), max(rows, cols), max(rows, cols), rank, oversample)
+    st = load_library().lrqmm_rsvd(_ptr(X), _ptr(amax), rows, cols, axis, bits, round_mode, rank, oversample,
+                                   power_iters, seed & 0xFFFFFFFFFFFFFFFF, _ptr(omega), _ptr(U), _ptr(Sigma),
+                                   _ptr(Vt), ctypes.c_void_p(workspace.ptr), workspace.nbytes, _stream())
+    _check(st, "lrqmm_rsvd")
+    return U, Sigma, Vt
+
+
+def lrqmm_gemm(Aq, amaxA, BqT, amaxB, bits: int, factors_a=None, factors_b=None, want_cint: bool = False,
+               workspace: Workspace | None = None, C=None):
+    """C = deq(Aq . Bq) + compensation; factors_a = (U, Sig, Vt), factors_b = (W, Gam, Zt) or None."""
+    import torch
+    _dev(Aq, torch.int8, "Aq")
+    _dev(BqT, torch.int8, "BqT")
+    _dev(amaxA, torch.float32, "amaxA")
+    _dev(amaxB, torch.float32, "amaxB")
+    M, K = Aq.shape
+    N, K2 = BqT.shape
+    if K != K2:
+        raise ValueError("Aq is M x K and BqT is N x K")
+    rank = 0
+    U = Sig = Vt = W = Gam = Zt = None
+    if factors_a is not None:
+        U, Sig, Vt = factors_a
+        W, Gam, Zt = factors_b
+        for n, t in (("U", U), ("Sig", Sig), ("Vt", Vt), ("W", W), ("Gam", Gam), ("Zt", Zt)):
+            _dev(t, torch.float32, n)
+        rank = Sig.numel()
+        if tuple(U.shape) != (M, rank) or tuple(Vt.shape) != (rank, K) or tuple(W.shape) != (K, rank) \
+                or tuple(Zt.shape) != (rank, N) or Gam.numel() != rank:
+            raise ValueError("factor shapes")
+    if C is None:
+        C = torch.empty((M, N), dtype=torch.float32, device=Aq.device)
+    Cint = torch.empty((M, N), dtype=torch.int32, device=Aq.device) if want_cint else None
+    if workspace is None:
+        workspace = Workspace.for_problem(M, N, K, rank, 0)
+    st = load_library().lrqmm_gemm(M, N, K, bits, rank, _ptr(Aq), _ptr(amaxA), _ptr(BqT), _ptr(amaxB),
+                                   _ptr(U), _ptr(Sig), _ptr(Vt), _ptr(W), _ptr(Gam), _ptr(Zt), _ptr(C),
+                                   _ptr(Cint), ctypes.c_void_p(workspace.ptr), workspace.nbytes, _stream())
+    _check(st, "lrqmm_gemm")
+    return (C, Cint) if want_cint else C
+
+
+def lrqmm_matmul(A, B, bits: int, rank: int, oversample: int = 0, power_iters: int = 0, seed: int = 0,
+                 round_mode: int = ROUND_FLOOR, workspace: Workspace | None = None, C=None):
+    """The whole hot path: C ~ A . B (Algorithm 2 lines 1-12)."""
+    import torch
+    _dev(A, torch.float32, "A")
+    _dev(B, torch.float32, "B")
+    M, K = A.shape
+    K2, N = B.shape
+    if K != K2:
+        raise ValueError("A is M x K and B is K x N")
+    if C is None:
+        C = torch.empty((M, N), dtype=torch.float32, device=A.device)
+    if workspace is None:
+        workspace = Workspace.for_problem(M, N, K, rank, oversample)
+    st = load_library().lrqmm_matmul(M, N, K, bits, rank, oversample, power_iters, seed & 0xFFFFFFFFFFFFFFFF,
+                                     round_mode, _ptr(A), _ptr(B), _ptr(C), ctypes.c_void_p(workspace.ptr),
+                                     workspace.nbytes, _stream())
+    _check(st, "lrqmm_matmul")
+    return C

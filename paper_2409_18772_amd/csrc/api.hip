@@ -1,0 +1,307 @@
+// C-ABI entry points of the LRQMM library: argument validation, workspace
+// carving and the launch sequence of each call (paper: Algorithm 2; Algorithm 1
+// for lrqmm_rsvd).  No device memory is allocated here; everything lives in the
+// caller's buffers and workspace.
+#include "kernels.h"
+
+namespace {
+
+struct Arena {
+    char* base;
+    size_t off;
+    explicit Arena(void* b) : base(static_cast<char*>(b)), off(0) {}
+    template <typename T>
+    T* take(size_t count) {
+        off = align_up(off, 256);
+        T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+        off += count * sizeof(T);
+        return p;
+    }
+};
+
+inline int pad_to(int x, int m) { return (x + m - 1) / m * m; }
+
+struct RsvdWs {
+    float *lam, *s, *Wc, *Yr, *partial;
+    double *gpart, *T, *Ur, *Mv;
+};
+
+size_t carve_rsvd(Arena& a, int rows, int cols, int axis, int LP, int rank, RsvdWs* w) {
+    const int nscale = axis == LRQMM_AXIS_ROW ? rows : cols;
+    const int npad = pad_to(nscale, 4);
+    const PassPlan pn = plan_pass_n(rows, cols), pt = plan_pass_t(rows, cols);
+    const size_t part = (size_t)LP * (size_t)((size_t)pn.splits * rows > (size_t)pt.splits * cols
+                                                  ? (size_t)pn.splits * rows
+                                                  : (size_t)pt.splits * cols);
+    const int nb = gram_blocks(rows > cols ? rows : cols);
+    RsvdWs t;
+    t.lam = a.take<float>(npad);
+    t.s = a.take<float>(npad);
+    t.Wc = a.take<float>((size_t)cols * LP);
+    t.Yr = a.take<float>((size_t)rows * LP);
+    t.partial = a.take<float>(part);
+    t.gpart = a.take<double>((size_t)nb * LP * LP);
+    t.T = a.take<double>((size_t)LP * LP);
+    t.Ur = a.take<double>((size_t)LP * rank);
+    t.Mv = a.take<double>((size_t)LP * rank);
+    if (w) *w = t;
+    return a.off;
+}
+
+struct GemmWs {
+    float *lamA, *sA, *lamB, *sB, *Wp, *Vp, *partial, *S, *Pv, *X, *Lp, *Rp;
+};
+
+size_t carve_gemm(Arena& a, int M, int N, int K, int rank, GemmWs* w) {
+    GemmWs t = {};
+    const int Mp = pad_to(M, 4), Np = pad_to(N, 4);
+    t.lamA = a.take<float>(Mp);
+    t.sA = a.take<float>(Mp);
+    t.lamB = a.take<float>(Np);
+    t.sB = a.take<float>(Np);
+    if (rank > 0) {
+        const int RP = pad_to(rank, 16), R2P = pad_to(2 * rank, 8);
+        const PassPlan pa = plan_pass_n(M, K), pb = plan_pass_n(N, K);
+        const size_t part = (size_t)RP * ((size_t)pa.splits * M > (size_t)pb.splits * N ? (size_t)pa.splits * M
+                                                                                       : (size_t)pb.splits * N);
+        t.Wp = a.take<float>((size_t)K * RP);
+        t.Vp = a.take<float>((size_t)K * RP);
+        t.partial = a.take<float>(part);
+        t.S = a.take<float>((size_t)M * RP);
+        t.Pv = a.take<float>((size_t)N * RP);
+        t.X = a.take<float>((size_t)rank * rank);
+        t.Lp = a.take<float>((size_t)M * R2P);
+        t.Rp = a.take<float>((size_t)N * R2P);
+    }
+    if (w) *w = t;
+    return a.off;
+}
+
+struct MatmulWs {
+    int8_t *Aq, *BqT;
+    float *amaxA, *amaxB, *U, *Sig, *Vt, *W, *Gam, *Zt;
+    void* sub;
+    size_t sub_bytes;
+};
+
+size_t carve_matmul(Arena& a, int M, int N, int K, int rank, int oversample, MatmulWs* w) {
+    MatmulWs t = {};
+    t.Aq = a.take<int8_t>((size_t)M * K);
+    t.BqT = a.take<int8_t>((size_t)N * K);
+    t.amaxA = a.take<float>(M);
+    t.amaxB = a.take<float>(N);
+    if (rank > 0) {
+        t.U = a.take<float>((size_t)M * rank);
+        t.Sig = a.take<float>(rank);
+        t.Vt = a.take<float>((size_t)rank * K);
+        t.W = a.take<float>((size_t)K * rank);
+        t.Gam = a.take<float>(rank);
+        t.Zt = a.take<float>((size_t)rank * N);
+    }
+    a.off = align_up(a.off, 256);
+    size_t sub = 0;
+    {
+        Arena g(nullptr);
+        sub = carve_gemm(g, M, N, K, rank, nullptr);
+    }
+    if (rank > 0) {
+        const int LP = pad_to(rank + oversample, 16);
+        Arena ra(nullptr), rb(nullptr);
+        const size_t sa = carve_rsvd(ra, M, K, LRQMM_AXIS_ROW, LP, rank, nullptr);
+        const size_t sb = carve_rsvd(rb, K, N, LRQMM_AXIS_COL, LP, rank, nullptr);
+        if (sa > sub) sub = sa;
+        if (sb > sub) sub = sb;
+    }
+    t.sub = a.base ? a.base + a.off : nullptr;
+    t.sub_bytes = sub;
+    a.off += sub;
+    if (w) *w = t;
+    return a.off;
+}
+
+bool bits_ok(int bits) { return bits >= 2 && bits <= 8; }
+
+// int32 accumulation is safe when K * (qmax+1)^2 < 2^31.
+bool k_fits_int32(int K, int bits) {
+    const long long lim = 1ll << (2 * (bits - 1));
+    return (long long)K * lim < (1ll << 31);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* lrqmm_status_string(int status) {
+    switch (status) {
+        case LRQMM_OK: return "ok";
+        case LRQMM_ERR_INVALID_ARG: return "invalid argument";
+        case LRQMM_ERR_UNSUPPORTED: return "unsupported configuration";
+        case LRQMM_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case LRQMM_ERR_HIP: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+size_t lrqmm_workspace_bytes(int M, int N, int K, int rank, int oversample) {
+    if (M < 0 || N < 0 || K < 0 || rank < 0 || oversample < 0) return 0;
+    if (rank + oversample > LRQMM_MAX_SKETCH) return 0;
+    Arena a(nullptr);
+    return carve_matmul(a, M, N, K, rank, oversample, nullptr) + 256;
+}
+
+int lrqmm_quantize(const float* X, int rows, int cols, int axis, int bits, int round_mode, int8_t* codes,
+                   float* amax, void* stream) {
+    if (rows < 0 || cols < 0) return LRQMM_ERR_INVALID_ARG;
+    if (axis != LRQMM_AXIS_ROW && axis != LRQMM_AXIS_COL) return LRQMM_ERR_INVALID_ARG;
+    if (round_mode != LRQMM_ROUND_FLOOR && round_mode != LRQMM_ROUND_NEAREST) return LRQMM_ERR_INVALID_ARG;
+    if (!bits_ok(bits)) return LRQMM_ERR_UNSUPPORTED;
+    if (rows == 0 || cols == 0) return LRQMM_OK;
+    if (!X || !codes || !amax) return LRQMM_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const QuantParams q = make_quant_params(bits, round_mode);
+    if (axis == LRQMM_AXIS_ROW) return launch_quantize_rows(X, rows, cols, q, codes, amax, st);
+    return launch_quantize_cols(X, rows, cols, q, codes, amax, st);
+}
+
+int lrqmm_fill_sketch(uint64_t seed, int stream_id, int rows, int cols, float* omega, void* stream) {
+    if (rows < 0 || cols < 0 || stream_id < 0) return LRQMM_ERR_INVALID_ARG;
+    if (rows == 0 || cols == 0) return LRQMM_OK;
+    if (!omega) return LRQMM_ERR_INVALID_ARG;
+    return launch_fill_sketch(seed, stream_id, rows, cols, cols, omega, static_cast<hipStream_t>(stream));
+}
+
+int lrqmm_rsvd(const float* X, const float* amax, int rows, int cols, int axis, int bits, int round_mode,
+               int rank, int oversample, int power_iters, uint64_t seed, const float* omega_or_null, float* U,
+               float* Sigma, float* Vt, void* workspace, size_t workspace_bytes, void* stream) {
+    if (rows < 0 || cols < 0 || rank < 1 || oversample < 0 || power_iters < 0) return LRQMM_ERR_INVALID_ARG;
+    if (axis != LRQMM_AXIS_ROW && axis != LRQMM_AXIS_COL) return LRQMM_ERR_INVALID_ARG;
+    if (round_mode != LRQMM_ROUND_FLOOR && round_mode != LRQMM_ROUND_NEAREST) return LRQMM_ERR_INVALID_ARG;
+    if (!bits_ok(bits)) return LRQMM_ERR_UNSUPPORTED;
+    if (rows == 0 || cols == 0) return LRQMM_OK;
+    const int ell = rank + oversample;
+    if (ell > rows || ell > cols) return LRQMM_ERR_INVALID_ARG;
+    if (ell > LRQMM_MAX_SKETCH) return LRQMM_ERR_UNSUPPORTED;
+    if (!X || !amax || !U || !Sigma || !Vt) return LRQMM_ERR_INVALID_ARG;
+    if (!workspace || ((uintptr_t)workspace & 255)) return LRQMM_ERR_WORKSPACE;
+    const int LP = pad_to(ell, 16);
+    RsvdWs w;
+    Arena a(workspace);
+    if (carve_rsvd(a, rows, cols, axis, LP, rank, &w) > workspace_bytes) return LRQMM_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const QuantParams q = make_quant_params(bits, round_mode);
+    const int nscale = axis == LRQMM_AXIS_ROW ? rows : cols;
+    int rc;
+#define LRQ_TRY(x)                  \
+    do {                            \
+        rc = (x);                   \
+        if (rc != LRQMM_OK) return rc; \
+    } while (0)
+    LRQ_TRY(launch_scales(amax, nscale, pad_to(nscale, 4), q.qmaxf, w.lam, w.s, st));
+    if (omega_or_null) LRQ_TRY(launch_pad_copy(omega_or_null, cols, ell, LP, w.Wc, st));
+    else LRQ_TRY(launch_fill_sketch(seed, axis, cols, ell, LP, w.Wc, st));
+    const PassPlan pn = plan_pass_n(rows, cols), pt = plan_pass_t(rows, cols);
+    // Q = orth(partial sums) in place: Gram (float64) -> Cholesky -> Q = Y T
+    auto orth = [&](int splits, int n, float* buf) -> int {
+        int r2 = launch_reduce_gram(w.partial, splits, n, LP, nullptr, buf, w.gpart, st);
+        if (r2 != LRQMM_OK) return r2;
+        r2 = launch_chol_inverse(w.gpart, gram_blocks(n), ell, LP, w.T, st);
+        if (r2 != LRQMM_OK) return r2;
+        return launch_apply(buf, n, LP, w.T, LP, LP, buf, LP, 0, st);
+    };
+    // Y = R Omega
+    LRQ_TRY(launch_resid_mul_n(X, rows, cols, axis, w.lam, w.s, q, w.Wc, LP, pn, w.partial, st));
+    LRQ_TRY(orth(pn.splits, rows, w.Yr));
+    for (int it = 0; it < power_iters; ++it) {
+        // Z = orth(R^T Q); Q = orth(R Z)
+        LRQ_TRY(launch_resid_mul_t(X, rows, cols, axis, w.lam, w.s, q, w.Yr, LP, pt, w.partial, st));
+        LRQ_TRY(orth(pt.splits, cols, w.Wc));
+        LRQ_TRY(launch_resid_mul_n(X, rows, cols, axis, w.lam, w.s, q, w.Wc, LP, pn, w.partial, st));
+        LRQ_TRY(orth(pn.splits, rows, w.Yr));
+    }
+    // B^T = R^T Q (cols x l), its Gram B B^T, small SVD, U = Q U', V = B^T U' / sigma
+    LRQ_TRY(launch_resid_mul_t(X, rows, cols, axis, w.lam, w.s, q, w.Yr, LP, pt, w.partial, st));
+    LRQ_TRY(launch_reduce_gram(w.partial, pt.splits, cols, LP, nullptr, w.Wc, w.gpart, st));
+    LRQ_TRY(launch_small_svd(w.gpart, gram_blocks(cols), ell, LP, rank, Sigma, w.Ur, w.Mv, st));
+    LRQ_TRY(launch_apply(w.Yr, rows, LP, w.Ur, rank, rank, U, rank, 0, st));
+    LRQ_TRY(launch_apply(w.Wc, cols, LP, w.Mv, rank, rank, Vt, cols, 1, st));
+    return LRQMM_OK;
+}
+
+int lrqmm_gemm(int M, int N, int K, int bits, int rank, const int8_t* Aq, const float* amaxA,
+               const int8_t* BqT, const float* amaxB, const float* U, const float* Sig, const float* Vt,
+               const float* W, const float* Gam, const float* Zt, float* C, int32_t* Cint_or_null,
+               void* workspace, size_t workspace_bytes, void* stream) {
+    if (M < 0 || N < 0 || K < 0 || rank < 0) return LRQMM_ERR_INVALID_ARG;
+    if (!bits_ok(bits)) return LRQMM_ERR_UNSUPPORTED;
+    if (!k_fits_int32(K, bits)) return LRQMM_ERR_UNSUPPORTED;
+    if (M == 0 || N == 0) return LRQMM_OK;
+    if (rank > K || rank > M || rank > N) return LRQMM_ERR_INVALID_ARG;
+    if (rank > LRQMM_MAX_SKETCH) return LRQMM_ERR_UNSUPPORTED;
+    if (!C || !amaxA || !amaxB || (K > 0 && (!Aq || !BqT))) return LRQMM_ERR_INVALID_ARG;
+    if (rank > 0 && (!U || !Sig || !Vt || !W || !Gam || !Zt)) return LRQMM_ERR_INVALID_ARG;
+    if (!workspace || ((uintptr_t)workspace & 255)) return LRQMM_ERR_WORKSPACE;
+    GemmWs w;
+    Arena a(workspace);
+    if (carve_gemm(a, M, N, K, rank, &w) > workspace_bytes) return LRQMM_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const QuantParams q = make_quant_params(bits, 0);
+    int rc;
+    LRQ_TRY(launch_scales(amaxA, M, pad_to(M, 4), q.qmaxf, w.lamA, w.sA, st));
+    LRQ_TRY(launch_scales(amaxB, N, pad_to(N, 4), q.qmaxf, w.lamB, w.sB, st));
+    int R2P = 0;
+    if (rank > 0) {
+        const int RP = pad_to(rank, 16);
+        R2P = pad_to(2 * rank, 8);
+        LRQ_TRY(launch_pack_kr(W, Vt, K, rank, RP, w.Wp, w.Vp, st));
+        // S = A~ W = diag(sA) (Aq W)
+        const PassPlan pa = plan_pass_n(M, K);
+        LRQ_TRY(launch_codes_mul_n(Aq, M, K, w.Wp, RP, pa, w.partial, st));
+        LRQ_TRY(launch_reduce_gram(w.partial, pa.splits, M, RP, w.sA, w.S, nullptr, st));
+        // Pv = (Vt B~)^T = diag(sB) (BqT V)
+        const PassPlan pb = plan_pass_n(N, K);
+        LRQ_TRY(launch_codes_mul_n(BqT, N, K, w.Vp, RP, pb, w.partial, st));
+        LRQ_TRY(launch_reduce_gram(w.partial, pb.splits, N, RP, w.sB, w.Pv, nullptr, st));
+        LRQ_TRY(launch_vtw(Vt, W, K, rank, w.X, st));
+        LRQ_TRY(launch_build_panels(M, N, rank, RP, R2P, U, Sig, w.S, w.Pv, w.X, Gam, Zt, w.Lp, w.Rp, st));
+    }
+    return launch_int8_gemm(M, N, K, Aq, BqT, w.sA, w.sB, rank > 0 ? w.Lp : nullptr, rank > 0 ? w.Rp : nullptr,
+                            R2P, C, Cint_or_null, st);
+}
+
+int lrqmm_matmul(int M, int N, int K, int bits, int rank, int oversample, int power_iters, uint64_t seed,
+                 int round_mode, const float* A, const float* B, float* C, void* workspace,
+                 size_t workspace_bytes, void* stream) {
+    if (M < 0 || N < 0 || K < 0 || rank < 0 || oversample < 0 || power_iters < 0) return LRQMM_ERR_INVALID_ARG;
+    if (round_mode != LRQMM_ROUND_FLOOR && round_mode != LRQMM_ROUND_NEAREST) return LRQMM_ERR_INVALID_ARG;
+    if (!bits_ok(bits)) return LRQMM_ERR_UNSUPPORTED;
+    if (!k_fits_int32(K, bits)) return LRQMM_ERR_UNSUPPORTED;
+    if (M == 0 || N == 0) return LRQMM_OK;
+    if (rank > 0) {
+        const int ell = rank + oversample;
+        if (ell > M || ell > N || ell > K) return LRQMM_ERR_INVALID_ARG;
+        if (ell > LRQMM_MAX_SKETCH) return LRQMM_ERR_UNSUPPORTED;
+    }
+    if (!C || (K > 0 && (!A || !B))) return LRQMM_ERR_INVALID_ARG;
+    if (!workspace || ((uintptr_t)workspace & 255)) return LRQMM_ERR_WORKSPACE;
+    MatmulWs w;
+    Arena a(workspace);
+    if (carve_matmul(a, M, N, K, rank, oversample, &w) > workspace_bytes) return LRQMM_ERR_WORKSPACE;
+    int rc;
+    if (K > 0) {
+        LRQ_TRY(lrqmm_quantize(A, M, K, LRQMM_AXIS_ROW, bits, round_mode, w.Aq, w.amaxA, stream));
+        LRQ_TRY(lrqmm_quantize(B, K, N, LRQMM_AXIS_COL, bits, round_mode, w.BqT, w.amaxB, stream));
+    } else {
+        LRQ_TRY(launch_pad_copy(nullptr, M, 0, 1, w.amaxA, static_cast<hipStream_t>(stream)));
+        LRQ_TRY(launch_pad_copy(nullptr, N, 0, 1, w.amaxB, static_cast<hipStream_t>(stream)));
+    }
+    if (rank > 0) {
+        LRQ_TRY(lrqmm_rsvd(A, w.amaxA, M, K, LRQMM_AXIS_ROW, bits, round_mode, rank, oversample, power_iters,
+                           seed, nullptr, w.U, w.Sig, w.Vt, w.sub, w.sub_bytes, stream));
+        LRQ_TRY(lrqmm_rsvd(B, w.amaxB, K, N, LRQMM_AXIS_COL, bits, round_mode, rank, oversample, power_iters,
+                           seed, nullptr, w.W, w.Gam, w.Zt, w.sub, w.sub_bytes, stream));
+    }
+    return lrqmm_gemm(M, N, K, bits, rank, w.Aq, w.amaxA, w.BqT, w.amaxB, w.U, w.Sig, w.Vt, w.W, w.Gam, w.Zt, C,
+                      nullptr, w.sub, w.sub_bytes, stream);
+}
+
+}  // extern "C"

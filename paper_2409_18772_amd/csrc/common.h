@@ -1,0 +1,86 @@
+// Internal helpers shared by the LRQMM HIP kernels (gfx950 only).
+// Compiled with -ffp-contract=off: a*b+c is never fused implicitly; every FMA
+// in this library is written as fmaf()/fma() on purpose.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+#define LRQ_WAVE 64
+
+static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Quantizer parameters of one call (Eq. (quantA)): qmax as float, clamp range, rounding mode.
+struct QuantParams {
+    float qmaxf;   // 2^(bits-1) - 1
+    float lo;      // -qmax - 1
+    float hi;      // qmax
+    int round_mode;
+};
+
+static inline QuantParams make_quant_params(int bits, int round_mode) {
+    QuantParams q;
+    int qm = (1 << (bits - 1)) - 1;
+    q.qmaxf = (float)qm;
+    q.lo = (float)(-qm - 1);
+    q.hi = (float)qm;
+    q.round_mode = round_mode;
+    return q;
+}
+
+// lambda = fl32(qmax / amax), s = fl32(amax / qmax); zero group when amax < 1e-30.
+__device__ __forceinline__ void make_scales(float amax, float qmaxf, float& lam, float& s) {
+    if (amax >= 1e-30f) {
+        lam = qmaxf / amax;
+        s = amax / qmaxf;
+    } else {
+        lam = 0.0f;
+        s = 0.0f;
+    }
+}
+
+// code = clamp(round(fl32(lambda * x))) as a float holding an integer value.
+__device__ __forceinline__ float quant_code(float x, float lam, const QuantParams& q) {
+    float t = x * lam;
+    float c = (q.round_mode == 0) ? floorf(t) : rintf(t);
+    return fminf(fmaxf(c, q.lo), q.hi);
+}
+
+// residual x - code * s with a single rounding.
+__device__ __forceinline__ float quant_residual(float x, float lam, float s, const QuantParams& q) {
+    float c = quant_code(x, lam, q);
+    return fmaf(-c, s, x);
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// 16-byte global load of 4 consecutive floats when allowed, else guarded scalar loads.
+// `k` is the first column, valid columns are [0, cols).  Rows out of range give zeros.
+template <bool VEC>
+__device__ __forceinline__ float4 load4f(const float* __restrict__ rowp, int k, int cols, bool row_ok) {
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (!row_ok) return v;
+    if (VEC) {
+        if (k < cols) v = *reinterpret_cast<const float4*>(rowp + k);
+    } else {
+        if (k + 0 < cols) v.x = rowp[k + 0];
+        if (k + 1 < cols) v.y = rowp[k + 1];
+        if (k + 2 < cols) v.z = rowp[k + 2];
+        if (k + 3 < cols) v.w = rowp[k + 3];
+    }
+    return v;
+}
+
+#define LRQ_CHECK_LAUNCH()                                   \
+    do {                                                     \
+        if (hipGetLastError() != hipSuccess) return LRQMM_ERR_HIP; \
+    } while (0)

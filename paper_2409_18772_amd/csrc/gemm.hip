@@ -1,0 +1,263 @@
+// Integer GEMM on the int8 matrix cores with a fused dequantize + low-rank
+// compensation epilogue (paper: Eq. (INTGEMM), Eq. (QUANTGEMM); Algorithm 2 lines
+// 2-3 and 8-12).
+//
+// The three compensation terms of Algorithm 2 are never formed as M x N matrices:
+//   RC1 + RC2 + RC3 = (U Sig)(Vt B~) + (A~ W)(Gam Zt) + (U Sig)(Vt W)(Gam Zt)
+//                   = [U Sig | A~ W] . [Vt B~ + (Vt W) Gam Zt ; Gam Zt]
+// i.e. a rank-2r update Lp . Rp^T applied to each output tile while its int32
+// accumulators are still in registers.
+//
+// Main loop: 128x128 workgroup tile, 4 waves in 2x2, each wave 64x64 as 2x2
+// v_mfma_i32_32x32x32_i8 tiles; both operands are K-major (A codes M x K, B codes
+// stored transposed N x K), staged through double-buffered LDS with a padded row
+// stride (80 B) that makes the 16-byte operand reads bank-conflict free.
+// 32x32 accumulator layout (lane l, register v): row 8*(v/4) + 4*(l/32) + v%4,
+// column l%32 -- identical for the i32 and f32 32x32 MFMAs, which lets the
+// epilogue continue on the same registers with v_mfma_f32_32x32x2_f32.
+#include "kernels.h"
+
+#define TM 128
+#define TN 128
+#define BK 64
+#define LDS_STRIDE 80
+
+template <bool VEC>
+__device__ __forceinline__ uint4 load16b(const int8_t* __restrict__ base, int row, int nrows, int K,
+                                         int k) {
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (row >= nrows) return v;
+    const int8_t* p = base + (size_t)row * K + k;
+    if (VEC) {
+        if (k < K) v = *reinterpret_cast<const uint4*>(p);
+    } else {
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int b = 0; b < 16; ++b)
+            if (k + b < K) w[b >> 2] |= (uint32_t)(uint8_t)p[b] << (8 * (b & 3));
+        v = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    return v;
+}
+
+template <bool VEC, bool COMP, bool WCINT>
+__global__ __launch_bounds__(256) void int8_gemm_kernel(int M, int N, int K,
+                                                        const int8_t* __restrict__ Aq,
+                                                        const int8_t* __restrict__ BqT,
+                                                        const float* __restrict__ sA,
+                                                        const float* __restrict__ sB,
+                                                        const float* __restrict__ Lp,
+                                                        const float* __restrict__ Rp, int R2P,
+                                                        float* __restrict__ C,
+                                                        int32_t* __restrict__ Cint, int tiles_n,
+                                                        int ntiles) {
+    __shared__ __align__(16) int8_t As[2][TM * LDS_STRIDE];
+    __shared__ __align__(16) int8_t Bs[2][TN * LDS_STRIDE];
+    // Workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a contiguous
+    // band of tiles so operand panels are shared inside its L2.
+    int tile = blockIdx.x;
+    if ((ntiles & 7) == 0) tile = (tile & 7) * (ntiles >> 3) + (tile >> 3);
+    const int m0 = (tile / tiles_n) * TM, n0 = (tile % tiles_n) * TN;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, lh = lane >> 5;
+
+    v16i acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0;
+
+    // staging: 512 16-byte chunks per operand tile, two per thread
+    const int srow0 = tid >> 2, skc = (tid & 3) * 16;
+    uint4 ra[2], rb[2];
+    auto gload = [&](int k0) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            ra[u] = load16b<VEC>(Aq, m0 + srow0 + 64 * u, M, K, k0 + skc);
+            rb[u] = load16b<VEC>(BqT, n0 + srow0 + 64 * u, N, K, k0 + skc);
+        }
+    };
+    auto sstore = [&](int buf) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            *reinterpret_cast<uint4*>(&As[buf][(srow0 + 64 * u) * LDS_STRIDE + skc]) = ra[u];
+            *reinterpret_cast<uint4*>(&Bs[buf][(srow0 + 64 * u) * LDS_STRIDE + skc]) = rb[u];
+        }
+    };
+    const int nk = (K + BK - 1) / BK;
+    gload(0);
+    sstore(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < nk) gload((kt + 1) * BK);
+#pragma unroll
+        for (int kk = 0; kk < BK / 32; ++kk) {
+            v4i af[2], bf[2];
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+                af[mt] = *reinterpret_cast<const v4i*>(
+                    &As[buf][(wm * 64 + mt * 32 + l32) * LDS_STRIDE + kk * 32 + lh * 16]);
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt)
+                bf[nt] = *reinterpret_cast<const v4i*>(
+                    &Bs[buf][(wn * 64 + nt * 32 + l32) * LDS_STRIDE + kk * 32 + lh * 16]);
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt)
+                    acc[mt][nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[mt], bf[nt], acc[mt][nt], 0, 0, 0);
+        }
+        if (kt + 1 < nk) sstore(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: dequantize, rank-2r update, store ----
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+        const int rbase = m0 + wm * 64 + mt * 32;
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            const int col = n0 + wn * 64 + nt * 32 + l32;
+            const bool col_ok = col < N;
+            const float sb = col_ok ? sB[col] : 0.f;
+            v16f f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = rbase + 8 * (v >> 2) + 4 * lh + (v & 3);
+                const float sa = (row < M) ? sA[row] : 0.f;
+                if (WCINT && row < M && col_ok) Cint[(size_t)row * N + col] = acc[mt][nt][v];
+                f[v] = ((float)acc[mt][nt][v] * sa) * sb;
+            }
+            if (COMP) {
+                const int lrow = rbase + l32;
+                const float* lp = Lp + (size_t)(lrow < M ? lrow : 0) * R2P + 4 * lh;
+                const float* rp = Rp + (size_t)(col_ok ? col : 0) * R2P + 4 * lh;
+                const bool lok = lrow < M;
+                for (int t0 = 0; t0 < R2P; t0 += 8) {
+                    float4 a4 = lok ? *reinterpret_cast<const float4*>(lp + t0) : make_float4(0.f, 0.f, 0.f, 0.f);
+                    float4 b4 = col_ok ? *reinterpret_cast<const float4*>(rp + t0) : make_float4(0.f, 0.f, 0.f, 0.f);
+                    f = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.x, b4.x, f, 0, 0, 0);
+                    f = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.y, b4.y, f, 0, 0, 0);
+                    f = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.z, b4.z, f, 0, 0, 0);
+                    f = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.w, b4.w, f, 0, 0, 0);
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = rbase + 8 * (v >> 2) + 4 * lh + (v & 3);
+                if (row < M && col_ok) C[(size_t)row * N + col] = f[v];
+            }
+        }
+    }
+}
+
+// X[t][u] = sum_k Vt[t][k] W[k][u]; one workgroup per entry.
+__global__ __launch_bounds__(256) void vtw_kernel(const float* __restrict__ Vt, const float* __restrict__ W,
+                                                  int K, int r, float* __restrict__ X) {
+    __shared__ double part[4];
+    const int t = blockIdx.x / r, u = blockIdx.x % r;
+    double acc = 0.0;
+    for (int k = threadIdx.x; k < K; k += 256) acc = fma((double)Vt[(size_t)t * K + k], (double)W[(size_t)k * r + u], acc);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) X[blockIdx.x] = (float)(((part[0] + part[1]) + part[2]) + part[3]);
+}
+
+__global__ void pack_kr_kernel(const float* __restrict__ W, const float* __restrict__ Vt, int K, int r, int RP,
+                               float* __restrict__ Wp, float* __restrict__ Vp) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)K * RP) return;
+    const int k = (int)(idx / RP), c = (int)(idx % RP);
+    Wp[idx] = (c < r) ? W[(size_t)k * r + c] : 0.f;
+    Vp[idx] = (c < r) ? Vt[(size_t)c * K + k] : 0.f;
+}
+
+__global__ void build_left_kernel(int M, int r, int RP, int R2P, const float* __restrict__ U,
+                                  const float* __restrict__ Sig, const float* __restrict__ S,
+                                  float* __restrict__ Lp) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)M * R2P) return;
+    const int i = (int)(idx / R2P), c = (int)(idx % R2P);
+    float v = 0.f;
+    if (c < r) v = U[(size_t)i * r + c] * Sig[c];
+    else if (c < 2 * r) v = S[(size_t)i * RP + (c - r)];
+    Lp[idx] = v;
+}
+
+__global__ void build_right_kernel(int N, int r, int RP, int R2P, const float* __restrict__ Pv,
+                                   const float* __restrict__ X, const float* __restrict__ Gam,
+                                   const float* __restrict__ Zt, float* __restrict__ Rp) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)N * R2P) return;
+    const int c = (int)(idx / N), j = (int)(idx % N);   // j fastest: coalesced reads of Zt
+    float v = 0.f;
+    if (c < r) {
+        float acc = Pv[(size_t)j * RP + c];
+        for (int u = 0; u < r; ++u) acc = fmaf(X[c * r + u] * Gam[u], Zt[(size_t)u * N + j], acc);
+        v = acc;
+    } else if (c < 2 * r) {
+        v = Gam[c - r] * Zt[(size_t)(c - r) * N + j];
+    }
+    Rp[(size_t)j * R2P + c] = v;
+}
+
+int launch_vtw(const float* Vt, const float* W, int K, int r, float* X, hipStream_t st) {
+    hipLaunchKernelGGL(vtw_kernel, dim3(r * r), dim3(256), 0, st, Vt, W, K, r, X);
+    LRQ_CHECK_LAUNCH();
+    return LRQMM_OK;
+}
+
+int launch_pack_kr(const float* W, const float* Vt, int K, int r, int RP, float* Wp, float* Vp,
+                   hipStream_t st) {
+    const size_t total = (size_t)K * RP;
+    hipLaunchKernelGGL(pack_kr_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, W, Vt, K, r, RP, Wp, Vp);
+    LRQ_CHECK_LAUNCH();
+    return LRQMM_OK;
+}
+
+int launch_build_panels(int M, int N, int r, int RP, int R2P, const float* U, const float* Sig,
+                        const float* S, const float* Pv, const float* X, const float* Gam,
+                        const float* Zt, float* Lp, float* Rp, hipStream_t st) {
+    size_t total = (size_t)M * R2P;
+    hipLaunchKernelGGL(build_left_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, M, r, RP, R2P, U, Sig, S, Lp);
+    LRQ_CHECK_LAUNCH();
+    total = (size_t)N * R2P;
+    hipLaunchKernelGGL(build_right_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, N, r, RP, R2P, Pv, X, Gam, Zt, Rp);
+    LRQ_CHECK_LAUNCH();
+    return LRQMM_OK;
+}
+
+template <bool VEC>
+static void dispatch_gemm(bool comp, bool wcint, dim3 grid, hipStream_t st, int M, int N, int K,
+                          const int8_t* Aq, const int8_t* BqT, const float* sA, const float* sB,
+                          const float* Lp, const float* Rp, int R2P, float* C, int32_t* Cint, int tiles_n,
+                          int ntiles) {
+#define LRQ_GEMM(COMP, WC) \
+    hipLaunchKernelGGL((int8_gemm_kernel<VEC, COMP, WC>), grid, dim3(256), 0, st, M, N, K, Aq, BqT, sA, sB, Lp, Rp, R2P, C, Cint, tiles_n, ntiles)
+    if (comp) {
+        if (wcint) LRQ_GEMM(true, true); else LRQ_GEMM(true, false);
+    } else {
+        if (wcint) LRQ_GEMM(false, true); else LRQ_GEMM(false, false);
+    }
+#undef LRQ_GEMM
+}
+
+int launch_int8_gemm(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, const float* sA,
+                     const float* sB, const float* Lp, const float* Rp, int R2P, float* C, int32_t* Cint,
+                     hipStream_t st) {
+    const int tiles_m = ceil_div(M, TM), tiles_n = ceil_div(N, TN);
+    const int ntiles = tiles_m * tiles_n;
+    const bool vec = (K % 16 == 0) && (((uintptr_t)Aq | (uintptr_t)BqT) & 15) == 0;
+    const bool comp = Lp != nullptr;
+    dim3 grid(ntiles);
+    if (vec) dispatch_gemm<true>(comp, Cint != nullptr, grid, st, M, N, K, Aq, BqT, sA, sB, Lp, Rp, R2P, C, Cint, tiles_n, ntiles);
+    else     dispatch_gemm<false>(comp, Cint != nullptr, grid, st, M, N, K, Aq, BqT, sA, sB, Lp, Rp, R2P, C, Cint, tiles_n, ntiles);
+    LRQ_CHECK_LAUNCH();
+    return LRQMM_OK;
+}

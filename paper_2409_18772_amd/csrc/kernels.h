@@ -1,0 +1,74 @@
+// Internal launch functions of the LRQMM library (one per step of the hot path).
+// All pointers are device pointers; every function only enqueues work on `st`
+// and returns LRQMM_OK or LRQMM_ERR_HIP.
+#pragma once
+#include "common.h"
+#include "../../include/lrqmm.h"
+
+// ---- quantize.hip -------------------------------------------------------
+int launch_quantize_rows(const float* X, int rows, int cols, QuantParams q, int8_t* codes,
+                         float* amax, hipStream_t st);
+int launch_quantize_cols(const float* X, int rows, int cols, QuantParams q, int8_t* codesT,
+                         float* amax, hipStream_t st);
+// lam[n], s[n] from amax[n]; entries n..npad-1 are zero-filled.
+int launch_scales(const float* amax, int n, int npad, float qmaxf, float* lam, float* s,
+                  hipStream_t st);
+
+// ---- sketch.hip ---------------------------------------------------------
+// omega[i*ld + j] for i < rows, j < ld; columns j >= cols are zero.
+int launch_fill_sketch(uint64_t seed, int stream_id, int rows, int cols, int ld, float* omega,
+                       hipStream_t st);
+// dst[i*ld + j] = (j < cols) ? src[i*cols + j] : 0
+int launch_pad_copy(const float* src, int rows, int cols, int ld, float* dst, hipStream_t st);
+
+// ---- passes.hip ---------------------------------------------------------
+struct PassPlan {
+    int splits;   // number of partial results
+    int chunk;    // reduction-index range per split (multiple of 64)
+};
+PassPlan plan_pass_n(int rows, int cols);
+PassPlan plan_pass_t(int rows, int cols);
+// partial[s][rows][LP] = R[:, chunk s] . W[chunk s, :]      (W is cols x LP)
+int launch_resid_mul_n(const float* X, int rows, int cols, int axis, const float* lam,
+                       const float* s, QuantParams q, const float* W, int LP, PassPlan plan,
+                       float* partial, hipStream_t st);
+// partial[s][cols][LP] = R[chunk s, :]^T . W[chunk s, :]    (W is rows x LP)
+int launch_resid_mul_t(const float* X, int rows, int cols, int axis, const float* lam,
+                       const float* s, QuantParams q, const float* W, int LP, PassPlan plan,
+                       float* partial, hipStream_t st);
+// partial[s][rows][LP] = scale-free codes[:, chunk s] . W[chunk s, :]  (codes rows x K int8)
+int launch_codes_mul_n(const int8_t* codes, int rows, int K, const float* W, int LP,
+                       PassPlan plan, float* partial, hipStream_t st);
+
+// ---- orth.hip -----------------------------------------------------------
+int gram_blocks(int n);
+// Y[n][LP] = sum_s partial[s][n][LP] (optionally times rowscale[i]);
+// gpart[b][LP*LP] = Gram of rows 64b..64b+63 of Y in float64.
+int launch_reduce_gram(const float* partial, int splits, int n, int LP, const float* rowscale,
+                       float* Y, double* gpart, hipStream_t st);
+// T (LP x LP float64, upper triangular) with (Y T)^T (Y T) = I on the live columns.
+int launch_chol_inverse(const double* gpart, int nb, int ell, int LP, double* T, hipStream_t st);
+// out = In[n x LP] . Mat[LP x cm]; normal: out[i*ldo + c]; transposed: out[c*ldo + i].
+int launch_apply(const float* In, int n, int LP, const double* Mat, int cm, int ldm, float* out,
+                 int ldo, int transposed, hipStream_t st);
+// Eigen-decomposition of sum_b gpart[b] (l x l): Sigma[r] = sqrt of the r largest
+// eigenvalues, Ur (LP x r) their eigenvectors, Mv = Ur diag(1/Sigma).
+int launch_small_svd(const double* gpart, int nb, int ell, int LP, int rank, float* Sigma,
+                     double* Ur, double* Mv, hipStream_t st);
+
+// ---- gemm.hip -----------------------------------------------------------
+// X[t][u] = sum_k Vt[t][k] W[k][u]   (r x r)
+int launch_vtw(const float* Vt, const float* W, int K, int r, float* X, hipStream_t st);
+// Wp[k][0..RP) = W[k][0..r) zero padded; Vp[k][t] = Vt[t][k] zero padded.
+int launch_pack_kr(const float* W, const float* Vt, int K, int r, int RP, float* Wp, float* Vp,
+                   hipStream_t st);
+// Left panel  Lp[i][0..r) = U[i][t] Sig[t],  Lp[i][r..2r) = S[i][u]      (S = A~ W, M x RP)
+// Right panel Rp[j][0..r) = Pv[j][t] + sum_u X[t][u] Gam[u] Zt[u][j]      (Pv = (Vt B~)^T, N x RP)
+//             Rp[j][r..2r) = Gam[u] Zt[u][j];   both zero padded to R2P columns.
+int launch_build_panels(int M, int N, int r, int RP, int R2P, const float* U, const float* Sig,
+                        const float* S, const float* Pv, const float* X, const float* Gam,
+                        const float* Zt, float* Lp, float* Rp, hipStream_t st);
+// C = diag(sA) (Aq . BqT^T) diag(sB) [+ Lp . Rp^T when Lp != null]; optional raw int32 output.
+int launch_int8_gemm(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, const float* sA,
+                     const float* sB, const float* Lp, const float* Rp, int R2P, float* C,
+                     int32_t* Cint, hipStream_t st);

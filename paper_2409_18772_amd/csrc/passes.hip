@@ -1,0 +1,346 @@
+// Streaming products with the quantization residual R = X - Dequant(Quant(X))
+// (paper: Algorithm 2 lines 4-5 for R; Background 2.1 / Algorithm 1 for the
+// products R.Omega, R^T Q, R Z, Q^T R of the randomized range finder), and the
+// code-matrix products of Algorithm 2 lines 9-10 (A~ W and V^T B~).
+//
+// R is never stored: each pass re-reads the float32 operand once from HBM and
+// regenerates the residual in registers from the per-group scales.  The
+// tall-skinny contraction runs on the fp32 matrix cores (v_mfma_f32_16x16x4_f32);
+// since the reduction index may be visited in any order, each lane loads 16
+// contiguous bytes and the MFMA k-index is permuted to match.
+//
+// MFMA 16x16x4 f32 operand layout (lane l): A[i = l%16][k = l/16],
+// B[k = l/16][j = l%16], D[i = 4*(l/16)+v][j = l%16] for v = 0..3.
+#include "kernels.h"
+
+#define KCHUNK 64   // reduction elements staged per LDS step in the N-type kernels
+
+__device__ __forceinline__ v4f mfma16(float a, float b, v4f c) {
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+// Stage W[k0 .. k0+63][0..LP) (row-major, ld = LP) into LDS with row stride LP+4.
+__device__ __forceinline__ void stage_w(const float* __restrict__ W, int k0, int kend, int LP,
+                                        float* __restrict__ wl) {
+    const int n4 = KCHUNK * LP / 4;
+    for (int idx = threadIdx.x; idx < n4; idx += 256) {
+        const int e = idx * 4;
+        const int kk = e / LP, n = e % LP;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (k0 + kk < kend) v = *reinterpret_cast<const float4*>(W + (size_t)(k0 + kk) * LP + n);
+        *reinterpret_cast<float4*>(wl + kk * (LP + 4) + n) = v;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// N-type: partial[split][rows][LP] = R[:, k-range] . W[k-range, :]
+// grid (ceil(rows/64), splits); 4 waves x 16 rows; W chunk staged in LDS.
+// ---------------------------------------------------------------------------
+template <int NT, int AXIS, bool VEC>
+__global__ __launch_bounds__(256) void resid_mul_n_kernel(
+    const float* __restrict__ X, int rows, int cols, const float* __restrict__ lam,
+    const float* __restrict__ sc, QuantParams q, const float* __restrict__ W, int chunk,
+    float* __restrict__ partial) {
+    constexpr int LP = NT * 16;
+    __shared__ __align__(16) float wl[KCHUNK * (LP + 4)];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int r = lane & 15, g = lane >> 4;
+    const int row = blockIdx.x * 64 + wave * 16 + r;
+    const bool row_ok = row < rows;
+    const float* xp = X + (size_t)(row_ok ? row : 0) * cols;
+    const int kb = blockIdx.y * chunk;
+    const int ke = min(cols, kb + chunk);
+    float lam_r = 0.f, s_r = 0.f;
+    if (AXIS == 0 && row_ok) {
+        lam_r = lam[row];
+        s_r = sc[row];
+    }
+    v4f acc[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[nt] = (v4f){0.f, 0.f, 0.f, 0.f};
+
+    for (int k0 = kb; k0 < ke; k0 += KCHUNK) {
+        __syncthreads();
+        stage_w(W, k0, ke, LP, wl);
+        float res[4][4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int k = k0 + 16 * j + 4 * g;
+            float4 x = load4f<VEC>(xp, k, ke, row_ok);
+            float4 l4, s4;
+            if (AXIS == 0) {
+                l4 = make_float4(lam_r, lam_r, lam_r, lam_r);
+                s4 = make_float4(s_r, s_r, s_r, s_r);
+            } else {
+                // lam / sc are padded with zeros to a multiple of 4 beyond `cols`
+                l4 = (k < ke) ? *reinterpret_cast<const float4*>(lam + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+                s4 = (k < ke) ? *reinterpret_cast<const float4*>(sc + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+            res[j][0] = quant_residual(x.x, l4.x, s4.x, q);
+            res[j][1] = quant_residual(x.y, l4.y, s4.y, q);
+            res[j][2] = quant_residual(x.z, l4.z, s4.z, q);
+            res[j][3] = quant_residual(x.w, l4.w, s4.w, q);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float* wrow = wl + (16 * j + 4 * g + t) * (LP + 4) + r;
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) acc[nt] = mfma16(res[j][t], wrow[16 * nt], acc[nt]);
+            }
+        }
+    }
+    float* out = partial + (size_t)blockIdx.y * rows * LP;
+    const int orow0 = blockIdx.x * 64 + wave * 16 + 4 * g;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            if (orow0 + v < rows) out[(size_t)(orow0 + v) * LP + 16 * nt + r] = acc[nt][v];
+}
+
+// Same contraction with an int8 code matrix as the streamed operand (no scales).
+template <int NT, bool VEC>
+__global__ __launch_bounds__(256) void codes_mul_n_kernel(const int8_t* __restrict__ Cq, int rows,
+                                                          int K, const float* __restrict__ W,
+                                                          int chunk, float* __restrict__ partial) {
+    constexpr int LP = NT * 16;
+    __shared__ __align__(16) float wl[KCHUNK * (LP + 4)];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int r = lane & 15, g = lane >> 4;
+    const int row = blockIdx.x * 64 + wave * 16 + r;
+    const bool row_ok = row < rows;
+    const int8_t* cp = Cq + (size_t)(row_ok ? row : 0) * K;
+    const int kb = blockIdx.y * chunk;
+    const int ke = min(K, kb + chunk);
+    v4f acc[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[nt] = (v4f){0.f, 0.f, 0.f, 0.f};
+    for (int k0 = kb; k0 < ke; k0 += KCHUNK) {
+        __syncthreads();
+        stage_w(W, k0, ke, LP, wl);
+        float res[4][4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int k = k0 + 16 * j + 4 * g;
+            int c[4] = {0, 0, 0, 0};
+            if (row_ok) {
+                if (VEC) {
+                    if (k < ke) {
+                        const uint32_t p = *reinterpret_cast<const uint32_t*>(cp + k);
+                        c[0] = (int8_t)(p & 0xff);
+                        c[1] = (int8_t)((p >> 8) & 0xff);
+                        c[2] = (int8_t)((p >> 16) & 0xff);
+                        c[3] = (int8_t)((p >> 24) & 0xff);
+                    }
+                } else {
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        if (k + t < ke) c[t] = cp[k + t];
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) res[j][t] = (float)c[t];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float* wrow = wl + (16 * j + 4 * g + t) * (LP + 4) + r;
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) acc[nt] = mfma16(res[j][t], wrow[16 * nt], acc[nt]);
+            }
+        }
+    }
+    float* out = partial + (size_t)blockIdx.y * rows * LP;
+    const int orow0 = blockIdx.x * 64 + wave * 16 + 4 * g;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            if (orow0 + v < rows) out[(size_t)(orow0 + v) * LP + 16 * nt + r] = acc[nt][v];
+}
+
+// ---------------------------------------------------------------------------
+// T-type: partial[split][cols][LP] = R[i-range, :]^T . W[i-range, :]
+// grid (ceil(cols/64), splits); the 4 waves of a block share one 64-column strip,
+// interleave rows, and merge their accumulators through LDS.
+// A lane's float4 holds columns c0+4c .. c0+4c+3; component t feeds M-tile t, so
+// M-tile t covers the columns {c0 + 4 c + t}.
+// ---------------------------------------------------------------------------
+template <int NT, int AXIS, bool VEC>
+__global__ __launch_bounds__(256) void resid_mul_t_kernel(
+    const float* __restrict__ X, int rows, int cols, const float* __restrict__ lam,
+    const float* __restrict__ sc, QuantParams q, const float* __restrict__ W, int chunk,
+    float* __restrict__ partial) {
+    constexpr int LP = NT * 16;
+    __shared__ __align__(16) float red[64 * LP];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int c = lane & 15, g = lane >> 4;
+    const int c0 = blockIdx.x * 64;
+    const int kc = c0 + 4 * c;
+    const int ib = blockIdx.y * chunk;
+    const int ie = min(rows, ib + chunk);
+    float4 l4 = make_float4(0.f, 0.f, 0.f, 0.f), s4 = l4;
+    if (AXIS == 1 && kc < cols) {   // padded with zeros to a multiple of 4
+        l4 = *reinterpret_cast<const float4*>(lam + kc);
+        s4 = *reinterpret_cast<const float4*>(sc + kc);
+    }
+    v4f acc[4][NT];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[t][nt] = (v4f){0.f, 0.f, 0.f, 0.f};
+
+    for (int i0 = ib + wave * 4; i0 < ie; i0 += 16) {
+        const int i = i0 + g;
+        const bool ok = i < ie;
+        const size_t ii = ok ? (size_t)i : 0;
+        float4 x = load4f<VEC>(X + ii * cols, kc, cols, ok);
+        if (AXIS == 0) {
+            const float lr = ok ? lam[ii] : 0.f, sr = ok ? sc[ii] : 0.f;
+            l4 = make_float4(lr, lr, lr, lr);
+            s4 = make_float4(sr, sr, sr, sr);
+        }
+        float w[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) w[nt] = ok ? W[ii * LP + 16 * nt + c] : 0.f;
+        float res[4];
+        res[0] = quant_residual(x.x, l4.x, s4.x, q);
+        res[1] = quant_residual(x.y, l4.y, s4.y, q);
+        res[2] = quant_residual(x.z, l4.z, s4.z, q);
+        res[3] = quant_residual(x.w, l4.w, s4.w, q);
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) acc[t][nt] = mfma16(res[t], w[nt], acc[t][nt]);
+    }
+    // merge the four waves (fixed order: deterministic)
+    for (int wv = 0; wv < 4; ++wv) {
+        if (wave == wv) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int cl = 16 * g + 4 * v + t;   // local column of D row 4g+v in M-tile t
+                        float* p = red + cl * LP + 16 * nt + c;
+                        *p = (wv == 0) ? acc[t][nt][v] : (*p + acc[t][nt][v]);
+                    }
+        }
+        __syncthreads();
+    }
+    float* out = partial + (size_t)blockIdx.y * cols * LP;
+    for (int idx = threadIdx.x; idx < 64 * LP / 4; idx += 256) {
+        const int e = idx * 4;
+        const int cl = e / LP, n = e % LP;
+        if (c0 + cl < cols)
+            *reinterpret_cast<float4*>(out + (size_t)(c0 + cl) * LP + n) =
+                *reinterpret_cast<const float4*>(red + cl * LP + n);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// launch plans and dispatch
+// ---------------------------------------------------------------------------
+static int pick_splits(int blocks_one_split, int reduce_len, int unit) {
+    // aim for ~1024 workgroups (4 per CU) but keep >= 4 `unit`-sized steps per split
+    int want = ceil_div(1024, max(1, blocks_one_split));
+    int max_splits = max(1, reduce_len / (4 * unit));
+    int s = max(1, min(want, min(max_splits, 32)));
+    return s;
+}
+
+PassPlan plan_pass_n(int rows, int cols) {
+    PassPlan p;
+    int s = pick_splits(ceil_div(rows, 64), cols, KCHUNK);
+    p.chunk = ceil_div(ceil_div(cols, s), KCHUNK) * KCHUNK;
+    p.splits = ceil_div(cols, p.chunk);
+    return p;
+}
+
+PassPlan plan_pass_t(int rows, int cols) {
+    PassPlan p;
+    int s = pick_splits(ceil_div(cols, 64), rows, 16);
+    p.chunk = ceil_div(ceil_div(rows, s), 16) * 16;
+    p.splits = ceil_div(rows, p.chunk);
+    return p;
+}
+
+static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+template <int NT>
+static void dispatch_n(int axis, bool vec, dim3 grid, hipStream_t st, const float* X, int rows, int cols,
+                       const float* lam, const float* s, QuantParams q, const float* W, int chunk,
+                       float* partial) {
+    if (axis == 0) {
+        if (vec) hipLaunchKernelGGL((resid_mul_n_kernel<NT, 0, true>), grid, dim3(256), 0, st, X, rows, cols, lam, s, q, W, chunk, partial);
+        else     hipLaunchKernelGGL((resid_mul_n_kernel<NT, 0, false>), grid, dim3(256), 0, st, X, rows, cols, lam, s, q, W, chunk, partial);
+    } else {
+        if (vec) hipLaunchKernelGGL((resid_mul_n_kernel<NT, 1, true>), grid, dim3(256), 0, st, X, rows, cols, lam, s, q, W, chunk, partial);
+        else     hipLaunchKernelGGL((resid_mul_n_kernel<NT, 1, false>), grid, dim3(256), 0, st, X, rows, cols, lam, s, q, W, chunk, partial);
+    }
+}
+
+template <int NT>
+static void dispatch_t(int axis, bool vec, dim3 grid, hipStream_t st, const float* X, int rows, int cols,
+                       const float* lam, const float* s, QuantParams q, const float* W, int chunk,
+                       float* partial) {
+    if (axis == 0) {
+        if (vec) hipLaunchKernelGGL((resid_mul_t_kernel<NT, 0, true>), grid, dim3(256), 0, st, X, rows, cols, lam, s, q, W, chunk, partial);
+        else     hipLaunchKernelGGL((resid_mul_t_kernel<NT, 0, false>), grid, dim3(256), 0, st, X, rows, cols, lam, s, q, W, chunk, partial);
+    } else {
+        if (vec) hipLaunchKernelGGL((resid_mul_t_kernel<NT, 1, true>), grid, dim3(256), 0, st, X, rows, cols, lam, s, q, W, chunk, partial);
+        else     hipLaunchKernelGGL((resid_mul_t_kernel<NT, 1, false>), grid, dim3(256), 0, st, X, rows, cols, lam, s, q, W, chunk, partial);
+    }
+}
+
+template <int NT>
+static void dispatch_c(bool vec, dim3 grid, hipStream_t st, const int8_t* Cq, int rows, int K, const float* W,
+                       int chunk, float* partial) {
+    if (vec) hipLaunchKernelGGL((codes_mul_n_kernel<NT, true>), grid, dim3(256), 0, st, Cq, rows, K, W, chunk, partial);
+    else     hipLaunchKernelGGL((codes_mul_n_kernel<NT, false>), grid, dim3(256), 0, st, Cq, rows, K, W, chunk, partial);
+}
+
+#define NT_SWITCH(NTV, CALL)            \
+    switch (NTV) {                      \
+        case 1: { constexpr int NT_ = 1; CALL; } break; \
+        case 2: { constexpr int NT_ = 2; CALL; } break; \
+        case 3: { constexpr int NT_ = 3; CALL; } break; \
+        case 4: { constexpr int NT_ = 4; CALL; } break; \
+        case 5: { constexpr int NT_ = 5; CALL; } break; \
+        default: return LRQMM_ERR_UNSUPPORTED;          \
+    }
+
+int launch_resid_mul_n(const float* X, int rows, int cols, int axis, const float* lam, const float* s,
+                       QuantParams q, const float* W, int LP, PassPlan plan, float* partial,
+                       hipStream_t st) {
+    const bool vec = (cols % 4 == 0) && aligned16(X);
+    dim3 grid(ceil_div(rows, 64), plan.splits);
+    NT_SWITCH(LP / 16, (dispatch_n<NT_>(axis, vec, grid, st, X, rows, cols, lam, s, q, W, plan.chunk, partial)));
+    LRQ_CHECK_LAUNCH();
+    return LRQMM_OK;
+}
+
+int launch_resid_mul_t(const float* X, int rows, int cols, int axis, const float* lam, const float* s,
+                       QuantParams q, const float* W, int LP, PassPlan plan, float* partial,
+                       hipStream_t st) {
+    const bool vec = (cols % 4 == 0) && aligned16(X);
+    dim3 grid(ceil_div(cols, 64), plan.splits);
+    NT_SWITCH(LP / 16, (dispatch_t<NT_>(axis, vec, grid, st, X, rows, cols, lam, s, q, W, plan.chunk, partial)));
+    LRQ_CHECK_LAUNCH();
+    return LRQMM_OK;
+}
+
+int launch_codes_mul_n(const int8_t* codes, int rows, int K, const float* W, int LP, PassPlan plan,
+                       float* partial, hipStream_t st) {
+    const bool vec = (K % 4 == 0) && ((uintptr_t)codes % 4 == 0);
+    dim3 grid(ceil_div(rows, 64), plan.splits);
+    NT_SWITCH(LP / 16, (dispatch_c<NT_>(vec, grid, st, codes, rows, K, W, plan.chunk, partial)));
+    LRQ_CHECK_LAUNCH();
+    return LRQMM_OK;
+}

@@ -1,0 +1,179 @@
+// Symmetric absmax quantization (paper: Background 2.2 Eq. (quantA); floor variant
+// Methodology Eq. (get_ra2); Algorithm 2 line 1).  HBM-streaming kernels: each
+// input element is read from HBM once (the second touch of a row/tile hits L2).
+#include "kernels.h"
+
+// One wavefront per row: absmax by wave reduction, then codes with 4-byte packed stores.
+template <bool VEC>
+__global__ __launch_bounds__(256) void quant_rows_kernel(const float* __restrict__ X, int rows,
+                                                         int cols, QuantParams q,
+                                                         int8_t* __restrict__ codes,
+                                                         float* __restrict__ amax) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + wave;
+    if (row >= rows) return;
+    const float* xp = X + (size_t)row * cols;
+    float m = 0.0f;
+    for (int k = lane * 4; k < cols; k += 256) {
+        float4 v = load4f<VEC>(xp, k, cols, true);
+        m = fmaxf(fmaxf(m, fabsf(v.x)), fmaxf(fabsf(v.y), fmaxf(fabsf(v.z), fabsf(v.w))));
+    }
+    m = wave_max(m);
+    float lam, s;
+    make_scales(m, q.qmaxf, lam, s);
+    if (lane == 0) amax[row] = m;
+    int8_t* cp = codes + (size_t)row * cols;
+    for (int k = lane * 4; k < cols; k += 256) {
+        float4 v = load4f<VEC>(xp, k, cols, true);
+        int c0 = (int)quant_code(v.x, lam, q), c1 = (int)quant_code(v.y, lam, q);
+        int c2 = (int)quant_code(v.z, lam, q), c3 = (int)quant_code(v.w, lam, q);
+        if (VEC) {
+            uint32_t p = (uint32_t)(c0 & 0xff) | ((uint32_t)(c1 & 0xff) << 8) |
+                         ((uint32_t)(c2 & 0xff) << 16) | ((uint32_t)(c3 & 0xff) << 24);
+            *reinterpret_cast<uint32_t*>(cp + k) = p;
+        } else {
+            if (k + 0 < cols) cp[k + 0] = (int8_t)c0;
+            if (k + 1 < cols) cp[k + 1] = (int8_t)c1;
+            if (k + 2 < cols) cp[k + 2] = (int8_t)c2;
+            if (k + 3 < cols) cp[k + 3] = (int8_t)c3;
+        }
+    }
+}
+
+__global__ void fill_u32_kernel(uint32_t* p, int n, uint32_t v) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// Column absmax of a row-major matrix: each thread owns 4 adjacent columns and walks a
+// slab of rows (coalesced 4 KB per row per block); slabs are merged with an unsigned
+// atomic max on the bit pattern of |x| (exact and order independent for x >= 0).
+template <bool VEC>
+__global__ __launch_bounds__(256) void absmax_cols_kernel(const float* __restrict__ X, int rows,
+                                                          int cols, int rows_per_block,
+                                                          uint32_t* __restrict__ amax_bits) {
+    const int c = (blockIdx.x * 256 + threadIdx.x) * 4;
+    if (c >= cols) return;
+    const int r0 = blockIdx.y * rows_per_block;
+    const int r1 = min(rows, r0 + rows_per_block);
+    float4 m = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
+    for (int r = r0; r < r1; ++r) {
+        float4 v = load4f<VEC>(X + (size_t)r * cols, c, cols, true);
+        m.x = fmaxf(m.x, fabsf(v.x));
+        m.y = fmaxf(m.y, fabsf(v.y));
+        m.z = fmaxf(m.z, fabsf(v.z));
+        m.w = fmaxf(m.w, fabsf(v.w));
+    }
+    if (c + 0 < cols) atomicMax(amax_bits + c + 0, __float_as_uint(m.x));
+    if (c + 1 < cols) atomicMax(amax_bits + c + 1, __float_as_uint(m.y));
+    if (c + 2 < cols) atomicMax(amax_bits + c + 2, __float_as_uint(m.z));
+    if (c + 3 < cols) atomicMax(amax_bits + c + 3, __float_as_uint(m.w));
+}
+
+// Quantize a 64(k) x 64(n) tile with per-column scales and store it transposed
+// (codesT is cols x rows, contiguous along the original row index k).
+template <bool VEC, bool VECOUT>
+__global__ __launch_bounds__(256) void quant_cols_kernel(const float* __restrict__ X, int rows,
+                                                         int cols, const float* __restrict__ amax,
+                                                         QuantParams q,
+                                                         int8_t* __restrict__ codesT) {
+    __shared__ __align__(16) int8_t tile[64][80];
+    const int n0 = blockIdx.x * 64, k0 = blockIdx.y * 64;
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int n = n0 + tx * 4;
+    float lam[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        float a = (n + t < cols) ? amax[n + t] : 0.0f;
+        float s_unused;
+        make_scales(a, q.qmaxf, lam[t], s_unused);
+    }
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+        const int kl = ty + 16 * rr;
+        const int k = k0 + kl;
+        float4 v = load4f<VEC>(X + (size_t)k * cols, n, cols, k < rows);
+        tile[tx * 4 + 0][kl] = (int8_t)(int)quant_code(v.x, lam[0], q);
+        tile[tx * 4 + 1][kl] = (int8_t)(int)quant_code(v.y, lam[1], q);
+        tile[tx * 4 + 2][kl] = (int8_t)(int)quant_code(v.z, lam[2], q);
+        tile[tx * 4 + 3][kl] = (int8_t)(int)quant_code(v.w, lam[3], q);
+    }
+    __syncthreads();
+    const int nl = threadIdx.x >> 2, chunk = threadIdx.x & 3;
+    const int nn = n0 + nl;
+    if (nn >= cols) return;
+    const int kb = k0 + chunk * 16;
+    int8_t* dst = codesT + (size_t)nn * rows + kb;
+    if (VECOUT) {
+        if (kb < rows) *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(&tile[nl][chunk * 16]);
+    } else {
+#pragma unroll
+        for (int b = 0; b < 16; ++b)
+            if (kb + b < rows) dst[b] = tile[nl][chunk * 16 + b];
+    }
+}
+
+__global__ void scales_kernel(const float* __restrict__ amax, int n, int npad, float qmaxf,
+                              float* __restrict__ lam, float* __restrict__ s) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= npad) return;
+    float l = 0.0f, st = 0.0f;
+    if (i < n) make_scales(amax[i], qmaxf, l, st);
+    lam[i] = l;
+    s[i] = st;
+}
+
+static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+int launch_quantize_rows(const float* X, int rows, int cols, QuantParams q, int8_t* codes,
+                         float* amax, hipStream_t st) {
+    const bool vec = (cols % 4 == 0) && aligned16(X) && (((uintptr_t)codes & 3) == 0);
+    dim3 grid(ceil_div(rows, 4));
+    if (vec)
+        hipLaunchKernelGGL(quant_rows_kernel<true>, grid, dim3(256), 0, st, X, rows, cols, q, codes, amax);
+    else
+        hipLaunchKernelGGL(quant_rows_kernel<false>, grid, dim3(256), 0, st, X, rows, cols, q, codes, amax);
+    LRQ_CHECK_LAUNCH();
+    return LRQMM_OK;
+}
+
+int launch_quantize_cols(const float* X, int rows, int cols, QuantParams q, int8_t* codesT,
+                         float* amax, hipStream_t st) {
+    const bool vec = (cols % 4 == 0) && aligned16(X);
+    const bool vecout = (rows % 16 == 0) && aligned16(codesT);
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(ceil_div(cols, 256)), dim3(256), 0, st,
+                       reinterpret_cast<uint32_t*>(amax), cols, 0u);
+    LRQ_CHECK_LAUNCH();
+    // enough row slabs to fill the chip, at least 32 rows each
+    const int col_blocks = ceil_div(cols, 1024);
+    int slabs = max(1, min(ceil_div(rows, 32), ceil_div(2048, col_blocks)));
+    const int rows_per_block = ceil_div(rows, slabs);
+    slabs = ceil_div(rows, rows_per_block);
+    dim3 g1(col_blocks, slabs);
+    if (vec)
+        hipLaunchKernelGGL(absmax_cols_kernel<true>, g1, dim3(256), 0, st, X, rows, cols, rows_per_block,
+                           reinterpret_cast<uint32_t*>(amax));
+    else
+        hipLaunchKernelGGL(absmax_cols_kernel<false>, g1, dim3(256), 0, st, X, rows, cols, rows_per_block,
+                           reinterpret_cast<uint32_t*>(amax));
+    LRQ_CHECK_LAUNCH();
+    dim3 g2(ceil_div(cols, 64), ceil_div(rows, 64));
+    if (vec && vecout)
+        hipLaunchKernelGGL((quant_cols_kernel<true, true>), g2, dim3(256), 0, st, X, rows, cols, amax, q, codesT);
+    else if (vec)
+        hipLaunchKernelGGL((quant_cols_kernel<true, false>), g2, dim3(256), 0, st, X, rows, cols, amax, q, codesT);
+    else if (vecout)
+        hipLaunchKernelGGL((quant_cols_kernel<false, true>), g2, dim3(256), 0, st, X, rows, cols, amax, q, codesT);
+    else
+        hipLaunchKernelGGL((quant_cols_kernel<false, false>), g2, dim3(256), 0, st, X, rows, cols, amax, q, codesT);
+    LRQ_CHECK_LAUNCH();
+    return LRQMM_OK;
+}
+
+int launch_scales(const float* amax, int n, int npad, float qmaxf, float* lam, float* s,
+                  hipStream_t st) {
+    hipLaunchKernelGGL(scales_kernel, dim3(ceil_div(npad, 256)), dim3(256), 0, st, amax, n, npad, qmaxf, lam, s);
+    LRQ_CHECK_LAUNCH();
+    return LRQMM_OK;
+}

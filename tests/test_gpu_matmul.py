@@ -1,0 +1,142 @@
+"""GPU parity: the whole hot path (lrqmm_matmul) against the oracle's Algorithm 2.
+
+Tolerance: relative Frobenius error of C against the float64 oracle
+    tol = max(1e-5, 2 * 2^-24 * kappa),   kappa = (|C0|_F + |C - C0|_F) / |C|_F.
+The GPU path computes the sketch products and the epilogue in float32 (Gram /
+Cholesky / Jacobi in float64); emulating the factorization arithmetic on the CPU
+gives 6e-9 (int8, Gaussian) to 5e-7 (int4 with outliers), so 1e-5 covers it with
+room for accumulation-order differences.  The epilogue adds the compensation to
+the dequantized product C0 in float32, so each output carries about one float32
+rounding of |C0| and one of |C - C0|: when the two nearly cancel (floor
+quantization of zero-mean data at 4 bits: |C0| is 40-200 times |C|) that
+rounding, 2^-24 * kappa relative to C, is the floor of what float32 can deliver;
+the factor 2 is margin for the 2r-term accumulation.
+"""
+import numpy as np
+import pytest
+
+from oracle import lrqmm_oracle as o
+import lrqmm_workloads as wl
+from gpu_util import say, to_dev, to_np, rel_fro
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5
+
+
+def tol_for(ref):
+    C, C0 = ref["C"], ref["C0"]
+    kappa = (np.linalg.norm(C0) + np.linalg.norm(C - C0)) / np.linalg.norm(C)
+    return max(TOL, 2 * 2.0 ** -24 * kappa)
+
+
+def _run_gpu(w, A, B):
+    import paper_2409_18772_amd as L
+    return to_np(L.lrqmm_matmul(to_dev(A), to_dev(B), w.bits, w.rank, w.oversample, w.power_iters,
+                                seed=w.sketch_seed))
+
+
+def test_config_one_full():
+    w = wl.CONFIGS["c1_256_int8_r8"]
+    A, B = wl.make_inputs(w)
+    say("matmul", w.name)
+    C = _run_gpu(w, A, B)
+    ref = o.lrqmm(A, B, w.bits, w.rank, w.oversample, w.power_iters, seed=w.sketch_seed)
+    assert rel_fro(ref["C"], C) < TOL
+    exact = o.exact_product(A, B)
+    assert o.rel_err(exact, C) <= o.rel_err(exact, ref["C0"])
+    # bit-identical on a second run (no atomics on floats, fixed reduction orders)
+    assert np.array_equal(C, _run_gpu(w, A, B))
+
+
+SMALL = [
+    # name, M, N, K   (ragged: not multiples of any tile size)
+    ("c2_4096_int8_r16", 200, 136, 328),
+    ("c3_4096_int4_r32_outliers", 333, 517, 260),
+    ("c4_16384_int4_r64", 640, 512, 768),
+    ("c5_resnet50_conv_int4_r8", 3000, 64, 576),
+    ("c1_256_int8_r8", 77, 50, 93),
+]
+
+
+@pytest.mark.parametrize("name,M,N,K", SMALL)
+def test_scaled_configs_full_output(name, M, N, K):
+    w = wl.scaled_config(name, M, N, K)
+    A, B = wl.make_inputs(w)
+    say("matmul", w.name)
+    C = _run_gpu(w, A, B)
+    ref = o.lrqmm(A, B, w.bits, w.rank, w.oversample, w.power_iters, seed=w.sketch_seed)
+    d = rel_fro(ref["C"], C)
+    say(w.name, "gpu vs oracle", d, "tol", tol_for(ref))
+    assert d < tol_for(ref)
+
+
+def test_rank_zero_is_direct_quant_and_modes():
+    import paper_2409_18772_amd as L
+    A = wl.random_matrix("normal", 150, 200, seed=1)
+    B = wl.random_matrix("normal", 200, 170, seed=2)
+    for mode in (o.FLOOR, o.NEAREST):
+        C = to_np(L.lrqmm_matmul(to_dev(A), to_dev(B), 8, 0, round_mode=mode))
+        ref = o.lrqmm(A, B, 8, 0, round_mode=mode)
+        assert rel_fro(ref["C"], C) < 1e-6
+    C = to_np(L.lrqmm_matmul(to_dev(A), to_dev(B), 4, 6, 2, 1, seed=3, round_mode=o.NEAREST))
+    ref = o.lrqmm(A, B, 4, 6, 2, 1, seed=3, round_mode=o.NEAREST)
+    assert rel_fro(ref["C"], C) < TOL
+
+
+def test_degenerate_inputs():
+    import torch
+    import paper_2409_18772_amd as L
+    A = np.zeros((64, 96), dtype=np.float32)
+    B = wl.random_matrix("normal", 96, 80, seed=2)
+    C = to_np(L.lrqmm_matmul(to_dev(A), to_dev(B), 8, 4, 2, 1))
+    assert np.all(C == 0)
+    A = wl.random_matrix("normal", 64, 96, seed=1)
+    A[5] = 0
+    B[:, 7] = 0
+    C = to_np(L.lrqmm_matmul(to_dev(A), to_dev(B), 8, 4, 2, 1, seed=5))
+    ref = o.lrqmm(A, B, 8, 4, 2, 1, seed=5)
+    assert rel_fro(ref["C"], C) < TOL
+    assert np.all(C[5] == 0) and np.all(C[:, 7] == 0)
+    with pytest.raises(L.LrqmmError):
+        L.lrqmm_matmul(to_dev(A), to_dev(B), 8, 60, 30)          # l > K
+    with pytest.raises(L.LrqmmError):
+        L.lrqmm_matmul(to_dev(A), to_dev(B), 8, 81, 0)
+    e = torch.empty((0, 96), dtype=torch.float32, device="cuda")
+    assert L.lrqmm_matmul(e, to_dev(B), 8, 0).shape == (0, 80)
+
+
+FULL = ["c2_4096_int8_r16", "c3_4096_int4_r32_outliers"]
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_full_size_sampled_rows(name):
+    """Full-size run in the benchmark's launch configuration, checked on sampled rows of C."""
+    w = wl.CONFIGS[name]
+    A, B = wl.make_inputs(w)
+    say("matmul full", w.name)
+    C = _run_gpu(w, A, B)
+    rows = np.random.default_rng(5).choice(w.M, size=24, replace=False)
+    say("oracle on", len(rows), "rows")
+    ref = o.lrqmm(A, B, w.bits, w.rank, w.oversample, w.power_iters, seed=w.sketch_seed, row_sample=rows,
+                  want_cint=False)
+    d = rel_fro(ref["C"], C[rows])
+    say(name, "gpu vs oracle", d, "tol", tol_for(ref))
+    assert d < tol_for(ref)
+    exact = o.exact_product(A[rows], B)
+    e_lr, e_dq = o.rel_err(exact, C[rows]), o.rel_err(exact, ref["C0"])
+    say(name, "err lrqmm", e_lr, "err direct quant", e_dq)
+    assert e_lr < e_dq
+    if "int4" in name:
+        assert e_dq / e_lr >= 10.0        # the headline claim on the outlier workload
+
+
+def test_resnet_conv_shape_sampled_rows():
+    w = wl.CONFIGS["c5_resnet50_conv_int4_r8"]
+    A, B = wl.make_inputs(w)
+    say("matmul full", w.name)
+    C = _run_gpu(w, A, B)
+    rows = np.random.default_rng(6).choice(w.M, size=512, replace=False)
+    ref = o.lrqmm(A, B, w.bits, w.rank, w.oversample, w.power_iters, seed=w.sketch_seed, row_sample=rows,
+                  want_cint=False)
+    assert rel_fro(ref["C"], C[rows]) < TOL
