@@ -132,6 +132,22 @@ LRQMM_API int lrqmm_matmul(int M, int N, int K, int bits, int rank, int oversamp
                  uint64_t seed, int round_mode, const float* A, const float* B, float* C,
                  void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Stage timing of lrqmm_matmul for measurement (the split of Algorithm 2 into
+ * quantization, the two residual factorizations, panel preparation and the
+ * integer GEMM with its fused epilogue).  While enabled, each lrqmm_matmul call
+ * records HIP events on its stream at the stage boundaries (up to 512 calls
+ * between reads).  lrqmm_profile_read waits for the last recorded call (host
+ * synchronisation), writes the per-stage mean duration in milliseconds to
+ * stage_ms[LRQMM_PROF_STAGES] (host pointer) and the number of calls averaged to
+ * *ncalls (host pointer), then resets the call counter.  Not thread safe.
+ *   stage 0 quantize A and B     stage 1 RSVD of R_A      stage 2 RSVD of R_B
+ *   stage 3 compensation panels  stage 4 int8 GEMM kernel with fused epilogue
+ */
+#define LRQMM_PROF_STAGES 5
+LRQMM_API int lrqmm_profile_enable(int on);
+LRQMM_API int lrqmm_profile_read(float* stage_ms, int* ncalls);
+
 #ifdef __cplusplus
 }
 #endif

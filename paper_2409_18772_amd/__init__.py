@@ -7,5 +7,6 @@ fallback: importing the binding without the built library raises.
 from .binding import (  # noqa: F401
     AXIS_COL, AXIS_ROW, ROUND_FLOOR, ROUND_NEAREST, MAX_SKETCH, LrqmmError,
     lib_path, load_library, lrqmm_fill_sketch, lrqmm_gemm, lrqmm_matmul, lrqmm_quantize,
-    lrqmm_rsvd, lrqmm_workspace_bytes, lrqmm_status_string, Workspace,
+    lrqmm_rsvd, lrqmm_workspace_bytes, lrqmm_status_string, Workspace, lrqmm_profile_enable,
+    lrqmm_profile_read, PROF_STAGES,
 )

@@ -15,7 +15,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
 EXPORTS = ("lrqmm_status_string", "lrqmm_workspace_bytes", "lrqmm_quantize", "lrqmm_fill_sketch",
-           "lrqmm_rsvd", "lrqmm_gemm", "lrqmm_matmul")
+           "lrqmm_rsvd", "lrqmm_gemm", "lrqmm_matmul", "lrqmm_profile_enable", "lrqmm_profile_read")
+PROF_STAGES = ("quantize", "rsvd_a", "rsvd_b", "panels", "gemm")
 
 
 class LrqmmError(RuntimeError):
@@ -54,6 +55,10 @@ def load_library() -> ctypes.CDLL:
     lib.lrqmm_gemm.argtypes = [c_int] * 5 + [c_vp] * 12 + [c_vp, c_sz, c_vp]
     lib.lrqmm_matmul.restype = c_int
     lib.lrqmm_matmul.argtypes = [c_int] * 7 + [c_u64, c_int, c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
+    lib.lrqmm_profile_enable.restype = c_int
+    lib.lrqmm_profile_enable.argtypes = [c_int]
+    lib.lrqmm_profile_read.restype = c_int
+    lib.lrqmm_profile_read.argtypes = [c_vp, c_vp]
     _LIB = lib
     return lib
 
@@ -206,3 +211,17 @@ def lrqmm_matmul(A, B, bits: int, rank: int, oversample: int = 0, power_iters: i
                                      workspace.nbytes, _stream())
     _check(st, "lrqmm_matmul")
     return C
+
+
+def lrqmm_profile_enable(on: bool):
+    _check(load_library().lrqmm_profile_enable(1 if on else 0), "lrqmm_profile_enable")
+
+
+def lrqmm_profile_read():
+    """Mean per-stage milliseconds of the lrqmm_matmul calls since the last read: (dict, ncalls)."""
+    ms = (ctypes.c_float * len(PROF_STAGES))()
+    n = ctypes.c_int(0)
+    _check(load_library().lrqmm_profile_read(ctypes.cast(ms, ctypes.c_void_p),
+                                              ctypes.cast(ctypes.byref(n), ctypes.c_void_p)),
+           "lrqmm_profile_read")
+    return dict(zip(PROF_STAGES, [float(x) for x in ms])), int(n.value)

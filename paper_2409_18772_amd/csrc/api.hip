@@ -119,6 +119,20 @@ size_t carve_matmul(Arena& a, int M, int N, int K, int rank, int oversample, Mat
     return a.off;
 }
 
+// Optional stage timing of lrqmm_matmul with HIP events recorded on the caller's stream.
+constexpr int kProfStages = LRQMM_PROF_STAGES;
+constexpr int kProfMaxCalls = 512;
+struct Prof {
+    bool on = false;
+    int ncalls = 0;
+    hipEvent_t ev[kProfMaxCalls][kProfStages + 1];
+    bool created = false;
+} g_prof;
+
+inline void prof_mark(int slot, int i, hipStream_t st) {
+    if (slot >= 0) (void)hipEventRecord(g_prof.ev[slot][i], st);
+}
+
 bool bits_ok(int bits) { return bits >= 2 && bits <= 8; }
 
 // int32 accumulation is safe when K * (qmax+1)^2 < 2^31.
@@ -227,10 +241,10 @@ int lrqmm_rsvd(const float* X, const float* amax, int rows, int cols, int axis, 
     return LRQMM_OK;
 }
 
-int lrqmm_gemm(int M, int N, int K, int bits, int rank, const int8_t* Aq, const float* amaxA,
-               const int8_t* BqT, const float* amaxB, const float* U, const float* Sig, const float* Vt,
-               const float* W, const float* Gam, const float* Zt, float* C, int32_t* Cint_or_null,
-               void* workspace, size_t workspace_bytes, void* stream) {
+static int gemm_impl(int M, int N, int K, int bits, int rank, const int8_t* Aq, const float* amaxA,
+                     const int8_t* BqT, const float* amaxB, const float* U, const float* Sig, const float* Vt,
+                     const float* W, const float* Gam, const float* Zt, float* C, int32_t* Cint_or_null,
+                     void* workspace, size_t workspace_bytes, void* stream, int prof_slot) {
     if (M < 0 || N < 0 || K < 0 || rank < 0) return LRQMM_ERR_INVALID_ARG;
     if (!bits_ok(bits)) return LRQMM_ERR_UNSUPPORTED;
     if (!k_fits_int32(K, bits)) return LRQMM_ERR_UNSUPPORTED;
@@ -264,8 +278,19 @@ int lrqmm_gemm(int M, int N, int K, int bits, int rank, const int8_t* Aq, const 
         LRQ_TRY(launch_vtw(Vt, W, K, rank, w.X, st));
         LRQ_TRY(launch_build_panels(M, N, rank, RP, R2P, U, Sig, w.S, w.Pv, w.X, Gam, Zt, w.Lp, w.Rp, st));
     }
-    return launch_int8_gemm(M, N, K, Aq, BqT, w.sA, w.sB, rank > 0 ? w.Lp : nullptr, rank > 0 ? w.Rp : nullptr,
-                            R2P, C, Cint_or_null, st);
+    prof_mark(prof_slot, 4, st);
+    rc = launch_int8_gemm(M, N, K, Aq, BqT, w.sA, w.sB, rank > 0 ? w.Lp : nullptr, rank > 0 ? w.Rp : nullptr,
+                          R2P, C, Cint_or_null, st);
+    prof_mark(prof_slot, 5, st);
+    return rc;
+}
+
+int lrqmm_gemm(int M, int N, int K, int bits, int rank, const int8_t* Aq, const float* amaxA,
+               const int8_t* BqT, const float* amaxB, const float* U, const float* Sig, const float* Vt,
+               const float* W, const float* Gam, const float* Zt, float* C, int32_t* Cint_or_null,
+               void* workspace, size_t workspace_bytes, void* stream) {
+    return gemm_impl(M, N, K, bits, rank, Aq, amaxA, BqT, amaxB, U, Sig, Vt, W, Gam, Zt, C, Cint_or_null,
+                     workspace, workspace_bytes, stream, -1);
 }
 
 int lrqmm_matmul(int M, int N, int K, int bits, int rank, int oversample, int power_iters, uint64_t seed,
@@ -287,6 +312,9 @@ int lrqmm_matmul(int M, int N, int K, int bits, int rank, int oversample, int po
     Arena a(workspace);
     if (carve_matmul(a, M, N, K, rank, oversample, &w) > workspace_bytes) return LRQMM_ERR_WORKSPACE;
     int rc;
+    hipStream_t pst = static_cast<hipStream_t>(stream);
+    const int slot = (g_prof.on && g_prof.ncalls < kProfMaxCalls) ? g_prof.ncalls++ : -1;
+    prof_mark(slot, 0, pst);
     if (K > 0) {
         LRQ_TRY(lrqmm_quantize(A, M, K, LRQMM_AXIS_ROW, bits, round_mode, w.Aq, w.amaxA, stream));
         LRQ_TRY(lrqmm_quantize(B, K, N, LRQMM_AXIS_COL, bits, round_mode, w.BqT, w.amaxB, stream));
@@ -294,14 +322,46 @@ int lrqmm_matmul(int M, int N, int K, int bits, int rank, int oversample, int po
         LRQ_TRY(launch_pad_copy(nullptr, M, 0, 1, w.amaxA, static_cast<hipStream_t>(stream)));
         LRQ_TRY(launch_pad_copy(nullptr, N, 0, 1, w.amaxB, static_cast<hipStream_t>(stream)));
     }
-    if (rank > 0) {
+    prof_mark(slot, 1, pst);
+    if (rank > 0)
         LRQ_TRY(lrqmm_rsvd(A, w.amaxA, M, K, LRQMM_AXIS_ROW, bits, round_mode, rank, oversample, power_iters,
                            seed, nullptr, w.U, w.Sig, w.Vt, w.sub, w.sub_bytes, stream));
+    prof_mark(slot, 2, pst);
+    if (rank > 0)
         LRQ_TRY(lrqmm_rsvd(B, w.amaxB, K, N, LRQMM_AXIS_COL, bits, round_mode, rank, oversample, power_iters,
                            seed, nullptr, w.W, w.Gam, w.Zt, w.sub, w.sub_bytes, stream));
+    prof_mark(slot, 3, pst);
+    return gemm_impl(M, N, K, bits, rank, w.Aq, w.amaxA, w.BqT, w.amaxB, w.U, w.Sig, w.Vt, w.W, w.Gam, w.Zt, C,
+                     nullptr, w.sub, w.sub_bytes, stream, slot);
+}
+
+int lrqmm_profile_enable(int on) {
+    if (on && !g_prof.created) {
+        for (int c = 0; c < kProfMaxCalls; ++c)
+            for (int i = 0; i <= kProfStages; ++i)
+                if (hipEventCreate(&g_prof.ev[c][i]) != hipSuccess) return LRQMM_ERR_HIP;
+        g_prof.created = true;
     }
-    return lrqmm_gemm(M, N, K, bits, rank, w.Aq, w.amaxA, w.BqT, w.amaxB, w.U, w.Sig, w.Vt, w.W, w.Gam, w.Zt, C,
-                      nullptr, w.sub, w.sub_bytes, stream);
+    g_prof.on = on != 0;
+    g_prof.ncalls = 0;
+    return LRQMM_OK;
+}
+
+int lrqmm_profile_read(float* stage_ms, int* ncalls) {
+    if (!stage_ms || !ncalls) return LRQMM_ERR_INVALID_ARG;
+    const int n = g_prof.ncalls;
+    *ncalls = n;
+    for (int i = 0; i < kProfStages; ++i) stage_ms[i] = 0.f;
+    if (n == 0) return LRQMM_OK;
+    if (hipEventSynchronize(g_prof.ev[n - 1][kProfStages]) != hipSuccess) return LRQMM_ERR_HIP;
+    for (int c = 0; c < n; ++c)
+        for (int i = 0; i < kProfStages; ++i) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, g_prof.ev[c][i], g_prof.ev[c][i + 1]) != hipSuccess) return LRQMM_ERR_HIP;
+            stage_ms[i] += ms / (float)n;
+        }
+    g_prof.ncalls = 0;
+    return LRQMM_OK;
 }
 
 }  // extern "C"

@@ -17,7 +17,7 @@ def _declared():
 def test_header_declares_the_three_named_calls():
     names = _declared()
     for n in ("lrqmm_quantize", "lrqmm_rsvd", "lrqmm_gemm", "lrqmm_matmul", "lrqmm_fill_sketch",
-              "lrqmm_workspace_bytes", "lrqmm_status_string"):
+              "lrqmm_workspace_bytes", "lrqmm_status_string", "lrqmm_profile_enable", "lrqmm_profile_read"):
         assert n in names
 
 
