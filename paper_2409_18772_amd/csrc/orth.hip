@@ -12,40 +12,96 @@
 // zero residual) are dropped: the corresponding columns of Q are zero.
 #include "kernels.h"
 
-#define GB_ROWS 64   // rows of Y per Gram partial
+#define GB_TILE 64        // rows of Y staged per LDS tile in the Gram kernel
+#define GRAM_MAX_BLOCKS 32
+#define GRAM_MIN_ROWS 256
+#define MAXL LRQMM_MAX_SKETCH
 
-int gram_blocks(int n) { return ceil_div(n, GB_ROWS); }
+static int gram_rows_per_block(int n) {
+    int nblk = min(GRAM_MAX_BLOCKS, max(1, ceil_div(n, GRAM_MIN_ROWS)));
+    return ceil_div(ceil_div(n, nblk), GB_TILE) * GB_TILE;
+}
 
+int gram_blocks(int n) { return max(1, ceil_div(n, gram_rows_per_block(n))); }
+
+// Y = sum of the pass partials (fixed order, optional row scale); gpart[block] = float64
+// Gram matrix of the block's rows.  Threads form a 16 x 16 grid; thread (ta, tb) keeps the
+// NT x NT Gram entries (ta + 16x, tb + 16y) in registers, so a staged row costs 2 NT LDS
+// reads for NT^2 float64 FMAs.
+template <int NT>
 __global__ __launch_bounds__(256) void reduce_gram_kernel(const float* __restrict__ partial, int splits,
-                                                          int n, int LP,
+                                                          int n, int rows_per_block,
                                                           const float* __restrict__ rowscale,
                                                           float* __restrict__ Y,
                                                           double* __restrict__ gpart) {
-    extern __shared__ float tile[];   // [GB_ROWS][LP+1]
-    const int r0 = blockIdx.x * GB_ROWS;
-    const int ld = LP + 1;
-    for (int idx = threadIdx.x; idx < GB_ROWS * LP; idx += 256) {
-        const int rr = idx / LP, c = idx % LP;
-        const int row = r0 + rr;
-        float v = 0.f;
-        if (row < n) {
-            const size_t off = (size_t)row * LP + c;
-            for (int s = 0; s < splits; ++s) v += partial[(size_t)s * n * LP + off];
-            if (rowscale) v *= rowscale[row];
-            Y[off] = v;
+    constexpr int LP = NT * 16;
+    constexpr int ld = LP + 1;
+    constexpr int Q4 = LP / 4;      // float4 groups per row
+    __shared__ float tile[GB_TILE * ld];
+    const int rb = blockIdx.x * rows_per_block;
+    const int re = min(n, rb + rows_per_block);
+    const int ta = threadIdx.x >> 4, tb = threadIdx.x & 15;
+    double acc[NT][NT];
+#pragma unroll
+    for (int x = 0; x < NT; ++x)
+#pragma unroll
+        for (int y = 0; y < NT; ++y) acc[x][y] = 0.0;
+    const size_t plane = (size_t)n * LP;
+    for (int r0 = rb; r0 < re; r0 += GB_TILE) {
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < GB_TILE * Q4; idx += 256) {
+            const int rr = idx / Q4, c = (idx % Q4) * 4;
+            const int row = r0 + rr;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (row < re) {
+                const size_t off = (size_t)row * LP + c;
+                int sp = 0;
+                for (; sp + 4 <= splits; sp += 4) {      // four independent loads in flight
+                    const float4 p0 = *reinterpret_cast<const float4*>(partial + (sp + 0) * plane + off);
+                    const float4 p1 = *reinterpret_cast<const float4*>(partial + (sp + 1) * plane + off);
+                    const float4 p2 = *reinterpret_cast<const float4*>(partial + (sp + 2) * plane + off);
+                    const float4 p3 = *reinterpret_cast<const float4*>(partial + (sp + 3) * plane + off);
+                    v.x = (((v.x + p0.x) + p1.x) + p2.x) + p3.x;
+                    v.y = (((v.y + p0.y) + p1.y) + p2.y) + p3.y;
+                    v.z = (((v.z + p0.z) + p1.z) + p2.z) + p3.z;
+                    v.w = (((v.w + p0.w) + p1.w) + p2.w) + p3.w;
+                }
+                for (; sp < splits; ++sp) {
+                    const float4 p0 = *reinterpret_cast<const float4*>(partial + sp * plane + off);
+                    v.x += p0.x; v.y += p0.y; v.z += p0.z; v.w += p0.w;
+                }
+                if (rowscale) {
+                    const float rs = rowscale[row];
+                    v.x *= rs; v.y *= rs; v.z *= rs; v.w *= rs;
+                }
+                *reinterpret_cast<float4*>(Y + off) = v;
+            }
+            float* t = tile + rr * ld + c;
+            t[0] = v.x; t[1] = v.y; t[2] = v.z; t[3] = v.w;
         }
-        tile[rr * ld + c] = v;
+        __syncthreads();
+        if (gpart) {
+#pragma unroll 4
+            for (int rr = 0; rr < GB_TILE; ++rr) {
+                double av[NT], bv[NT];
+#pragma unroll
+                for (int x = 0; x < NT; ++x) {
+                    av[x] = (double)tile[rr * ld + ta + 16 * x];
+                    bv[x] = (double)tile[rr * ld + tb + 16 * x];
+                }
+#pragma unroll
+                for (int x = 0; x < NT; ++x)
+#pragma unroll
+                    for (int y = 0; y < NT; ++y) acc[x][y] = fma(av[x], bv[y], acc[x][y]);
+            }
+        }
     }
-    __syncthreads();
-    if (!gpart) return;
-    double* gp = gpart + (size_t)blockIdx.x * LP * LP;
-    for (int idx = threadIdx.x; idx < LP * LP; idx += 256) {
-        const int a = idx / LP, b = idx % LP;
-        double acc = 0.0;
-#pragma unroll 8
-        for (int rr = 0; rr < GB_ROWS; ++rr)
-            acc = fma((double)tile[rr * ld + a], (double)tile[rr * ld + b], acc);
-        gp[idx] = acc;
+    if (gpart) {
+        double* gp = gpart + (size_t)blockIdx.x * LP * LP;
+#pragma unroll
+        for (int x = 0; x < NT; ++x)
+#pragma unroll
+            for (int y = 0; y < NT; ++y) gp[(ta + 16 * x) * LP + tb + 16 * y] = acc[x][y];
     }
 }
 
@@ -54,56 +110,94 @@ __device__ static void load_gram(const double* __restrict__ gpart, int nb, int e
                                  double* __restrict__ G, int ldg) {
     for (int idx = threadIdx.x; idx < ell * ell; idx += blockDim.x) {
         const int a = idx / ell, b = idx % ell;
+        const double* src = gpart + a * LP + b;
+        const size_t st = (size_t)LP * LP;
         double acc = 0.0;
-        for (int blk = 0; blk < nb; ++blk) acc += gpart[(size_t)blk * LP * LP + a * LP + b];
+        int blk = 0;
+        for (; blk + 8 <= nb; blk += 8) {     // eight independent loads in flight
+            const double v0 = src[(blk + 0) * st], v1 = src[(blk + 1) * st], v2 = src[(blk + 2) * st],
+                         v3 = src[(blk + 3) * st], v4 = src[(blk + 4) * st], v5 = src[(blk + 5) * st],
+                         v6 = src[(blk + 6) * st], v7 = src[(blk + 7) * st];
+            acc = (((((((acc + v0) + v1) + v2) + v3) + v4) + v5) + v6) + v7;
+        }
+        for (; blk < nb; ++blk) acc += src[blk * st];
         G[a * ldg + b] = acc;
     }
 }
 
-#define MAXL LRQMM_MAX_SKETCH
+// Order LDS traffic inside one wavefront: all earlier LDS reads/writes of every lane of
+// this wave are complete and the compiler moves no memory access across.
+__device__ __forceinline__ void wave_lds_fence() { __asm__ volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
-// Cholesky G = L L^T, then T = L^-T (upper triangular) so that Q = Y T.
+// dot_{k in [lo, hi)} row[k] * other[k] over two LDS rows, eight loads in flight.
+__device__ __forceinline__ double lds_dot(const double* __restrict__ row, const double* __restrict__ other,
+                                          int lo, int hi) {
+    double s = 0.0;
+    int k = lo;
+    for (; k + 8 <= hi; k += 8) {
+        double a[8], b[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { a[u] = row[k + u]; b[u] = other[k + u]; }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s = fma(a[u], b[u], s);
+    }
+    for (; k < hi; ++k) s = fma(row[k], other[k], s);
+    return s;
+}
+
+// Cholesky G = L L^T and T = L^-T (upper triangular, Q = Y T) in one left-looking sweep on
+// a single wavefront.  Lane t owns row t of the LDS matrix: its lower part becomes row t
+// of L, its upper part column t of X = L^-1 (G[t][k] = X[k][t], k > t).  At column j every
+// lane forms one dot product with the shared row j of L:
+//   t >= j:  L[t][j] = (G[t][j] - sum_{k<j} L[t][k] L[j][k]) / L[j][j]
+//   t <  j:  X[j][t] = -(sum_{t<=k<j} L[j][k] X[k][t]) / L[j][j]
+// so the inverse comes out of the same loop with no workgroup barrier inside it.
 __global__ __launch_bounds__(256) void chol_inverse_kernel(const double* __restrict__ gpart, int nb,
                                                            int ell, int LP, double* __restrict__ T) {
     __shared__ double G[MAXL * (MAXL + 1)];
-    __shared__ double diag0[MAXL];
     __shared__ double dinv[MAXL];
     __shared__ int dead[MAXL];
     const int ldg = MAXL + 1;
     const int tid = threadIdx.x;
     load_gram(gpart, nb, ell, LP, G, ldg);
     __syncthreads();
-    if (tid < ell) diag0[tid] = G[tid * ldg + tid];
-    __syncthreads();
-    for (int j = 0; j < ell; ++j) {
-        if (tid == 0) {
-            const double d = G[j * ldg + j];
-            const bool live = d > 1e-10 * diag0[j] && d > 0.0;
-            dead[j] = live ? 0 : 1;
-            G[j * ldg + j] = live ? sqrt(d) : 1.0;
+    if (tid < 64) {
+        double dorig[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int t = tid + 64 * h;
+            dorig[h] = (t < ell) ? G[t * ldg + t] : 0.0;
         }
-        __syncthreads();
-        const double piv = G[j * ldg + j];
-        const int dj = dead[j];
-        for (int i = j + 1 + tid; i < ell; i += 256) G[i * ldg + j] = dj ? 0.0 : G[i * ldg + j] / piv;
-        __syncthreads();
-        const int nrem = ell - j - 1;
-        for (int idx = tid; idx < nrem * nrem; idx += 256) {
-            const int i = j + 1 + idx / nrem, k = j + 1 + idx % nrem;
-            if (k <= i) G[i * ldg + k] = fma(-G[i * ldg + j], G[k * ldg + j], G[i * ldg + k]);
-        }
-        __syncthreads();
-    }
-    // Inverse of L by forward substitution; column c of L^-1 is kept in row c of the
-    // (unused) strict upper triangle of G: G[c][i] = Linv[i][c], i > c.
-    if (tid < ell) {
-        const int c = tid;
-        const double xc = 1.0 / G[c * ldg + c];
-        dinv[c] = xc;
-        for (int i = c + 1; i < ell; ++i) {
-            double sum = G[i * ldg + c] * xc;
-            for (int k = c + 1; k < i; ++k) sum = fma(G[i * ldg + k], G[c * ldg + k], sum);
-            G[c * ldg + i] = -sum / G[i * ldg + i];
+        for (int j = 0; j < ell; ++j) {
+            const double* rowj = G + j * ldg;
+            double val[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int t = tid + 64 * h;
+                val[h] = 0.0;
+                if (t >= ell) continue;
+                if (t >= j) {
+                    val[h] = G[t * ldg + j] - lds_dot(G + t * ldg, rowj, 0, j);
+                } else {
+                    // k = t term uses X[t][t] = 1 / L[t][t]
+                    val[h] = -(rowj[t] * dinv[t] + lds_dot(G + t * ldg, rowj, t + 1, j));
+                }
+            }
+            const double dj = __shfl(val[j >> 6], j & 63, 64);
+            const double d0 = __shfl(dorig[j >> 6], j & 63, 64);
+            const bool live = dj > 1e-10 * d0 && dj > 0.0;
+            const double inv = live ? 1.0 / sqrt(dj) : 0.0;
+            if (tid == 0) {
+                dead[j] = live ? 0 : 1;
+                dinv[j] = live ? inv : 1.0;
+            }
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int t = tid + 64 * h;
+                if (t >= ell) continue;
+                G[t * ldg + j] = (t == j) ? (live ? dj * inv : 1.0) : val[h] * inv;
+            }
+            wave_lds_fence();
         }
     }
     __syncthreads();
@@ -118,112 +212,149 @@ __global__ __launch_bounds__(256) void chol_inverse_kernel(const double* __restr
     }
 }
 
-// out = In . Mat for 32 rows per workgroup, float64 accumulation.
-__global__ __launch_bounds__(256) void apply_kernel(const float* __restrict__ In, int n, int LP,
+// out = In . Mat for 32 rows per workgroup, float64 accumulation.  Thread (row, g) computes
+// the outputs of its row in columns g, g+8, g+16, ...
+template <int NT>
+__global__ __launch_bounds__(256) void apply_kernel(const float* __restrict__ In, int n,
                                                     const double* __restrict__ Mat, int cm, int ldm,
                                                     float* __restrict__ out, int ldo, int transposed) {
-    extern __shared__ double smem[];
-    double* mat = smem;                                        // [LP][cm]
-    float* tile = reinterpret_cast<float*>(smem + LP * cm);    // [32][LP+1]
-    const int ld = LP + 1;
+    constexpr int LP = NT * 16;
+    constexpr int E = LP / 8;
+    constexpr int ld = LP + 1;
+    __shared__ double mat[LP * LP];
+    __shared__ float tile[32 * ld];
     const int r0 = blockIdx.x * 32;
-    for (int idx = threadIdx.x; idx < LP * cm; idx += 256) mat[idx] = Mat[(idx / cm) * ldm + idx % cm];
+    for (int idx = threadIdx.x; idx < LP * LP; idx += 256) {
+        const int a = idx / LP, c = idx % LP;
+        mat[idx] = (c < cm) ? Mat[a * ldm + c] : 0.0;
+    }
     for (int idx = threadIdx.x; idx < 32 * LP; idx += 256) {
         const int rr = idx / LP, c = idx % LP;
         tile[rr * ld + c] = (r0 + rr < n) ? In[(size_t)(r0 + rr) * LP + c] : 0.f;
     }
     __syncthreads();
-    for (int idx = threadIdx.x; idx < 32 * cm; idx += 256) {
-        int rr, c;
-        if (transposed) { rr = idx % 32; c = idx / 32; }
-        else            { rr = idx / cm; c = idx % cm; }
-        if (r0 + rr >= n) continue;
-        double acc = 0.0;
-        for (int a = 0; a < LP; ++a) acc = fma((double)tile[rr * ld + a], mat[a * cm + c], acc);
-        if (transposed) out[(size_t)c * ldo + r0 + rr] = (float)acc;
-        else            out[(size_t)(r0 + rr) * ldo + c] = (float)acc;
+    const int rr = threadIdx.x & 31, g = threadIdx.x >> 5;
+    double acc[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) acc[e] = 0.0;
+#pragma unroll 4
+    for (int a = 0; a < LP; ++a) {
+        const double x = (double)tile[rr * ld + a];
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc[e] = fma(x, mat[a * LP + g + 8 * e], acc[e]);
+    }
+    if (r0 + rr >= n) return;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        const int c = g + 8 * e;
+        if (c < cm) {
+            if (transposed) out[(size_t)c * ldo + r0 + rr] = (float)acc[e];
+            else            out[(size_t)(r0 + rr) * ldo + c] = (float)acc[e];
+        }
     }
 }
 
-// Cyclic Jacobi eigen-solve of the l x l matrix G = B B^T (B = Q^T R), round-robin
-// pairing so l/2 disjoint rotations run per step.  Eigenvalues are the squared
-// singular values of B, eigenvectors its left singular vectors U'.
-__global__ __launch_bounds__(256) void small_svd_kernel(const double* __restrict__ gpart, int nb, int ell,
-                                                        int LP, int rank, float* __restrict__ Sigma,
-                                                        double* __restrict__ Ur, double* __restrict__ Mv) {
+// Cyclic Jacobi eigen-solve of the l x l matrix G = B B^T (B = Q^T R), round-robin pairing
+// so l/2 disjoint rotations run per step.  A step is two phases: (1) one thread per pair
+// derives its rotation from the pair's 2x2 diagonal block; (2) one thread per (row pair,
+// column pair) updates that 2x2 block of G = J^T G J and of V = V J in place (every
+// element belongs to exactly one block, so no double buffering is needed).
+// Eigenvalues are the squared singular values of B, eigenvectors its left singular vectors.
+#define SVD_THREADS 512
+__global__ __launch_bounds__(SVD_THREADS) void small_svd_kernel(const double* __restrict__ gpart, int nb,
+                                                                int ell, int LP, int rank,
+                                                                float* __restrict__ Sigma,
+                                                                double* __restrict__ Ur,
+                                                                double* __restrict__ Mv) {
     __shared__ double G[MAXL * (MAXL + 1)];
     __shared__ double V[MAXL * (MAXL + 1)];
     __shared__ double cs[MAXL / 2], sn[MAXL / 2];
-    __shared__ int pp[MAXL / 2], qq[MAXL / 2];
     __shared__ int order[MAXL];
     __shared__ int rotated;
-    __shared__ double gscale;
     const int ldg = MAXL + 1;
     const int tid = threadIdx.x;
-    load_gram(gpart, nb, ell, LP, G, ldg);
-    for (int idx = tid; idx < ell * ell; idx += 256) {
-        const int a = idx / ell, b = idx % ell;
+    const int m = (ell + 1) & ~1;   // even number of players; a zero dummy row/column when ell is odd
+    for (int idx = tid; idx < m * m; idx += SVD_THREADS) {
+        const int a = idx / m, b = idx % m;
+        G[a * ldg + b] = 0.0;
         V[a * ldg + b] = (a == b) ? 1.0 : 0.0;
     }
     __syncthreads();
-    if (tid == 0) {
-        double mx = 0.0;
-        for (int a = 0; a < ell; ++a) mx = fmax(mx, fabs(G[a * ldg + a]));
-        gscale = mx;
-    }
+    load_gram(gpart, nb, ell, LP, G, ldg);
     __syncthreads();
-    const double off_tol = 1e-15 * gscale;   // off-diagonals below this are left alone
-    const int m = (ell + 1) & ~1;   // even number of players (a bye when ell is odd)
     const int half = m / 2;
-    for (int sweep = 0; sweep < 30; ++sweep) {
+    // round-robin tournament: player m-1 stays, the others rotate (no integer division)
+    auto pair_of = [&](int slot, int step, int& p, int& q) {
+        int a = step + slot;
+        if (a >= m - 1) a -= m - 1;
+        if (slot == 0) a = m - 1;
+        int b = step - slot;
+        if (b < 0) b += m - 1;
+        p = min(a, b);
+        q = max(a, b);
+    };
+    double gmax = 0.0;
+    for (int a = 0; a < ell; ++a) gmax = fmax(gmax, fabs(G[a * ldg + a]));
+    const double gsc = gmax > 0.0 ? 1.0 / gmax : 0.0;
+    for (int sweep = 0; sweep < 15; ++sweep) {
         if (tid == 0) rotated = 0;
         __syncthreads();
         for (int step = 0; step < m - 1; ++step) {
-            // round-robin: player m-1 fixed, the others rotate
             if (tid < half) {
-                int a = (tid == 0) ? m - 1 : (step + tid) % (m - 1);
-                int b = (step + m - 1 - tid) % (m - 1);
-                int p = min(a, b), q2 = max(a, b);
+                int p, q;
+                pair_of(tid, step, p, q);
+                const double gpq = G[p * ldg + q];
+                const double gpp = G[p * ldg + p], gqq = G[q * ldg + q];
                 double c = 1.0, s = 0.0;
-                if (q2 < ell) {
-                    const double gpq = G[p * ldg + q2];
-                    const double gpp = G[p * ldg + p], gqq = G[q2 * ldg + q2];
-                    if (fabs(gpq) > off_tol) {
-                        const double theta = (gqq - gpp) / (2.0 * gpq);
-                        const double t = (theta >= 0.0 ? 1.0 : -1.0) / (fabs(theta) + sqrt(theta * theta + 1.0));
-                        c = 1.0 / sqrt(t * t + 1.0);
-                        s = t * c;
-                        rotated = 1;
-                    }
-                } else {
-                    q2 = -1;
+                const float bf = (float)(2.0 * gpq * gsc);
+                if (gpq * gpq > 1e-26 * fabs(gpp * gqq) && bf != 0.0f) {
+                    // The angle only needs float accuracy (a slightly inexact angle still
+                    // converges); c and s are then made orthonormal to float64 accuracy.
+                    const float th = (float)((gqq - gpp) * gsc) * __builtin_amdgcn_rcpf(bf);
+                    const float tf = copysignf(1.0f, th) *
+                                     __builtin_amdgcn_rcpf(fabsf(th) + __builtin_amdgcn_sqrtf(th * th + 1.0f));
+                    const double t = (double)tf;
+                    const double x = fma(t, t, 1.0);
+                    double r = __builtin_amdgcn_rsq(x);
+                    r = r * fma(-0.5 * x, r * r, 1.5);
+                    r = r * fma(-0.5 * x, r * r, 1.5);
+                    r = r * fma(-0.5 * x, r * r, 1.5);
+                    c = r;
+                    s = t * r;
+                    rotated = 1;
                 }
-                pp[tid] = p; qq[tid] = q2; cs[tid] = c; sn[tid] = s;
+                cs[tid] = c;
+                sn[tid] = s;
             }
             __syncthreads();
-            // rows: G <- J^T G
-            for (int idx = tid; idx < half * ell; idx += 256) {
-                const int pr = idx / ell, k = idx % ell;
-                const int p = pp[pr], q2 = qq[pr];
-                if (q2 < 0) continue;
-                const double c = cs[pr], s = sn[pr];
-                const double gp = G[p * ldg + k], gq = G[q2 * ldg + k];
-                G[p * ldg + k] = c * gp - s * gq;
-                G[q2 * ldg + k] = s * gp + c * gq;
-            }
-            __syncthreads();
-            // columns: G <- G J, V <- V J
-            for (int idx = tid; idx < half * ell; idx += 256) {
-                const int pr = idx / ell, k = idx % ell;
-                const int p = pp[pr], q2 = qq[pr];
-                if (q2 < 0) continue;
-                const double c = cs[pr], s = sn[pr];
-                const double gp = G[k * ldg + p], gq = G[k * ldg + q2];
-                G[k * ldg + p] = c * gp - s * gq;
-                G[k * ldg + q2] = s * gp + c * gq;
-                const double vp = V[k * ldg + p], vq = V[k * ldg + q2];
-                V[k * ldg + p] = c * vp - s * vq;
-                V[k * ldg + q2] = s * vp + c * vq;
+            for (int blk = tid; blk < half * half; blk += SVD_THREADS) {
+                const int P = blk / half, Q = blk % half;
+                int p1, q1, p2, q2;
+                pair_of(P, step, p1, q1);
+                pair_of(Q, step, p2, q2);
+                const double c1 = cs[P], s1 = sn[P], c2 = cs[Q], s2 = sn[Q];
+                double* g11 = &G[p1 * ldg + p2];
+                double* g12 = &G[p1 * ldg + q2];
+                double* g21 = &G[q1 * ldg + p2];
+                double* g22 = &G[q1 * ldg + q2];
+                const double a11 = *g11, a12 = *g12, a21 = *g21, a22 = *g22;
+                // rows: J^T G
+                const double r11 = c1 * a11 - s1 * a21, r12 = c1 * a12 - s1 * a22;
+                const double r21 = s1 * a11 + c1 * a21, r22 = s1 * a12 + c1 * a22;
+                // columns: (.) J
+                *g11 = c2 * r11 - s2 * r12;
+                *g12 = s2 * r11 + c2 * r12;
+                *g21 = c2 * r21 - s2 * r22;
+                *g22 = s2 * r21 + c2 * r22;
+                double* v11 = &V[p1 * ldg + p2];
+                double* v12 = &V[p1 * ldg + q2];
+                double* v21 = &V[q1 * ldg + p2];
+                double* v22 = &V[q1 * ldg + q2];
+                const double b11 = *v11, b12 = *v12, b21 = *v21, b22 = *v22;
+                *v11 = c2 * b11 - s2 * b12;
+                *v12 = s2 * b11 + c2 * b12;
+                *v21 = c2 * b21 - s2 * b22;
+                *v22 = s2 * b21 + c2 * b22;
             }
             __syncthreads();
         }
@@ -243,7 +374,7 @@ __global__ __launch_bounds__(256) void small_svd_kernel(const double* __restrict
     __syncthreads();
     if (tid < rank) Sigma[tid] = (float)sqrt(fmax(G[order[tid] * ldg + order[tid]], 0.0));
     const double top = sqrt(fmax(G[order[0] * ldg + order[0]], 0.0));
-    for (int idx = tid; idx < LP * rank; idx += 256) {
+    for (int idx = tid; idx < LP * rank; idx += SVD_THREADS) {
         const int a = idx / rank, t = idx % rank;
         double u = 0.0, mv = 0.0;
         if (a < ell) {
@@ -257,11 +388,22 @@ __global__ __launch_bounds__(256) void small_svd_kernel(const double* __restrict
     }
 }
 
+#define NT_SWITCH(NTV, CALL)            \
+    switch (NTV) {                      \
+        case 1: { constexpr int NT_ = 1; CALL; } break; \
+        case 2: { constexpr int NT_ = 2; CALL; } break; \
+        case 3: { constexpr int NT_ = 3; CALL; } break; \
+        case 4: { constexpr int NT_ = 4; CALL; } break; \
+        case 5: { constexpr int NT_ = 5; CALL; } break; \
+        default: return LRQMM_ERR_UNSUPPORTED;          \
+    }
+
 int launch_reduce_gram(const float* partial, int splits, int n, int LP, const float* rowscale, float* Y,
                        double* gpart, hipStream_t st) {
-    const size_t lds = (size_t)GB_ROWS * (LP + 1) * sizeof(float);
-    hipLaunchKernelGGL(reduce_gram_kernel, dim3(gram_blocks(n)), dim3(256), lds, st, partial, splits, n, LP,
-                       rowscale, Y, gpart);
+    const int rpb = gram_rows_per_block(n);
+    dim3 grid(gram_blocks(n));
+    NT_SWITCH(LP / 16, hipLaunchKernelGGL((reduce_gram_kernel<NT_>), grid, dim3(256), 0, st, partial, splits, n,
+                                          rpb, rowscale, Y, gpart));
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }
@@ -274,16 +416,17 @@ int launch_chol_inverse(const double* gpart, int nb, int ell, int LP, double* T,
 
 int launch_apply(const float* In, int n, int LP, const double* Mat, int cm, int ldm, float* out, int ldo,
                  int transposed, hipStream_t st) {
-    const size_t lds = (size_t)LP * cm * sizeof(double) + (size_t)32 * (LP + 1) * sizeof(float);
-    hipLaunchKernelGGL(apply_kernel, dim3(ceil_div(n, 32)), dim3(256), lds, st, In, n, LP, Mat, cm, ldm, out,
-                       ldo, transposed);
+    dim3 grid(ceil_div(n, 32));
+    NT_SWITCH(LP / 16, hipLaunchKernelGGL((apply_kernel<NT_>), grid, dim3(256), 0, st, In, n, Mat, cm, ldm, out,
+                                          ldo, transposed));
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }
 
 int launch_small_svd(const double* gpart, int nb, int ell, int LP, int rank, float* Sigma, double* Ur,
                      double* Mv, hipStream_t st) {
-    hipLaunchKernelGGL(small_svd_kernel, dim3(1), dim3(256), 0, st, gpart, nb, ell, LP, rank, Sigma, Ur, Mv);
+    hipLaunchKernelGGL(small_svd_kernel, dim3(1), dim3(SVD_THREADS), 0, st, gpart, nb, ell, LP, rank, Sigma, Ur,
+                       Mv);
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }

@@ -248,10 +248,10 @@ __global__ __launch_bounds__(256) void resid_mul_t_kernel(
 // launch plans and dispatch
 // ---------------------------------------------------------------------------
 static int pick_splits(int blocks_one_split, int reduce_len, int unit) {
-    // aim for ~1024 workgroups (4 per CU) but keep >= 4 `unit`-sized steps per split
-    int want = ceil_div(1024, max(1, blocks_one_split));
+    // aim for ~512 workgroups (2 per CU) but keep >= 4 `unit`-sized steps per split
+    int want = ceil_div(512, max(1, blocks_one_split));
     int max_splits = max(1, reduce_len / (4 * unit));
-    int s = max(1, min(want, min(max_splits, 32)));
+    int s = max(1, min(want, min(max_splits, 8)));
     return s;
 }
 
