@@ -142,9 +142,9 @@ def main():
     }
     # quantize: A read twice (second touch from cache) -> algorithmic 4 B read + 1 B written per element;
     # B additionally one absmax pass
-    q_bytes = 5.0 * w.M * w.K + 9.0 * w.K * w.N
-    stage_info["quantize"].update(algorithmic_GBs=round(q_bytes / (stages["quantize"] * 1e-3) / 1e9, 1),
-                                  frac_hbm=round(q_bytes / (stages["quantize"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4))
+    for key, q_bytes in (("quantize_a", 5.0 * w.M * w.K), ("quantize_b", 9.0 * w.K * w.N)):
+        gbs = q_bytes / (stages[key] * 1e-3) / 1e9
+        stage_info[key].update(algorithmic_GBs=round(gbs, 1), frac_hbm=round(gbs / PEAK_HBM_GBS, 4))
     for key, elems in (("rsvd_a", w.M * w.K), ("rsvd_b", w.K * w.N)):
         if stages[key] > 0:
             gbs = passes * 4.0 * elems / (stages[key] * 1e-3) / 1e9

@@ -127,6 +127,11 @@ LRQMM_API int lrqmm_gemm(int M, int N, int K, int bits, int rank,
  * B (K x N) to float32 C (M x N): quantize both operands, factor both residuals
  * (sketch seeds (seed, 0) and (seed, 1)), integer GEMM, fused compensation.
  * rank == 0 runs the direct-quantization pipeline only.
+ * With rank > 0 the work on B (quantization, factorization of R_B) is enqueued on
+ * a second stream owned by the library (created on first use, default priority),
+ * forked from and joined back into `stream` with events, so the call is still
+ * ordered like a single-stream call from the caller's point of view.  Calls must
+ * not be issued concurrently from several host threads.
  */
 LRQMM_API int lrqmm_matmul(int M, int N, int K, int bits, int rank, int oversample, int power_iters,
                  uint64_t seed, int round_mode, const float* A, const float* B, float* C,
@@ -141,10 +146,11 @@ LRQMM_API int lrqmm_matmul(int M, int N, int K, int bits, int rank, int oversamp
  * synchronisation), writes the per-stage mean duration in milliseconds to
  * stage_ms[LRQMM_PROF_STAGES] (host pointer) and the number of calls averaged to
  * *ncalls (host pointer), then resets the call counter.  Not thread safe.
- *   stage 0 quantize A and B     stage 1 RSVD of R_A      stage 2 RSVD of R_B
- *   stage 3 compensation panels  stage 4 int8 GEMM kernel with fused epilogue
+ *   stage 0 quantize A   stage 1 RSVD of R_A     (caller's stream)
+ *   stage 2 quantize B   stage 3 RSVD of R_B     (library's second stream, concurrent with 0-1)
+ *   stage 4 compensation panels   stage 5 int8 GEMM kernel with fused epilogue
  */
-#define LRQMM_PROF_STAGES 5
+#define LRQMM_PROF_STAGES 6
 LRQMM_API int lrqmm_profile_enable(int on);
 LRQMM_API int lrqmm_profile_read(float* stage_ms, int* ncalls);
 

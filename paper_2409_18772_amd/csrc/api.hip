@@ -80,8 +80,8 @@ size_t carve_gemm(Arena& a, int M, int N, int K, int rank, GemmWs* w) {
 struct MatmulWs {
     int8_t *Aq, *BqT;
     float *amaxA, *amaxB, *U, *Sig, *Vt, *W, *Gam, *Zt;
-    void* sub;
-    size_t sub_bytes;
+    void *sub, *subA, *subB;          // gemm scratch aliases the two rsvd regions
+    size_t sub_bytes, subA_bytes, subB_bytes;
 };
 
 size_t carve_matmul(Arena& a, int M, int N, int K, int rank, int oversample, MatmulWs* w) {
@@ -99,21 +99,25 @@ size_t carve_matmul(Arena& a, int M, int N, int K, int rank, int oversample, Mat
         t.Zt = a.take<float>((size_t)rank * N);
     }
     a.off = align_up(a.off, 256);
-    size_t sub = 0;
+    size_t sub = 0, sa = 0, sb = 0;
     {
         Arena g(nullptr);
         sub = carve_gemm(g, M, N, K, rank, nullptr);
     }
     if (rank > 0) {
+        // the two residual factorizations run concurrently: each gets its own region
         const int LP = pad_to(rank + oversample, 16);
         Arena ra(nullptr), rb(nullptr);
-        const size_t sa = carve_rsvd(ra, M, K, LRQMM_AXIS_ROW, LP, rank, nullptr);
-        const size_t sb = carve_rsvd(rb, K, N, LRQMM_AXIS_COL, LP, rank, nullptr);
-        if (sa > sub) sub = sa;
-        if (sb > sub) sub = sb;
+        sa = align_up(carve_rsvd(ra, M, K, LRQMM_AXIS_ROW, LP, rank, nullptr), 256);
+        sb = align_up(carve_rsvd(rb, K, N, LRQMM_AXIS_COL, LP, rank, nullptr), 256);
+        if (sa + sb > sub) sub = sa + sb;
     }
     t.sub = a.base ? a.base + a.off : nullptr;
     t.sub_bytes = sub;
+    t.subA = t.sub;
+    t.subA_bytes = sa;
+    t.subB = a.base ? a.base + a.off + sa : nullptr;
+    t.subB_bytes = sb;
     a.off += sub;
     if (w) *w = t;
     return a.off;
@@ -121,13 +125,34 @@ size_t carve_matmul(Arena& a, int M, int N, int K, int rank, int oversample, Mat
 
 // Optional stage timing of lrqmm_matmul with HIP events recorded on the caller's stream.
 constexpr int kProfStages = LRQMM_PROF_STAGES;
+constexpr int kProfEvents = 9;
 constexpr int kProfMaxCalls = 512;
+// event indices: 0-2 main stream (quantize A, RSVD A), 3-5 side stream (quantize B, RSVD B),
+// 6-8 main stream after the join (panels, GEMM)
+constexpr int kStageBegin[kProfStages] = {0, 1, 3, 4, 6, 7};
+constexpr int kStageEnd[kProfStages] = {1, 2, 4, 5, 7, 8};
 struct Prof {
     bool on = false;
     int ncalls = 0;
-    hipEvent_t ev[kProfMaxCalls][kProfStages + 1];
+    hipEvent_t ev[kProfMaxCalls][kProfEvents];
     bool created = false;
 } g_prof;
+
+// Second stream (default priority) on which the factorization of R_B runs next to R_A's.
+struct Side {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+    bool ok = false;
+} g_side;
+
+bool side_ready() {
+    if (g_side.ok) return true;
+    if (hipStreamCreateWithFlags(&g_side.stream, hipStreamNonBlocking) != hipSuccess) return false;
+    if (hipEventCreateWithFlags(&g_side.fork, hipEventDisableTiming) != hipSuccess) return false;
+    if (hipEventCreateWithFlags(&g_side.join, hipEventDisableTiming) != hipSuccess) return false;
+    g_side.ok = true;
+    return true;
+}
 
 inline void prof_mark(int slot, int i, hipStream_t st) {
     if (slot >= 0) (void)hipEventRecord(g_prof.ev[slot][i], st);
@@ -278,10 +303,10 @@ static int gemm_impl(int M, int N, int K, int bits, int rank, const int8_t* Aq, 
         LRQ_TRY(launch_vtw(Vt, W, K, rank, w.X, st));
         LRQ_TRY(launch_build_panels(M, N, rank, RP, R2P, U, Sig, w.S, w.Pv, w.X, Gam, Zt, w.Lp, w.Rp, st));
     }
-    prof_mark(prof_slot, 4, st);
+    prof_mark(prof_slot, 7, st);
     rc = launch_int8_gemm(M, N, K, Aq, BqT, w.sA, w.sB, rank > 0 ? w.Lp : nullptr, rank > 0 ? w.Rp : nullptr,
                           R2P, C, Cint_or_null, st);
-    prof_mark(prof_slot, 5, st);
+    prof_mark(prof_slot, 8, st);
     return rc;
 }
 
@@ -314,23 +339,34 @@ int lrqmm_matmul(int M, int N, int K, int bits, int rank, int oversample, int po
     int rc;
     hipStream_t pst = static_cast<hipStream_t>(stream);
     const int slot = (g_prof.on && g_prof.ncalls < kProfMaxCalls) ? g_prof.ncalls++ : -1;
-    prof_mark(slot, 0, pst);
-    if (K > 0) {
-        LRQ_TRY(lrqmm_quantize(A, M, K, LRQMM_AXIS_ROW, bits, round_mode, w.Aq, w.amaxA, stream));
-        LRQ_TRY(lrqmm_quantize(B, K, N, LRQMM_AXIS_COL, bits, round_mode, w.BqT, w.amaxB, stream));
-    } else {
-        LRQ_TRY(launch_pad_copy(nullptr, M, 0, 1, w.amaxA, static_cast<hipStream_t>(stream)));
-        LRQ_TRY(launch_pad_copy(nullptr, N, 0, 1, w.amaxB, static_cast<hipStream_t>(stream)));
+    // B's quantization and factorization run on a second stream next to A's; rank 0 stays on one stream
+    const bool overlap = rank > 0 && K > 0 && side_ready();
+    hipStream_t bst = overlap ? g_side.stream : pst;
+    if (overlap) {
+        if (hipEventRecord(g_side.fork, pst) != hipSuccess) return LRQMM_ERR_HIP;
+        if (hipStreamWaitEvent(bst, g_side.fork, 0) != hipSuccess) return LRQMM_ERR_HIP;
     }
+    prof_mark(slot, 0, pst);
+    if (K > 0) LRQ_TRY(lrqmm_quantize(A, M, K, LRQMM_AXIS_ROW, bits, round_mode, w.Aq, w.amaxA, pst));
+    else LRQ_TRY(launch_pad_copy(nullptr, M, 0, 1, w.amaxA, pst));
     prof_mark(slot, 1, pst);
     if (rank > 0)
         LRQ_TRY(lrqmm_rsvd(A, w.amaxA, M, K, LRQMM_AXIS_ROW, bits, round_mode, rank, oversample, power_iters,
-                           seed, nullptr, w.U, w.Sig, w.Vt, w.sub, w.sub_bytes, stream));
+                           seed, nullptr, w.U, w.Sig, w.Vt, w.subA, w.subA_bytes, pst));
     prof_mark(slot, 2, pst);
+    prof_mark(slot, 3, bst);
+    if (K > 0) LRQ_TRY(lrqmm_quantize(B, K, N, LRQMM_AXIS_COL, bits, round_mode, w.BqT, w.amaxB, bst));
+    else LRQ_TRY(launch_pad_copy(nullptr, N, 0, 1, w.amaxB, bst));
+    prof_mark(slot, 4, bst);
     if (rank > 0)
         LRQ_TRY(lrqmm_rsvd(B, w.amaxB, K, N, LRQMM_AXIS_COL, bits, round_mode, rank, oversample, power_iters,
-                           seed, nullptr, w.W, w.Gam, w.Zt, w.sub, w.sub_bytes, stream));
-    prof_mark(slot, 3, pst);
+                           seed, nullptr, w.W, w.Gam, w.Zt, w.subB, w.subB_bytes, bst));
+    prof_mark(slot, 5, bst);
+    if (overlap) {
+        if (hipEventRecord(g_side.join, bst) != hipSuccess) return LRQMM_ERR_HIP;
+        if (hipStreamWaitEvent(pst, g_side.join, 0) != hipSuccess) return LRQMM_ERR_HIP;
+    }
+    prof_mark(slot, 6, pst);
     return gemm_impl(M, N, K, bits, rank, w.Aq, w.amaxA, w.BqT, w.amaxB, w.U, w.Sig, w.Vt, w.W, w.Gam, w.Zt, C,
                      nullptr, w.sub, w.sub_bytes, stream, slot);
 }
@@ -338,7 +374,7 @@ int lrqmm_matmul(int M, int N, int K, int bits, int rank, int oversample, int po
 int lrqmm_profile_enable(int on) {
     if (on && !g_prof.created) {
         for (int c = 0; c < kProfMaxCalls; ++c)
-            for (int i = 0; i <= kProfStages; ++i)
+            for (int i = 0; i < kProfEvents; ++i)
                 if (hipEventCreate(&g_prof.ev[c][i]) != hipSuccess) return LRQMM_ERR_HIP;
         g_prof.created = true;
     }
@@ -353,11 +389,12 @@ int lrqmm_profile_read(float* stage_ms, int* ncalls) {
     *ncalls = n;
     for (int i = 0; i < kProfStages; ++i) stage_ms[i] = 0.f;
     if (n == 0) return LRQMM_OK;
-    if (hipEventSynchronize(g_prof.ev[n - 1][kProfStages]) != hipSuccess) return LRQMM_ERR_HIP;
+    if (hipEventSynchronize(g_prof.ev[n - 1][kProfEvents - 1]) != hipSuccess) return LRQMM_ERR_HIP;
     for (int c = 0; c < n; ++c)
         for (int i = 0; i < kProfStages; ++i) {
             float ms = 0.f;
-            if (hipEventElapsedTime(&ms, g_prof.ev[c][i], g_prof.ev[c][i + 1]) != hipSuccess) return LRQMM_ERR_HIP;
+            if (hipEventElapsedTime(&ms, g_prof.ev[c][kStageBegin[i]], g_prof.ev[c][kStageEnd[i]]) != hipSuccess)
+                return LRQMM_ERR_HIP;
             stage_ms[i] += ms / (float)n;
         }
     g_prof.ncalls = 0;

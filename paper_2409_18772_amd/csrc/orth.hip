@@ -13,7 +13,7 @@
 #include "kernels.h"
 
 #define GB_TILE 64        // rows of Y staged per LDS tile in the Gram kernel
-#define GRAM_MAX_BLOCKS 32
+#define GRAM_MAX_BLOCKS 16
 #define GRAM_MIN_ROWS 256
 #define MAXL LRQMM_MAX_SKETCH
 
@@ -105,23 +105,34 @@ __global__ __launch_bounds__(256) void reduce_gram_kernel(const float* __restric
     }
 }
 
-// Sum the Gram partials (fixed order) into LDS, G[a][b] for a, b < ell.
+// Sum the Gram partials (fixed order) into LDS, G[a][b] for a, b < ell.  The partials were
+// written by other workgroups (other XCDs), so every load is a long-latency miss: each
+// thread issues the loads of four entries (up to 4 x GRAM_MAX_BLOCKS) before summing.
 __device__ static void load_gram(const double* __restrict__ gpart, int nb, int ell, int LP,
                                  double* __restrict__ G, int ldg) {
-    for (int idx = threadIdx.x; idx < ell * ell; idx += blockDim.x) {
-        const int a = idx / ell, b = idx % ell;
-        const double* src = gpart + a * LP + b;
-        const size_t st = (size_t)LP * LP;
-        double acc = 0.0;
-        int blk = 0;
-        for (; blk + 8 <= nb; blk += 8) {     // eight independent loads in flight
-            const double v0 = src[(blk + 0) * st], v1 = src[(blk + 1) * st], v2 = src[(blk + 2) * st],
-                         v3 = src[(blk + 3) * st], v4 = src[(blk + 4) * st], v5 = src[(blk + 5) * st],
-                         v6 = src[(blk + 6) * st], v7 = src[(blk + 7) * st];
-            acc = (((((((acc + v0) + v1) + v2) + v3) + v4) + v5) + v6) + v7;
+    const size_t st = (size_t)LP * LP;
+    const int total = ell * ell;
+    for (int base = threadIdx.x; base < total; base += 4 * blockDim.x) {
+        double v[4][GRAM_MAX_BLOCKS];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = base + u * blockDim.x;
+            const int a = idx / ell, b = idx % ell;
+            const double* src = gpart + a * LP + b;
+#pragma unroll
+            for (int blk = 0; blk < GRAM_MAX_BLOCKS; ++blk)
+                v[u][blk] = (idx < total && blk < nb) ? src[blk * st] : 0.0;
         }
-        for (; blk < nb; ++blk) acc += src[blk * st];
-        G[a * ldg + b] = acc;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = base + u * blockDim.x;
+            if (idx < total) {
+                double acc = 0.0;
+#pragma unroll
+                for (int blk = 0; blk < GRAM_MAX_BLOCKS; ++blk) acc += v[u][blk];
+                G[(idx / ell) * ldg + idx % ell] = acc;
+            }
+        }
     }
 }
 
@@ -129,19 +140,25 @@ __device__ static void load_gram(const double* __restrict__ gpart, int nb, int e
 // this wave are complete and the compiler moves no memory access across.
 __device__ __forceinline__ void wave_lds_fence() { __asm__ volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
-// dot_{k in [lo, hi)} row[k] * other[k] over two LDS rows, eight loads in flight.
+// sum_{k in [lo, hi)} row[k] * other[k] over two LDS rows.  The trip count depends on hi
+// only (uniform across the wave); lo is applied as a per-lane mask, so lanes with different
+// ranges never diverge.  Eight loads of each row are in flight per batch.
 __device__ __forceinline__ double lds_dot(const double* __restrict__ row, const double* __restrict__ other,
                                           int lo, int hi) {
     double s = 0.0;
-    int k = lo;
-    for (; k + 8 <= hi; k += 8) {
+    for (int k = 0; k < hi; k += 8) {
         double a[8], b[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) { a[u] = row[k + u]; b[u] = other[k + u]; }
+        for (int u = 0; u < 8; ++u) {      // rows are MAXL+1 long: k+u stays inside the row
+            a[u] = row[k + u];
+            b[u] = other[k + u];
+        }
 #pragma unroll
-        for (int u = 0; u < 8; ++u) s = fma(a[u], b[u], s);
+        for (int u = 0; u < 8; ++u) {
+            const bool in = (k + u >= lo) && (k + u < hi);
+            s = fma(in ? a[u] : 0.0, b[u], s);
+        }
     }
-    for (; k < hi; ++k) s = fma(row[k], other[k], s);
     return s;
 }
 
@@ -175,18 +192,24 @@ __global__ __launch_bounds__(256) void chol_inverse_kernel(const double* __restr
             for (int h = 0; h < 2; ++h) {
                 const int t = tid + 64 * h;
                 val[h] = 0.0;
-                if (t >= ell) continue;
-                if (t >= j) {
-                    val[h] = G[t * ldg + j] - lds_dot(G + t * ldg, rowj, 0, j);
-                } else {
-                    // k = t term uses X[t][t] = 1 / L[t][t]
-                    val[h] = -(rowj[t] * dinv[t] + lds_dot(G + t * ldg, rowj, t + 1, j));
-                }
+                if (h == 1 && ell <= 64) continue;          // uniform: second row set unused
+                const int tt = min(t, ell - 1);             // lanes beyond ell shadow the last row
+                const bool lower = tt >= j;
+                const double dot = lds_dot(G + tt * ldg, rowj, lower ? 0 : tt + 1, j);
+                // t < j: the k = t term uses X[t][t] = 1 / L[t][t]
+                const double head = lower ? G[tt * ldg + j] : rowj[tt] * dinv[tt];
+                val[h] = lower ? head - dot : -(head + dot);
             }
             const double dj = __shfl(val[j >> 6], j & 63, 64);
             const double d0 = __shfl(dorig[j >> 6], j & 63, 64);
             const bool live = dj > 1e-10 * d0 && dj > 0.0;
-            const double inv = live ? 1.0 / sqrt(dj) : 0.0;
+            double inv = 0.0;
+            if (live) {   // 1/sqrt by the hardware estimate and three Newton steps
+                inv = __builtin_amdgcn_rsq(dj);
+                inv = inv * fma(-0.5 * dj, inv * inv, 1.5);
+                inv = inv * fma(-0.5 * dj, inv * inv, 1.5);
+                inv = inv * fma(-0.5 * dj, inv * inv, 1.5);
+            }
             if (tid == 0) {
                 dead[j] = live ? 0 : 1;
                 dinv[j] = live ? inv : 1.0;
@@ -254,11 +277,33 @@ __global__ __launch_bounds__(256) void apply_kernel(const float* __restrict__ In
     }
 }
 
+// Jacobi rotation that annihilates the off-diagonal entry of [[gpp, gpq], [gpq, gqq]]
+// under G <- J^T G J with J = [[c, s], [-s, c]].  The angle is formed in float (an inexact
+// angle still converges); c and s are then made orthonormal to float64 accuracy.
+__device__ __forceinline__ bool jacobi_rotation(double gpp, double gqq, double gpq, double gsc, double& c,
+                                                double& s) {
+    c = 1.0;
+    s = 0.0;
+    const float bf = (float)(2.0 * gpq * gsc);
+    if (!(gpq * gpq > 1e-24 * fabs(gpp * gqq)) || bf == 0.0f) return false;
+    const float th = (float)((gqq - gpp) * gsc) * __builtin_amdgcn_rcpf(bf);
+    const float tf = copysignf(1.0f, th) * __builtin_amdgcn_rcpf(fabsf(th) + __builtin_amdgcn_sqrtf(th * th + 1.0f));
+    const double t = (double)tf;
+    const double x = fma(t, t, 1.0);
+    double r = __builtin_amdgcn_rsq(x);
+    r = r * fma(-0.5 * x, r * r, 1.5);
+    r = r * fma(-0.5 * x, r * r, 1.5);
+    r = r * fma(-0.5 * x, r * r, 1.5);
+    c = r;
+    s = t * r;
+    return true;
+}
+
 // Cyclic Jacobi eigen-solve of the l x l matrix G = B B^T (B = Q^T R), round-robin pairing
-// so l/2 disjoint rotations run per step.  A step is two phases: (1) one thread per pair
-// derives its rotation from the pair's 2x2 diagonal block; (2) one thread per (row pair,
-// column pair) updates that 2x2 block of G = J^T G J and of V = V J in place (every
-// element belongs to exactly one block, so no double buffering is needed).
+// so l/2 disjoint rotations run per step.  One thread per (row pair, column pair) derives
+// both rotations itself from the two 2x2 diagonal blocks and writes its 2x2 block of
+// J^T G J into the other of two ping-pong copies of G, so a step needs a single barrier;
+// V = V J is updated in place (every element belongs to exactly one block).
 // Eigenvalues are the squared singular values of B, eigenvectors its left singular vectors.
 #define SVD_THREADS 512
 __global__ __launch_bounds__(SVD_THREADS) void small_svd_kernel(const double* __restrict__ gpart, int nb,
@@ -266,9 +311,9 @@ __global__ __launch_bounds__(SVD_THREADS) void small_svd_kernel(const double* __
                                                                 float* __restrict__ Sigma,
                                                                 double* __restrict__ Ur,
                                                                 double* __restrict__ Mv) {
-    __shared__ double G[MAXL * (MAXL + 1)];
+    __shared__ double G0[MAXL * (MAXL + 1)];
+    __shared__ double G1[MAXL * (MAXL + 1)];
     __shared__ double V[MAXL * (MAXL + 1)];
-    __shared__ double cs[MAXL / 2], sn[MAXL / 2];
     __shared__ int order[MAXL];
     __shared__ int rotated;
     const int ldg = MAXL + 1;
@@ -276,11 +321,12 @@ __global__ __launch_bounds__(SVD_THREADS) void small_svd_kernel(const double* __
     const int m = (ell + 1) & ~1;   // even number of players; a zero dummy row/column when ell is odd
     for (int idx = tid; idx < m * m; idx += SVD_THREADS) {
         const int a = idx / m, b = idx % m;
-        G[a * ldg + b] = 0.0;
+        G0[a * ldg + b] = 0.0;
         V[a * ldg + b] = (a == b) ? 1.0 : 0.0;
     }
+    if (tid == 0) rotated = 0;
     __syncthreads();
-    load_gram(gpart, nb, ell, LP, G, ldg);
+    load_gram(gpart, nb, ell, LP, G0, ldg);
     __syncthreads();
     const int half = m / 2;
     // round-robin tournament: player m-1 stays, the others rotate (no integer division)
@@ -294,73 +340,54 @@ __global__ __launch_bounds__(SVD_THREADS) void small_svd_kernel(const double* __
         q = max(a, b);
     };
     double gmax = 0.0;
-    for (int a = 0; a < ell; ++a) gmax = fmax(gmax, fabs(G[a * ldg + a]));
+    for (int a = 0; a < ell; ++a) gmax = fmax(gmax, fabs(G0[a * ldg + a]));
     const double gsc = gmax > 0.0 ? 1.0 / gmax : 0.0;
-    for (int sweep = 0; sweep < 15; ++sweep) {
-        if (tid == 0) rotated = 0;
-        __syncthreads();
+    double* Gc = G0;
+    double* Gn = G1;
+    for (int sweep = 0; sweep < 16; ++sweep) {
         for (int step = 0; step < m - 1; ++step) {
-            if (tid < half) {
-                int p, q;
-                pair_of(tid, step, p, q);
-                const double gpq = G[p * ldg + q];
-                const double gpp = G[p * ldg + p], gqq = G[q * ldg + q];
-                double c = 1.0, s = 0.0;
-                const float bf = (float)(2.0 * gpq * gsc);
-                if (gpq * gpq > 1e-26 * fabs(gpp * gqq) && bf != 0.0f) {
-                    // The angle only needs float accuracy (a slightly inexact angle still
-                    // converges); c and s are then made orthonormal to float64 accuracy.
-                    const float th = (float)((gqq - gpp) * gsc) * __builtin_amdgcn_rcpf(bf);
-                    const float tf = copysignf(1.0f, th) *
-                                     __builtin_amdgcn_rcpf(fabsf(th) + __builtin_amdgcn_sqrtf(th * th + 1.0f));
-                    const double t = (double)tf;
-                    const double x = fma(t, t, 1.0);
-                    double r = __builtin_amdgcn_rsq(x);
-                    r = r * fma(-0.5 * x, r * r, 1.5);
-                    r = r * fma(-0.5 * x, r * r, 1.5);
-                    r = r * fma(-0.5 * x, r * r, 1.5);
-                    c = r;
-                    s = t * r;
-                    rotated = 1;
-                }
-                cs[tid] = c;
-                sn[tid] = s;
-            }
-            __syncthreads();
             for (int blk = tid; blk < half * half; blk += SVD_THREADS) {
-                const int P = blk / half, Q = blk % half;
+                const int P = blk / half, Q = blk - P * half;
                 int p1, q1, p2, q2;
                 pair_of(P, step, p1, q1);
                 pair_of(Q, step, p2, q2);
-                const double c1 = cs[P], s1 = sn[P], c2 = cs[Q], s2 = sn[Q];
-                double* g11 = &G[p1 * ldg + p2];
-                double* g12 = &G[p1 * ldg + q2];
-                double* g21 = &G[q1 * ldg + p2];
-                double* g22 = &G[q1 * ldg + q2];
-                const double a11 = *g11, a12 = *g12, a21 = *g21, a22 = *g22;
-                // rows: J^T G
-                const double r11 = c1 * a11 - s1 * a21, r12 = c1 * a12 - s1 * a22;
-                const double r21 = s1 * a11 + c1 * a21, r22 = s1 * a12 + c1 * a22;
-                // columns: (.) J
-                *g11 = c2 * r11 - s2 * r12;
-                *g12 = s2 * r11 + c2 * r12;
-                *g21 = c2 * r21 - s2 * r22;
-                *g22 = s2 * r21 + c2 * r22;
+                const double dpp = Gc[p1 * ldg + p1], dqq = Gc[q1 * ldg + q1], dpq = Gc[p1 * ldg + q1];
+                const double epp = Gc[p2 * ldg + p2], eqq = Gc[q2 * ldg + q2], epq = Gc[p2 * ldg + q2];
+                const double a11 = Gc[p1 * ldg + p2], a12 = Gc[p1 * ldg + q2];
+                const double a21 = Gc[q1 * ldg + p2], a22 = Gc[q1 * ldg + q2];
                 double* v11 = &V[p1 * ldg + p2];
                 double* v12 = &V[p1 * ldg + q2];
                 double* v21 = &V[q1 * ldg + p2];
                 double* v22 = &V[q1 * ldg + q2];
                 const double b11 = *v11, b12 = *v12, b21 = *v21, b22 = *v22;
+                double c1, s1, c2, s2;
+                const bool did = jacobi_rotation(dpp, dqq, dpq, gsc, c1, s1);
+                jacobi_rotation(epp, eqq, epq, gsc, c2, s2);
+                if (P == Q && did) rotated = 1;
+                // rows: J^T G, then columns: (.) J
+                const double r11 = c1 * a11 - s1 * a21, r12 = c1 * a12 - s1 * a22;
+                const double r21 = s1 * a11 + c1 * a21, r22 = s1 * a12 + c1 * a22;
+                Gn[p1 * ldg + p2] = c2 * r11 - s2 * r12;
+                Gn[p1 * ldg + q2] = s2 * r11 + c2 * r12;
+                Gn[q1 * ldg + p2] = c2 * r21 - s2 * r22;
+                Gn[q1 * ldg + q2] = s2 * r21 + c2 * r22;
                 *v11 = c2 * b11 - s2 * b12;
                 *v12 = s2 * b11 + c2 * b12;
                 *v21 = c2 * b21 - s2 * b22;
                 *v22 = s2 * b21 + c2 * b22;
             }
             __syncthreads();
+            double* tmp = Gc;
+            Gc = Gn;
+            Gn = tmp;
         }
-        if (!rotated) break;
+        const int any = rotated;
         __syncthreads();
+        if (tid == 0) rotated = 0;
+        __syncthreads();
+        if (!any) break;
     }
+    const double* G = Gc;
     // rank eigenvalues: order[pos] = index of the pos-th largest (ties by index)
     if (tid < ell) {
         const double mine = G[tid * ldg + tid];
