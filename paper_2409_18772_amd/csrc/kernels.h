@@ -22,6 +22,7 @@ int launch_fill_sketch(uint64_t seed, int stream_id, int rows, int cols, int ld,
 int launch_pad_copy(const float* src, int rows, int cols, int ld, float* dst, hipStream_t st);
 
 // ---- passes.hip ---------------------------------------------------------
+#define MAX_SPLITS 8    // upper bound on PassPlan::splits
 struct PassPlan {
     int splits;   // number of partial results
     int chunk;    // reduction-index range per split (multiple of 64)

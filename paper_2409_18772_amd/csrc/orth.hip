@@ -13,8 +13,8 @@
 #include "kernels.h"
 
 #define GB_TILE 64        // rows of Y staged per LDS tile in the Gram kernel
-#define GRAM_MAX_BLOCKS 16
-#define GRAM_MIN_ROWS 256
+#define GRAM_MAX_BLOCKS 64
+#define GRAM_MIN_ROWS 64
 #define MAXL LRQMM_MAX_SKETCH
 
 static int gram_rows_per_block(int n) {
@@ -55,20 +55,15 @@ __global__ __launch_bounds__(256) void reduce_gram_kernel(const float* __restric
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
             if (row < re) {
                 const size_t off = (size_t)row * LP + c;
-                int sp = 0;
-                for (; sp + 4 <= splits; sp += 4) {      // four independent loads in flight
-                    const float4 p0 = *reinterpret_cast<const float4*>(partial + (sp + 0) * plane + off);
-                    const float4 p1 = *reinterpret_cast<const float4*>(partial + (sp + 1) * plane + off);
-                    const float4 p2 = *reinterpret_cast<const float4*>(partial + (sp + 2) * plane + off);
-                    const float4 p3 = *reinterpret_cast<const float4*>(partial + (sp + 3) * plane + off);
-                    v.x = (((v.x + p0.x) + p1.x) + p2.x) + p3.x;
-                    v.y = (((v.y + p0.y) + p1.y) + p2.y) + p3.y;
-                    v.z = (((v.z + p0.z) + p1.z) + p2.z) + p3.z;
-                    v.w = (((v.w + p0.w) + p1.w) + p2.w) + p3.w;
-                }
-                for (; sp < splits; ++sp) {
-                    const float4 p0 = *reinterpret_cast<const float4*>(partial + sp * plane + off);
-                    v.x += p0.x; v.y += p0.y; v.z += p0.z; v.w += p0.w;
+                // every split's load is issued before the first add (splits <= MAX_SPLITS)
+                float4 p[MAX_SPLITS];
+#pragma unroll
+                for (int sp = 0; sp < MAX_SPLITS; ++sp)
+                    p[sp] = (sp < splits) ? *reinterpret_cast<const float4*>(partial + sp * plane + off)
+                                          : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                for (int sp = 0; sp < MAX_SPLITS; ++sp) {
+                    v.x += p[sp].x; v.y += p[sp].y; v.z += p[sp].z; v.w += p[sp].w;
                 }
                 if (rowscale) {
                     const float rs = rowscale[row];
@@ -106,33 +101,22 @@ __global__ __launch_bounds__(256) void reduce_gram_kernel(const float* __restric
 }
 
 // Sum the Gram partials (fixed order) into LDS, G[a][b] for a, b < ell.  The partials were
-// written by other workgroups (other XCDs), so every load is a long-latency miss: each
-// thread issues the loads of four entries (up to 4 x GRAM_MAX_BLOCKS) before summing.
+// written by other workgroups (other XCDs), so every load is a long-latency miss: a thread
+// issues all (up to GRAM_MAX_BLOCKS) loads of an entry before summing them.
 __device__ static void load_gram(const double* __restrict__ gpart, int nb, int ell, int LP,
                                  double* __restrict__ G, int ldg) {
     const size_t st = (size_t)LP * LP;
     const int total = ell * ell;
-    for (int base = threadIdx.x; base < total; base += 4 * blockDim.x) {
-        double v[4][GRAM_MAX_BLOCKS];
+    for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
+        const int a = idx / ell, b = idx % ell;
+        const double* src = gpart + a * LP + b;
+        double v[GRAM_MAX_BLOCKS];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int idx = base + u * blockDim.x;
-            const int a = idx / ell, b = idx % ell;
-            const double* src = gpart + a * LP + b;
+        for (int blk = 0; blk < GRAM_MAX_BLOCKS; ++blk) v[blk] = (blk < nb) ? src[blk * st] : 0.0;
+        double acc = 0.0;
 #pragma unroll
-            for (int blk = 0; blk < GRAM_MAX_BLOCKS; ++blk)
-                v[u][blk] = (idx < total && blk < nb) ? src[blk * st] : 0.0;
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int idx = base + u * blockDim.x;
-            if (idx < total) {
-                double acc = 0.0;
-#pragma unroll
-                for (int blk = 0; blk < GRAM_MAX_BLOCKS; ++blk) acc += v[u][blk];
-                G[(idx / ell) * ldg + idx % ell] = acc;
-            }
-        }
+        for (int blk = 0; blk < GRAM_MAX_BLOCKS; ++blk) acc += v[blk];
+        G[a * ldg + b] = acc;
     }
 }
 
@@ -169,7 +153,8 @@ __device__ __forceinline__ double lds_dot(const double* __restrict__ row, const 
 //   t >= j:  L[t][j] = (G[t][j] - sum_{k<j} L[t][k] L[j][k]) / L[j][j]
 //   t <  j:  X[j][t] = -(sum_{t<=k<j} L[j][k] X[k][t]) / L[j][j]
 // so the inverse comes out of the same loop with no workgroup barrier inside it.
-__global__ __launch_bounds__(256) void chol_inverse_kernel(const double* __restrict__ gpart, int nb,
+#define CHOL_THREADS 1024
+__global__ __launch_bounds__(CHOL_THREADS) void chol_inverse_kernel(const double* __restrict__ gpart, int nb,
                                                            int ell, int LP, double* __restrict__ T) {
     __shared__ double G[MAXL * (MAXL + 1)];
     __shared__ double dinv[MAXL];
@@ -224,7 +209,7 @@ __global__ __launch_bounds__(256) void chol_inverse_kernel(const double* __restr
         }
     }
     __syncthreads();
-    for (int idx = tid; idx < LP * LP; idx += 256) {
+    for (int idx = tid; idx < LP * LP; idx += CHOL_THREADS) {
         const int a = idx / LP, b = idx % LP;
         double v = 0.0;
         if (a < ell && b < ell && !dead[b] && !dead[a]) {
@@ -280,12 +265,17 @@ __global__ __launch_bounds__(256) void apply_kernel(const float* __restrict__ In
 // Jacobi rotation that annihilates the off-diagonal entry of [[gpp, gpq], [gpq, gqq]]
 // under G <- J^T G J with J = [[c, s], [-s, c]].  The angle is formed in float (an inexact
 // angle still converges); c and s are then made orthonormal to float64 accuracy.
+// Returns true when the entry was still "large" (|gpq| > 1e-5 sqrt(gpp gqq)) before the
+// rotation: Jacobi converges quadratically, so a sweep that saw no large entry leaves
+// off-diagonals of relative size ~1e-10 and is the last one.
 __device__ __forceinline__ bool jacobi_rotation(double gpp, double gqq, double gpq, double gsc, double& c,
                                                 double& s) {
     c = 1.0;
     s = 0.0;
     const float bf = (float)(2.0 * gpq * gsc);
-    if (!(gpq * gpq > 1e-24 * fabs(gpp * gqq)) || bf == 0.0f) return false;
+    const double g2 = gpq * gpq, dd = fabs(gpp * gqq);
+    if (!(g2 > 1e-24 * dd) || bf == 0.0f) return false;
+    const bool large = g2 > 1e-10 * dd;
     const float th = (float)((gqq - gpp) * gsc) * __builtin_amdgcn_rcpf(bf);
     const float tf = copysignf(1.0f, th) * __builtin_amdgcn_rcpf(fabsf(th) + __builtin_amdgcn_sqrtf(th * th + 1.0f));
     const double t = (double)tf;
@@ -296,14 +286,15 @@ __device__ __forceinline__ bool jacobi_rotation(double gpp, double gqq, double g
     r = r * fma(-0.5 * x, r * r, 1.5);
     c = r;
     s = t * r;
-    return true;
+    return large;
 }
 
 // Cyclic Jacobi eigen-solve of the l x l matrix G = B B^T (B = Q^T R), round-robin pairing
-// so l/2 disjoint rotations run per step.  One thread per (row pair, column pair) derives
-// both rotations itself from the two 2x2 diagonal blocks and writes its 2x2 block of
-// J^T G J into the other of two ping-pong copies of G, so a step needs a single barrier;
-// V = V J is updated in place (every element belongs to exactly one block).
+// so l/2 disjoint rotations run per step.  A step is two phases: (1) one thread per pair
+// derives its rotation from the pair's 2x2 diagonal block; (2) one thread per (row pair,
+// column pair) updates that 2x2 block of G = J^T G J and of V = V J in place (every
+// element belongs to exactly one block, so no double buffering is needed).  The kernel is
+// bound by instruction issue, so phase 2 is kept to index arithmetic plus 24 multiply/FMA.
 // Eigenvalues are the squared singular values of B, eigenvectors its left singular vectors.
 #define SVD_THREADS 512
 __global__ __launch_bounds__(SVD_THREADS) void small_svd_kernel(const double* __restrict__ gpart, int nb,
@@ -311,9 +302,9 @@ __global__ __launch_bounds__(SVD_THREADS) void small_svd_kernel(const double* __
                                                                 float* __restrict__ Sigma,
                                                                 double* __restrict__ Ur,
                                                                 double* __restrict__ Mv) {
-    __shared__ double G0[MAXL * (MAXL + 1)];
-    __shared__ double G1[MAXL * (MAXL + 1)];
+    __shared__ double G[MAXL * (MAXL + 1)];
     __shared__ double V[MAXL * (MAXL + 1)];
+    __shared__ double cs[MAXL / 2], sn[MAXL / 2];
     __shared__ int order[MAXL];
     __shared__ int rotated;
     const int ldg = MAXL + 1;
@@ -321,12 +312,12 @@ __global__ __launch_bounds__(SVD_THREADS) void small_svd_kernel(const double* __
     const int m = (ell + 1) & ~1;   // even number of players; a zero dummy row/column when ell is odd
     for (int idx = tid; idx < m * m; idx += SVD_THREADS) {
         const int a = idx / m, b = idx % m;
-        G0[a * ldg + b] = 0.0;
+        G[a * ldg + b] = 0.0;
         V[a * ldg + b] = (a == b) ? 1.0 : 0.0;
     }
     if (tid == 0) rotated = 0;
     __syncthreads();
-    load_gram(gpart, nb, ell, LP, G0, ldg);
+    load_gram(gpart, nb, ell, LP, G, ldg);
     __syncthreads();
     const int half = m / 2;
     // round-robin tournament: player m-1 stays, the others rotate (no integer division)
@@ -339,47 +330,46 @@ __global__ __launch_bounds__(SVD_THREADS) void small_svd_kernel(const double* __
         p = min(a, b);
         q = max(a, b);
     };
-    double gmax = 0.0;
-    for (int a = 0; a < ell; ++a) gmax = fmax(gmax, fabs(G0[a * ldg + a]));
-    const double gsc = gmax > 0.0 ? 1.0 / gmax : 0.0;
-    double* Gc = G0;
-    double* Gn = G1;
+    double gsc = 0.0;
+    if (tid < half) {
+        double gmax = 0.0;
+        for (int a = 0; a < ell; ++a) gmax = fmax(gmax, fabs(G[a * ldg + a]));
+        gsc = gmax > 0.0 ? 1.0 / gmax : 0.0;
+    }
+    // a thread's blocks are fixed for the whole run: (P, Q) = (blk / half, blk % half)
     for (int sweep = 0; sweep < 16; ++sweep) {
         for (int step = 0; step < m - 1; ++step) {
+            if (tid < half) {
+                int p, q;
+                pair_of(tid, step, p, q);
+                double c, s;
+                if (jacobi_rotation(G[p * ldg + p], G[q * ldg + q], G[p * ldg + q], gsc, c, s)) rotated = 1;
+                cs[tid] = c;
+                sn[tid] = s;
+            }
+            __syncthreads();
             for (int blk = tid; blk < half * half; blk += SVD_THREADS) {
                 const int P = blk / half, Q = blk - P * half;
                 int p1, q1, p2, q2;
                 pair_of(P, step, p1, q1);
                 pair_of(Q, step, p2, q2);
-                const double dpp = Gc[p1 * ldg + p1], dqq = Gc[q1 * ldg + q1], dpq = Gc[p1 * ldg + q1];
-                const double epp = Gc[p2 * ldg + p2], eqq = Gc[q2 * ldg + q2], epq = Gc[p2 * ldg + q2];
-                const double a11 = Gc[p1 * ldg + p2], a12 = Gc[p1 * ldg + q2];
-                const double a21 = Gc[q1 * ldg + p2], a22 = Gc[q1 * ldg + q2];
-                double* v11 = &V[p1 * ldg + p2];
-                double* v12 = &V[p1 * ldg + q2];
-                double* v21 = &V[q1 * ldg + p2];
-                double* v22 = &V[q1 * ldg + q2];
-                const double b11 = *v11, b12 = *v12, b21 = *v21, b22 = *v22;
-                double c1, s1, c2, s2;
-                const bool did = jacobi_rotation(dpp, dqq, dpq, gsc, c1, s1);
-                jacobi_rotation(epp, eqq, epq, gsc, c2, s2);
-                if (P == Q && did) rotated = 1;
+                const double c1 = cs[P], s1 = sn[P], c2 = cs[Q], s2 = sn[Q];
+                const int r1 = p1 * ldg, r2 = q1 * ldg;
+                const double a11 = G[r1 + p2], a12 = G[r1 + q2], a21 = G[r2 + p2], a22 = G[r2 + q2];
+                const double b11 = V[r1 + p2], b12 = V[r1 + q2], b21 = V[r2 + p2], b22 = V[r2 + q2];
                 // rows: J^T G, then columns: (.) J
-                const double r11 = c1 * a11 - s1 * a21, r12 = c1 * a12 - s1 * a22;
-                const double r21 = s1 * a11 + c1 * a21, r22 = s1 * a12 + c1 * a22;
-                Gn[p1 * ldg + p2] = c2 * r11 - s2 * r12;
-                Gn[p1 * ldg + q2] = s2 * r11 + c2 * r12;
-                Gn[q1 * ldg + p2] = c2 * r21 - s2 * r22;
-                Gn[q1 * ldg + q2] = s2 * r21 + c2 * r22;
-                *v11 = c2 * b11 - s2 * b12;
-                *v12 = s2 * b11 + c2 * b12;
-                *v21 = c2 * b21 - s2 * b22;
-                *v22 = s2 * b21 + c2 * b22;
+                const double t11 = fma(c1, a11, -(s1 * a21)), t12 = fma(c1, a12, -(s1 * a22));
+                const double t21 = fma(s1, a11, c1 * a21), t22 = fma(s1, a12, c1 * a22);
+                G[r1 + p2] = fma(c2, t11, -(s2 * t12));
+                G[r1 + q2] = fma(s2, t11, c2 * t12);
+                G[r2 + p2] = fma(c2, t21, -(s2 * t22));
+                G[r2 + q2] = fma(s2, t21, c2 * t22);
+                V[r1 + p2] = fma(c2, b11, -(s2 * b12));
+                V[r1 + q2] = fma(s2, b11, c2 * b12);
+                V[r2 + p2] = fma(c2, b21, -(s2 * b22));
+                V[r2 + q2] = fma(s2, b21, c2 * b22);
             }
             __syncthreads();
-            double* tmp = Gc;
-            Gc = Gn;
-            Gn = tmp;
         }
         const int any = rotated;
         __syncthreads();
@@ -387,7 +377,6 @@ __global__ __launch_bounds__(SVD_THREADS) void small_svd_kernel(const double* __
         __syncthreads();
         if (!any) break;
     }
-    const double* G = Gc;
     // rank eigenvalues: order[pos] = index of the pos-th largest (ties by index)
     if (tid < ell) {
         const double mine = G[tid * ldg + tid];
@@ -436,7 +425,7 @@ int launch_reduce_gram(const float* partial, int splits, int n, int LP, const fl
 }
 
 int launch_chol_inverse(const double* gpart, int nb, int ell, int LP, double* T, hipStream_t st) {
-    hipLaunchKernelGGL(chol_inverse_kernel, dim3(1), dim3(256), 0, st, gpart, nb, ell, LP, T);
+    hipLaunchKernelGGL(chol_inverse_kernel, dim3(1), dim3(CHOL_THREADS), 0, st, gpart, nb, ell, LP, T);
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }

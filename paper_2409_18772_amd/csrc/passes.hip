@@ -13,28 +13,43 @@
 // B[k = l/16][j = l%16], D[i = 4*(l/16)+v][j = l%16] for v = 0..3.
 #include "kernels.h"
 
-#define KCHUNK 64   // reduction elements staged per LDS step in the N-type kernels
+#define KCHUNK 128   // reduction elements staged per LDS step in the N-type kernels
+#define KSUB (KCHUNK / 16)   // float4 loads per lane per chunk
 
 __device__ __forceinline__ v4f mfma16(float a, float b, v4f c) {
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
 
-// Stage W[k0 .. k0+63][0..LP) (row-major, ld = LP) into LDS with row stride LP+4.
-__device__ __forceinline__ void stage_w(const float* __restrict__ W, int k0, int kend, int LP,
-                                        float* __restrict__ wl) {
-    const int n4 = KCHUNK * LP / 4;
-    for (int idx = threadIdx.x; idx < n4; idx += 256) {
-        const int e = idx * 4;
-        const int kk = e / LP, n = e % LP;
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (k0 + kk < kend) v = *reinterpret_cast<const float4*>(W + (size_t)(k0 + kk) * LP + n);
-        *reinterpret_cast<float4*>(wl + kk * (LP + 4) + n) = v;
+// Register image of one thread's share of W[k0 .. k0+KCHUNK)[0..LP) (row-major, ld = LP).
+template <int NT>
+struct WStage {
+    static constexpr int LP = NT * 16;
+    static constexpr int N4 = KCHUNK * LP / 4 / 256;   // float4 per thread (LP multiple of 16)
+    float4 v[N4];
+    __device__ __forceinline__ void load(const float* __restrict__ W, int k0, int kend) {
+#pragma unroll
+        for (int u = 0; u < N4; ++u) {
+            const int e = (threadIdx.x + 256 * u) * 4;
+            const int kk = e / LP, n = e % LP;
+            v[u] = (k0 + kk < kend) ? *reinterpret_cast<const float4*>(W + (size_t)(k0 + kk) * LP + n)
+                                    : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
     }
-}
+    __device__ __forceinline__ void store(float* __restrict__ wl) const {   // LDS row stride LP+4
+#pragma unroll
+        for (int u = 0; u < N4; ++u) {
+            const int e = (threadIdx.x + 256 * u) * 4;
+            const int kk = e / LP, n = e % LP;
+            *reinterpret_cast<float4*>(wl + kk * (LP + 4) + n) = v[u];
+        }
+    }
+};
 
 // ---------------------------------------------------------------------------
 // N-type: partial[split][rows][LP] = R[:, k-range] . W[k-range, :]
-// grid (ceil(rows/64), splits); 4 waves x 16 rows; W chunk staged in LDS.
+// grid (ceil(rows/64), splits); 4 waves x 16 rows.  Per KCHUNK columns: the W chunk goes
+// through double-buffered LDS, and both the next chunk of X and of W are already in
+// flight (in registers) while the matrix cores work on the current one.
 // ---------------------------------------------------------------------------
 template <int NT, int AXIS, bool VEC>
 __global__ __launch_bounds__(256) void resid_mul_n_kernel(
@@ -42,7 +57,7 @@ __global__ __launch_bounds__(256) void resid_mul_n_kernel(
     const float* __restrict__ sc, QuantParams q, const float* __restrict__ W, int chunk,
     float* __restrict__ partial) {
     constexpr int LP = NT * 16;
-    __shared__ __align__(16) float wl[KCHUNK * (LP + 4)];
+    __shared__ __align__(16) float wl[2][KCHUNK * (LP + 4)];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r = lane & 15, g = lane >> 4;
     const int row = blockIdx.x * 64 + wave * 16 + r;
@@ -59,34 +74,53 @@ __global__ __launch_bounds__(256) void resid_mul_n_kernel(
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) acc[nt] = (v4f){0.f, 0.f, 0.f, 0.f};
 
-    for (int k0 = kb; k0 < ke; k0 += KCHUNK) {
-        __syncthreads();
-        stage_w(W, k0, ke, LP, wl);
-        float res[4][4];
+    float4 xr[KSUB], lr[KSUB], sr[KSUB];
+    WStage<NT> ws;
+    auto load_x = [&](int k0) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < KSUB; ++j) {
             const int k = k0 + 16 * j + 4 * g;
-            float4 x = load4f<VEC>(xp, k, ke, row_ok);
+            xr[j] = load4f<VEC>(xp, k, ke, row_ok);
+            if (AXIS == 1) {   // lam / sc are padded with zeros to a multiple of 4 beyond `cols`
+                lr[j] = (k < ke) ? *reinterpret_cast<const float4*>(lam + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+                sr[j] = (k < ke) ? *reinterpret_cast<const float4*>(sc + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+    };
+    if (kb < ke) {
+        load_x(kb);
+        ws.load(W, kb, ke);
+    }
+    int buf = 0;
+    for (int k0 = kb; k0 < ke; k0 += KCHUNK, buf ^= 1) {
+        ws.store(wl[buf]);
+        float res[KSUB][4];
+#pragma unroll
+        for (int j = 0; j < KSUB; ++j) {
             float4 l4, s4;
             if (AXIS == 0) {
                 l4 = make_float4(lam_r, lam_r, lam_r, lam_r);
                 s4 = make_float4(s_r, s_r, s_r, s_r);
             } else {
-                // lam / sc are padded with zeros to a multiple of 4 beyond `cols`
-                l4 = (k < ke) ? *reinterpret_cast<const float4*>(lam + k) : make_float4(0.f, 0.f, 0.f, 0.f);
-                s4 = (k < ke) ? *reinterpret_cast<const float4*>(sc + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+                l4 = lr[j];
+                s4 = sr[j];
             }
-            res[j][0] = quant_residual(x.x, l4.x, s4.x, q);
-            res[j][1] = quant_residual(x.y, l4.y, s4.y, q);
-            res[j][2] = quant_residual(x.z, l4.z, s4.z, q);
-            res[j][3] = quant_residual(x.w, l4.w, s4.w, q);
+            res[j][0] = quant_residual(xr[j].x, l4.x, s4.x, q);
+            res[j][1] = quant_residual(xr[j].y, l4.y, s4.y, q);
+            res[j][2] = quant_residual(xr[j].z, l4.z, s4.z, q);
+            res[j][3] = quant_residual(xr[j].w, l4.w, s4.w, q);
         }
-        __syncthreads();
+        if (k0 + KCHUNK < ke) {      // next chunk's loads fly during this chunk's MFMAs
+            load_x(k0 + KCHUNK);
+            ws.load(W, k0 + KCHUNK, ke);
+        }
+        __syncthreads();             // wl[buf] complete; wl[buf^1] no longer read by anyone
+        const float* wb = wl[buf];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < KSUB; ++j) {
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                const float* wrow = wl + (16 * j + 4 * g + t) * (LP + 4) + r;
+                const float* wrow = wb + (16 * j + 4 * g + t) * (LP + 4) + r;
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) acc[nt] = mfma16(res[j][t], wrow[16 * nt], acc[nt]);
             }
@@ -107,7 +141,7 @@ __global__ __launch_bounds__(256) void codes_mul_n_kernel(const int8_t* __restri
                                                           int K, const float* __restrict__ W,
                                                           int chunk, float* __restrict__ partial) {
     constexpr int LP = NT * 16;
-    __shared__ __align__(16) float wl[KCHUNK * (LP + 4)];
+    __shared__ __align__(16) float wl[2][KCHUNK * (LP + 4)];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r = lane & 15, g = lane >> 4;
     const int row = blockIdx.x * 64 + wave * 16 + r;
@@ -118,38 +152,48 @@ __global__ __launch_bounds__(256) void codes_mul_n_kernel(const int8_t* __restri
     v4f acc[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) acc[nt] = (v4f){0.f, 0.f, 0.f, 0.f};
-    for (int k0 = kb; k0 < ke; k0 += KCHUNK) {
-        __syncthreads();
-        stage_w(W, k0, ke, LP, wl);
-        float res[4][4];
+    uint32_t cr[KSUB];
+    WStage<NT> ws;
+    auto load_c = [&](int k0) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < KSUB; ++j) {
             const int k = k0 + 16 * j + 4 * g;
-            int c[4] = {0, 0, 0, 0};
+            uint32_t p = 0;
             if (row_ok) {
                 if (VEC) {
-                    if (k < ke) {
-                        const uint32_t p = *reinterpret_cast<const uint32_t*>(cp + k);
-                        c[0] = (int8_t)(p & 0xff);
-                        c[1] = (int8_t)((p >> 8) & 0xff);
-                        c[2] = (int8_t)((p >> 16) & 0xff);
-                        c[3] = (int8_t)((p >> 24) & 0xff);
-                    }
+                    if (k < ke) p = *reinterpret_cast<const uint32_t*>(cp + k);
                 } else {
 #pragma unroll
                     for (int t = 0; t < 4; ++t)
-                        if (k + t < ke) c[t] = cp[k + t];
+                        if (k + t < ke) p |= (uint32_t)(uint8_t)cp[k + t] << (8 * t);
                 }
             }
+            cr[j] = p;
+        }
+    };
+    if (kb < ke) {
+        load_c(kb);
+        ws.load(W, kb, ke);
+    }
+    int buf = 0;
+    for (int k0 = kb; k0 < ke; k0 += KCHUNK, buf ^= 1) {
+        ws.store(wl[buf]);
+        float res[KSUB][4];
 #pragma unroll
-            for (int t = 0; t < 4; ++t) res[j][t] = (float)c[t];
+        for (int j = 0; j < KSUB; ++j)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) res[j][t] = (float)(int8_t)((cr[j] >> (8 * t)) & 0xff);
+        if (k0 + KCHUNK < ke) {
+            load_c(k0 + KCHUNK);
+            ws.load(W, k0 + KCHUNK, ke);
         }
         __syncthreads();
+        const float* wb = wl[buf];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < KSUB; ++j) {
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                const float* wrow = wl + (16 * j + 4 * g + t) * (LP + 4) + r;
+                const float* wrow = wb + (16 * j + 4 * g + t) * (LP + 4) + r;
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) acc[nt] = mfma16(res[j][t], wrow[16 * nt], acc[nt]);
             }
@@ -169,8 +213,11 @@ __global__ __launch_bounds__(256) void codes_mul_n_kernel(const int8_t* __restri
 // grid (ceil(cols/64), splits); the 4 waves of a block share one 64-column strip,
 // interleave rows, and merge their accumulators through LDS.
 // A lane's float4 holds columns c0+4c .. c0+4c+3; component t feeds M-tile t, so
-// M-tile t covers the columns {c0 + 4 c + t}.
+// M-tile t covers the columns {c0 + 4 c + t}.  Likewise N-tile nt covers the W columns
+// {NT c + nt}, so a lane's B operands are NT consecutive floats (one wide load).
+// Loads run TUNR row groups ahead of the matrix cores (register double buffering).
 // ---------------------------------------------------------------------------
+#define TUNR 4
 template <int NT, int AXIS, bool VEC>
 __global__ __launch_bounds__(256) void resid_mul_t_kernel(
     const float* __restrict__ X, int rows, int cols, const float* __restrict__ lam,
@@ -184,10 +231,10 @@ __global__ __launch_bounds__(256) void resid_mul_t_kernel(
     const int kc = c0 + 4 * c;
     const int ib = blockIdx.y * chunk;
     const int ie = min(rows, ib + chunk);
-    float4 l4 = make_float4(0.f, 0.f, 0.f, 0.f), s4 = l4;
+    float4 lc = make_float4(0.f, 0.f, 0.f, 0.f), scol = lc;
     if (AXIS == 1 && kc < cols) {   // padded with zeros to a multiple of 4
-        l4 = *reinterpret_cast<const float4*>(lam + kc);
-        s4 = *reinterpret_cast<const float4*>(sc + kc);
+        lc = *reinterpret_cast<const float4*>(lam + kc);
+        scol = *reinterpret_cast<const float4*>(sc + kc);
     }
     v4f acc[4][NT];
 #pragma unroll
@@ -195,28 +242,50 @@ __global__ __launch_bounds__(256) void resid_mul_t_kernel(
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[t][nt] = (v4f){0.f, 0.f, 0.f, 0.f};
 
-    for (int i0 = ib + wave * 4; i0 < ie; i0 += 16) {
+    struct Frag {
+        float4 x;
+        float lr, sr;
+        float w[NT];
+    };
+    auto load_frag = [&](int i0, Frag& f) {
         const int i = i0 + g;
         const bool ok = i < ie;
         const size_t ii = ok ? (size_t)i : 0;
-        float4 x = load4f<VEC>(X + ii * cols, kc, cols, ok);
+        f.x = load4f<VEC>(X + ii * cols, kc, cols, ok);
         if (AXIS == 0) {
-            const float lr = ok ? lam[ii] : 0.f, sr = ok ? sc[ii] : 0.f;
-            l4 = make_float4(lr, lr, lr, lr);
-            s4 = make_float4(sr, sr, sr, sr);
+            f.lr = ok ? lam[ii] : 0.f;
+            f.sr = ok ? sc[ii] : 0.f;
         }
-        float w[NT];
+        const float* wp = W + ii * LP + NT * c;
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) w[nt] = ok ? W[ii * LP + 16 * nt + c] : 0.f;
-        float res[4];
-        res[0] = quant_residual(x.x, l4.x, s4.x, q);
-        res[1] = quant_residual(x.y, l4.y, s4.y, q);
-        res[2] = quant_residual(x.z, l4.z, s4.z, q);
-        res[3] = quant_residual(x.w, l4.w, s4.w, q);
+        for (int nt = 0; nt < NT; ++nt) f.w[nt] = ok ? wp[nt] : 0.f;
+    };
+    Frag cur[TUNR], nxt[TUNR];
+    const int istart = ib + wave * 4;
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
+    for (int u = 0; u < TUNR; ++u) load_frag(istart + 16 * u, cur[u]);
+    for (int i0 = istart; i0 < ie; i0 += 16 * TUNR) {
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) acc[t][nt] = mfma16(res[t], w[nt], acc[t][nt]);
+        for (int u = 0; u < TUNR; ++u) load_frag(i0 + 16 * (TUNR + u), nxt[u]);
+#pragma unroll
+        for (int u = 0; u < TUNR; ++u) {
+            float4 l4 = lc, s4 = scol;
+            if (AXIS == 0) {
+                l4 = make_float4(cur[u].lr, cur[u].lr, cur[u].lr, cur[u].lr);
+                s4 = make_float4(cur[u].sr, cur[u].sr, cur[u].sr, cur[u].sr);
+            }
+            float res[4];
+            res[0] = quant_residual(cur[u].x.x, l4.x, s4.x, q);
+            res[1] = quant_residual(cur[u].x.y, l4.y, s4.y, q);
+            res[2] = quant_residual(cur[u].x.z, l4.z, s4.z, q);
+            res[3] = quant_residual(cur[u].x.w, l4.w, s4.w, q);
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) acc[t][nt] = mfma16(res[t], cur[u].w[nt], acc[t][nt]);
+        }
+#pragma unroll
+        for (int u = 0; u < TUNR; ++u) cur[u] = nxt[u];
     }
     // merge the four waves (fixed order: deterministic)
     for (int wv = 0; wv < 4; ++wv) {
@@ -228,7 +297,7 @@ __global__ __launch_bounds__(256) void resid_mul_t_kernel(
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         const int cl = 16 * g + 4 * v + t;   // local column of D row 4g+v in M-tile t
-                        float* p = red + cl * LP + 16 * nt + c;
+                        float* p = red + cl * LP + NT * c + nt;
                         *p = (wv == 0) ? acc[t][nt][v] : (*p + acc[t][nt][v]);
                     }
         }
@@ -251,7 +320,7 @@ static int pick_splits(int blocks_one_split, int reduce_len, int unit) {
     // aim for ~512 workgroups (2 per CU) but keep >= 4 `unit`-sized steps per split
     int want = ceil_div(512, max(1, blocks_one_split));
     int max_splits = max(1, reduce_len / (4 * unit));
-    int s = max(1, min(want, min(max_splits, 8)));
+    int s = max(1, min(want, min(max_splits, MAX_SPLITS)));
     return s;
 }
 
