@@ -155,6 +155,130 @@ __global__ __launch_bounds__(256) void int8_gemm_kernel(int M, int N, int K,
     }
 }
 
+// Large-tile variant for big problems: 256x256 workgroup tile, 4 waves in 2x2, each wave
+// 128x128 as 4x4 MFMA tiles (256 accumulator registers per lane), one workgroup per CU.
+// Per 32-deep MFMA step a wave reads 8 KB of operands from LDS for 16 MFMAs (512 MFMA
+// cycles), half the LDS traffic per MFMA of the 64x64 wave tile.
+#define BTM 256
+#define BTN 256
+template <bool VEC, bool COMP, bool WCINT>
+__global__ __launch_bounds__(256, 1) void int8_gemm256_kernel(int M, int N, int K,
+                                                              const int8_t* __restrict__ Aq,
+                                                              const int8_t* __restrict__ BqT,
+                                                              const float* __restrict__ sA,
+                                                              const float* __restrict__ sB,
+                                                              const float* __restrict__ Lp,
+                                                              const float* __restrict__ Rp, int R2P,
+                                                              float* __restrict__ C,
+                                                              int32_t* __restrict__ Cint, int tiles_n,
+                                                              int ntiles) {
+    __shared__ __align__(16) int8_t As[2][BTM * LDS_STRIDE];
+    __shared__ __align__(16) int8_t Bs[2][BTN * LDS_STRIDE];
+    int tile = blockIdx.x;
+    if ((ntiles & 7) == 0) tile = (tile & 7) * (ntiles >> 3) + (tile >> 3);
+    const int m0 = (tile / tiles_n) * BTM, n0 = (tile % tiles_n) * BTN;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, lh = lane >> 5;
+
+    v16i acc[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0;
+
+    // staging: 1024 16-byte chunks per operand tile, four per thread
+    const int srow0 = tid >> 2, skc = (tid & 3) * 16;
+    uint4 ra[4], rb[4];
+    auto gload = [&](int k0) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            ra[u] = load16b<VEC>(Aq, m0 + srow0 + 64 * u, M, K, k0 + skc);
+            rb[u] = load16b<VEC>(BqT, n0 + srow0 + 64 * u, N, K, k0 + skc);
+        }
+    };
+    auto sstore = [&](int buf) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            *reinterpret_cast<uint4*>(&As[buf][(srow0 + 64 * u) * LDS_STRIDE + skc]) = ra[u];
+            *reinterpret_cast<uint4*>(&Bs[buf][(srow0 + 64 * u) * LDS_STRIDE + skc]) = rb[u];
+        }
+    };
+    const int nk = (K + BK - 1) / BK;
+    gload(0);
+    sstore(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < nk) gload((kt + 1) * BK);
+#pragma unroll
+        for (int kk = 0; kk < BK / 32; ++kk) {
+            v4i af[4], bf[4];
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+                af[mt] = *reinterpret_cast<const v4i*>(
+                    &As[buf][(wm * 128 + mt * 32 + l32) * LDS_STRIDE + kk * 32 + lh * 16]);
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt)
+                bf[nt] = *reinterpret_cast<const v4i*>(
+                    &Bs[buf][(wn * 128 + nt * 32 + l32) * LDS_STRIDE + kk * 32 + lh * 16]);
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt)
+                    acc[mt][nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[mt], bf[nt], acc[mt][nt], 0, 0, 0);
+        }
+        if (kt + 1 < nk) sstore(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: dequantize, rank-2r update, store ----
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+        const int rbase = m0 + wm * 128 + mt * 32;
+        const int lrow = rbase + l32;
+        const bool lok = lrow < M;
+        const float* lp = COMP ? Lp + (size_t)(lok ? lrow : 0) * R2P + 4 * lh : nullptr;
+        float sa[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = rbase + 8 * (v >> 2) + 4 * lh + (v & 3);
+            sa[v] = (row < M) ? sA[row] : 0.f;
+        }
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) {
+            const int col = n0 + wn * 128 + nt * 32 + l32;
+            const bool col_ok = col < N;
+            const float sb = col_ok ? sB[col] : 0.f;
+            v16f f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = rbase + 8 * (v >> 2) + 4 * lh + (v & 3);
+                if (WCINT && row < M && col_ok) Cint[(size_t)row * N + col] = acc[mt][nt][v];
+                f[v] = ((float)acc[mt][nt][v] * sa[v]) * sb;
+            }
+            if (COMP) {
+                const float* rp = Rp + (size_t)(col_ok ? col : 0) * R2P + 4 * lh;
+                for (int t0 = 0; t0 < R2P; t0 += 8) {
+                    float4 a4 = lok ? *reinterpret_cast<const float4*>(lp + t0) : make_float4(0.f, 0.f, 0.f, 0.f);
+                    float4 b4 = col_ok ? *reinterpret_cast<const float4*>(rp + t0) : make_float4(0.f, 0.f, 0.f, 0.f);
+                    f = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.x, b4.x, f, 0, 0, 0);
+                    f = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.y, b4.y, f, 0, 0, 0);
+                    f = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.z, b4.z, f, 0, 0, 0);
+                    f = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.w, b4.w, f, 0, 0, 0);
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = rbase + 8 * (v >> 2) + 4 * lh + (v & 3);
+                if (row < M && col_ok) C[(size_t)row * N + col] = f[v];
+            }
+        }
+    }
+}
+
 // X[t][u] = sum_k Vt[t][k] W[k][u]; one workgroup per entry.
 __global__ __launch_bounds__(256) void vtw_kernel(const float* __restrict__ Vt, const float* __restrict__ W,
                                                   int K, int r, float* __restrict__ X) {
@@ -234,6 +358,21 @@ int launch_build_panels(int M, int N, int r, int RP, int R2P, const float* U, co
 }
 
 template <bool VEC>
+static void dispatch_gemm256(bool comp, bool wcint, dim3 grid, hipStream_t st, int M, int N, int K,
+                             const int8_t* Aq, const int8_t* BqT, const float* sA, const float* sB,
+                             const float* Lp, const float* Rp, int R2P, float* C, int32_t* Cint, int tiles_n,
+                             int ntiles) {
+#define LRQ_GEMM(COMP, WC) \
+    hipLaunchKernelGGL((int8_gemm256_kernel<VEC, COMP, WC>), grid, dim3(256), 0, st, M, N, K, Aq, BqT, sA, sB, Lp, Rp, R2P, C, Cint, tiles_n, ntiles)
+    if (comp) {
+        if (wcint) LRQ_GEMM(true, true); else LRQ_GEMM(true, false);
+    } else {
+        if (wcint) LRQ_GEMM(false, true); else LRQ_GEMM(false, false);
+    }
+#undef LRQ_GEMM
+}
+
+template <bool VEC>
 static void dispatch_gemm(bool comp, bool wcint, dim3 grid, hipStream_t st, int M, int N, int K,
                           const int8_t* Aq, const int8_t* BqT, const float* sA, const float* sB,
                           const float* Lp, const float* Rp, int R2P, float* C, int32_t* Cint, int tiles_n,
@@ -251,10 +390,20 @@ static void dispatch_gemm(bool comp, bool wcint, dim3 grid, hipStream_t st, int 
 int launch_int8_gemm(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, const float* sA,
                      const float* sB, const float* Lp, const float* Rp, int R2P, float* C, int32_t* Cint,
                      hipStream_t st) {
-    const int tiles_m = ceil_div(M, TM), tiles_n = ceil_div(N, TN);
-    const int ntiles = tiles_m * tiles_n;
     const bool vec = (K % 16 == 0) && (((uintptr_t)Aq | (uintptr_t)BqT) & 15) == 0;
     const bool comp = Lp != nullptr;
+    // big problems: 256x256 tiles, one workgroup per CU
+    const int btiles = ceil_div(M, BTM) * ceil_div(N, BTN);
+    if (M >= BTM && N >= BTN && btiles >= 128) {
+        const int btn = ceil_div(N, BTN);
+        dim3 bgrid(btiles);
+        if (vec) dispatch_gemm256<true>(comp, Cint != nullptr, bgrid, st, M, N, K, Aq, BqT, sA, sB, Lp, Rp, R2P, C, Cint, btn, btiles);
+        else     dispatch_gemm256<false>(comp, Cint != nullptr, bgrid, st, M, N, K, Aq, BqT, sA, sB, Lp, Rp, R2P, C, Cint, btn, btiles);
+        LRQ_CHECK_LAUNCH();
+        return LRQMM_OK;
+    }
+    const int tiles_m = ceil_div(M, TM), tiles_n = ceil_div(N, TN);
+    const int ntiles = tiles_m * tiles_n;
     dim3 grid(ntiles);
     if (vec) dispatch_gemm<true>(comp, Cint != nullptr, grid, st, M, N, K, Aq, BqT, sA, sB, Lp, Rp, R2P, C, Cint, tiles_n, ntiles);
     else     dispatch_gemm<false>(comp, Cint != nullptr, grid, st, M, N, K, Aq, BqT, sA, sB, Lp, Rp, R2P, C, Cint, tiles_n, ntiles);
