@@ -65,19 +65,37 @@ __device__ __forceinline__ float wave_max(float v) {
 
 // 16-byte global load of 4 consecutive floats when allowed, else guarded scalar loads.
 // `k` is the first column, valid columns are [0, cols).  Rows out of range give zeros.
+// The vector path is branch free (clamped address, then a select): a load under a branch
+// makes the compiler wait for every outstanding load, which defeats software prefetching.
+// It needs cols % 4 == 0, cols >= 4 and a valid row pointer even when row_ok is false.
 template <bool VEC>
 __device__ __forceinline__ float4 load4f(const float* __restrict__ rowp, int k, int cols, bool row_ok) {
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (!row_ok) return v;
     if (VEC) {
-        if (k < cols) v = *reinterpret_cast<const float4*>(rowp + k);
+        const int kc = min(k, cols - 4);
+        const float4 t = *reinterpret_cast<const float4*>(rowp + kc);
+        const bool ok = row_ok && k < cols;
+        v.x = ok ? t.x : 0.f;
+        v.y = ok ? t.y : 0.f;
+        v.z = ok ? t.z : 0.f;
+        v.w = ok ? t.w : 0.f;
     } else {
+        if (!row_ok) return v;
         if (k + 0 < cols) v.x = rowp[k + 0];
         if (k + 1 < cols) v.y = rowp[k + 1];
         if (k + 2 < cols) v.z = rowp[k + 2];
         if (k + 3 < cols) v.w = rowp[k + 3];
     }
     return v;
+}
+
+// Branch-free float4 load from a vector padded to a multiple of 4: element k .. k+3 when
+// k < n, zeros otherwise (n >= 4, n % 4 == 0 after padding).
+__device__ __forceinline__ float4 load4_padded(const float* __restrict__ p, int k, int n) {
+    const int kc = max(0, min(k, n - 4));
+    const float4 t = *reinterpret_cast<const float4*>(p + kc);
+    const bool ok = k < n;
+    return make_float4(ok ? t.x : 0.f, ok ? t.y : 0.f, ok ? t.z : 0.f, ok ? t.w : 0.f);
 }
 
 #define LRQ_CHECK_LAUNCH()                                   \

@@ -20,17 +20,28 @@
 #define TM 128
 #define TN 128
 #define BK 64
+#ifndef LDS_STRIDE
 #define LDS_STRIDE 80
+#endif
 
+// 16 code bytes of one operand row.  The vector path (K % 16 == 0) is branch free: clamped
+// address, then a select; a load under a branch would make the compiler drain every
+// outstanding load each iteration and defeat the prefetch ring.
 template <bool VEC>
 __device__ __forceinline__ uint4 load16b(const int8_t* __restrict__ base, int row, int nrows, int K,
                                          int k) {
     uint4 v = make_uint4(0u, 0u, 0u, 0u);
-    if (row >= nrows) return v;
-    const int8_t* p = base + (size_t)row * K + k;
     if (VEC) {
-        if (k < K) v = *reinterpret_cast<const uint4*>(p);
+        const int rc = min(row, nrows - 1), kc = min(k, K - 16);
+        const uint4 t = *reinterpret_cast<const uint4*>(base + (size_t)rc * K + kc);
+        const bool ok = row < nrows && k < K;
+        v.x = ok ? t.x : 0u;
+        v.y = ok ? t.y : 0u;
+        v.z = ok ? t.z : 0u;
+        v.w = ok ? t.w : 0u;
     } else {
+        if (row >= nrows) return v;
+        const int8_t* p = base + (size_t)row * K + k;
         uint32_t w[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
         for (int b = 0; b < 16; ++b)
@@ -155,14 +166,36 @@ __global__ __launch_bounds__(256) void int8_gemm_kernel(int M, int N, int K,
     }
 }
 
-// Large-tile variant for big problems: 256x256 workgroup tile, 4 waves in 2x2, each wave
-// 128x128 as 4x4 MFMA tiles (256 accumulator registers per lane), one workgroup per CU.
-// Per 32-deep MFMA step a wave reads 8 KB of operands from LDS for 16 MFMAs (512 MFMA
-// cycles), half the LDS traffic per MFMA of the 64x64 wave tile.
+// Large-tile variant for big problems: 256x256 workgroup tile, one workgroup of 8 waves per
+// CU (two waves per SIMD, so one wave's LDS/global waits and barrier stalls are covered by
+// the other's MFMAs).  Waves form a 4x2 grid, each 64x128 = 2x4 MFMA tiles (128 accumulator
+// registers); per 32-deep MFMA step a wave reads 6 KB of operands from LDS for 8 MFMAs.
+#ifdef LRQ_ABLATE_LDS_BROADCAST   // timing experiment only: every lane reads row 0 (wrong results)
+#define LRQ_ABL_ROW(x) 0
+#else
+#define LRQ_ABL_ROW(x) (x)
+#endif
+#ifdef LRQ_ABLATE_GLOAD
+#define LRQ_ABL_GLOAD(x)
+#else
+#define LRQ_ABL_GLOAD(x) x
+#endif
+#ifdef LRQ_ABLATE_SSTORE
+#define LRQ_ABL_SSTORE(x)
+#else
+#define LRQ_ABL_SSTORE(x) x
+#endif
+#ifdef LRQ_ABLATE_SYNC
+#define LRQ_ABL_SYNC(x)
+#else
+#define LRQ_ABL_SYNC(x) x
+#endif
 #define BTM 256
 #define BTN 256
-template <bool VEC, bool COMP, bool WCINT>
-__global__ __launch_bounds__(256, 1) void int8_gemm256_kernel(int M, int N, int K,
+// FULL: M, N multiples of 256 and K a multiple of 64 -- operand loads carry no guard at all, so
+// nothing consumes a loaded register before it is written to LDS two iterations later.
+template <bool VEC, bool COMP, bool WCINT, bool FULL>
+__global__ __launch_bounds__(512, 1) void int8_gemm256_kernel(int M, int N, int K,
                                                               const int8_t* __restrict__ Aq,
                                                               const int8_t* __restrict__ BqT,
                                                               const float* __restrict__ sA,
@@ -181,63 +214,93 @@ __global__ __launch_bounds__(256, 1) void int8_gemm256_kernel(int M, int N, int 
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, lh = lane >> 5;
 
-    v16i acc[4][4];
+    v16i acc[2][4];
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < 2; ++a)
 #pragma unroll
         for (int b = 0; b < 4; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0;
 
-    // staging: 1024 16-byte chunks per operand tile, four per thread
+    // staging: 1024 16-byte chunks per operand tile, two per thread.  Global loads run three
+    // K-tiles ahead of the matrix cores in a ring of three register sets (a tile's MFMA time,
+    // ~1000 cycles, is well below global-load latency, so one tile of lookahead stalls every
+    // iteration); LDS holds the current and the next tile.
     const int srow0 = tid >> 2, skc = (tid & 3) * 16;
-    uint4 ra[4], rb[4];
-    auto gload = [&](int k0) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            ra[u] = load16b<VEC>(Aq, m0 + srow0 + 64 * u, M, K, k0 + skc);
-            rb[u] = load16b<VEC>(BqT, n0 + srow0 + 64 * u, N, K, k0 + skc);
-        }
+    // The three register sets are individually named scalars (not arrays passed by reference):
+    // that keeps them in VGPRs; as arrays they were demoted to scratch memory.
+    auto ldA = [&](int u, int k0) -> uint4 {
+        if (FULL)   // tiles past the end of K are loaded (clamped) but never stored or used
+            return *reinterpret_cast<const uint4*>(Aq + (size_t)(m0 + srow0 + 128 * u) * K + min(k0, K - BK) + skc);
+        return load16b<VEC>(Aq, m0 + srow0 + 128 * u, M, K, k0 + skc);
     };
-    auto sstore = [&](int buf) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            *reinterpret_cast<uint4*>(&As[buf][(srow0 + 64 * u) * LDS_STRIDE + skc]) = ra[u];
-            *reinterpret_cast<uint4*>(&Bs[buf][(srow0 + 64 * u) * LDS_STRIDE + skc]) = rb[u];
-        }
+    auto ldB = [&](int u, int k0) -> uint4 {
+        if (FULL)
+            return *reinterpret_cast<const uint4*>(BqT + (size_t)(n0 + srow0 + 128 * u) * K + min(k0, K - BK) + skc);
+        return load16b<VEC>(BqT, n0 + srow0 + 128 * u, N, K, k0 + skc);
     };
-    const int nk = (K + BK - 1) / BK;
-    gload(0);
-    sstore(0);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nk) gload((kt + 1) * BK);
+    auto stA = [&](int u, int buf, uint4 v) {
+        *reinterpret_cast<uint4*>(&As[buf][(srow0 + 128 * u) * LDS_STRIDE + skc]) = v;
+    };
+    auto stB = [&](int u, int buf, uint4 v) {
+        *reinterpret_cast<uint4*>(&Bs[buf][(srow0 + 128 * u) * LDS_STRIDE + skc]) = v;
+    };
+#define LRQ_DECL(S) uint4 S##a0, S##a1, S##b0, S##b1
+#define LRQ_GLOAD(S, k0)                                                   \
+    S##a0 = ldA(0, k0); S##b0 = ldB(0, k0); S##a1 = ldA(1, k0); S##b1 = ldB(1, k0)
+#define LRQ_SSTORE(S, buf)                                                         \
+    stA(0, buf, S##a0); stB(0, buf, S##b0); stA(1, buf, S##a1); stB(1, buf, S##b1)
+    LRQ_DECL(r0);
+    LRQ_DECL(r1);
+    LRQ_DECL(r2);
+    auto compute = [&](int buf) {
 #pragma unroll
         for (int kk = 0; kk < BK / 32; ++kk) {
-            v4i af[4], bf[4];
+            v4i af[2], bf[4];
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
+            for (int mt = 0; mt < 2; ++mt)
                 af[mt] = *reinterpret_cast<const v4i*>(
-                    &As[buf][(wm * 128 + mt * 32 + l32) * LDS_STRIDE + kk * 32 + lh * 16]);
+                    &As[buf][(wm * 64 + mt * 32 + LRQ_ABL_ROW(l32)) * LDS_STRIDE + kk * 32 + LRQ_ABL_ROW(lh) * 16]);
 #pragma unroll
             for (int nt = 0; nt < 4; ++nt)
                 bf[nt] = *reinterpret_cast<const v4i*>(
-                    &Bs[buf][(wn * 128 + nt * 32 + l32) * LDS_STRIDE + kk * 32 + lh * 16]);
+                    &Bs[buf][(wn * 128 + nt * 32 + LRQ_ABL_ROW(l32)) * LDS_STRIDE + kk * 32 + LRQ_ABL_ROW(lh) * 16]);
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
+            for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
                 for (int nt = 0; nt < 4; ++nt)
                     acc[mt][nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[mt], bf[nt], acc[mt][nt], 0, 0, 0);
         }
-        if (kt + 1 < nk) sstore(buf ^ 1);
-        __syncthreads();
+    };
+    const int nk = (K + BK - 1) / BK;
+    LRQ_GLOAD(r0, 0);
+    LRQ_GLOAD(r1, BK);
+    LRQ_GLOAD(r2, 2 * BK);
+    LRQ_SSTORE(r0, 0);
+    __syncthreads();
+    // iteration i: set i%3 is free -> load tile i+3; compute tile i; publish tile i+1
+#define LRQ_GEMM_STEP(J, SCUR, SNEXT)                  \
+    if (kt + J < nk) {                                 \
+        const int i = kt + J;                          \
+        LRQ_ABL_GLOAD(LRQ_GLOAD(SCUR, (i + 3) * BK));  \
+        compute(i & 1);                                \
+        if (i + 1 < nk) { LRQ_ABL_SSTORE(LRQ_SSTORE(SNEXT, (i + 1) & 1)); } \
+        LRQ_ABL_SYNC(__syncthreads());                 \
     }
+    for (int kt = 0; kt < nk; kt += 3) {
+        LRQ_GEMM_STEP(0, r0, r1)
+        LRQ_GEMM_STEP(1, r1, r2)
+        LRQ_GEMM_STEP(2, r2, r0)
+    }
+#undef LRQ_GEMM_STEP
+#undef LRQ_DECL
+#undef LRQ_GLOAD
+#undef LRQ_SSTORE
 
     // ---- epilogue: dequantize, rank-2r update, store ----
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) {
-        const int rbase = m0 + wm * 128 + mt * 32;
+    for (int mt = 0; mt < 2; ++mt) {
+        const int rbase = m0 + wm * 64 + mt * 32;
         const int lrow = rbase + l32;
         const bool lok = lrow < M;
         const float* lp = COMP ? Lp + (size_t)(lok ? lrow : 0) * R2P + 4 * lh : nullptr;
@@ -362,8 +425,16 @@ static void dispatch_gemm256(bool comp, bool wcint, dim3 grid, hipStream_t st, i
                              const int8_t* Aq, const int8_t* BqT, const float* sA, const float* sB,
                              const float* Lp, const float* Rp, int R2P, float* C, int32_t* Cint, int tiles_n,
                              int ntiles) {
-#define LRQ_GEMM(COMP, WC) \
-    hipLaunchKernelGGL((int8_gemm256_kernel<VEC, COMP, WC>), grid, dim3(256), 0, st, M, N, K, Aq, BqT, sA, sB, Lp, Rp, R2P, C, Cint, tiles_n, ntiles)
+    const bool full = VEC && (M % BTM == 0) && (N % BTN == 0) && (K % BK == 0) && K >= BK;
+#define LRQ_GEMM(COMP, WC)                                                                                   \
+    do {                                                                                                     \
+        if (full)                                                                                            \
+            hipLaunchKernelGGL((int8_gemm256_kernel<VEC, COMP, WC, VEC>), grid, dim3(512), 0, st, M, N, K, Aq, \
+                               BqT, sA, sB, Lp, Rp, R2P, C, Cint, tiles_n, ntiles);                           \
+        else                                                                                                 \
+            hipLaunchKernelGGL((int8_gemm256_kernel<VEC, COMP, WC, false>), grid, dim3(512), 0, st, M, N, K,  \
+                               Aq, BqT, sA, sB, Lp, Rp, R2P, C, Cint, tiles_n, ntiles);                       \
+    } while (0)
     if (comp) {
         if (wcint) LRQ_GEMM(true, true); else LRQ_GEMM(true, false);
     } else {

@@ -31,8 +31,10 @@ struct WStage {
         for (int u = 0; u < N4; ++u) {
             const int e = (threadIdx.x + 256 * u) * 4;
             const int kk = e / LP, n = e % LP;
-            v[u] = (k0 + kk < kend) ? *reinterpret_cast<const float4*>(W + (size_t)(k0 + kk) * LP + n)
-                                    : make_float4(0.f, 0.f, 0.f, 0.f);
+            const int kr = min(k0 + kk, kend - 1);          // branch free: clamp, then select
+            const float4 t = *reinterpret_cast<const float4*>(W + (size_t)kr * LP + n);
+            const bool ok = k0 + kk < kend;
+            v[u] = make_float4(ok ? t.x : 0.f, ok ? t.y : 0.f, ok ? t.z : 0.f, ok ? t.w : 0.f);
         }
     }
     __device__ __forceinline__ void store(float* __restrict__ wl) const {   // LDS row stride LP+4
@@ -65,6 +67,7 @@ __global__ __launch_bounds__(256) void resid_mul_n_kernel(
     const float* xp = X + (size_t)(row_ok ? row : 0) * cols;
     const int kb = blockIdx.y * chunk;
     const int ke = min(cols, kb + chunk);
+    const int kpad = (ke + 3) & ~3;     // lam / sc are zero padded to a multiple of 4
     float lam_r = 0.f, s_r = 0.f;
     if (AXIS == 0 && row_ok) {
         lam_r = lam[row];
@@ -82,8 +85,8 @@ __global__ __launch_bounds__(256) void resid_mul_n_kernel(
             const int k = k0 + 16 * j + 4 * g;
             xr[j] = load4f<VEC>(xp, k, ke, row_ok);
             if (AXIS == 1) {   // lam / sc are padded with zeros to a multiple of 4 beyond `cols`
-                lr[j] = (k < ke) ? *reinterpret_cast<const float4*>(lam + k) : make_float4(0.f, 0.f, 0.f, 0.f);
-                sr[j] = (k < ke) ? *reinterpret_cast<const float4*>(sc + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+                lr[j] = load4_padded(lam, k, kpad);
+                sr[j] = load4_padded(sc, k, kpad);
             }
         }
     };
@@ -159,10 +162,11 @@ __global__ __launch_bounds__(256) void codes_mul_n_kernel(const int8_t* __restri
         for (int j = 0; j < KSUB; ++j) {
             const int k = k0 + 16 * j + 4 * g;
             uint32_t p = 0;
-            if (row_ok) {
-                if (VEC) {
-                    if (k < ke) p = *reinterpret_cast<const uint32_t*>(cp + k);
-                } else {
+            if (VEC) {      // branch free: clamp, then select (K % 4 == 0)
+                const uint32_t t = *reinterpret_cast<const uint32_t*>(cp + min(k, ke - 4));
+                p = (row_ok && k < ke) ? t : 0u;
+            } else if (row_ok) {
+                {
 #pragma unroll
                     for (int t = 0; t < 4; ++t)
                         if (k + t < ke) p |= (uint32_t)(uint8_t)cp[k + t] << (8 * t);
@@ -252,13 +256,17 @@ __global__ __launch_bounds__(256) void resid_mul_t_kernel(
         const bool ok = i < ie;
         const size_t ii = ok ? (size_t)i : 0;
         f.x = load4f<VEC>(X + ii * cols, kc, cols, ok);
-        if (AXIS == 0) {
-            f.lr = ok ? lam[ii] : 0.f;
-            f.sr = ok ? sc[ii] : 0.f;
+        if (AXIS == 0) {            // unconditional loads from a valid row, then selects
+            const float l = lam[ii], sv = sc[ii];
+            f.lr = ok ? l : 0.f;
+            f.sr = ok ? sv : 0.f;
         }
         const float* wp = W + ii * LP + NT * c;
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) f.w[nt] = ok ? wp[nt] : 0.f;
+        for (int nt = 0; nt < NT; ++nt) {
+            const float wv = wp[nt];
+            f.w[nt] = ok ? wv : 0.f;
+        }
     };
     Frag cur[TUNR], nxt[TUNR];
     const int istart = ib + wave * 4;

@@ -93,7 +93,7 @@ __global__ __launch_bounds__(256) void quant_cols_kernel(const float* __restrict
     for (int rr = 0; rr < 4; ++rr) {
         const int kl = ty + 16 * rr;
         const int k = k0 + kl;
-        float4 v = load4f<VEC>(X + (size_t)k * cols, n, cols, k < rows);
+        float4 v = load4f<VEC>(X + (size_t)min(k, rows - 1) * cols, n, cols, k < rows);
         tile[tx * 4 + 0][kl] = (int8_t)(int)quant_code(v.x, lam[0], q);
         tile[tx * 4 + 1][kl] = (int8_t)(int)quant_code(v.y, lam[1], q);
         tile[tx * 4 + 2][kl] = (int8_t)(int)quant_code(v.z, lam[2], q);
