@@ -192,7 +192,14 @@ __global__ __launch_bounds__(256) void int8_gemm_kernel(int M, int N, int K,
 #endif
 #define BTM 256
 #define BTN 256
-// FULL: M, N multiples of 256 and K a multiple of 64 -- operand loads carry no guard at all, so
+#ifndef BBK
+#define BBK 64                  // K depth of one staged tile of the large-tile kernel
+#endif
+#define BSTRIDE (BBK + 16)      // padded LDS row stride, conflict-free 16-byte reads
+#define BCHUNKS (BBK / 16)      // 16-byte chunks per staged row
+#define BROWS (512 / BCHUNKS)   // rows covered by one pass of the 512 threads
+#define BLOADS (256 / BROWS)    // staged 16-byte chunks per thread and operand
+// FULL: M, N multiples of 256 and K a multiple of the tile depth -- operand loads carry no guard at all, so
 // nothing consumes a loaded register before it is written to LDS two iterations later.
 template <bool VEC, bool COMP, bool WCINT, bool FULL>
 __global__ __launch_bounds__(512, 1) void int8_gemm256_kernel(int M, int N, int K,
@@ -205,8 +212,8 @@ __global__ __launch_bounds__(512, 1) void int8_gemm256_kernel(int M, int N, int 
                                                               float* __restrict__ C,
                                                               int32_t* __restrict__ Cint, int tiles_n,
                                                               int ntiles) {
-    __shared__ __align__(16) int8_t As[2][BTM * LDS_STRIDE];
-    __shared__ __align__(16) int8_t Bs[2][BTN * LDS_STRIDE];
+    __shared__ __align__(16) int8_t As[2][BTM * BSTRIDE];
+    __shared__ __align__(16) int8_t Bs[2][BTN * BSTRIDE];
     int tile = blockIdx.x;
     if ((ntiles & 7) == 0) tile = (tile & 7) * (ntiles >> 3) + (tile >> 3);
     const int m0 = (tile / tiles_n) * BTM, n0 = (tile % tiles_n) * BTN;
@@ -226,45 +233,47 @@ __global__ __launch_bounds__(512, 1) void int8_gemm256_kernel(int M, int N, int 
     // K-tiles ahead of the matrix cores in a ring of three register sets (a tile's MFMA time,
     // ~1000 cycles, is well below global-load latency, so one tile of lookahead stalls every
     // iteration); LDS holds the current and the next tile.
-    const int srow0 = tid >> 2, skc = (tid & 3) * 16;
+    const int srow0 = tid / BCHUNKS, skc = (tid % BCHUNKS) * 16;
     // The three register sets are individually named scalars (not arrays passed by reference):
     // that keeps them in VGPRs; as arrays they were demoted to scratch memory.
     auto ldA = [&](int u, int k0) -> uint4 {
         if (FULL)   // tiles past the end of K are loaded (clamped) but never stored or used
-            return *reinterpret_cast<const uint4*>(Aq + (size_t)(m0 + srow0 + 128 * u) * K + min(k0, K - BK) + skc);
-        return load16b<VEC>(Aq, m0 + srow0 + 128 * u, M, K, k0 + skc);
+            return *reinterpret_cast<const uint4*>(Aq + (size_t)(m0 + srow0 + BROWS * u) * K + min(k0, K - BBK) + skc);
+        return load16b<VEC>(Aq, m0 + srow0 + BROWS * u, M, K, k0 + skc);
     };
     auto ldB = [&](int u, int k0) -> uint4 {
         if (FULL)
-            return *reinterpret_cast<const uint4*>(BqT + (size_t)(n0 + srow0 + 128 * u) * K + min(k0, K - BK) + skc);
-        return load16b<VEC>(BqT, n0 + srow0 + 128 * u, N, K, k0 + skc);
+            return *reinterpret_cast<const uint4*>(BqT + (size_t)(n0 + srow0 + BROWS * u) * K + min(k0, K - BBK) + skc);
+        return load16b<VEC>(BqT, n0 + srow0 + BROWS * u, N, K, k0 + skc);
     };
     auto stA = [&](int u, int buf, uint4 v) {
-        *reinterpret_cast<uint4*>(&As[buf][(srow0 + 128 * u) * LDS_STRIDE + skc]) = v;
+        *reinterpret_cast<uint4*>(&As[buf][(srow0 + BROWS * u) * BSTRIDE + skc]) = v;
     };
     auto stB = [&](int u, int buf, uint4 v) {
-        *reinterpret_cast<uint4*>(&Bs[buf][(srow0 + 128 * u) * LDS_STRIDE + skc]) = v;
+        *reinterpret_cast<uint4*>(&Bs[buf][(srow0 + BROWS * u) * BSTRIDE + skc]) = v;
     };
-#define LRQ_DECL(S) uint4 S##a0, S##a1, S##b0, S##b1
+#define LRQ_DECL(S) uint4 S##a0, S##a1, S##a2, S##a3, S##b0, S##b1, S##b2, S##b3
 #define LRQ_GLOAD(S, k0)                                                   \
-    S##a0 = ldA(0, k0); S##b0 = ldB(0, k0); S##a1 = ldA(1, k0); S##b1 = ldB(1, k0)
+    S##a0 = ldA(0, k0); S##b0 = ldB(0, k0); S##a1 = ldA(1, k0); S##b1 = ldB(1, k0); \
+    if (BLOADS == 4) { S##a2 = ldA(2, k0); S##b2 = ldB(2, k0); S##a3 = ldA(3, k0); S##b3 = ldB(3, k0); }
 #define LRQ_SSTORE(S, buf)                                                         \
-    stA(0, buf, S##a0); stB(0, buf, S##b0); stA(1, buf, S##a1); stB(1, buf, S##b1)
+    stA(0, buf, S##a0); stB(0, buf, S##b0); stA(1, buf, S##a1); stB(1, buf, S##b1); \
+    if (BLOADS == 4) { stA(2, buf, S##a2); stB(2, buf, S##b2); stA(3, buf, S##a3); stB(3, buf, S##b3); }
     LRQ_DECL(r0);
     LRQ_DECL(r1);
     LRQ_DECL(r2);
     auto compute = [&](int buf) {
 #pragma unroll
-        for (int kk = 0; kk < BK / 32; ++kk) {
+        for (int kk = 0; kk < BBK / 32; ++kk) {
             v4i af[2], bf[4];
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
                 af[mt] = *reinterpret_cast<const v4i*>(
-                    &As[buf][(wm * 64 + mt * 32 + LRQ_ABL_ROW(l32)) * LDS_STRIDE + kk * 32 + LRQ_ABL_ROW(lh) * 16]);
+                    &As[buf][(wm * 64 + mt * 32 + LRQ_ABL_ROW(l32)) * BSTRIDE + kk * 32 + LRQ_ABL_ROW(lh) * 16]);
 #pragma unroll
             for (int nt = 0; nt < 4; ++nt)
                 bf[nt] = *reinterpret_cast<const v4i*>(
-                    &Bs[buf][(wn * 128 + nt * 32 + LRQ_ABL_ROW(l32)) * LDS_STRIDE + kk * 32 + LRQ_ABL_ROW(lh) * 16]);
+                    &Bs[buf][(wn * 128 + nt * 32 + LRQ_ABL_ROW(l32)) * BSTRIDE + kk * 32 + LRQ_ABL_ROW(lh) * 16]);
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
@@ -272,17 +281,17 @@ __global__ __launch_bounds__(512, 1) void int8_gemm256_kernel(int M, int N, int 
                     acc[mt][nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[mt], bf[nt], acc[mt][nt], 0, 0, 0);
         }
     };
-    const int nk = (K + BK - 1) / BK;
+    const int nk = (K + BBK - 1) / BBK;
     LRQ_GLOAD(r0, 0);
-    LRQ_GLOAD(r1, BK);
-    LRQ_GLOAD(r2, 2 * BK);
+    LRQ_GLOAD(r1, BBK);
+    LRQ_GLOAD(r2, 2 * BBK);
     LRQ_SSTORE(r0, 0);
     __syncthreads();
     // iteration i: set i%3 is free -> load tile i+3; compute tile i; publish tile i+1
 #define LRQ_GEMM_STEP(J, SCUR, SNEXT)                  \
     if (kt + J < nk) {                                 \
         const int i = kt + J;                          \
-        LRQ_ABL_GLOAD(LRQ_GLOAD(SCUR, (i + 3) * BK));  \
+        LRQ_ABL_GLOAD(LRQ_GLOAD(SCUR, (i + 3) * BBK));  \
         compute(i & 1);                                \
         if (i + 1 < nk) { LRQ_ABL_SSTORE(LRQ_SSTORE(SNEXT, (i + 1) & 1)); } \
         LRQ_ABL_SYNC(__syncthreads());                 \
@@ -425,7 +434,7 @@ static void dispatch_gemm256(bool comp, bool wcint, dim3 grid, hipStream_t st, i
                              const int8_t* Aq, const int8_t* BqT, const float* sA, const float* sB,
                              const float* Lp, const float* Rp, int R2P, float* C, int32_t* Cint, int tiles_n,
                              int ntiles) {
-    const bool full = VEC && (M % BTM == 0) && (N % BTN == 0) && (K % BK == 0) && K >= BK;
+    const bool full = VEC && (M % BTM == 0) && (N % BTN == 0) && (K % BBK == 0) && K >= BBK;
 #define LRQ_GEMM(COMP, WC)                                                                                   \
     do {                                                                                                     \
         if (full)                                                                                            \
