@@ -60,6 +60,7 @@ __global__ __launch_bounds__(256) void resid_mul_n_kernel(
     float* __restrict__ partial) {
     constexpr int LP = NT * 16;
     __shared__ __align__(16) float wl[2][KCHUNK * (LP + 4)];
+    __shared__ __align__(16) float sl[2][2 * KCHUNK];   // per-column lambda | step of the chunk (AXIS 1)
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r = lane & 15, g = lane >> 4;
     const int row = blockIdx.x * 64 + wave * 16 + r;
@@ -67,7 +68,6 @@ __global__ __launch_bounds__(256) void resid_mul_n_kernel(
     const float* xp = X + (size_t)(row_ok ? row : 0) * cols;
     const int kb = blockIdx.y * chunk;
     const int ke = min(cols, kb + chunk);
-    const int kpad = (ke + 3) & ~3;     // lam / sc are zero padded to a multiple of 4
     float lam_r = 0.f, s_r = 0.f;
     if (AXIS == 0 && row_ok) {
         lam_r = lam[row];
@@ -77,17 +77,17 @@ __global__ __launch_bounds__(256) void resid_mul_n_kernel(
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) acc[nt] = (v4f){0.f, 0.f, 0.f, 0.f};
 
-    float4 xr[KSUB], lr[KSUB], sr[KSUB];
+    float4 xr[KSUB];
+    float scale_reg = 0.f;     // this thread's element of the chunk's lambda (t < 128) or step vector
     WStage<NT> ws;
     auto load_x = [&](int k0) {
 #pragma unroll
-        for (int j = 0; j < KSUB; ++j) {
-            const int k = k0 + 16 * j + 4 * g;
-            xr[j] = load4f<VEC>(xp, k, ke, row_ok);
-            if (AXIS == 1) {   // lam / sc are padded with zeros to a multiple of 4 beyond `cols`
-                lr[j] = load4_padded(lam, k, kpad);
-                sr[j] = load4_padded(sc, k, kpad);
-            }
+        for (int j = 0; j < KSUB; ++j) xr[j] = load4f<VEC>(xp, k0 + 16 * j + 4 * g, ke, row_ok);
+        if (AXIS == 1) {
+            const int t = threadIdx.x & (KCHUNK - 1);
+            const int kc = min(k0 + t, ke - 1);
+            const float v = (threadIdx.x < KCHUNK) ? lam[kc] : sc[kc];
+            scale_reg = (k0 + t < ke) ? v : 0.f;
         }
     };
     if (kb < ke) {
@@ -97,6 +97,8 @@ __global__ __launch_bounds__(256) void resid_mul_n_kernel(
     int buf = 0;
     for (int k0 = kb; k0 < ke; k0 += KCHUNK, buf ^= 1) {
         ws.store(wl[buf]);
+        if (AXIS == 1) sl[buf][threadIdx.x] = scale_reg;
+        __syncthreads();             // wl[buf], sl[buf] complete; the other buffers no longer read
         float res[KSUB][4];
 #pragma unroll
         for (int j = 0; j < KSUB; ++j) {
@@ -105,8 +107,8 @@ __global__ __launch_bounds__(256) void resid_mul_n_kernel(
                 l4 = make_float4(lam_r, lam_r, lam_r, lam_r);
                 s4 = make_float4(s_r, s_r, s_r, s_r);
             } else {
-                l4 = lr[j];
-                s4 = sr[j];
+                l4 = *reinterpret_cast<const float4*>(&sl[buf][16 * j + 4 * g]);
+                s4 = *reinterpret_cast<const float4*>(&sl[buf][KCHUNK + 16 * j + 4 * g]);
             }
             res[j][0] = quant_residual(xr[j].x, l4.x, s4.x, q);
             res[j][1] = quant_residual(xr[j].y, l4.y, s4.y, q);
@@ -117,7 +119,6 @@ __global__ __launch_bounds__(256) void resid_mul_n_kernel(
             load_x(k0 + KCHUNK);
             ws.load(W, k0 + KCHUNK, ke);
         }
-        __syncthreads();             // wl[buf] complete; wl[buf^1] no longer read by anyone
         const float* wb = wl[buf];
 #pragma unroll
         for (int j = 0; j < KSUB; ++j) {
