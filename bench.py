@@ -79,6 +79,8 @@ def main():
     ap.add_argument("--workload", default="c3_4096_int4_r32_outliers")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=48)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 64 MiB device copy (reference for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU (one MI355X); run with --gpus 1")
@@ -96,6 +98,12 @@ def main():
     dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
     C = torch.empty((w.M, w.N), dtype=torch.float32, device="cuda")
     ws = L.Workspace.for_problem(w.M, w.N, w.K, w.rank, w.oversample)
+
+    if args.calibrate_copy:
+        src = torch.zeros(16 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)              # 64 MiB read + 64 MiB written by one copy kernel
+        torch.cuda.synchronize()
 
     def step(rank=w.rank):
         L.lrqmm_matmul(dA, dB, w.bits, rank, w.oversample, w.power_iters, seed=w.sketch_seed, workspace=ws, C=C)
@@ -170,7 +178,7 @@ def main():
         "config": {"workload": w.name, "M": w.M, "N": w.N, "K": w.K, "bits": w.bits, "rank": w.rank,
                    "oversample": w.oversample, "power_iters": w.power_iters, "sketch_seed": w.sketch_seed,
                    "inputs": "N(0,1) with 0.1% entries from N(0,20^2), seeds 0/1"},
-        "roofline": {"kernel": "int8_gemm_kernel (int8 MFMA GEMM + fused dequant and rank-2r epilogue)",
+        "roofline": {"kernel": "int8_gemm256_kernel (int8 MFMA GEMM + fused dequant and rank-2r epilogue)",
                      "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                      "frac": round(achieved / PEAK_INT8_TOPS, 4),
                      "traffic": read_traffic("int8_gemm_c3_pmc.txt"),

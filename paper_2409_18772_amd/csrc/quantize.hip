@@ -40,6 +40,57 @@ __global__ __launch_bounds__(256) void quant_rows_kernel(const float* __restrict
     }
 }
 
+// Single-read variant: the row is kept in registers between the absmax reduction and the
+// code computation (NV float4 per thread, NV <= 16), so A is fetched from HBM once.  TPR threads
+// cooperate on a row: 64 (one wavefront, cols <= 4096) or 256 (a workgroup, cols <= 16384).
+template <bool VEC, int TPR, int NV>
+__global__ __launch_bounds__(256) void quant_rows_cached_kernel(const float* __restrict__ X, int rows,
+                                                                int cols, QuantParams q,
+                                                                int8_t* __restrict__ codes,
+                                                                float* __restrict__ amax) {
+    __shared__ float wmax[4];
+    const int t = threadIdx.x % TPR;
+    const int row = blockIdx.x * (256 / TPR) + threadIdx.x / TPR;
+    const bool row_ok = row < rows;
+    const float* xp = X + (size_t)(row_ok ? row : 0) * cols;
+    float4 v[NV];
+    float m = 0.0f;
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+        const int k = (t + TPR * u) * 4;
+        v[u] = load4f<VEC>(xp, k, cols, row_ok);
+        m = fmaxf(fmaxf(m, fabsf(v[u].x)), fmaxf(fabsf(v[u].y), fmaxf(fabsf(v[u].z), fabsf(v[u].w))));
+    }
+    m = wave_max(m);
+    if (TPR == 256) {
+        if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = m;
+        __syncthreads();
+        m = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+    }
+    if (!row_ok) return;
+    float lam, s;
+    make_scales(m, q.qmaxf, lam, s);
+    if (t == 0) amax[row] = m;
+    int8_t* cp = codes + (size_t)row * cols;
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+        const int k = (t + TPR * u) * 4;
+        if (k >= cols) continue;
+        const int c0 = (int)quant_code(v[u].x, lam, q), c1 = (int)quant_code(v[u].y, lam, q);
+        const int c2 = (int)quant_code(v[u].z, lam, q), c3 = (int)quant_code(v[u].w, lam, q);
+        if (VEC) {
+            const uint32_t p = (uint32_t)(c0 & 0xff) | ((uint32_t)(c1 & 0xff) << 8) |
+                               ((uint32_t)(c2 & 0xff) << 16) | ((uint32_t)(c3 & 0xff) << 24);
+            *reinterpret_cast<uint32_t*>(cp + k) = p;
+        } else {
+            if (k + 0 < cols) cp[k + 0] = (int8_t)c0;
+            if (k + 1 < cols) cp[k + 1] = (int8_t)c1;
+            if (k + 2 < cols) cp[k + 2] = (int8_t)c2;
+            if (k + 3 < cols) cp[k + 3] = (int8_t)c3;
+        }
+    }
+}
+
 __global__ void fill_u32_kernel(uint32_t* p, int n, uint32_t v) {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = v;
@@ -129,11 +180,24 @@ static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 int launch_quantize_rows(const float* X, int rows, int cols, QuantParams q, int8_t* codes,
                          float* amax, hipStream_t st) {
     const bool vec = (cols % 4 == 0) && aligned16(X) && (((uintptr_t)codes & 3) == 0);
-    dim3 grid(ceil_div(rows, 4));
-    if (vec)
-        hipLaunchKernelGGL(quant_rows_kernel<true>, grid, dim3(256), 0, st, X, rows, cols, q, codes, amax);
-    else
-        hipLaunchKernelGGL(quant_rows_kernel<false>, grid, dim3(256), 0, st, X, rows, cols, q, codes, amax);
+    if (cols <= 256 * 4 * 16) {
+        // Row cached in registers: one wavefront per row up to 4096 columns, else one workgroup.
+        const bool wave = cols <= 64 * 4 * 16;
+        const int per = wave ? 256 : 1024;
+        const int need = ceil_div(cols, per);
+        dim3 grid(wave ? ceil_div(rows, 4) : rows);
+#define LRQ_QR(V, T, N) hipLaunchKernelGGL((quant_rows_cached_kernel<V, T, N>), grid, dim3(256), 0, st, X, rows, cols, q, codes, amax)
+#define LRQ_QR_NV(V, T) do { if (need <= 1) LRQ_QR(V, T, 1); else if (need <= 2) LRQ_QR(V, T, 2); \
+        else if (need <= 4) LRQ_QR(V, T, 4); else if (need <= 8) LRQ_QR(V, T, 8); else LRQ_QR(V, T, 16); } while (0)
+        if (wave) { if (vec) LRQ_QR_NV(true, 64); else LRQ_QR_NV(false, 64); }
+        else      { if (vec) LRQ_QR_NV(true, 256); else LRQ_QR_NV(false, 256); }
+#undef LRQ_QR_NV
+#undef LRQ_QR
+    } else {                              // very long rows: two passes over the row
+        dim3 grid(ceil_div(rows, 4));
+        if (vec) hipLaunchKernelGGL(quant_rows_kernel<true>, grid, dim3(256), 0, st, X, rows, cols, q, codes, amax);
+        else     hipLaunchKernelGGL(quant_rows_kernel<false>, grid, dim3(256), 0, st, X, rows, cols, q, codes, amax);
+    }
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }
