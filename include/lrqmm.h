@@ -59,7 +59,7 @@ LRQMM_API size_t lrqmm_workspace_bytes(int M, int N, int K, int rank, int oversa
 
 /*
  * Symmetric data-free quantization (Background 2.2, Eq. (quantA); floor variant
- * Methodology Eq. (get_ra2); Algorithm 2 line 1).
+ * Methodology Eq. (get_ra2); Algorithm 2, quantization step).
  *   X      rows x cols float32, row-major (device, read only)
  *   axis   LRQMM_AXIS_ROW: one scale per row,  amax[rows],
  *                          codes rows x cols row-major;
@@ -84,7 +84,7 @@ LRQMM_API int lrqmm_fill_sketch(uint64_t seed, int stream_id, int rows, int cols
 
 /*
  * Rank-`rank` randomized SVD of the quantization residual
- *     R = X - Dequant(Quant(X))          (Algorithm 2 lines 4-7; Algorithm 1)
+ *     R = X - Dequant(Quant(X))          (Algorithm 2, residual and RSVD steps; Algorithm 1)
  * R is never stored: it is regenerated from X and amax inside every pass.
  *   X, amax, rows, cols, axis, bits, round_mode   as for lrqmm_quantize
  *   rank r >= 1, oversample p >= 0, l = r + p <= min(rows, cols, LRQMM_MAX_SKETCH)
@@ -102,7 +102,7 @@ LRQMM_API int lrqmm_rsvd(const float* X, const float* amax, int rows, int cols, 
 
 /*
  * Quantized GEMM with fused dequantization and rank-2r compensation
- * (Eq. (INTGEMM), Eq. (QUANTGEMM); Algorithm 2 lines 2-3 and 8-12):
+ * (Eq. (INTGEMM), Eq. (QUANTGEMM); Algorithm 2, integer product, dequantization and compensation steps):
  *   C[i,j] = sA[i] sB[j] sum_k Aq[i,k] BqT[j,k]
  *            + (U Sig)(Vt B~) + (A~ W)(Gam Zt) + (U Sig)(Vt W)(Gam Zt)
  * with A~ = diag(sA) Aq, B~ = Bq diag(sB).
@@ -123,7 +123,7 @@ LRQMM_API int lrqmm_gemm(int M, int N, int K, int bits, int rank,
                void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * The whole hot path, Algorithm 2 lines 1-12, from float32 A (M x K) and
+ * The whole hot path, all of Algorithm 2 except its final alpha/beta update, from float32 A (M x K) and
  * B (K x N) to float32 C (M x N): quantize both operands, factor both residuals
  * (sketch seeds (seed, 0) and (seed, 1)), integer GEMM, fused compensation.
  * rank == 0 runs the direct-quantization pipeline only.

@@ -111,7 +111,7 @@ def quantize(X: np.ndarray, amax: np.ndarray, axis: int, bits: int,
 
 
 # --------------------------------------------------------------------------
-# Integer GEMM and dequantization (Eq. (INTGEMM), Eq. (QUANTGEMM); Alg. 2 lines 2-3)
+# Integer GEMM and dequantization (Eq. (INTGEMM), Eq. (QUANTGEMM); Alg. 2, integer product and dequantization steps)
 # --------------------------------------------------------------------------
 def int_gemm(Aq: np.ndarray, Bq: np.ndarray) -> np.ndarray:
     """C_int = A_int . B_int accumulated in int64; must fit int32."""
@@ -129,12 +129,12 @@ def dequant(Cint: np.ndarray, sA: np.ndarray, sB: np.ndarray) -> np.ndarray:
 
 
 def dequant_matrix(codes: np.ndarray, s: np.ndarray, axis: int) -> np.ndarray:
-    """A_F = Dequant(A_int) (Alg. 2 line 4), float64."""
+    """A_F = Dequant(A_int) (Alg. 2, operand dequantization step), float64."""
     return codes.astype(np.float64) * _broadcast(np.asarray(s, np.float64), axis, codes.shape)
 
 
 def residual(X: np.ndarray, codes: np.ndarray, s: np.ndarray, axis: int) -> np.ndarray:
-    """R = X - Dequant(Quant(X)) (Eq. (AFP); Alg. 2 line 5), float64, exact."""
+    """R = X - Dequant(Quant(X)) (Eq. (AFP); Alg. 2, residual step), float64, exact."""
     return np.asarray(X, dtype=np.float64) - dequant_matrix(codes, s, axis)
 
 
@@ -299,7 +299,7 @@ def lrqmm(A: np.ndarray, B: np.ndarray, bits: int, rank: int, oversample: int = 
           per_tensor: bool = False, omega_a: np.ndarray | None = None,
           omega_b: np.ndarray | None = None, want_cint: bool = True,
           row_sample: np.ndarray | None = None) -> dict:
-    """Algorithm 2, lines 1-12 (the alpha/beta update of its last line excluded).
+    """Algorithm 2 step by step (its final alpha/beta update excluded).
 
     rank == 0 gives the direct-quantization product only (first term of
     Eq. (gemm_r_split)).  Returns every intermediate by name.
@@ -317,7 +317,7 @@ def lrqmm(A: np.ndarray, B: np.ndarray, bits: int, rank: int, oversample: int = 
         raise ValueError("shape")
     ax_a, ax_b = (TENSOR, TENSOR) if per_tensor else (ROWWISE, COLWISE)
     out = {}
-    # line 1: quantize
+    # quantize both operands
     amax_a, amax_b = absmax(A, ax_a), absmax(B, ax_b)
     _, sa = scales(amax_a, bits)
     _, sb = scales(amax_b, bits)
@@ -326,7 +326,7 @@ def lrqmm(A: np.ndarray, B: np.ndarray, bits: int, rank: int, oversample: int = 
     sa_rows = np.broadcast_to(sa, (M,)) if per_tensor else sa
     sb_cols = np.broadcast_to(sb, (N,)) if per_tensor else sb
     out.update(amax_a=amax_a, amax_b=amax_b, sa=sa, sb=sb, Aq=Aq, Bq=Bq)
-    # lines 2-3: integer product and dequantization
+    # integer product and its dequantization
     sel = slice(None) if row_sample is None else np.asarray(row_sample, dtype=np.int64)
     Cint = int_gemm(Aq[sel], Bq)
     C0 = dequant(Cint, np.asarray(sa_rows)[sel], sb_cols)
@@ -336,12 +336,12 @@ def lrqmm(A: np.ndarray, B: np.ndarray, bits: int, rank: int, oversample: int = 
     if rank == 0:
         out["C"] = C0
         return out
-    # lines 4-5: dequantized operands and residuals
+    # dequantized operands and residuals
     Af = dequant_matrix(Aq, sa, ax_a)
     Bf = dequant_matrix(Bq, sb, ax_b)
     Ra = A.astype(np.float64) - Af
     Rb = B.astype(np.float64) - Bf
-    # lines 6-7: rank-r factorizations of the residuals
+    # rank-r factorizations of the residuals (RSVD)
     ell = rank + oversample
     if omega_a is None:
         omega_a = gaussian_sketch(seed, STREAM_A, K, ell)
@@ -349,14 +349,14 @@ def lrqmm(A: np.ndarray, B: np.ndarray, bits: int, rank: int, oversample: int = 
         omega_b = gaussian_sketch(seed, STREAM_B, N, ell)
     U, Sig, Vt = rsvd(Ra, rank, omega_a, power_iters)
     W, Gam, Zt = rsvd(Rb, rank, omega_b, power_iters)
-    # line 8: fold the singular values
+    # fold the singular values into the left factors
     Ut = U * Sig.reshape(1, -1)
     Ztp = Gam.reshape(-1, 1) * Zt
-    # lines 9-11: the three compensation terms
+    # the three compensation terms
     RC1 = Ut[sel] @ (Vt @ Bf)
     RC2 = (Af[sel] @ W) @ Ztp
     RC3 = (Ut[sel] @ (Vt @ W)) @ Ztp
-    # line 12
+    # sum of the dequantized product and the compensation terms
     C = C0 + RC1 + RC2 + RC3
     out.update(Ra=Ra, Rb=Rb, omega_a=omega_a, omega_b=omega_b, U=U, Sig=Sig, Vt=Vt,
                W=W, Gam=Gam, Zt=Zt, Af=Af, Bf=Bf, C=C)
@@ -364,7 +364,7 @@ def lrqmm(A: np.ndarray, B: np.ndarray, bits: int, rank: int, oversample: int = 
 
 
 def compensate(Aq, sa, Bq, sb, U, Sig, Vt, W, Gam, Zt) -> np.ndarray:
-    """Alg. 2 lines 2-3 and 8-12 from given codes, steps and factors (row/column scales)."""
+    """Alg. 2 integer product, dequantization and compensation steps from given codes, steps and factors (row/column scales)."""
     Af = dequant_matrix(Aq, sa, ROWWISE)
     Bf = dequant_matrix(Bq, sb, COLWISE)
     C0 = dequant(int_gemm(Aq, Bq), sa, sb)

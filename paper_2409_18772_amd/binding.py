@@ -194,7 +194,7 @@ def lrqmm_gemm(Aq, amaxA, BqT, amaxB, bits: int, factors_a=None, factors_b=None,
 
 def lrqmm_matmul(A, B, bits: int, rank: int, oversample: int = 0, power_iters: int = 0, seed: int = 0,
                  round_mode: int = ROUND_FLOOR, workspace: Workspace | None = None, C=None):
-    """The whole hot path: C ~ A . B (Algorithm 2 lines 1-12)."""
+    """The whole hot path: C ~ A . B (all of Algorithm 2 except its final alpha/beta update)."""
     import torch
     _dev(A, torch.float32, "A")
     _dev(B, torch.float32, "B")

@@ -23,7 +23,7 @@ inline int pad_to(int x, int m) { return (x + m - 1) / m * m; }
 
 struct RsvdWs {
     float *lam, *s, *Wc, *Yr, *partial;
-    double *gpart, *T, *Ur, *Mv;
+    double *gpart, *gram, *T, *Ur, *Mv;
 };
 
 size_t carve_rsvd(Arena& a, int rows, int cols, int axis, int LP, int rank, RsvdWs* w) {
@@ -41,6 +41,7 @@ size_t carve_rsvd(Arena& a, int rows, int cols, int axis, int LP, int rank, Rsvd
     t.Yr = a.take<float>((size_t)rows * LP);
     t.partial = a.take<float>(part);
     t.gpart = a.take<double>((size_t)nb * LP * LP);
+    t.gram = a.take<double>((size_t)LP * LP);
     t.T = a.take<double>((size_t)LP * LP);
     t.Ur = a.take<double>((size_t)LP * rank);
     t.Mv = a.take<double>((size_t)LP * rank);
@@ -243,7 +244,9 @@ int lrqmm_rsvd(const float* X, const float* amax, int rows, int cols, int axis, 
     auto orth = [&](int splits, int n, float* buf) -> int {
         int r2 = launch_reduce_gram(w.partial, splits, n, LP, nullptr, buf, w.gpart, st);
         if (r2 != LRQMM_OK) return r2;
-        r2 = launch_chol_inverse(w.gpart, gram_blocks(n), ell, LP, w.T, st);
+        r2 = launch_gram_sum(w.gpart, gram_blocks(n), LP, w.gram, st);
+        if (r2 != LRQMM_OK) return r2;
+        r2 = launch_chol_inverse(w.gram, ell, LP, w.T, st);
         if (r2 != LRQMM_OK) return r2;
         return launch_apply(buf, n, LP, w.T, LP, LP, buf, LP, 0, st);
     };
@@ -260,7 +263,8 @@ int lrqmm_rsvd(const float* X, const float* amax, int rows, int cols, int axis, 
     // B^T = R^T Q (cols x l), its Gram B B^T, small SVD, U = Q U', V = B^T U' / sigma
     LRQ_TRY(launch_resid_mul_t(X, rows, cols, axis, w.lam, w.s, q, w.Yr, LP, pt, w.partial, st));
     LRQ_TRY(launch_reduce_gram(w.partial, pt.splits, cols, LP, nullptr, w.Wc, w.gpart, st));
-    LRQ_TRY(launch_small_svd(w.gpart, gram_blocks(cols), ell, LP, rank, Sigma, w.Ur, w.Mv, st));
+    LRQ_TRY(launch_gram_sum(w.gpart, gram_blocks(cols), LP, w.gram, st));
+    LRQ_TRY(launch_small_svd(w.gram, ell, LP, rank, Sigma, w.Ur, w.Mv, st));
     LRQ_TRY(launch_apply(w.Yr, rows, LP, w.Ur, rank, rank, U, rank, 0, st));
     LRQ_TRY(launch_apply(w.Wc, cols, LP, w.Mv, rank, rank, Vt, cols, 1, st));
     return LRQMM_OK;

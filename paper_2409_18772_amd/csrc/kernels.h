@@ -47,15 +47,18 @@ int gram_blocks(int n);
 // gpart[b][LP*LP] = Gram of rows 64b..64b+63 of Y in float64.
 int launch_reduce_gram(const float* partial, int splits, int n, int LP, const float* rowscale,
                        float* Y, double* gpart, hipStream_t st);
-// T (LP x LP float64, upper triangular) with (Y T)^T (Y T) = I on the live columns.
-int launch_chol_inverse(const double* gpart, int nb, int ell, int LP, double* T, hipStream_t st);
+// gram (LP x LP float64) = sum over b < nb of gpart[b], in fixed order.
+int launch_gram_sum(const double* gpart, int nb, int LP, double* gram, hipStream_t st);
+// T (LP x LP float64, upper triangular) with (Y T)^T (Y T) = I on the live columns, from
+// the Gram matrix of Y.
+int launch_chol_inverse(const double* gram, int ell, int LP, double* T, hipStream_t st);
 // out = In[n x LP] . Mat[LP x cm]; normal: out[i*ldo + c]; transposed: out[c*ldo + i].
 int launch_apply(const float* In, int n, int LP, const double* Mat, int cm, int ldm, float* out,
                  int ldo, int transposed, hipStream_t st);
-// Eigen-decomposition of sum_b gpart[b] (l x l): Sigma[r] = sqrt of the r largest
-// eigenvalues, Ur (LP x r) their eigenvectors, Mv = Ur diag(1/Sigma).
-int launch_small_svd(const double* gpart, int nb, int ell, int LP, int rank, float* Sigma,
-                     double* Ur, double* Mv, hipStream_t st);
+// Eigen-decomposition of the Gram matrix (l x l, leading dimension LP): Sigma[r] = sqrt of
+// the r largest eigenvalues, Ur (LP x r) their eigenvectors, Mv = Ur diag(1/Sigma).
+int launch_small_svd(const double* gram, int ell, int LP, int rank, float* Sigma, double* Ur,
+                     double* Mv, hipStream_t st);
 
 // ---- gemm.hip -----------------------------------------------------------
 // X[t][u] = sum_k Vt[t][k] W[k][u]   (r x r)

@@ -1,5 +1,5 @@
 // Orthonormalization and the small SVD of the randomized range finder (paper:
-// Background 2.1 stage 1 "Q with orthogonal columns", Algorithm 1 lines 2-3,
+// Background 2.1 stage 1 "Q with orthogonal columns", Algorithm 1 (range basis and small SVD),
 // truncation Eq. (k-svd)).
 //
 // The tall factors are l <= 80 columns wide, so all O(l^3) work happens on an
@@ -100,123 +100,143 @@ __global__ __launch_bounds__(256) void reduce_gram_kernel(const float* __restric
     }
 }
 
-// Sum the Gram partials (fixed order) into LDS, G[a][b] for a, b < ell.  The partials were
-// written by other workgroups (other XCDs), so every load is a long-latency miss: a thread
-// issues all (up to GRAM_MAX_BLOCKS) loads of an entry before summing them.
-__device__ static void load_gram(const double* __restrict__ gpart, int nb, int ell, int LP,
-                                 double* __restrict__ G, int ldg) {
-    const size_t st = (size_t)LP * LP;
-    const int total = ell * ell;
-    for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
-        const int a = idx / ell, b = idx % ell;
-        const double* src = gpart + a * LP + b;
-        double v[GRAM_MAX_BLOCKS];
+// Gram matrix = the nb <= GRAM_MAX_BLOCKS block partials summed in fixed order, one thread per
+// entry.  The partials were written by other workgroups (other XCDs), so every load is a
+// long-latency miss: a thread issues all its loads before the first add, without branches (a
+// clamped index re-reads the last partial, whose value is then masked), and the entries are
+// spread over many small workgroups because one compute unit alone is load-bandwidth bound.
+__global__ __launch_bounds__(64) void gram_sum_kernel(const double* __restrict__ gpart, int nb, int entries,
+                                                      double* __restrict__ gram) {
+    const int idx = blockIdx.x * 64 + threadIdx.x;
+    if (idx >= entries) return;
+    const double* src = gpart + idx;
+    double v[GRAM_MAX_BLOCKS];
 #pragma unroll
-        for (int blk = 0; blk < GRAM_MAX_BLOCKS; ++blk) v[blk] = (blk < nb) ? src[blk * st] : 0.0;
-        double acc = 0.0;
+    for (int blk = 0; blk < GRAM_MAX_BLOCKS; ++blk) v[blk] = src[(size_t)min(blk, nb - 1) * entries];
+    double acc = 0.0;
 #pragma unroll
-        for (int blk = 0; blk < GRAM_MAX_BLOCKS; ++blk) acc += v[blk];
-        G[a * ldg + b] = acc;
-    }
+    for (int blk = 0; blk < GRAM_MAX_BLOCKS; ++blk) acc += (blk < nb) ? v[blk] : 0.0;
+    gram[idx] = acc;
 }
 
-// Order LDS traffic inside one wavefront: all earlier LDS reads/writes of every lane of
-// this wave are complete and the compiler moves no memory access across.
-__device__ __forceinline__ void wave_lds_fence() { __asm__ volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
-
-// sum_{k in [lo, hi)} row[k] * other[k] over two LDS rows.  The trip count depends on hi
-// only (uniform across the wave); lo is applied as a per-lane mask, so lanes with different
-// ranges never diverge.  Eight loads of each row are in flight per batch.
-__device__ __forceinline__ double lds_dot(const double* __restrict__ row, const double* __restrict__ other,
-                                          int lo, int hi) {
-    double s = 0.0;
-    for (int k = 0; k < hi; k += 8) {
-        double a[8], b[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {      // rows are MAXL+1 long: k+u stays inside the row
-            a[u] = row[k + u];
-            b[u] = other[k + u];
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const bool in = (k + u >= lo) && (k + u < hi);
-            s = fma(in ? a[u] : 0.0, b[u], s);
-        }
-    }
-    return s;
-}
-
-// Cholesky G = L L^T and T = L^-T (upper triangular, Q = Y T) in one left-looking sweep on
-// a single wavefront.  Lane t owns row t of the LDS matrix: its lower part becomes row t
-// of L, its upper part column t of X = L^-1 (G[t][k] = X[k][t], k > t).  At column j every
-// lane forms one dot product with the shared row j of L:
-//   t >= j:  L[t][j] = (G[t][j] - sum_{k<j} L[t][k] L[j][k]) / L[j][j]
-//   t <  j:  X[j][t] = -(sum_{t<=k<j} L[j][k] X[k][t]) / L[j][j]
-// so the inverse comes out of the same loop with no workgroup barrier inside it.
+// Cholesky-QR factor T = L^-T (upper triangular, Q = Y T) of the Gram matrix G = L L^T, by
+// symmetric elimination of the augmented matrix [G | I]: step j subtracts
+// (M[i][j] / d_j) * (row j) from every row i > j, d_j the pivot M[j][j].  The left half is then
+// L^T with rows unscaled (row j times sqrt(d_j)), the right half is L^-1 with row j unscaled
+// the same way, so T[a][b] = M[b][LP + a] / sqrt(d_b).
+//
+// The matrix lives in registers as KR x KC tiles with strided ownership: worker (ti, tg)
+// owns rows ti + NTI*ir (ir < KR) and columns tg + NTI*kc (kc < KC = 2 KR; NTI = LP / KR
+// workers each way), so pivot j = tj + NTI*jr sits in register row jr and register column
+// jr: compile-time constants inside the unrolled jr loop.  A thread reads KR + KC + 2 LDS
+// words per step for KR*KC updates, and at most four wavefronts (one per SIMD) do the work
+// for l <= 64.  A step publishes the pivot row and pivot column in LDS (two generations, so
+// one workgroup barrier per step is enough).  The serial chain per step is LDS write ->
+// barrier -> LDS read -> reciprocal -> FMA; the square roots are taken once at the end.
+// A pivot below 1e-10 of its original diagonal (rank-deficient sketch) is dead: it
+// eliminates nothing and its row and column of T are zero.  All 1024 threads stage the Gram
+// matrix in LDS; the waves that own no tile then leave.
+template <int NT>
+struct CholShape {
+    static constexpr int LP = 16 * NT;
+    static constexpr int KR = 4, KC = 8;            // register tile per worker
+    static constexpr int NTI = LP / KR;             // workers per row and per column
+    static constexpr int WORKERS = NTI * NTI;
+};
 #define CHOL_THREADS 1024
-__global__ __launch_bounds__(CHOL_THREADS) void chol_inverse_kernel(const double* __restrict__ gpart, int nb,
-                                                           int ell, int LP, double* __restrict__ T) {
-    __shared__ double G[MAXL * (MAXL + 1)];
-    __shared__ double dinv[MAXL];
-    __shared__ int dead[MAXL];
-    const int ldg = MAXL + 1;
+
+template <int NT>
+__global__ __launch_bounds__(CHOL_THREADS) void chol_inverse_kernel(const double* __restrict__ gram, int ell,
+                                                                    double* __restrict__ T) {
+    using S = CholShape<NT>;
+    constexpr int LP = S::LP, KR = S::KR, KC = S::KC, NTI = S::NTI;
+    __shared__ double Gs[LP * (LP + 1)];
+    __shared__ double rowb[2][2 * LP];
+    __shared__ double colb[2][LP];
+    __shared__ __align__(16) double2 pivb[2];
     const int tid = threadIdx.x;
-    load_gram(gpart, nb, ell, LP, G, ldg);
-    __syncthreads();
-    if (tid < 64) {
-        double dorig[2];
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int t = tid + 64 * h;
-            dorig[h] = (t < ell) ? G[t * ldg + t] : 0.0;
-        }
-        for (int j = 0; j < ell; ++j) {
-            const double* rowj = G + j * ldg;
-            double val[2];
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int t = tid + 64 * h;
-                val[h] = 0.0;
-                if (h == 1 && ell <= 64) continue;          // uniform: second row set unused
-                const int tt = min(t, ell - 1);             // lanes beyond ell shadow the last row
-                const bool lower = tt >= j;
-                const double dot = lds_dot(G + tt * ldg, rowj, lower ? 0 : tt + 1, j);
-                // t < j: the k = t term uses X[t][t] = 1 / L[t][t]
-                const double head = lower ? G[tt * ldg + j] : rowj[tt] * dinv[tt];
-                val[h] = lower ? head - dot : -(head + dot);
-            }
-            const double dj = __shfl(val[j >> 6], j & 63, 64);
-            const double d0 = __shfl(dorig[j >> 6], j & 63, 64);
-            const bool live = dj > 1e-10 * d0 && dj > 0.0;
-            double inv = 0.0;
-            if (live) {   // 1/sqrt by the hardware estimate and three Newton steps
-                inv = __builtin_amdgcn_rsq(dj);
-                inv = inv * fma(-0.5 * dj, inv * inv, 1.5);
-                inv = inv * fma(-0.5 * dj, inv * inv, 1.5);
-                inv = inv * fma(-0.5 * dj, inv * inv, 1.5);
-            }
-            if (tid == 0) {
-                dead[j] = live ? 0 : 1;
-                dinv[j] = live ? inv : 1.0;
-            }
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int t = tid + 64 * h;
-                if (t >= ell) continue;
-                G[t * ldg + j] = (t == j) ? (live ? dj * inv : 1.0) : val[h] * inv;
-            }
-            wave_lds_fence();
-        }
+    for (int idx = tid; idx < LP * LP; idx += CHOL_THREADS) {
+        const int a = idx / LP, b = idx - a * LP;
+        Gs[a * (LP + 1) + b] = (a < ell && b < ell) ? gram[idx] : 0.0;
     }
     __syncthreads();
-    for (int idx = tid; idx < LP * LP; idx += CHOL_THREADS) {
-        const int a = idx / LP, b = idx % LP;
-        double v = 0.0;
-        if (a < ell && b < ell && !dead[b] && !dead[a]) {
-            if (a == b) v = dinv[a];
-            else if (b > a) v = G[a * ldg + b];
+    if (tid >= (S::WORKERS + 63) / 64 * 64) return;      // whole waves without a tile
+    const bool worker = tid < S::WORKERS;
+    const int ti = worker ? tid / NTI : 0, tg = worker ? tid - ti * NTI : 0;
+    double mreg[KR][KC];
+    double thr[KR];             // 1e-10 * original diagonal of the thread's rows
+#pragma unroll
+    for (int ir = 0; ir < KR; ++ir) {
+        const int i = ti + NTI * ir;
+        thr[ir] = 1e-10 * Gs[i * (LP + 1) + i];
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) {
+            const int c = tg + NTI * kc;
+            mreg[ir][kc] = (c < LP) ? Gs[i * (LP + 1) + c] : ((c - LP == i && i < ell) ? 1.0 : 0.0);
         }
-        T[idx] = v;
+    }
+    double pivot[KR];           // pivots of the thread's rows, 0 when dead
+#pragma unroll
+    for (int ir = 0; ir < KR; ++ir) pivot[ir] = 0.0;
+    int par = 0;
+#pragma unroll
+    for (int jr = 0; jr < KR; ++jr) {
+        for (int tj = 0; tj < NTI; ++tj) {
+            const int j = tj + NTI * jr;
+            if (j >= ell) break;
+            if (worker) {
+                if (tg == tj) {
+#pragma unroll
+                    for (int ir = 0; ir < KR; ++ir) colb[par][ti + NTI * ir] = mreg[ir][jr];
+                }
+                if (ti == tj) {
+#pragma unroll
+                    for (int kc = 0; kc < KC; ++kc) rowb[par][tg + NTI * kc] = mreg[jr][kc];
+                    if (tg == tj) pivb[par] = make_double2(mreg[jr][jr], thr[jr]);
+                }
+            }
+            __syncthreads();
+            const double2 pv = pivb[par];
+            double l[KR], r[KC];
+#pragma unroll
+            for (int ir = 0; ir < KR; ++ir) l[ir] = colb[par][ti + NTI * ir];
+#pragma unroll
+            for (int kc = 0; kc < KC; ++kc) r[kc] = rowb[par][tg + NTI * kc];
+            const double d = pv.x;
+            const bool live = d > pv.y && d > 0.0;
+            double q = 0.0;
+            if (live) {         // 1/d: hardware estimate and two Newton steps
+                q = __builtin_amdgcn_rcp(d);
+                q = fma(fma(-d, q, 1.0), q, q);
+                q = fma(fma(-d, q, 1.0), q, q);
+            }
+            if (ti == tj) pivot[jr] = live ? d : 0.0;
+#pragma unroll
+            for (int ir = 0; ir < KR; ++ir) {
+                const double lq = (ti + NTI * ir > j) ? -(l[ir] * q) : 0.0;
+#pragma unroll
+                for (int kc = 0; kc < KC; ++kc) mreg[ir][kc] = fma(lq, r[kc], mreg[ir][kc]);
+            }
+            par ^= 1;
+        }
+    }
+    if (!worker) return;
+#pragma unroll
+    for (int ir = 0; ir < KR; ++ir) {
+        const double pv = pivot[ir];
+        double inv = 0.0;
+        if (pv > 0.0) {      // 1/sqrt by the hardware estimate and three Newton steps
+            inv = __builtin_amdgcn_rsq(pv);
+            inv = inv * fma(-0.5 * pv, inv * inv, 1.5);
+            inv = inv * fma(-0.5 * pv, inv * inv, 1.5);
+            inv = inv * fma(-0.5 * pv, inv * inv, 1.5);
+        }
+        const int i = ti + NTI * ir;
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) {
+            const int c = tg + NTI * kc;
+            if (c >= LP) T[(c - LP) * LP + i] = mreg[ir][kc] * inv;
+        }
     }
 }
 
@@ -283,120 +303,229 @@ __device__ __forceinline__ bool jacobi_rotation(double gpp, double gqq, double g
     double r = __builtin_amdgcn_rsq(x);
     r = r * fma(-0.5 * x, r * r, 1.5);
     r = r * fma(-0.5 * x, r * r, 1.5);
-    r = r * fma(-0.5 * x, r * r, 1.5);
     c = r;
     s = t * r;
     return large;
 }
 
-// Cyclic Jacobi eigen-solve of the l x l matrix G = B B^T (B = Q^T R), round-robin pairing
-// so l/2 disjoint rotations run per step.  A step is two phases: (1) one thread per pair
-// derives its rotation from the pair's 2x2 diagonal block; (2) one thread per (row pair,
-// column pair) updates that 2x2 block of G = J^T G J and of V = V J in place (every
-// element belongs to exactly one block, so no double buffering is needed).  The kernel is
-// bound by instruction issue, so phase 2 is kept to index arithmetic plus 24 multiply/FMA.
+// Cyclic Jacobi eigen-solve of the l x l matrix G = B B^T (B = Q^T R) with round-robin
+// pairing, so l/2 disjoint rotations run per step.
+//
+// Tournament on m (even) players, circle method: positions 0..m-2 rotate, position m-1 is
+// fixed, and slot i pairs positions (i, m-1-i); after a step the player at position c moves
+// to c-1 (mod m-1), and position c holds player (step + c) mod (m-1).  G is stored BY SLOT
+// (index i = first member of slot i, index half+i = its second member) and moved as part of
+// the update (read from one LDS copy, written permuted to the other), so every read and
+// write address of a thread is the same in every step: the loop carries no index
+// arithmetic, and with a row stride = half (mod 32) consecutive threads hit consecutive
+// LDS banks.  The eigenvector matrix is kept transposed and by player (Vt[player][component])
+// and is updated in place with 16-byte accesses.  After a whole sweep the arrangement is
+// the identity again.
+//
+// A step has one workgroup barrier:
+//  * the update waves apply the step's rotations: thread (P, Q) updates the 2x2 block
+//    (slot P rows, slot Q columns) of G <- J^T G J and two components of the column pair
+//    of slot P of V <- V J;
+//  * meanwhile the rotation wave (wave 0, one lane per pair of the NEXT step) forms the
+//    three entries its next pair will have after this step's rotations, in registers, from
+//    the copy being read, and derives the next rotation from them.
 // Eigenvalues are the squared singular values of B, eigenvectors its left singular vectors.
-#define SVD_THREADS 512
-__global__ __launch_bounds__(SVD_THREADS) void small_svd_kernel(const double* __restrict__ gpart, int nb,
-                                                                int ell, int LP, int rank,
+#define SVD_UPDATE_THREADS 448
+#define SVD_THREADS (64 + SVD_UPDATE_THREADS)
+#define SVD_POOL 19600     // float64 words of LDS for the two copies of G and for Vt
+
+// Loop-invariant addresses of one 2x2 block task of an update thread.
+struct SvdTask {
+    int active;
+    int P, Q;
+    int o11, o12, o21, o22;     // read offsets in G (words)
+    int w11, w12, w21, w22;     // write offsets in the other copy
+    int v1, v2;                 // word offsets in Vt of the slot's two eigenvector columns
+    int v1_wrap, v2_wrap, dv2;  // both run up one player (ldv words) per step and wrap after player m-2
+};
+
+template <int NB>
+__global__ __launch_bounds__(SVD_THREADS) void small_svd_kernel(const double* __restrict__ gram, int ell,
+                                                                int LP, int rank,
                                                                 float* __restrict__ Sigma,
                                                                 double* __restrict__ Ur,
                                                                 double* __restrict__ Mv) {
-    __shared__ double G[MAXL * (MAXL + 1)];
-    __shared__ double V[MAXL * (MAXL + 1)];
-    __shared__ double cs[MAXL / 2], sn[MAXL / 2];
+    __shared__ __align__(16) double pool[SVD_POOL];
+    __shared__ __align__(16) double2 rot[2][MAXL / 2];      // (c, s) per slot, two generations
     __shared__ int order[MAXL];
-    __shared__ int rotated;
-    const int ldg = MAXL + 1;
+    __shared__ int finished;
     const int tid = threadIdx.x;
     const int m = (ell + 1) & ~1;   // even number of players; a zero dummy row/column when ell is odd
-    for (int idx = tid; idx < m * m; idx += SVD_THREADS) {
-        const int a = idx / m, b = idx % m;
-        G[a * ldg + b] = 0.0;
-        V[a * ldg + b] = (a == b) ? 1.0 : 0.0;
-    }
-    if (tid == 0) rotated = 0;
-    __syncthreads();
-    load_gram(gpart, nb, ell, LP, G, ldg);
-    __syncthreads();
     const int half = m / 2;
-    // round-robin tournament: player m-1 stays, the others rotate (no integer division)
-    auto pair_of = [&](int slot, int step, int& p, int& q) {
-        int a = step + slot;
-        if (a >= m - 1) a -= m - 1;
-        if (slot == 0) a = m - 1;
-        int b = step - slot;
-        if (b < 0) b += m - 1;
-        p = min(a, b);
-        q = max(a, b);
+    int ldg = m + ((half - m) & 31);                      // >= m, = half (mod 32)
+    if (2 * m * ldg + m * m > SVD_POOL) ldg = m + 1;       // largest sketches: accept bank conflicts
+    const int ldv = m;
+    double* const G0 = pool;
+    double* const G1 = pool + m * ldg;
+    double* const Vt = pool + 2 * m * ldg;
+    // slot index of a player when the arrangement is the identity (start of a sweep)
+    auto home = [&](int e) { return e < half ? e : half + (m - 1 - e); };
+    // slot index after one step of the tournament
+    auto moved = [&](int x) {
+        if (m == 2) return x;
+        if (x < half) return x == 0 ? half + 1 : x - 1;
+        const int y = x - half;
+        return y == 0 ? half : (y == half - 1 ? half - 1 : x + 1);
     };
+    for (int idx = tid; idx < m * ldg; idx += SVD_THREADS) G0[idx] = 0.0;
+    for (int idx = tid; idx < m * m; idx += SVD_THREADS) Vt[idx] = (idx / m == idx % m) ? 1.0 : 0.0;
+    if (tid == 0) finished = 0;
+    __syncthreads();
+    for (int idx = tid; idx < ell * ell; idx += SVD_THREADS) {      // stored by slot
+        const int a = idx / ell, b = idx % ell;
+        G0[home(a) * ldg + home(b)] = gram[a * LP + b];
+    }
+    __syncthreads();
+
+    // rotation wave: addresses of the ten entries behind the lane's next pair (loop invariant)
     double gsc = 0.0;
+    bool seen_large = false;
+    int iaa = 0, iab = 0, ibb = 0, jaa = 0, jab = 0, jbb = 0, x11i = 0, x12i = 0, x21i = 0, x22i = 0, sa = 0, sb = 0;
+    bool xfirst = true, yfirst = true;
+    SvdTask task[NB];
     if (tid < half) {
         double gmax = 0.0;
-        for (int a = 0; a < ell; ++a) gmax = fmax(gmax, fabs(G[a * ldg + a]));
+        for (int a = 0; a < m; ++a) gmax = fmax(gmax, fabs(G0[a * ldg + a]));
         gsc = gmax > 0.0 ? 1.0 / gmax : 0.0;
-    }
-    // a thread's blocks are fixed for the whole run: (P, Q) = (blk / half, blk % half)
-    for (int sweep = 0; sweep < 16; ++sweep) {
-        for (int step = 0; step < m - 1; ++step) {
-            if (tid < half) {
-                int p, q;
-                pair_of(tid, step, p, q);
-                double c, s;
-                if (jacobi_rotation(G[p * ldg + p], G[q * ldg + q], G[p * ldg + q], gsc, c, s)) rotated = 1;
-                cs[tid] = c;
-                sn[tid] = s;
-            }
-            __syncthreads();
-            for (int blk = tid; blk < half * half; blk += SVD_THREADS) {
-                const int P = blk / half, Q = blk - P * half;
-                int p1, q1, p2, q2;
-                pair_of(P, step, p1, q1);
-                pair_of(Q, step, p2, q2);
-                const double c1 = cs[P], s1 = sn[P], c2 = cs[Q], s2 = sn[Q];
-                const int r1 = p1 * ldg, r2 = q1 * ldg;
-                const double a11 = G[r1 + p2], a12 = G[r1 + q2], a21 = G[r2 + p2], a22 = G[r2 + q2];
-                const double b11 = V[r1 + p2], b12 = V[r1 + q2], b21 = V[r2 + p2], b22 = V[r2 + q2];
-                // rows: J^T G, then columns: (.) J
-                const double t11 = fma(c1, a11, -(s1 * a21)), t12 = fma(c1, a12, -(s1 * a22));
-                const double t21 = fma(s1, a11, c1 * a21), t22 = fma(s1, a12, c1 * a22);
-                G[r1 + p2] = fma(c2, t11, -(s2 * t12));
-                G[r1 + q2] = fma(s2, t11, c2 * t12);
-                G[r2 + p2] = fma(c2, t21, -(s2 * t22));
-                G[r2 + q2] = fma(s2, t21, c2 * t22);
-                V[r1 + p2] = fma(c2, b11, -(s2 * b12));
-                V[r1 + q2] = fma(s2, b11, c2 * b12);
-                V[r2 + p2] = fma(c2, b21, -(s2 * b22));
-                V[r2 + q2] = fma(s2, b21, c2 * b22);
-            }
-            __syncthreads();
+        const int p = tid, q = half + tid;
+        double c, s;
+        seen_large = jacobi_rotation(G0[p * ldg + p], G0[q * ldg + q], G0[p * ldg + q], gsc, c, s);
+        rot[0][tid] = make_double2(c, s);
+        int cx = p, cy = q;                                // where the next pair sits now
+        for (int x = 0; x < m; ++x) {
+            const int y = moved(x);
+            if (y == p) cx = x;
+            if (y == q) cy = x;
         }
-        const int any = rotated;
-        __syncthreads();
-        if (tid == 0) rotated = 0;
-        __syncthreads();
-        if (!any) break;
+        xfirst = cx < half;
+        yfirst = cy < half;
+        sa = xfirst ? cx : cx - half;
+        sb = yfirst ? cy : cy - half;
+        const int pa = sa, qa = half + sa, pb = sb, qb = half + sb;
+        iaa = pa * ldg + pa; iab = pa * ldg + qa; ibb = qa * ldg + qa;
+        jaa = pb * ldg + pb; jab = pb * ldg + qb; jbb = qb * ldg + qb;
+        x11i = pa * ldg + pb; x12i = pa * ldg + qb; x21i = qa * ldg + pb; x22i = qa * ldg + qb;
     }
+#pragma unroll
+    for (int t = 0; t < NB; ++t) {
+        SvdTask& k = task[t];
+        const int blk = tid - 64 + t * SVD_UPDATE_THREADS;
+        k.active = tid >= 64 && blk < half * half;
+        const int P = k.active ? blk / half : 0, Q = k.active ? blk - P * half : 0;
+        k.P = P; k.Q = Q;
+        k.o11 = P * ldg + Q; k.o12 = k.o11 + half; k.o21 = (half + P) * ldg + Q; k.o22 = k.o21 + half;
+        const int n1 = moved(P) * ldg, n2 = moved(half + P) * ldg, k1 = moved(Q), k2 = moved(half + Q);
+        k.w11 = n1 + k1; k.w12 = n1 + k2; k.w21 = n2 + k1; k.w22 = n2 + k2;
+        // eigenvector columns of slot P at step 0: players P and (m - 1 - P) (slot 0: m - 1, fixed)
+        k.v1 = P * ldv + 2 * Q;
+        k.v2 = (m - 1 - P) * ldv + 2 * Q;
+        k.dv2 = (P == 0) ? 0 : ldv;
+        k.v1_wrap = (m - 1) * ldv + 2 * Q;     // first offset past player m - 2
+        k.v2_wrap = (P == 0) ? 0x7fffffff : k.v1_wrap;   // player m - 1 never moves
+    }
+    __syncthreads();
+    // one tournament step: reads G/rr, writes Gn/rn
+    auto do_step = [&](const double* __restrict__ G, double* __restrict__ Gn, const double2* __restrict__ rr,
+                       double2* __restrict__ rn, bool last_of_sweep) {
+        if (tid < 64) {
+            if (tid < half) {
+                const double2 ra = rr[sa], rb = rr[sb];
+                const double ca = ra.x, sna = ra.y, cb = rb.x, snb = rb.y;
+                const double a11 = G[iaa], a12 = G[iab], a22 = G[ibb];
+                const double b11 = G[jaa], b12 = G[jab], b22 = G[jbb];
+                const double x11 = G[x11i], x12 = G[x12i], x21 = G[x21i], x22 = G[x22i];
+                // diagonal entry of J^T D J for a symmetric 2x2 block D:
+                //   first : c^2 d11 - 2 c s d12 + s^2 d22     second: s^2 d11 + 2 c s d12 + c^2 d22
+                const double wa = 2.0 * ca * sna * a12, wb = 2.0 * cb * snb * b12;
+                const double ca2 = ca * ca, sa2 = sna * sna, cb2 = cb * cb, sb2 = snb * snb;
+                const double gxx = xfirst ? fma(ca2, a11, fma(sa2, a22, -wa)) : fma(sa2, a11, fma(ca2, a22, wa));
+                const double gyy = yfirst ? fma(cb2, b11, fma(sb2, b22, -wb)) : fma(sb2, b11, fma(cb2, b22, wb));
+                // entry (x, y) of J_a^T X J_b: column of J_a for x, column of J_b for y
+                const double al0 = xfirst ? ca : sna, al1 = xfirst ? -sna : ca;
+                const double be0 = yfirst ? cb : snb, be1 = yfirst ? -snb : cb;
+                const double gxy = fma(al0, fma(x11, be0, x12 * be1), al1 * fma(x21, be0, x22 * be1));
+                double c, s;
+                const bool large = jacobi_rotation(gxx, gyy, gxy, gsc, c, s);
+                rn[tid] = make_double2(c, s);
+                // the flags of a sweep cover the rotations applied in it; the one just
+                // formed at the last step opens the next sweep
+                if (last_of_sweep) {
+                    const bool any = __any(seen_large);
+                    if (tid == 0) finished = any ? 0 : 1;
+                    seen_large = large;
+                } else {
+                    seen_large = seen_large || large;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < NB; ++t) {
+                SvdTask& k = task[t];
+                if (k.active) {
+                    const double2 r1 = rr[k.P], r2 = rr[k.Q];
+                    const double c1 = r1.x, s1 = r1.y, c2 = r2.x, s2 = r2.y;
+                    const double a11 = G[k.o11], a12 = G[k.o12], a21 = G[k.o21], a22 = G[k.o22];
+                    double2* e1p = reinterpret_cast<double2*>(Vt + k.v1);
+                    double2* e2p = reinterpret_cast<double2*>(Vt + k.v2);
+                    const double2 e1 = *e1p, e2 = *e2p;
+                    // rows: J^T G, then columns: (.) J
+                    const double t11 = fma(c1, a11, -(s1 * a21)), t12 = fma(c1, a12, -(s1 * a22));
+                    const double t21 = fma(s1, a11, c1 * a21), t22 = fma(s1, a12, c1 * a22);
+                    Gn[k.w11] = fma(c2, t11, -(s2 * t12));
+                    Gn[k.w12] = fma(s2, t11, c2 * t12);
+                    Gn[k.w21] = fma(c2, t21, -(s2 * t22));
+                    Gn[k.w22] = fma(s2, t21, c2 * t22);
+                    *e1p = make_double2(fma(c1, e1.x, -(s1 * e2.x)), fma(c1, e1.y, -(s1 * e2.y)));
+                    *e2p = make_double2(fma(s1, e1.x, c1 * e2.x), fma(s1, e1.y, c1 * e2.y));
+                    // next step: both columns of the slot are one player further
+                    k.v1 += ldv;
+                    if (k.v1 >= k.v1_wrap) k.v1 -= (m - 1) * ldv;
+                    k.v2 += k.dv2;
+                    if (k.v2 >= k.v2_wrap) k.v2 -= (m - 1) * ldv;
+                }
+            }
+        }
+        __syncthreads();
+    };
+    int cur = 0, step = 0, sweeps = 0;
+    for (;;) {
+        const bool last = (step + 1 == m - 1);
+        if (cur == 0) do_step(G0, G1, rot[0], rot[1], last);
+        else          do_step(G1, G0, rot[1], rot[0], last);
+        cur ^= 1;
+        if (last) {
+            step = 0;
+            if (++sweeps == 16 || finished) break;
+        } else {
+            ++step;
+        }
+    }
+    const double* G = cur ? G1 : G0;
     // rank eigenvalues: order[pos] = index of the pos-th largest (ties by index)
     if (tid < ell) {
-        const double mine = G[tid * ldg + tid];
+        const double mine = G[home(tid) * ldg + home(tid)];
         int pos = 0;
         for (int o = 0; o < ell; ++o) {
-            const double other = G[o * ldg + o];
+            const double other = G[home(o) * ldg + home(o)];
             if (other > mine || (other == mine && o < tid)) ++pos;
         }
         order[pos] = tid;
     }
     __syncthreads();
-    if (tid < rank) Sigma[tid] = (float)sqrt(fmax(G[order[tid] * ldg + order[tid]], 0.0));
-    const double top = sqrt(fmax(G[order[0] * ldg + order[0]], 0.0));
+    if (tid < rank) Sigma[tid] = (float)sqrt(fmax(G[home(order[tid]) * ldg + home(order[tid])], 0.0));
+    const double top = sqrt(fmax(G[home(order[0]) * ldg + home(order[0])], 0.0));
     for (int idx = tid; idx < LP * rank; idx += SVD_THREADS) {
         const int a = idx / rank, t = idx % rank;
         double u = 0.0, mv = 0.0;
         if (a < ell) {
             const int e = order[t];
-            u = V[a * ldg + e];
-            const double sg = sqrt(fmax(G[e * ldg + e], 0.0));
+            u = Vt[e * ldv + a];
+            const double sg = sqrt(fmax(G[home(e) * ldg + home(e)], 0.0));
             mv = (sg > 1e-14 * top && sg > 0.0) ? u / sg : 0.0;
         }
         Ur[idx] = u;
@@ -424,8 +553,15 @@ int launch_reduce_gram(const float* partial, int splits, int n, int LP, const fl
     return LRQMM_OK;
 }
 
-int launch_chol_inverse(const double* gpart, int nb, int ell, int LP, double* T, hipStream_t st) {
-    hipLaunchKernelGGL(chol_inverse_kernel, dim3(1), dim3(CHOL_THREADS), 0, st, gpart, nb, ell, LP, T);
+int launch_gram_sum(const double* gpart, int nb, int LP, double* gram, hipStream_t st) {
+    hipLaunchKernelGGL(gram_sum_kernel, dim3(ceil_div(LP * LP, 64)), dim3(64), 0, st, gpart, nb, LP * LP, gram);
+    LRQ_CHECK_LAUNCH();
+    return LRQMM_OK;
+}
+
+int launch_chol_inverse(const double* gram, int ell, int LP, double* T, hipStream_t st) {
+    NT_SWITCH(LP / 16, hipLaunchKernelGGL((chol_inverse_kernel<NT_>), dim3(1), dim3(CHOL_THREADS), 0, st, gram, ell,
+                                          T));
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }
@@ -439,10 +575,16 @@ int launch_apply(const float* In, int n, int LP, const double* Mat, int cm, int 
     return LRQMM_OK;
 }
 
-int launch_small_svd(const double* gpart, int nb, int ell, int LP, int rank, float* Sigma, double* Ur,
-                     double* Mv, hipStream_t st) {
-    hipLaunchKernelGGL(small_svd_kernel, dim3(1), dim3(SVD_THREADS), 0, st, gpart, nb, ell, LP, rank, Sigma, Ur,
-                       Mv);
+int launch_small_svd(const double* gram, int ell, int LP, int rank, float* Sigma, double* Ur, double* Mv,
+                     hipStream_t st) {
+    const int m = (ell + 1) & ~1, blocks = (m / 2) * (m / 2);
+    switch (ceil_div(blocks, SVD_UPDATE_THREADS)) {      // 2x2 blocks per update thread
+        case 1: hipLaunchKernelGGL(small_svd_kernel<1>, dim3(1), dim3(SVD_THREADS), 0, st, gram, ell, LP, rank, Sigma, Ur, Mv); break;
+        case 2: hipLaunchKernelGGL(small_svd_kernel<2>, dim3(1), dim3(SVD_THREADS), 0, st, gram, ell, LP, rank, Sigma, Ur, Mv); break;
+        case 3: hipLaunchKernelGGL(small_svd_kernel<3>, dim3(1), dim3(SVD_THREADS), 0, st, gram, ell, LP, rank, Sigma, Ur, Mv); break;
+        case 4: hipLaunchKernelGGL(small_svd_kernel<4>, dim3(1), dim3(SVD_THREADS), 0, st, gram, ell, LP, rank, Sigma, Ur, Mv); break;
+        default: return LRQMM_ERR_UNSUPPORTED;
+    }
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }

@@ -1,7 +1,7 @@
 // Streaming products with the quantization residual R = X - Dequant(Quant(X))
-// (paper: Algorithm 2 lines 4-5 for R; Background 2.1 / Algorithm 1 for the
+// (paper: Algorithm 2, dequantization and residual steps, for R; Background 2.1 / Algorithm 1 for the
 // products R.Omega, R^T Q, R Z, Q^T R of the randomized range finder), and the
-// code-matrix products of Algorithm 2 lines 9-10 (A~ W and V^T B~).
+// code-matrix products in the compensation terms of Algorithm 2 (A~ W and V^T B~).
 //
 // R is never stored: each pass re-reads the float32 operand once from HBM and
 // regenerates the residual in registers from the per-group scales.  The

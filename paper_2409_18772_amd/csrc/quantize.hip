@@ -1,5 +1,5 @@
 // Symmetric absmax quantization (paper: Background 2.2 Eq. (quantA); floor variant
-// Methodology Eq. (get_ra2); Algorithm 2 line 1).  HBM-streaming kernels: each
+// Methodology Eq. (get_ra2); Algorithm 2, quantization step).  HBM-streaming kernels: each
 // input element is read from HBM once (the second touch of a row/tile hits L2).
 #include "kernels.h"
 

@@ -24,7 +24,7 @@ def _tables():
 
 @pytest.mark.parametrize("bits,p,q", [(8, 0, 0), (4, 3, 1)])
 def test_output_is_product_of_corrected_operands(bits, p, q):
-    """Expanding Alg. 2 lines 9-12: C = (A~ + R_Ar)(B~ + R_Br), non-square shapes."""
+    """Expanding the compensation terms of Alg. 2: C = (A~ + R_Ar)(B~ + R_Br), non-square shapes."""
     M, K, N, r = 37, 29, 23, 4
     A = wl.random_matrix("normal", M, K, seed=1)
     B = wl.random_matrix("uniform01", K, N, seed=2)
