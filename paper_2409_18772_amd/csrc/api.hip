@@ -3,6 +3,8 @@
 // for lrqmm_rsvd).  No device memory is allocated here; everything lives in the
 // caller's buffers and workspace.
 #include "kernels.h"
+#include <functional>
+#include <vector>
 
 namespace {
 
@@ -50,7 +52,7 @@ size_t carve_rsvd(Arena& a, int rows, int cols, int axis, int LP, int rank, Rsvd
 }
 
 struct GemmWs {
-    float *lamA, *sA, *lamB, *sB, *Wp, *Vp, *partial, *S, *Pv, *X, *Lp, *Rp;
+    float *lamA, *sA, *lamB, *sB, *Wp, *Vp, *partialA, *partialB, *S, *Pv, *X, *Lp, *Rp;
 };
 
 size_t carve_gemm(Arena& a, int M, int N, int K, int rank, GemmWs* w) {
@@ -63,14 +65,13 @@ size_t carve_gemm(Arena& a, int M, int N, int K, int rank, GemmWs* w) {
     if (rank > 0) {
         const int RP = pad_to(rank, 16), R2P = pad_to(2 * rank, 8);
         const PassPlan pa = plan_pass_n(M, K), pb = plan_pass_n(N, K);
-        const size_t part = (size_t)RP * ((size_t)pa.splits * M > (size_t)pb.splits * N ? (size_t)pa.splits * M
-                                                                                       : (size_t)pb.splits * N);
         t.Wp = a.take<float>((size_t)K * RP);
         t.Vp = a.take<float>((size_t)K * RP);
-        t.partial = a.take<float>(part);
+        t.partialA = a.take<float>((size_t)RP * pa.splits * M);
+        t.partialB = a.take<float>((size_t)RP * pb.splits * N);
         t.S = a.take<float>((size_t)M * RP);
         t.Pv = a.take<float>((size_t)N * RP);
-        t.X = a.take<float>((size_t)rank * rank);
+        t.X = a.take<float>((size_t)rank * rank * LRQ_VTW_MAX_SLICES);
         t.Lp = a.take<float>((size_t)M * R2P);
         t.Rp = a.take<float>((size_t)N * R2P);
     }
@@ -142,7 +143,7 @@ struct Prof {
 // Second stream (default priority) on which the factorization of R_B runs next to R_A's.
 struct Side {
     hipStream_t stream = nullptr;
-    hipEvent_t fork = nullptr, join = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr, fork2 = nullptr, join2 = nullptr, xready = nullptr;
     bool ok = false;
 } g_side;
 
@@ -151,6 +152,9 @@ bool side_ready() {
     if (hipStreamCreateWithFlags(&g_side.stream, hipStreamNonBlocking) != hipSuccess) return false;
     if (hipEventCreateWithFlags(&g_side.fork, hipEventDisableTiming) != hipSuccess) return false;
     if (hipEventCreateWithFlags(&g_side.join, hipEventDisableTiming) != hipSuccess) return false;
+    if (hipEventCreateWithFlags(&g_side.fork2, hipEventDisableTiming) != hipSuccess) return false;
+    if (hipEventCreateWithFlags(&g_side.join2, hipEventDisableTiming) != hipSuccess) return false;
+    if (hipEventCreateWithFlags(&g_side.xready, hipEventDisableTiming) != hipSuccess) return false;
     g_side.ok = true;
     return true;
 }
@@ -166,6 +170,91 @@ bool k_fits_int32(int K, int bits) {
     const long long lim = 1ll << (2 * (bits - 1));
     return (long long)K * lim < (1ll << 31);
 }
+
+// A factorization is first planned as a list of kernel launches and then issued, so that
+// lrqmm_matmul can issue the launches of its two factorizations alternately: both streams
+// then receive work at the same pace instead of one after the other (the host needs several
+// microseconds per launch, and each list holds ~30).
+using LaunchList = std::vector<std::function<int()>>;
+
+static int run_interleaved(const LaunchList& a, const LaunchList& b) {
+    const size_t n = a.size() > b.size() ? a.size() : b.size();
+    for (size_t i = 0; i < n; ++i) {
+        if (i < a.size()) {
+            const int rc = a[i]();
+            if (rc != LRQMM_OK) return rc;
+        }
+        if (i < b.size()) {
+            const int rc = b[i]();
+            if (rc != LRQMM_OK) return rc;
+        }
+    }
+    return LRQMM_OK;
+}
+
+// Validates the arguments of lrqmm_rsvd and appends its launches to `ops`.
+static int rsvd_plan(LaunchList& ops, const float* X, const float* amax, int rows, int cols, int axis, int bits,
+                     int round_mode, int rank, int oversample, int power_iters, uint64_t seed,
+                     const float* omega_or_null, float* U, float* Sigma, float* Vt, void* workspace,
+                     size_t workspace_bytes, hipStream_t st) {
+    if (rows < 0 || cols < 0 || rank < 1 || oversample < 0 || power_iters < 0) return LRQMM_ERR_INVALID_ARG;
+    if (axis != LRQMM_AXIS_ROW && axis != LRQMM_AXIS_COL) return LRQMM_ERR_INVALID_ARG;
+    if (round_mode != LRQMM_ROUND_FLOOR && round_mode != LRQMM_ROUND_NEAREST) return LRQMM_ERR_INVALID_ARG;
+    if (!bits_ok(bits)) return LRQMM_ERR_UNSUPPORTED;
+    if (rows == 0 || cols == 0) return LRQMM_OK;
+    const int ell = rank + oversample;
+    if (ell > rows || ell > cols) return LRQMM_ERR_INVALID_ARG;
+    if (ell > LRQMM_MAX_SKETCH) return LRQMM_ERR_UNSUPPORTED;
+    if (!X || !amax || !U || !Sigma || !Vt) return LRQMM_ERR_INVALID_ARG;
+    if (!workspace || ((uintptr_t)workspace & 255)) return LRQMM_ERR_WORKSPACE;
+    const int LP = pad_to(ell, 16);
+    RsvdWs w;
+    Arena a(workspace);
+    if (carve_rsvd(a, rows, cols, axis, LP, rank, &w) > workspace_bytes) return LRQMM_ERR_WORKSPACE;
+    const QuantParams q = make_quant_params(bits, round_mode);
+    const int nscale = axis == LRQMM_AXIS_ROW ? rows : cols;
+    ops.push_back([=] { return launch_scales(amax, nscale, pad_to(nscale, 4), q.qmaxf, w.lam, w.s, st); });
+    if (omega_or_null) ops.push_back([=] { return launch_pad_copy(omega_or_null, cols, ell, LP, w.Wc, st); });
+    else ops.push_back([=] { return launch_fill_sketch(seed, axis, cols, ell, LP, w.Wc, st); });
+    const PassPlan pn = plan_pass_n(rows, cols), pt = plan_pass_t(rows, cols);
+    // Q = orth(partial sums) in place: Gram (float64) -> Cholesky -> Q = Y T
+    auto orth = [&](int splits, int n, float* buf) {
+        ops.push_back([=] { return launch_reduce_gram(w.partial, splits, n, LP, nullptr, buf, w.gpart, st); });
+        ops.push_back([=] { return launch_gram_sum(w.gpart, gram_blocks(n), LP, w.gram, st); });
+        ops.push_back([=] { return launch_chol_inverse(w.gram, ell, LP, w.T, st); });
+        ops.push_back([=] { return launch_apply(buf, n, LP, w.T, LP, LP, buf, LP, 0, st); });
+    };
+    auto pass_n = [&] {
+        ops.push_back([=] { return launch_resid_mul_n(X, rows, cols, axis, w.lam, w.s, q, w.Wc, LP, pn, w.partial, st); });
+    };
+    auto pass_t = [&] {
+        ops.push_back([=] { return launch_resid_mul_t(X, rows, cols, axis, w.lam, w.s, q, w.Yr, LP, pt, w.partial, st); });
+    };
+    // Y = R Omega
+    pass_n();
+    orth(pn.splits, rows, w.Yr);
+    for (int it = 0; it < power_iters; ++it) {
+        // Z = orth(R^T Q); Q = orth(R Z)
+        pass_t();
+        orth(pt.splits, cols, w.Wc);
+        pass_n();
+        orth(pn.splits, rows, w.Yr);
+    }
+    // B^T = R^T Q (cols x l), its Gram B B^T, small SVD, U = Q U', V = B^T U' / sigma
+    pass_t();
+    ops.push_back([=] { return launch_reduce_gram(w.partial, pt.splits, cols, LP, nullptr, w.Wc, w.gpart, st); });
+    ops.push_back([=] { return launch_gram_sum(w.gpart, gram_blocks(cols), LP, w.gram, st); });
+    ops.push_back([=] { return launch_small_svd(w.gram, ell, LP, rank, Sigma, w.Ur, w.Mv, st); });
+    ops.push_back([=] { return launch_apply(w.Yr, rows, LP, w.Ur, rank, rank, U, rank, 0, st); });
+    ops.push_back([=] { return launch_apply(w.Wc, cols, LP, w.Mv, rank, rank, Vt, cols, 1, st); });
+    return LRQMM_OK;
+}
+
+#define LRQ_TRY(x)                  \
+    do {                            \
+        rc = (x);                   \
+        if (rc != LRQMM_OK) return rc; \
+    } while (0)
 
 }  // namespace
 
@@ -213,61 +302,11 @@ int lrqmm_fill_sketch(uint64_t seed, int stream_id, int rows, int cols, float* o
 int lrqmm_rsvd(const float* X, const float* amax, int rows, int cols, int axis, int bits, int round_mode,
                int rank, int oversample, int power_iters, uint64_t seed, const float* omega_or_null, float* U,
                float* Sigma, float* Vt, void* workspace, size_t workspace_bytes, void* stream) {
-    if (rows < 0 || cols < 0 || rank < 1 || oversample < 0 || power_iters < 0) return LRQMM_ERR_INVALID_ARG;
-    if (axis != LRQMM_AXIS_ROW && axis != LRQMM_AXIS_COL) return LRQMM_ERR_INVALID_ARG;
-    if (round_mode != LRQMM_ROUND_FLOOR && round_mode != LRQMM_ROUND_NEAREST) return LRQMM_ERR_INVALID_ARG;
-    if (!bits_ok(bits)) return LRQMM_ERR_UNSUPPORTED;
-    if (rows == 0 || cols == 0) return LRQMM_OK;
-    const int ell = rank + oversample;
-    if (ell > rows || ell > cols) return LRQMM_ERR_INVALID_ARG;
-    if (ell > LRQMM_MAX_SKETCH) return LRQMM_ERR_UNSUPPORTED;
-    if (!X || !amax || !U || !Sigma || !Vt) return LRQMM_ERR_INVALID_ARG;
-    if (!workspace || ((uintptr_t)workspace & 255)) return LRQMM_ERR_WORKSPACE;
-    const int LP = pad_to(ell, 16);
-    RsvdWs w;
-    Arena a(workspace);
-    if (carve_rsvd(a, rows, cols, axis, LP, rank, &w) > workspace_bytes) return LRQMM_ERR_WORKSPACE;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const QuantParams q = make_quant_params(bits, round_mode);
-    const int nscale = axis == LRQMM_AXIS_ROW ? rows : cols;
-    int rc;
-#define LRQ_TRY(x)                  \
-    do {                            \
-        rc = (x);                   \
-        if (rc != LRQMM_OK) return rc; \
-    } while (0)
-    LRQ_TRY(launch_scales(amax, nscale, pad_to(nscale, 4), q.qmaxf, w.lam, w.s, st));
-    if (omega_or_null) LRQ_TRY(launch_pad_copy(omega_or_null, cols, ell, LP, w.Wc, st));
-    else LRQ_TRY(launch_fill_sketch(seed, axis, cols, ell, LP, w.Wc, st));
-    const PassPlan pn = plan_pass_n(rows, cols), pt = plan_pass_t(rows, cols);
-    // Q = orth(partial sums) in place: Gram (float64) -> Cholesky -> Q = Y T
-    auto orth = [&](int splits, int n, float* buf) -> int {
-        int r2 = launch_reduce_gram(w.partial, splits, n, LP, nullptr, buf, w.gpart, st);
-        if (r2 != LRQMM_OK) return r2;
-        r2 = launch_gram_sum(w.gpart, gram_blocks(n), LP, w.gram, st);
-        if (r2 != LRQMM_OK) return r2;
-        r2 = launch_chol_inverse(w.gram, ell, LP, w.T, st);
-        if (r2 != LRQMM_OK) return r2;
-        return launch_apply(buf, n, LP, w.T, LP, LP, buf, LP, 0, st);
-    };
-    // Y = R Omega
-    LRQ_TRY(launch_resid_mul_n(X, rows, cols, axis, w.lam, w.s, q, w.Wc, LP, pn, w.partial, st));
-    LRQ_TRY(orth(pn.splits, rows, w.Yr));
-    for (int it = 0; it < power_iters; ++it) {
-        // Z = orth(R^T Q); Q = orth(R Z)
-        LRQ_TRY(launch_resid_mul_t(X, rows, cols, axis, w.lam, w.s, q, w.Yr, LP, pt, w.partial, st));
-        LRQ_TRY(orth(pt.splits, cols, w.Wc));
-        LRQ_TRY(launch_resid_mul_n(X, rows, cols, axis, w.lam, w.s, q, w.Wc, LP, pn, w.partial, st));
-        LRQ_TRY(orth(pn.splits, rows, w.Yr));
-    }
-    // B^T = R^T Q (cols x l), its Gram B B^T, small SVD, U = Q U', V = B^T U' / sigma
-    LRQ_TRY(launch_resid_mul_t(X, rows, cols, axis, w.lam, w.s, q, w.Yr, LP, pt, w.partial, st));
-    LRQ_TRY(launch_reduce_gram(w.partial, pt.splits, cols, LP, nullptr, w.Wc, w.gpart, st));
-    LRQ_TRY(launch_gram_sum(w.gpart, gram_blocks(cols), LP, w.gram, st));
-    LRQ_TRY(launch_small_svd(w.gram, ell, LP, rank, Sigma, w.Ur, w.Mv, st));
-    LRQ_TRY(launch_apply(w.Yr, rows, LP, w.Ur, rank, rank, U, rank, 0, st));
-    LRQ_TRY(launch_apply(w.Wc, cols, LP, w.Mv, rank, rank, Vt, cols, 1, st));
-    return LRQMM_OK;
+    LaunchList ops;
+    int rc = rsvd_plan(ops, X, amax, rows, cols, axis, bits, round_mode, rank, oversample, power_iters, seed,
+                       omega_or_null, U, Sigma, Vt, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+    if (rc != LRQMM_OK) return rc;
+    return run_interleaved(ops, LaunchList());
 }
 
 static int gemm_impl(int M, int N, int K, int bits, int rank, const int8_t* Aq, const float* amaxA,
@@ -289,23 +328,43 @@ static int gemm_impl(int M, int N, int K, int bits, int rank, const int8_t* Aq, 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const QuantParams q = make_quant_params(bits, 0);
     int rc;
+    // The panels of the two sides are independent until the GEMM: those built from B's codes
+    // (and V^T W) run on the second stream next to those built from A's codes.
+    hipStream_t sst = (rank > 0 && side_ready()) ? g_side.stream : st;
+    const bool two = sst != st;
     LRQ_TRY(launch_scales(amaxA, M, pad_to(M, 4), q.qmaxf, w.lamA, w.sA, st));
-    LRQ_TRY(launch_scales(amaxB, N, pad_to(N, 4), q.qmaxf, w.lamB, w.sB, st));
     int R2P = 0;
     if (rank > 0) {
         const int RP = pad_to(rank, 16);
         R2P = pad_to(2 * rank, 8);
         LRQ_TRY(launch_pack_kr(W, Vt, K, rank, RP, w.Wp, w.Vp, st));
-        // S = A~ W = diag(sA) (Aq W)
-        const PassPlan pa = plan_pass_n(M, K);
-        LRQ_TRY(launch_codes_mul_n(Aq, M, K, w.Wp, RP, pa, w.partial, st));
-        LRQ_TRY(launch_reduce_gram(w.partial, pa.splits, M, RP, w.sA, w.S, nullptr, st));
-        // Pv = (Vt B~)^T = diag(sB) (BqT V)
+        if (two) {
+            if (hipEventRecord(g_side.fork2, st) != hipSuccess) return LRQMM_ERR_HIP;
+            if (hipStreamWaitEvent(sst, g_side.fork2, 0) != hipSuccess) return LRQMM_ERR_HIP;
+        }
+        // Pv = (Vt B~)^T = diag(sB) (BqT V);  right panel [Pv^T + (Vt W) Gamma Zt ; Gamma Zt]
+        LRQ_TRY(launch_scales(amaxB, N, pad_to(N, 4), q.qmaxf, w.lamB, w.sB, sst));
         const PassPlan pb = plan_pass_n(N, K);
-        LRQ_TRY(launch_codes_mul_n(BqT, N, K, w.Vp, RP, pb, w.partial, st));
-        LRQ_TRY(launch_reduce_gram(w.partial, pb.splits, N, RP, w.sB, w.Pv, nullptr, st));
+        LRQ_TRY(launch_codes_mul_n(BqT, N, K, w.Vp, RP, pb, w.partialB, sst));
+        LRQ_TRY(launch_reduce_gram(w.partialB, pb.splits, N, RP, w.sB, w.Pv, nullptr, sst));
+        // X = Vt W (tiny) goes first on the caller's stream; the right panel waits for it
         LRQ_TRY(launch_vtw(Vt, W, K, rank, w.X, st));
-        LRQ_TRY(launch_build_panels(M, N, rank, RP, R2P, U, Sig, w.S, w.Pv, w.X, Gam, Zt, w.Lp, w.Rp, st));
+        if (two) {
+            if (hipEventRecord(g_side.xready, st) != hipSuccess) return LRQMM_ERR_HIP;
+            if (hipStreamWaitEvent(sst, g_side.xready, 0) != hipSuccess) return LRQMM_ERR_HIP;
+        }
+        LRQ_TRY(launch_build_right(N, K, rank, RP, R2P, w.Pv, w.X, Gam, Zt, w.Rp, sst));
+        // S = A~ W = diag(sA) (Aq W);  left panel [U Sigma | S]
+        const PassPlan pa = plan_pass_n(M, K);
+        LRQ_TRY(launch_codes_mul_n(Aq, M, K, w.Wp, RP, pa, w.partialA, st));
+        LRQ_TRY(launch_reduce_gram(w.partialA, pa.splits, M, RP, w.sA, w.S, nullptr, st));
+        LRQ_TRY(launch_build_left(M, rank, RP, R2P, U, Sig, w.S, w.Lp, st));
+        if (two) {
+            if (hipEventRecord(g_side.join2, sst) != hipSuccess) return LRQMM_ERR_HIP;
+            if (hipStreamWaitEvent(st, g_side.join2, 0) != hipSuccess) return LRQMM_ERR_HIP;
+        }
+    } else {
+        LRQ_TRY(launch_scales(amaxB, N, pad_to(N, 4), q.qmaxf, w.lamB, w.sB, st));
     }
     prof_mark(prof_slot, 7, st);
     rc = launch_int8_gemm(M, N, K, Aq, BqT, w.sA, w.sB, rank > 0 ? w.Lp : nullptr, rank > 0 ? w.Rp : nullptr,
@@ -350,22 +409,25 @@ int lrqmm_matmul(int M, int N, int K, int bits, int rank, int oversample, int po
         if (hipEventRecord(g_side.fork, pst) != hipSuccess) return LRQMM_ERR_HIP;
         if (hipStreamWaitEvent(bst, g_side.fork, 0) != hipSuccess) return LRQMM_ERR_HIP;
     }
-    prof_mark(slot, 0, pst);
-    if (K > 0) LRQ_TRY(lrqmm_quantize(A, M, K, LRQMM_AXIS_ROW, bits, round_mode, w.Aq, w.amaxA, pst));
-    else LRQ_TRY(launch_pad_copy(nullptr, M, 0, 1, w.amaxA, pst));
-    prof_mark(slot, 1, pst);
+    // the two sides are planned first and then issued alternately (see LaunchList)
+    LaunchList opsA, opsB;
+    opsA.push_back([=] { prof_mark(slot, 0, pst); return LRQMM_OK; });
+    if (K > 0) opsA.push_back([=] { return lrqmm_quantize(A, M, K, LRQMM_AXIS_ROW, bits, round_mode, w.Aq, w.amaxA, pst); });
+    else opsA.push_back([=] { return launch_pad_copy(nullptr, M, 0, 1, w.amaxA, pst); });
+    opsA.push_back([=] { prof_mark(slot, 1, pst); return LRQMM_OK; });
     if (rank > 0)
-        LRQ_TRY(lrqmm_rsvd(A, w.amaxA, M, K, LRQMM_AXIS_ROW, bits, round_mode, rank, oversample, power_iters,
-                           seed, nullptr, w.U, w.Sig, w.Vt, w.subA, w.subA_bytes, pst));
-    prof_mark(slot, 2, pst);
-    prof_mark(slot, 3, bst);
-    if (K > 0) LRQ_TRY(lrqmm_quantize(B, K, N, LRQMM_AXIS_COL, bits, round_mode, w.BqT, w.amaxB, bst));
-    else LRQ_TRY(launch_pad_copy(nullptr, N, 0, 1, w.amaxB, bst));
-    prof_mark(slot, 4, bst);
+        LRQ_TRY(rsvd_plan(opsA, A, w.amaxA, M, K, LRQMM_AXIS_ROW, bits, round_mode, rank, oversample, power_iters,
+                          seed, nullptr, w.U, w.Sig, w.Vt, w.subA, w.subA_bytes, pst));
+    opsA.push_back([=] { prof_mark(slot, 2, pst); return LRQMM_OK; });
+    opsB.push_back([=] { prof_mark(slot, 3, bst); return LRQMM_OK; });
+    if (K > 0) opsB.push_back([=] { return lrqmm_quantize(B, K, N, LRQMM_AXIS_COL, bits, round_mode, w.BqT, w.amaxB, bst); });
+    else opsB.push_back([=] { return launch_pad_copy(nullptr, N, 0, 1, w.amaxB, bst); });
+    opsB.push_back([=] { prof_mark(slot, 4, bst); return LRQMM_OK; });
     if (rank > 0)
-        LRQ_TRY(lrqmm_rsvd(B, w.amaxB, K, N, LRQMM_AXIS_COL, bits, round_mode, rank, oversample, power_iters,
-                           seed, nullptr, w.W, w.Gam, w.Zt, w.subB, w.subB_bytes, bst));
-    prof_mark(slot, 5, bst);
+        LRQ_TRY(rsvd_plan(opsB, B, w.amaxB, K, N, LRQMM_AXIS_COL, bits, round_mode, rank, oversample, power_iters,
+                          seed, nullptr, w.W, w.Gam, w.Zt, w.subB, w.subB_bytes, bst));
+    opsB.push_back([=] { prof_mark(slot, 5, bst); return LRQMM_OK; });
+    LRQ_TRY(run_interleaved(opsA, opsB));
     if (overlap) {
         if (hipEventRecord(g_side.join, bst) != hipSuccess) return LRQMM_ERR_HIP;
         if (hipStreamWaitEvent(pst, g_side.join, 0) != hipSuccess) return LRQMM_ERR_HIP;

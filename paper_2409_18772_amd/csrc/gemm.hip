@@ -350,19 +350,41 @@ __global__ __launch_bounds__(512, 1) void int8_gemm256_kernel(int M, int N, int 
         }
     }
 }
-
-// X[t][u] = sum_k Vt[t][k] W[k][u]; one workgroup per entry.
+// Xp[ks][t][u] = sum over the ks-th slice of k of Vt[t][k] W[k][u] (r x r per slice), float64
+// accumulation.  One workgroup per (row t, slice); thread (kg, u) walks k = kg, kg + G, ... so
+// a wavefront reads whole rows of W (coalesced) against a broadcast element of Vt, eight
+// loads deep; the G partial sums are merged through LDS in fixed order.  The slices are
+// summed (fixed order) where X is used.
+template <int RU>
 __global__ __launch_bounds__(256) void vtw_kernel(const float* __restrict__ Vt, const float* __restrict__ W,
-                                                  int K, int r, float* __restrict__ X) {
-    __shared__ double part[4];
-    const int t = blockIdx.x / r, u = blockIdx.x % r;
+                                                  int K, int r, int kslice, float* __restrict__ Xp) {
+    constexpr int G = 256 / RU;
+    __shared__ double part[G][RU];
+    const int t = blockIdx.x, u = threadIdx.x % RU, kg = threadIdx.x / RU;
+    const int uc = min(u, r - 1);
+    const int kb = blockIdx.y * kslice, ke = min(K, kb + kslice);
+    const float* vrow = Vt + (size_t)t * K;
     double acc = 0.0;
-    for (int k = threadIdx.x; k < K; k += 256) acc = fma((double)Vt[(size_t)t * K + k], (double)W[(size_t)k * r + u], acc);
+    for (int k0 = kb + kg; k0 < ke; k0 += 8 * G) {
+        float v[8], w[8];
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
-    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+        for (int j = 0; j < 8; ++j) {
+            const int k = min(k0 + j * G, K - 1);
+            v[j] = vrow[k];
+            w[j] = W[(size_t)k * r + uc];
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (k0 + j * G < ke) acc = fma((double)v[j], (double)w[j], acc);
+    }
+    part[kg][u] = acc;
     __syncthreads();
-    if (threadIdx.x == 0) X[blockIdx.x] = (float)(((part[0] + part[1]) + part[2]) + part[3]);
+    if (kg == 0 && u < r) {
+        double sum = 0.0;
+#pragma unroll
+        for (int g = 0; g < G; ++g) sum += part[g][u];
+        Xp[((size_t)blockIdx.y * r + t) * r + u] = (float)sum;
+    }
 }
 
 __global__ void pack_kr_kernel(const float* __restrict__ W, const float* __restrict__ Vt, int K, int r, int RP,
@@ -386,16 +408,27 @@ __global__ void build_left_kernel(int M, int r, int RP, int R2P, const float* __
     Lp[idx] = v;
 }
 
-__global__ void build_right_kernel(int N, int r, int RP, int R2P, const float* __restrict__ Pv,
-                                   const float* __restrict__ X, const float* __restrict__ Gam,
-                                   const float* __restrict__ Zt, float* __restrict__ Rp) {
-    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (size_t)N * R2P) return;
-    const int c = (int)(idx / N), j = (int)(idx % N);   // j fastest: coalesced reads of Zt
+// grid (ceil(N / 256), R2P): block column c of the right panel for 256 values of j.
+__global__ __launch_bounds__(256) void build_right_kernel(int N, int r, int RP, int R2P,
+                                                          const float* __restrict__ Pv,
+                                                          const float* __restrict__ Xp, int nslices,
+                                                          const float* __restrict__ Gam,
+                                                          const float* __restrict__ Zt, float* __restrict__ Rp) {
+    __shared__ float xg[LRQMM_MAX_SKETCH];      // X[c][u] Gam[u]
+    const int c = blockIdx.y;
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (c < r && threadIdx.x < r) {
+        const int u = threadIdx.x;
+        float x = 0.f;
+        for (int ks = 0; ks < nslices; ++ks) x += Xp[((size_t)ks * r + c) * r + u];
+        xg[u] = x * Gam[u];
+    }
+    __syncthreads();
+    if (j >= N) return;
     float v = 0.f;
     if (c < r) {
         float acc = Pv[(size_t)j * RP + c];
-        for (int u = 0; u < r; ++u) acc = fmaf(X[c * r + u] * Gam[u], Zt[(size_t)u * N + j], acc);
+        for (int u = 0; u < r; ++u) acc = fmaf(xg[u], Zt[(size_t)u * N + j], acc);
         v = acc;
     } else if (c < 2 * r) {
         v = Gam[c - r] * Zt[(size_t)(c - r) * N + j];
@@ -403,8 +436,15 @@ __global__ void build_right_kernel(int N, int r, int RP, int R2P, const float* _
     Rp[(size_t)j * R2P + c] = v;
 }
 
-int launch_vtw(const float* Vt, const float* W, int K, int r, float* X, hipStream_t st) {
-    hipLaunchKernelGGL(vtw_kernel, dim3(r * r), dim3(256), 0, st, Vt, W, K, r, X);
+int vtw_slices(int K) { return max(1, min(LRQ_VTW_MAX_SLICES, K / 256)); }
+
+int launch_vtw(const float* Vt, const float* W, int K, int r, float* Xp, hipStream_t st) {
+    const int ns = vtw_slices(K);
+    const int kslice = ceil_div(K, ns);
+    dim3 grid(r, ceil_div(K, kslice));
+    if (r <= 32)      hipLaunchKernelGGL(vtw_kernel<32>, grid, dim3(256), 0, st, Vt, W, K, r, kslice, Xp);
+    else if (r <= 64) hipLaunchKernelGGL(vtw_kernel<64>, grid, dim3(256), 0, st, Vt, W, K, r, kslice, Xp);
+    else              hipLaunchKernelGGL(vtw_kernel<128>, grid, dim3(256), 0, st, Vt, W, K, r, kslice, Xp);
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }
@@ -417,14 +457,20 @@ int launch_pack_kr(const float* W, const float* Vt, int K, int r, int RP, float*
     return LRQMM_OK;
 }
 
-int launch_build_panels(int M, int N, int r, int RP, int R2P, const float* U, const float* Sig,
-                        const float* S, const float* Pv, const float* X, const float* Gam,
-                        const float* Zt, float* Lp, float* Rp, hipStream_t st) {
-    size_t total = (size_t)M * R2P;
+int launch_build_left(int M, int r, int RP, int R2P, const float* U, const float* Sig, const float* S, float* Lp,
+                      hipStream_t st) {
+    const size_t total = (size_t)M * R2P;
     hipLaunchKernelGGL(build_left_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, M, r, RP, R2P, U, Sig, S, Lp);
     LRQ_CHECK_LAUNCH();
-    total = (size_t)N * R2P;
-    hipLaunchKernelGGL(build_right_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, N, r, RP, R2P, Pv, X, Gam, Zt, Rp);
+    return LRQMM_OK;
+}
+
+int launch_build_right(int N, int K, int r, int RP, int R2P, const float* Pv, const float* Xp, const float* Gam,
+                       const float* Zt, float* Rp, hipStream_t st) {
+    const int ns = vtw_slices(K);
+    const int nslices = ceil_div(K, ceil_div(K, ns));
+    hipLaunchKernelGGL(build_right_kernel, dim3(ceil_div(N, 256), R2P), dim3(256), 0, st, N, r, RP, R2P, Pv, Xp,
+                       nslices, Gam, Zt, Rp);
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }

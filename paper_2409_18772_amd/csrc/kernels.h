@@ -61,7 +61,9 @@ int launch_small_svd(const double* gram, int ell, int LP, int rank, float* Sigma
                      double* Mv, hipStream_t st);
 
 // ---- gemm.hip -----------------------------------------------------------
-// X[t][u] = sum_k Vt[t][k] W[k][u]   (r x r)
+// Xp[ks][t][u] = slice ks of sum_k Vt[t][k] W[k][u]   (vtw_slices(K) slices of r x r)
+#define LRQ_VTW_MAX_SLICES 16
+int vtw_slices(int K);
 int launch_vtw(const float* Vt, const float* W, int K, int r, float* X, hipStream_t st);
 // Wp[k][0..RP) = W[k][0..r) zero padded; Vp[k][t] = Vt[t][k] zero padded.
 int launch_pack_kr(const float* W, const float* Vt, int K, int r, int RP, float* Wp, float* Vp,
@@ -69,9 +71,10 @@ int launch_pack_kr(const float* W, const float* Vt, int K, int r, int RP, float*
 // Left panel  Lp[i][0..r) = U[i][t] Sig[t],  Lp[i][r..2r) = S[i][u]      (S = A~ W, M x RP)
 // Right panel Rp[j][0..r) = Pv[j][t] + sum_u X[t][u] Gam[u] Zt[u][j]      (Pv = (Vt B~)^T, N x RP)
 //             Rp[j][r..2r) = Gam[u] Zt[u][j];   both zero padded to R2P columns.
-int launch_build_panels(int M, int N, int r, int RP, int R2P, const float* U, const float* Sig,
-                        const float* S, const float* Pv, const float* X, const float* Gam,
-                        const float* Zt, float* Lp, float* Rp, hipStream_t st);
+int launch_build_left(int M, int r, int RP, int R2P, const float* U, const float* Sig, const float* S, float* Lp,
+                      hipStream_t st);
+int launch_build_right(int N, int K, int r, int RP, int R2P, const float* Pv, const float* Xp, const float* Gam,
+                       const float* Zt, float* Rp, hipStream_t st);
 // C = diag(sA) (Aq . BqT^T) diag(sB) [+ Lp . Rp^T when Lp != null]; optional raw int32 output.
 int launch_int8_gemm(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, const float* sA,
                      const float* sB, const float* Lp, const float* Rp, int R2P, float* C,
