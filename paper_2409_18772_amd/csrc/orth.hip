@@ -240,44 +240,67 @@ __global__ __launch_bounds__(CHOL_THREADS) void chol_inverse_kernel(const double
     }
 }
 
-// out = In . Mat for 32 rows per workgroup, float64 accumulation.  Thread (row, g) computes
-// the outputs of its row in columns g, g+8, g+16, ...
+// out = In . Mat with float64 accumulation on the float64 matrix cores, one wavefront per 16
+// rows.  v_mfma_f64_16x16x4 operand layout (lane l): A[i = l%16][k = l/16], B[k = l/16][j = l%16],
+// D[i = 4v + l/16][j = l%16] for v = 0..3.  The reduction index may be visited in any order, so
+// lane group l/16 takes the contiguous quarter [kq KQ, (kq+1) KQ) of the LP columns: a lane
+// loads KQ consecutive floats of its row (the wavefront's 16 rows form one contiguous block)
+// and, per step, one element of Mat.  Every wavefront reads all its rows before it writes any,
+// so `out` may alias `In` (same leading dimension).
 template <int NT>
-__global__ __launch_bounds__(256) void apply_kernel(const float* __restrict__ In, int n,
-                                                    const double* __restrict__ Mat, int cm, int ldm,
-                                                    float* __restrict__ out, int ldo, int transposed) {
+__global__ __launch_bounds__(64) void apply_kernel(const float* __restrict__ In, int n,
+                                                   const double* __restrict__ Mat, int cm, int ldm,
+                                                   float* __restrict__ out, int ldo, int transposed) {
     constexpr int LP = NT * 16;
-    constexpr int E = LP / 8;
-    constexpr int ld = LP + 1;
-    __shared__ double mat[LP * LP];
-    __shared__ float tile[32 * ld];
-    const int r0 = blockIdx.x * 32;
-    for (int idx = threadIdx.x; idx < LP * LP; idx += 256) {
-        const int a = idx / LP, c = idx % LP;
-        mat[idx] = (c < cm) ? Mat[a * ldm + c] : 0.0;
-    }
-    for (int idx = threadIdx.x; idx < 32 * LP; idx += 256) {
-        const int rr = idx / LP, c = idx % LP;
-        tile[rr * ld + c] = (r0 + rr < n) ? In[(size_t)(r0 + rr) * LP + c] : 0.f;
-    }
-    __syncthreads();
-    const int rr = threadIdx.x & 31, g = threadIdx.x >> 5;
-    double acc[E];
+    constexpr int KQ = LP / 4;
+    const int l = threadIdx.x, li = l & 15, kq = l >> 4;
+    const int r0 = blockIdx.x * 16;
+    const int row = min(r0 + li, n - 1);
+    const bool row_ok = r0 + li < n;
+    float a[KQ];
+    const float4* ip = reinterpret_cast<const float4*>(In + (size_t)row * LP + kq * KQ);
 #pragma unroll
-    for (int e = 0; e < E; ++e) acc[e] = 0.0;
-#pragma unroll 4
-    for (int a = 0; a < LP; ++a) {
-        const double x = (double)tile[rr * ld + a];
-#pragma unroll
-        for (int e = 0; e < E; ++e) acc[e] = fma(x, mat[a * LP + g + 8 * e], acc[e]);
+    for (int u = 0; u < KQ / 4; ++u) {
+        const float4 t = ip[u];
+        a[4 * u + 0] = row_ok ? t.x : 0.f;
+        a[4 * u + 1] = row_ok ? t.y : 0.f;
+        a[4 * u + 2] = row_ok ? t.z : 0.f;
+        a[4 * u + 3] = row_ok ? t.w : 0.f;
     }
-    if (r0 + rr >= n) return;
+    typedef double v4d __attribute__((ext_vector_type(4)));
+    v4d acc[NT];
 #pragma unroll
-    for (int e = 0; e < E; ++e) {
-        const int c = g + 8 * e;
-        if (c < cm) {
-            if (transposed) out[(size_t)c * ldo + r0 + rr] = (float)acc[e];
-            else            out[(size_t)(r0 + rr) * ldo + c] = (float)acc[e];
+    for (int ct = 0; ct < NT; ++ct) acc[ct] = (v4d){0.0, 0.0, 0.0, 0.0};
+    const int nct = (cm + 15) >> 4;         // column tiles that hold output
+#pragma unroll
+    for (int ct = 0; ct < NT; ++ct) {
+        if (ct < nct) {                     // uniform
+            const int c = 16 * ct + li;
+            const bool c_ok = c < cm;
+            const double* mp = Mat + (size_t)(kq * KQ) * ldm + (c_ok ? c : 0);
+            double b[KQ];
+#pragma unroll
+            for (int sidx = 0; sidx < KQ; ++sidx) {
+                const double t = mp[(size_t)sidx * ldm];
+                b[sidx] = c_ok ? t : 0.0;
+            }
+#pragma unroll
+            for (int sidx = 0; sidx < KQ; ++sidx)
+                acc[ct] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a[sidx], b[sidx], acc[ct], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int ct = 0; ct < NT; ++ct) {
+        const int c = 16 * ct + li;
+        if (ct < nct && c < cm) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int orow = r0 + 4 * v + kq;
+                if (orow < n) {
+                    if (transposed) out[(size_t)c * ldo + orow] = (float)acc[ct][v];
+                    else            out[(size_t)orow * ldo + c] = (float)acc[ct][v];
+                }
+            }
         }
     }
 }
@@ -568,8 +591,9 @@ int launch_chol_inverse(const double* gram, int ell, int LP, double* T, hipStrea
 
 int launch_apply(const float* In, int n, int LP, const double* Mat, int cm, int ldm, float* out, int ldo,
                  int transposed, hipStream_t st) {
-    dim3 grid(ceil_div(n, 32));
-    NT_SWITCH(LP / 16, hipLaunchKernelGGL((apply_kernel<NT_>), grid, dim3(256), 0, st, In, n, Mat, cm, ldm, out,
+    if (n <= 0) return LRQMM_OK;
+    dim3 grid(ceil_div(n, 16));
+    NT_SWITCH(LP / 16, hipLaunchKernelGGL((apply_kernel<NT_>), grid, dim3(64), 0, st, In, n, Mat, cm, ldm, out,
                                           ldo, transposed));
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
