@@ -52,7 +52,7 @@ size_t carve_rsvd(Arena& a, int rows, int cols, int axis, int LP, int rank, Rsvd
 }
 
 struct GemmWs {
-    float *lamA, *sA, *lamB, *sB, *Wp, *Vp, *partialA, *partialB, *S, *Pv, *X, *Lp, *Rp;
+    float *lamA, *sA, *lamB, *sB, *Wp, *Vp, *partialA, *partialB, *X, *Lp, *Rp;
 };
 
 size_t carve_gemm(Arena& a, int M, int N, int K, int rank, GemmWs* w) {
@@ -69,8 +69,6 @@ size_t carve_gemm(Arena& a, int M, int N, int K, int rank, GemmWs* w) {
         t.Vp = a.take<float>((size_t)K * RP);
         t.partialA = a.take<float>((size_t)RP * pa.splits * M);
         t.partialB = a.take<float>((size_t)RP * pb.splits * N);
-        t.S = a.take<float>((size_t)M * RP);
-        t.Pv = a.take<float>((size_t)N * RP);
         t.X = a.take<float>((size_t)rank * rank * LRQ_VTW_MAX_SLICES);
         t.Lp = a.take<float>((size_t)M * R2P);
         t.Rp = a.take<float>((size_t)N * R2P);
@@ -143,7 +141,7 @@ struct Prof {
 // Second stream (default priority) on which the factorization of R_B runs next to R_A's.
 struct Side {
     hipStream_t stream = nullptr;
-    hipEvent_t fork = nullptr, join = nullptr, fork2 = nullptr, join2 = nullptr, xready = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
     bool ok = false;
 } g_side;
 
@@ -152,9 +150,6 @@ bool side_ready() {
     if (hipStreamCreateWithFlags(&g_side.stream, hipStreamNonBlocking) != hipSuccess) return false;
     if (hipEventCreateWithFlags(&g_side.fork, hipEventDisableTiming) != hipSuccess) return false;
     if (hipEventCreateWithFlags(&g_side.join, hipEventDisableTiming) != hipSuccess) return false;
-    if (hipEventCreateWithFlags(&g_side.fork2, hipEventDisableTiming) != hipSuccess) return false;
-    if (hipEventCreateWithFlags(&g_side.join2, hipEventDisableTiming) != hipSuccess) return false;
-    if (hipEventCreateWithFlags(&g_side.xready, hipEventDisableTiming) != hipSuccess) return false;
     g_side.ok = true;
     return true;
 }
@@ -328,43 +323,17 @@ static int gemm_impl(int M, int N, int K, int bits, int rank, const int8_t* Aq, 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const QuantParams q = make_quant_params(bits, 0);
     int rc;
-    // The panels of the two sides are independent until the GEMM: those built from B's codes
-    // (and V^T W) run on the second stream next to those built from A's codes.
-    hipStream_t sst = (rank > 0 && side_ready()) ? g_side.stream : st;
-    const bool two = sst != st;
-    LRQ_TRY(launch_scales(amaxA, M, pad_to(M, 4), q.qmaxf, w.lamA, w.sA, st));
     int R2P = 0;
+    const int RP = pad_to(rank, 16);
+    LRQ_TRY(launch_panel_prep(M, N, K, rank, RP, q.qmaxf, amaxA, amaxB, W, Vt, w.lamA, w.sA, w.lamB, w.sB, w.Wp,
+                              w.Vp, w.X, st));
     if (rank > 0) {
-        const int RP = pad_to(rank, 16);
         R2P = pad_to(2 * rank, 8);
-        LRQ_TRY(launch_pack_kr(W, Vt, K, rank, RP, w.Wp, w.Vp, st));
-        if (two) {
-            if (hipEventRecord(g_side.fork2, st) != hipSuccess) return LRQMM_ERR_HIP;
-            if (hipStreamWaitEvent(sst, g_side.fork2, 0) != hipSuccess) return LRQMM_ERR_HIP;
-        }
-        // Pv = (Vt B~)^T = diag(sB) (BqT V);  right panel [Pv^T + (Vt W) Gamma Zt ; Gamma Zt]
-        LRQ_TRY(launch_scales(amaxB, N, pad_to(N, 4), q.qmaxf, w.lamB, w.sB, sst));
-        const PassPlan pb = plan_pass_n(N, K);
-        LRQ_TRY(launch_codes_mul_n(BqT, N, K, w.Vp, RP, pb, w.partialB, sst));
-        LRQ_TRY(launch_reduce_gram(w.partialB, pb.splits, N, RP, w.sB, w.Pv, nullptr, sst));
-        // X = Vt W (tiny) goes first on the caller's stream; the right panel waits for it
-        LRQ_TRY(launch_vtw(Vt, W, K, rank, w.X, st));
-        if (two) {
-            if (hipEventRecord(g_side.xready, st) != hipSuccess) return LRQMM_ERR_HIP;
-            if (hipStreamWaitEvent(sst, g_side.xready, 0) != hipSuccess) return LRQMM_ERR_HIP;
-        }
-        LRQ_TRY(launch_build_right(N, K, rank, RP, R2P, w.Pv, w.X, Gam, Zt, w.Rp, sst));
-        // S = A~ W = diag(sA) (Aq W);  left panel [U Sigma | S]
-        const PassPlan pa = plan_pass_n(M, K);
-        LRQ_TRY(launch_codes_mul_n(Aq, M, K, w.Wp, RP, pa, w.partialA, st));
-        LRQ_TRY(launch_reduce_gram(w.partialA, pa.splits, M, RP, w.sA, w.S, nullptr, st));
-        LRQ_TRY(launch_build_left(M, rank, RP, R2P, U, Sig, w.S, w.Lp, st));
-        if (two) {
-            if (hipEventRecord(g_side.join2, sst) != hipSuccess) return LRQMM_ERR_HIP;
-            if (hipStreamWaitEvent(st, g_side.join2, 0) != hipSuccess) return LRQMM_ERR_HIP;
-        }
-    } else {
-        LRQ_TRY(launch_scales(amaxB, N, pad_to(N, 4), q.qmaxf, w.lamB, w.sB, st));
+        // A~ W and (V^T B~)^T without their step vectors, split along K; one launch for both
+        const PassPlan pa = plan_pass_n(M, K), pb = plan_pass_n(N, K);
+        LRQ_TRY(launch_codes_mul_n2(Aq, M, w.Wp, pa, w.partialA, BqT, N, w.Vp, pb, w.partialB, K, RP, st));
+        LRQ_TRY(launch_build_panels(M, N, K, rank, RP, R2P, U, Sig, w.sA, w.partialA, pa.splits, w.sB,
+                                    w.partialB, pb.splits, w.X, Gam, Zt, w.Lp, w.Rp, st));
     }
     prof_mark(prof_slot, 7, st);
     rc = launch_int8_gemm(M, N, K, Aq, BqT, w.sA, w.sB, rank > 0 ? w.Lp : nullptr, rank > 0 ? w.Rp : nullptr,

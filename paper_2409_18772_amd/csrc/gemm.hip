@@ -350,19 +350,29 @@ __global__ __launch_bounds__(512, 1) void int8_gemm256_kernel(int M, int N, int 
         }
     }
 }
+// ---------------------------------------------------------------------------
+// Panels of the rank-2r update (compensation terms of Algorithm 2 regrouped):
+//   C = C0 + [U Sigma | A~ W] . [V^T B~ + (V^T W) Gamma Z^T ; Gamma Z^T]
+// Two small launches surround the two code-matrix products A~ W and (V^T B~)^T:
+//   panel_prep:   step vectors of both operands, zero-padded copies of W and V for the
+//                 matrix-core kernels, and X = V^T W in k-slices;
+//   build_panels: sums the split partials of the code products, applies the steps and
+//                 assembles the left (M x R2P) and right (N x R2P) panels.
+// ---------------------------------------------------------------------------
+
 // Xp[ks][t][u] = sum over the ks-th slice of k of Vt[t][k] W[k][u] (r x r per slice), float64
-// accumulation.  One workgroup per (row t, slice); thread (kg, u) walks k = kg, kg + G, ... so
-// a wavefront reads whole rows of W (coalesced) against a broadcast element of Vt, eight
-// loads deep; the G partial sums are merged through LDS in fixed order.  The slices are
-// summed (fixed order) where X is used.
+// accumulation, for the workgroup (t, ks).  Thread (kg, u) walks k = kg, kg + G, ... so a
+// wavefront reads whole rows of W (coalesced) against a broadcast element of Vt, eight loads
+// deep; the G partial sums are merged through LDS in fixed order.  The slices are summed
+// (fixed order) where X is used.
 template <int RU>
-__global__ __launch_bounds__(256) void vtw_kernel(const float* __restrict__ Vt, const float* __restrict__ W,
-                                                  int K, int r, int kslice, float* __restrict__ Xp) {
+__device__ __forceinline__ void vtw_block(const float* __restrict__ Vt, const float* __restrict__ W, int K,
+                                          int r, int kslice, int t, int ks, float* __restrict__ Xp,
+                                          double* __restrict__ part) {
     constexpr int G = 256 / RU;
-    __shared__ double part[G][RU];
-    const int t = blockIdx.x, u = threadIdx.x % RU, kg = threadIdx.x / RU;
+    const int u = threadIdx.x % RU, kg = threadIdx.x / RU;
     const int uc = min(u, r - 1);
-    const int kb = blockIdx.y * kslice, ke = min(K, kb + kslice);
+    const int kb = ks * kslice, ke = min(K, kb + kslice);
     const float* vrow = Vt + (size_t)t * K;
     double acc = 0.0;
     for (int k0 = kb + kg; k0 < ke; k0 += 8 * G) {
@@ -377,100 +387,166 @@ __global__ __launch_bounds__(256) void vtw_kernel(const float* __restrict__ Vt, 
         for (int j = 0; j < 8; ++j)
             if (k0 + j * G < ke) acc = fma((double)v[j], (double)w[j], acc);
     }
-    part[kg][u] = acc;
+    part[kg * RU + u] = acc;
     __syncthreads();
     if (kg == 0 && u < r) {
         double sum = 0.0;
 #pragma unroll
-        for (int g = 0; g < G; ++g) sum += part[g][u];
-        Xp[((size_t)blockIdx.y * r + t) * r + u] = (float)sum;
+        for (int g = 0; g < G; ++g) sum += part[g * RU + u];
+        Xp[((size_t)ks * r + t) * r + u] = (float)sum;
     }
 }
 
-__global__ void pack_kr_kernel(const float* __restrict__ W, const float* __restrict__ Vt, int K, int r, int RP,
-                               float* __restrict__ Wp, float* __restrict__ Vp) {
-    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (size_t)K * RP) return;
-    const int k = (int)(idx / RP), c = (int)(idx % RP);
-    Wp[idx] = (c < r) ? W[(size_t)k * r + c] : 0.f;
-    Vp[idx] = (c < r) ? Vt[(size_t)c * K + k] : 0.f;
+struct PrepArgs {
+    const float *amaxA, *amaxB, *W, *Vt;
+    float *lamA, *sA, *lamB, *sB, *Wp, *Vp, *Xp;
+    int M, Mp, N, Np, K, r, RP, kslice, nslices;
+    float qmaxf;
+    int nbA, nbB, nbP;      // workgroups of the first three sections
+};
+
+// Workgroup ranges: [0, nbA) steps of A, [nbA, nbA+nbB) steps of B, then nbP workgroups that
+// pad W (K x r) and V = Vt^T to K x RP, then r * nslices workgroups of V^T W.
+__global__ __launch_bounds__(256) void panel_prep_kernel(PrepArgs a) {
+    __shared__ double part[256];
+    int b = blockIdx.x;
+    if (b < a.nbA + a.nbB) {
+        const bool isA = b < a.nbA;
+        const int i = (isA ? b : b - a.nbA) * 256 + threadIdx.x;
+        const int n = isA ? a.M : a.N, npad = isA ? a.Mp : a.Np;
+        if (i >= npad) return;
+        float l = 0.0f, st = 0.0f;
+        if (i < n) make_scales((isA ? a.amaxA : a.amaxB)[i], a.qmaxf, l, st);
+        (isA ? a.lamA : a.lamB)[i] = l;
+        (isA ? a.sA : a.sB)[i] = st;
+        return;
+    }
+    b -= a.nbA + a.nbB;
+    if (b < a.nbP) {
+        const size_t idx = (size_t)b * 256 + threadIdx.x;
+        if (idx >= (size_t)a.K * a.RP) return;
+        const int k = (int)(idx / a.RP), c = (int)(idx % a.RP);
+        a.Wp[idx] = (c < a.r) ? a.W[(size_t)k * a.r + c] : 0.f;
+        a.Vp[idx] = (c < a.r) ? a.Vt[(size_t)c * a.K + k] : 0.f;
+        return;
+    }
+    b -= a.nbP;
+    const int t = b % a.r, ks = b / a.r;
+    if (a.r <= 32)      vtw_block<32>(a.Vt, a.W, a.K, a.r, a.kslice, t, ks, a.Xp, part);
+    else if (a.r <= 64) vtw_block<64>(a.Vt, a.W, a.K, a.r, a.kslice, t, ks, a.Xp, part);
+    else                vtw_block<128>(a.Vt, a.W, a.K, a.r, a.kslice, t, ks, a.Xp, part);
 }
 
-__global__ void build_left_kernel(int M, int r, int RP, int R2P, const float* __restrict__ U,
-                                  const float* __restrict__ Sig, const float* __restrict__ S,
-                                  float* __restrict__ Lp) {
-    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (size_t)M * R2P) return;
-    const int i = (int)(idx / R2P), c = (int)(idx % R2P);
-    float v = 0.f;
-    if (c < r) v = U[(size_t)i * r + c] * Sig[c];
-    else if (c < 2 * r) v = S[(size_t)i * RP + (c - r)];
-    Lp[idx] = v;
+// p[0] + p[stride] + ... (n <= MAXN terms, fixed order).  All loads are issued before the first
+// add, without branches: a clamped index re-reads the last term, whose value is then masked.
+template <int MAXN>
+__device__ __forceinline__ float sum_slices(const float* __restrict__ p, int n, size_t stride) {
+    float v[MAXN];
+#pragma unroll
+    for (int t = 0; t < MAXN; ++t) v[t] = p[(size_t)min(t, n - 1) * stride];
+    float acc = 0.f;
+#pragma unroll
+    for (int t = 0; t < MAXN; ++t) acc += (t < n) ? v[t] : 0.f;
+    return acc;
 }
 
-// grid (ceil(N / 256), R2P): block column c of the right panel for 256 values of j.
-__global__ __launch_bounds__(256) void build_right_kernel(int N, int r, int RP, int R2P,
-                                                          const float* __restrict__ Pv,
-                                                          const float* __restrict__ Xp, int nslices,
-                                                          const float* __restrict__ Gam,
-                                                          const float* __restrict__ Zt, float* __restrict__ Rp) {
-    __shared__ float xg[LRQMM_MAX_SKETCH];      // X[c][u] Gam[u]
-    const int c = blockIdx.y;
-    const int j = blockIdx.x * 256 + threadIdx.x;
-    if (c < r && threadIdx.x < r) {
-        const int u = threadIdx.x;
-        float x = 0.f;
-        for (int ks = 0; ks < nslices; ++ks) x += Xp[((size_t)ks * r + c) * r + u];
-        xg[u] = x * Gam[u];
+struct BuildArgs {
+    const float *U, *Sig, *sA, *partialA, *sB, *partialB, *Xp, *Gam, *Zt;
+    float *Lp, *Rp;
+    int M, N, r, RP, R2P, splitsA, splitsB, nslices, nbL;
+};
+
+#define BR_J 64     // columns j of C per workgroup of the right panel
+// Workgroups [0, nbL): left panel, one thread per entry:
+//   Lp[i][c] = U[i][c] Sig[c] (c < r),  sA[i] sum_sp partialA[sp][i][c-r] (r <= c < 2r), 0 beyond.
+// Then one workgroup per BR_J rows j of the right panel:
+//   Rp[j][c] = sB[j] sum_sp partialB[sp][j][c] + sum_u X[c][u] Gam[u] Zt[u][j]   (c < r),
+//              Gam[c-r] Zt[c-r][j] (r <= c < 2r), 0 beyond,
+// with X Gamma and the Zt strip staged in LDS so that global reads and writes stay coalesced.
+__global__ __launch_bounds__(256) void build_panels_kernel(BuildArgs a) {
+    __shared__ float xg[LRQMM_MAX_SKETCH * (LRQMM_MAX_SKETCH + 1)];
+    __shared__ float zt[LRQMM_MAX_SKETCH * (BR_J + 1)];
+    const int r = a.r, RP = a.RP, R2P = a.R2P;
+    if ((int)blockIdx.x < a.nbL) {
+        const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+        if (idx >= (size_t)a.M * R2P) return;
+        const int i = (int)(idx / R2P), c = (int)(idx % R2P);
+        float v = 0.f;
+        if (c < r) {
+            v = a.U[(size_t)i * r + c] * a.Sig[c];
+        } else if (c < 2 * r) {
+            const size_t plane = (size_t)a.M * RP;
+            v = sum_slices<MAX_SPLITS>(a.partialA + (size_t)i * RP + (c - r), a.splitsA, plane) * a.sA[i];
+        }
+        a.Lp[idx] = v;
+        return;
+    }
+    const int j0 = ((int)blockIdx.x - a.nbL) * BR_J;
+    for (int e = threadIdx.x; e < r * r; e += 256) {
+        const int c = e / r, u = e - c * r;
+        xg[c * (r + 1) + u] = sum_slices<LRQ_VTW_MAX_SLICES>(a.Xp + e, a.nslices, (size_t)r * r) * a.Gam[u];
+    }
+    for (int e = threadIdx.x; e < r * BR_J; e += 256) {
+        const int u = e / BR_J, jl = e - u * BR_J;
+        zt[u * (BR_J + 1) + jl] = (j0 + jl < a.N) ? a.Zt[(size_t)u * a.N + j0 + jl] : 0.f;
     }
     __syncthreads();
-    if (j >= N) return;
-    float v = 0.f;
-    if (c < r) {
-        float acc = Pv[(size_t)j * RP + c];
-        for (int u = 0; u < r; ++u) acc = fmaf(xg[u], Zt[(size_t)u * N + j], acc);
-        v = acc;
-    } else if (c < 2 * r) {
-        v = Gam[c - r] * Zt[(size_t)(c - r) * N + j];
+    const size_t plane = (size_t)a.N * RP;
+    for (int e = threadIdx.x; e < BR_J * R2P; e += 256) {
+        const int jl = e / R2P, c = e - jl * R2P;
+        const int j = j0 + jl;
+        if (j >= a.N) break;
+        float v = 0.f;
+        if (c < r) {
+            float acc = sum_slices<MAX_SPLITS>(a.partialB + (size_t)j * RP + c, a.splitsB, plane) * a.sB[j];
+            for (int u = 0; u < r; ++u) acc = fmaf(xg[c * (r + 1) + u], zt[u * (BR_J + 1) + jl], acc);
+            v = acc;
+        } else if (c < 2 * r) {
+            v = a.Gam[c - r] * zt[(c - r) * (BR_J + 1) + jl];
+        }
+        a.Rp[(size_t)j * R2P + c] = v;
     }
-    Rp[(size_t)j * R2P + c] = v;
 }
 
 int vtw_slices(int K) { return max(1, min(LRQ_VTW_MAX_SLICES, K / 256)); }
 
-int launch_vtw(const float* Vt, const float* W, int K, int r, float* Xp, hipStream_t st) {
-    const int ns = vtw_slices(K);
-    const int kslice = ceil_div(K, ns);
-    dim3 grid(r, ceil_div(K, kslice));
-    if (r <= 32)      hipLaunchKernelGGL(vtw_kernel<32>, grid, dim3(256), 0, st, Vt, W, K, r, kslice, Xp);
-    else if (r <= 64) hipLaunchKernelGGL(vtw_kernel<64>, grid, dim3(256), 0, st, Vt, W, K, r, kslice, Xp);
-    else              hipLaunchKernelGGL(vtw_kernel<128>, grid, dim3(256), 0, st, Vt, W, K, r, kslice, Xp);
+int launch_panel_prep(int M, int N, int K, int r, int RP, float qmaxf, const float* amaxA, const float* amaxB,
+                      const float* W, const float* Vt, float* lamA, float* sA, float* lamB, float* sB, float* Wp,
+                      float* Vp, float* Xp, hipStream_t st) {
+    PrepArgs a;
+    a.amaxA = amaxA; a.amaxB = amaxB; a.W = W; a.Vt = Vt;
+    a.lamA = lamA; a.sA = sA; a.lamB = lamB; a.sB = sB; a.Wp = Wp; a.Vp = Vp; a.Xp = Xp;
+    a.M = M; a.Mp = (M + 3) / 4 * 4; a.N = N; a.Np = (N + 3) / 4 * 4; a.K = K; a.r = r; a.RP = RP;
+    a.qmaxf = qmaxf;
+    a.nbA = ceil_div(a.Mp, 256);
+    a.nbB = ceil_div(a.Np, 256);
+    int nbV = 0;
+    a.nbP = 0; a.kslice = 1; a.nslices = 0;
+    if (r > 0) {
+        a.nbP = (int)(((size_t)K * RP + 255) / 256);
+        a.kslice = ceil_div(K, vtw_slices(K));
+        a.nslices = ceil_div(K, a.kslice);
+        nbV = r * a.nslices;
+    }
+    const int total = a.nbA + a.nbB + a.nbP + nbV;
+    if (total == 0) return LRQMM_OK;
+    hipLaunchKernelGGL(panel_prep_kernel, dim3(total), dim3(256), 0, st, a);
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }
 
-int launch_pack_kr(const float* W, const float* Vt, int K, int r, int RP, float* Wp, float* Vp,
-                   hipStream_t st) {
-    const size_t total = (size_t)K * RP;
-    hipLaunchKernelGGL(pack_kr_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, W, Vt, K, r, RP, Wp, Vp);
-    LRQ_CHECK_LAUNCH();
-    return LRQMM_OK;
-}
-
-int launch_build_left(int M, int r, int RP, int R2P, const float* U, const float* Sig, const float* S, float* Lp,
-                      hipStream_t st) {
-    const size_t total = (size_t)M * R2P;
-    hipLaunchKernelGGL(build_left_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, M, r, RP, R2P, U, Sig, S, Lp);
-    LRQ_CHECK_LAUNCH();
-    return LRQMM_OK;
-}
-
-int launch_build_right(int N, int K, int r, int RP, int R2P, const float* Pv, const float* Xp, const float* Gam,
-                       const float* Zt, float* Rp, hipStream_t st) {
-    const int ns = vtw_slices(K);
-    const int nslices = ceil_div(K, ceil_div(K, ns));
-    hipLaunchKernelGGL(build_right_kernel, dim3(ceil_div(N, 256), R2P), dim3(256), 0, st, N, r, RP, R2P, Pv, Xp,
-                       nslices, Gam, Zt, Rp);
+int launch_build_panels(int M, int N, int K, int r, int RP, int R2P, const float* U, const float* Sig,
+                        const float* sA, const float* partialA, int splitsA, const float* sB,
+                        const float* partialB, int splitsB, const float* Xp, const float* Gam, const float* Zt,
+                        float* Lp, float* Rp, hipStream_t st) {
+    BuildArgs a;
+    a.U = U; a.Sig = Sig; a.sA = sA; a.partialA = partialA; a.sB = sB; a.partialB = partialB; a.Xp = Xp;
+    a.Gam = Gam; a.Zt = Zt; a.Lp = Lp; a.Rp = Rp;
+    a.M = M; a.N = N; a.r = r; a.RP = RP; a.R2P = R2P; a.splitsA = splitsA; a.splitsB = splitsB;
+    a.nslices = ceil_div(K, ceil_div(K, vtw_slices(K)));
+    a.nbL = (int)(((size_t)M * R2P + 255) / 256);
+    const int total = a.nbL + ceil_div(N, BR_J);
+    hipLaunchKernelGGL(build_panels_kernel, dim3(total), dim3(256), 0, st, a);
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }

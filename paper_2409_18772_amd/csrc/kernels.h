@@ -37,9 +37,11 @@ int launch_resid_mul_n(const float* X, int rows, int cols, int axis, const float
 int launch_resid_mul_t(const float* X, int rows, int cols, int axis, const float* lam,
                        const float* s, QuantParams q, const float* W, int LP, PassPlan plan,
                        float* partial, hipStream_t st);
-// partial[s][rows][LP] = scale-free codes[:, chunk s] . W[chunk s, :]  (codes rows x K int8)
-int launch_codes_mul_n(const int8_t* codes, int rows, int K, const float* W, int LP,
-                       PassPlan plan, float* partial, hipStream_t st);
+// Two independent products in one launch:
+// partialX[s][rowsX][LP] = scale-free codesX[:, chunk s] . WX[chunk s, :]  (codesX rowsX x K int8)
+int launch_codes_mul_n2(const int8_t* codesA, int rowsA, const float* WA, PassPlan planA, float* partialA,
+                        const int8_t* codesB, int rowsB, const float* WB, PassPlan planB, float* partialB,
+                        int K, int LP, hipStream_t st);
 
 // ---- orth.hip -----------------------------------------------------------
 int gram_blocks(int n);
@@ -61,20 +63,21 @@ int launch_small_svd(const double* gram, int ell, int LP, int rank, float* Sigma
                      double* Mv, hipStream_t st);
 
 // ---- gemm.hip -----------------------------------------------------------
-// Xp[ks][t][u] = slice ks of sum_k Vt[t][k] W[k][u]   (vtw_slices(K) slices of r x r)
+// X = V^T W is kept as vtw_slices(K) k-slices Xp[ks][t][u] that are summed where X is used.
 #define LRQ_VTW_MAX_SLICES 16
 int vtw_slices(int K);
-int launch_vtw(const float* Vt, const float* W, int K, int r, float* X, hipStream_t st);
-// Wp[k][0..RP) = W[k][0..r) zero padded; Vp[k][t] = Vt[t][k] zero padded.
-int launch_pack_kr(const float* W, const float* Vt, int K, int r, int RP, float* Wp, float* Vp,
-                   hipStream_t st);
-// Left panel  Lp[i][0..r) = U[i][t] Sig[t],  Lp[i][r..2r) = S[i][u]      (S = A~ W, M x RP)
-// Right panel Rp[j][0..r) = Pv[j][t] + sum_u X[t][u] Gam[u] Zt[u][j]      (Pv = (Vt B~)^T, N x RP)
+// One launch: step vectors lamX/sX (padded to a multiple of 4) of both operands and, when
+// r > 0, the zero-padded K x RP copies Wp of W and Vp of Vt^T and the slices Xp of V^T W.
+int launch_panel_prep(int M, int N, int K, int r, int RP, float qmaxf, const float* amaxA, const float* amaxB,
+                      const float* W, const float* Vt, float* lamA, float* sA, float* lamB, float* sB, float* Wp,
+                      float* Vp, float* Xp, hipStream_t st);
+// Left panel  Lp[i][0..r) = U[i][t] Sig[t],  Lp[i][r..2r) = sA[i] sum_s partialA[s][i][u]
+// Right panel Rp[j][0..r) = sB[j] sum_s partialB[s][j][t] + sum_u X[t][u] Gam[u] Zt[u][j]
 //             Rp[j][r..2r) = Gam[u] Zt[u][j];   both zero padded to R2P columns.
-int launch_build_left(int M, int r, int RP, int R2P, const float* U, const float* Sig, const float* S, float* Lp,
-                      hipStream_t st);
-int launch_build_right(int N, int K, int r, int RP, int R2P, const float* Pv, const float* Xp, const float* Gam,
-                       const float* Zt, float* Rp, hipStream_t st);
+int launch_build_panels(int M, int N, int K, int r, int RP, int R2P, const float* U, const float* Sig,
+                        const float* sA, const float* partialA, int splitsA, const float* sB,
+                        const float* partialB, int splitsB, const float* Xp, const float* Gam, const float* Zt,
+                        float* Lp, float* Rp, hipStream_t st);
 // C = diag(sA) (Aq . BqT^T) diag(sB) [+ Lp . Rp^T when Lp != null]; optional raw int32 output.
 int launch_int8_gemm(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, const float* sA,
                      const float* sB, const float* Lp, const float* Rp, int R2P, float* C,

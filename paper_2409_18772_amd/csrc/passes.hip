@@ -140,12 +140,24 @@ __global__ __launch_bounds__(256) void resid_mul_n_kernel(
 }
 
 // Same contraction with an int8 code matrix as the streamed operand (no scales).
+// blockIdx.z selects one of two independent jobs (A~ W and (V^T B~)^T share one launch).
+struct CodesJob {
+    const int8_t* Cq;   // rows x K codes
+    const float* W;     // K x LP
+    float* partial;     // [splits][rows][LP]
+    int rows, chunk, splits;
+};
+
 template <int NT, bool VEC>
-__global__ __launch_bounds__(256) void codes_mul_n_kernel(const int8_t* __restrict__ Cq, int rows,
-                                                          int K, const float* __restrict__ W,
-                                                          int chunk, float* __restrict__ partial) {
+__global__ __launch_bounds__(256) void codes_mul_n_kernel(CodesJob j0, CodesJob j1, int K) {
     constexpr int LP = NT * 16;
     __shared__ __align__(16) float wl[2][KCHUNK * (LP + 4)];
+    const CodesJob job = blockIdx.z == 0 ? j0 : j1;
+    if ((int)blockIdx.x * 64 >= job.rows || (int)blockIdx.y >= job.splits) return;
+    const int8_t* __restrict__ Cq = job.Cq;
+    const float* __restrict__ W = job.W;
+    float* __restrict__ partial = job.partial;
+    const int rows = job.rows, chunk = job.chunk;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r = lane & 15, g = lane >> 4;
     const int row = blockIdx.x * 64 + wave * 16 + r;
@@ -378,10 +390,9 @@ static void dispatch_t(int axis, bool vec, dim3 grid, hipStream_t st, const floa
 }
 
 template <int NT>
-static void dispatch_c(bool vec, dim3 grid, hipStream_t st, const int8_t* Cq, int rows, int K, const float* W,
-                       int chunk, float* partial) {
-    if (vec) hipLaunchKernelGGL((codes_mul_n_kernel<NT, true>), grid, dim3(256), 0, st, Cq, rows, K, W, chunk, partial);
-    else     hipLaunchKernelGGL((codes_mul_n_kernel<NT, false>), grid, dim3(256), 0, st, Cq, rows, K, W, chunk, partial);
+static void dispatch_c(bool vec, dim3 grid, hipStream_t st, CodesJob j0, CodesJob j1, int K) {
+    if (vec) hipLaunchKernelGGL((codes_mul_n_kernel<NT, true>), grid, dim3(256), 0, st, j0, j1, K);
+    else     hipLaunchKernelGGL((codes_mul_n_kernel<NT, false>), grid, dim3(256), 0, st, j0, j1, K);
 }
 
 #define NT_SWITCH(NTV, CALL)            \
@@ -414,11 +425,14 @@ int launch_resid_mul_t(const float* X, int rows, int cols, int axis, const float
     return LRQMM_OK;
 }
 
-int launch_codes_mul_n(const int8_t* codes, int rows, int K, const float* W, int LP, PassPlan plan,
-                       float* partial, hipStream_t st) {
-    const bool vec = (K % 4 == 0) && ((uintptr_t)codes % 4 == 0);
-    dim3 grid(ceil_div(rows, 64), plan.splits);
-    NT_SWITCH(LP / 16, (dispatch_c<NT_>(vec, grid, st, codes, rows, K, W, plan.chunk, partial)));
+int launch_codes_mul_n2(const int8_t* codesA, int rowsA, const float* WA, PassPlan planA, float* partialA,
+                        const int8_t* codesB, int rowsB, const float* WB, PassPlan planB, float* partialB,
+                        int K, int LP, hipStream_t st) {
+    const bool vec = (K % 4 == 0) && ((uintptr_t)codesA % 4 == 0) && ((uintptr_t)codesB % 4 == 0);
+    CodesJob j0 = {codesA, WA, partialA, rowsA, planA.chunk, planA.splits};
+    CodesJob j1 = {codesB, WB, partialB, rowsB, planB.chunk, planB.splits};
+    dim3 grid(ceil_div(max(rowsA, rowsB), 64), max(planA.splits, planB.splits), 2);
+    NT_SWITCH(LP / 16, (dispatch_c<NT_>(vec, grid, st, j0, j1, K)));
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }
