@@ -53,6 +53,7 @@ size_t carve_rsvd(Arena& a, int rows, int cols, int axis, int LP, int rank, Rsvd
 
 struct GemmWs {
     float *lamA, *sA, *lamB, *sB, *Wp, *Vp, *partialA, *partialB, *X, *Lp, *Rp;
+    uint16_t *Wp3, *Vp3;
 };
 
 size_t carve_gemm(Arena& a, int M, int N, int K, int rank, GemmWs* w) {
@@ -67,6 +68,8 @@ size_t carve_gemm(Arena& a, int M, int N, int K, int rank, GemmWs* w) {
         const PassPlan pa = plan_pass_n(M, K), pb = plan_pass_n(N, K);
         t.Wp = a.take<float>((size_t)K * RP);
         t.Vp = a.take<float>((size_t)K * RP);
+        t.Wp3 = a.take<uint16_t>((size_t)3 * RP * pad_to(K, 64));
+        t.Vp3 = a.take<uint16_t>((size_t)3 * RP * pad_to(K, 64));
         t.partialA = a.take<float>((size_t)RP * pa.splits * M);
         t.partialB = a.take<float>((size_t)RP * pb.splits * N);
         t.X = a.take<float>((size_t)rank * rank * LRQ_VTW_MAX_SLICES);
@@ -326,12 +329,13 @@ static int gemm_impl(int M, int N, int K, int bits, int rank, const int8_t* Aq, 
     int R2P = 0;
     const int RP = pad_to(rank, 16);
     LRQ_TRY(launch_panel_prep(M, N, K, rank, RP, q.qmaxf, amaxA, amaxB, W, Vt, w.lamA, w.sA, w.lamB, w.sB, w.Wp,
-                              w.Vp, w.X, st));
+                              w.Vp, w.Wp3, w.Vp3, w.X, st));
     if (rank > 0) {
         R2P = pad_to(2 * rank, 8);
         // A~ W and (V^T B~)^T without their step vectors, split along K; one launch for both
         const PassPlan pa = plan_pass_n(M, K), pb = plan_pass_n(N, K);
-        LRQ_TRY(launch_codes_mul_n2(Aq, M, w.Wp, pa, w.partialA, BqT, N, w.Vp, pb, w.partialB, K, RP, st));
+        LRQ_TRY(launch_codes_mul_n2(Aq, M, w.Wp, w.Wp3, pa, w.partialA, BqT, N, w.Vp, w.Vp3, pb, w.partialB, K,
+                                    pad_to(K, 64), RP, st));
         LRQ_TRY(launch_build_panels(M, N, K, rank, RP, R2P, U, Sig, w.sA, w.partialA, pa.splits, w.sB,
                                     w.partialB, pb.splits, w.X, Gam, Zt, w.Lp, w.Rp, st));
     }

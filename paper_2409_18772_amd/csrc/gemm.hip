@@ -397,16 +397,32 @@ __device__ __forceinline__ void vtw_block(const float* __restrict__ Vt, const fl
     }
 }
 
+// x = hi + mid + lo with each term a bfloat16 (the upper 16 bits of a float32): every term
+// takes the next 8 significant bits by truncation and the subtractions are exact, so the sum
+// carries 24 bits (the remainder is below 2^-23 |x|, and exactly zero for most inputs).
+__device__ __forceinline__ void split_bf16x3(float x, uint16_t (&h)[3]) {
+    const uint32_t b0 = __float_as_uint(x) & 0xffff0000u;
+    const float r1 = x - __uint_as_float(b0);
+    const uint32_t b1 = __float_as_uint(r1) & 0xffff0000u;
+    const float r2 = r1 - __uint_as_float(b1);
+    const uint32_t b2 = __float_as_uint(r2) & 0xffff0000u;
+    h[0] = (uint16_t)(b0 >> 16);
+    h[1] = (uint16_t)(b1 >> 16);
+    h[2] = (uint16_t)(b2 >> 16);
+}
+
 struct PrepArgs {
     const float *amaxA, *amaxB, *W, *Vt;
     float *lamA, *sA, *lamB, *sB, *Wp, *Vp, *Xp;
-    int M, Mp, N, Np, K, r, RP, kslice, nslices;
+    uint16_t *Wp3, *Vp3;
+    int M, Mp, N, Np, K, Kp, r, RP, kslice, nslices;
     float qmaxf;
     int nbA, nbB, nbP;      // workgroups of the first three sections
 };
 
 // Workgroup ranges: [0, nbA) steps of A, [nbA, nbA+nbB) steps of B, then nbP workgroups that
-// pad W (K x r) and V = Vt^T to K x RP, then r * nslices workgroups of V^T W.
+// pad W (K x r) and V = Vt^T to K x RP (float32) and write their bfloat16 planes, then
+// r * nslices workgroups of V^T W.
 __global__ __launch_bounds__(256) void panel_prep_kernel(PrepArgs a) {
     __shared__ double part[256];
     int b = blockIdx.x;
@@ -423,11 +439,22 @@ __global__ __launch_bounds__(256) void panel_prep_kernel(PrepArgs a) {
     }
     b -= a.nbA + a.nbB;
     if (b < a.nbP) {
-        const size_t idx = (size_t)b * 256 + threadIdx.x;
-        if (idx >= (size_t)a.K * a.RP) return;
-        const int k = (int)(idx / a.RP), c = (int)(idx % a.RP);
-        a.Wp[idx] = (c < a.r) ? a.W[(size_t)k * a.r + c] : 0.f;
-        a.Vp[idx] = (c < a.r) ? a.Vt[(size_t)c * a.K + k] : 0.f;
+        const size_t idx = (size_t)b * 256 + threadIdx.x;     // k fastest: coalesced plane writes
+        if (idx >= (size_t)a.Kp * a.RP) return;
+        const int c = (int)(idx / a.Kp), k = (int)(idx % a.Kp);
+        const bool in = c < a.r && k < a.K;
+        const float wv = in ? a.W[(size_t)k * a.r + c] : 0.f;
+        const float vv = in ? a.Vt[(size_t)c * a.K + k] : 0.f;
+        if (k < a.K) {
+            a.Wp[(size_t)k * a.RP + c] = wv;
+            a.Vp[(size_t)k * a.RP + c] = vv;
+        }
+        uint16_t h[3];
+        const size_t plane = (size_t)a.RP * a.Kp;
+        split_bf16x3(wv, h);
+        a.Wp3[idx] = h[0]; a.Wp3[plane + idx] = h[1]; a.Wp3[2 * plane + idx] = h[2];
+        split_bf16x3(vv, h);
+        a.Vp3[idx] = h[0]; a.Vp3[plane + idx] = h[1]; a.Vp3[2 * plane + idx] = h[2];
         return;
     }
     b -= a.nbP;
@@ -512,10 +539,11 @@ int vtw_slices(int K) { return max(1, min(LRQ_VTW_MAX_SLICES, K / 256)); }
 
 int launch_panel_prep(int M, int N, int K, int r, int RP, float qmaxf, const float* amaxA, const float* amaxB,
                       const float* W, const float* Vt, float* lamA, float* sA, float* lamB, float* sB, float* Wp,
-                      float* Vp, float* Xp, hipStream_t st) {
+                      float* Vp, uint16_t* Wp3, uint16_t* Vp3, float* Xp, hipStream_t st) {
     PrepArgs a;
     a.amaxA = amaxA; a.amaxB = amaxB; a.W = W; a.Vt = Vt;
     a.lamA = lamA; a.sA = sA; a.lamB = lamB; a.sB = sB; a.Wp = Wp; a.Vp = Vp; a.Xp = Xp;
+    a.Wp3 = Wp3; a.Vp3 = Vp3; a.Kp = (K + 63) / 64 * 64;
     a.M = M; a.Mp = (M + 3) / 4 * 4; a.N = N; a.Np = (N + 3) / 4 * 4; a.K = K; a.r = r; a.RP = RP;
     a.qmaxf = qmaxf;
     a.nbA = ceil_div(a.Mp, 256);
@@ -523,7 +551,7 @@ int launch_panel_prep(int M, int N, int K, int r, int RP, float qmaxf, const flo
     int nbV = 0;
     a.nbP = 0; a.kslice = 1; a.nslices = 0;
     if (r > 0) {
-        a.nbP = (int)(((size_t)K * RP + 255) / 256);
+        a.nbP = (int)(((size_t)a.Kp * RP + 255) / 256);
         a.kslice = ceil_div(K, vtw_slices(K));
         a.nslices = ceil_div(K, a.kslice);
         nbV = r * a.nslices;

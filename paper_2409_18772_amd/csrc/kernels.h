@@ -39,9 +39,11 @@ int launch_resid_mul_t(const float* X, int rows, int cols, int axis, const float
                        float* partial, hipStream_t st);
 // Two independent products in one launch:
 // partialX[s][rowsX][LP] = scale-free codesX[:, chunk s] . WX[chunk s, :]  (codesX rowsX x K int8)
-int launch_codes_mul_n2(const int8_t* codesA, int rowsA, const float* WA, PassPlan planA, float* partialA,
-                        const int8_t* codesB, int rowsB, const float* WB, PassPlan planB, float* partialB,
-                        int K, int LP, hipStream_t st);
+// WX: K x LP float32; WX3: the same factor as three bfloat16 planes [3][LP][Kp] (k fastest,
+// Kp = K rounded up to 64, zero padded), used when K % 16 == 0.
+int launch_codes_mul_n2(const int8_t* codesA, int rowsA, const float* WA, const uint16_t* WA3, PassPlan planA,
+                        float* partialA, const int8_t* codesB, int rowsB, const float* WB, const uint16_t* WB3,
+                        PassPlan planB, float* partialB, int K, int Kp, int LP, hipStream_t st);
 
 // ---- orth.hip -----------------------------------------------------------
 int gram_blocks(int n);
@@ -68,9 +70,10 @@ int launch_small_svd(const double* gram, int ell, int LP, int rank, float* Sigma
 int vtw_slices(int K);
 // One launch: step vectors lamX/sX (padded to a multiple of 4) of both operands and, when
 // r > 0, the zero-padded K x RP copies Wp of W and Vp of Vt^T and the slices Xp of V^T W.
+// Wp3 / Vp3: the same two factors as bfloat16 planes [3][RP][Kp] (see launch_codes_mul_n2).
 int launch_panel_prep(int M, int N, int K, int r, int RP, float qmaxf, const float* amaxA, const float* amaxB,
                       const float* W, const float* Vt, float* lamA, float* sA, float* lamB, float* sB, float* Wp,
-                      float* Vp, float* Xp, hipStream_t st);
+                      float* Vp, uint16_t* Wp3, uint16_t* Vp3, float* Xp, hipStream_t st);
 // Left panel  Lp[i][0..r) = U[i][t] Sig[t],  Lp[i][r..2r) = sA[i] sum_s partialA[s][i][u]
 // Right panel Rp[j][0..r) = sB[j] sum_s partialB[s][j][t] + sum_u X[t][u] Gam[u] Zt[u][j]
 //             Rp[j][r..2r) = Gam[u] Zt[u][j];   both zero padded to R2P columns.

@@ -225,6 +225,115 @@ __global__ __launch_bounds__(256) void codes_mul_n_kernel(CodesJob j0, CodesJob 
             if (orow0 + v < rows) out[(size_t)(orow0 + v) * LP + 16 * nt + r] = acc[nt][v];
 }
 
+// The same code-matrix product on the bf16 matrix cores.  An int8 code is exact in bfloat16
+// (8 significant bits) and the float32 factor is supplied as three bfloat16 planes
+// hi + mid + lo (24 significant bits together, see split_bf16x3), so
+//   code . w = code . hi + code . mid + code . lo
+// holds with every product exact and float32 accumulation in the matrix core: float32
+// accuracy at a fraction of the float32 MFMA cost (3 x 16 cycles instead of 8 x 32 per 32 k).
+// v_mfma_f32_16x16x32_bf16 operand layout (lane l): A[i = l%16][k = 8(l/16) .. +8],
+// B[k = 8(l/16) .. +8][j = l%16], D[i = 4(l/16)+v][j = l%16].  The reduction index may be
+// visited in any order: in a 64-deep chunk lane group kq = l/16 owns k = 16 kq .. 16 kq + 15
+// (one 16-byte load of codes), first half in MFMA step 0, second half in step 1.
+// Bp: [3][RP][Kp] bfloat16 planes of the factor, k fastest, zero padded (Kp % 64 == 0).
+// grid (ceil(rows/128), splits, 2 jobs); a wave owns 32 rows, the 4 waves share the chunk of
+// Bp through double-buffered LDS.  Needs K % 16 == 0, K >= 16 and 16-byte aligned codes.
+struct CodesJobBf16 {
+    const int8_t* Cq;       // rows x K codes
+    const uint16_t* Bp;     // [3][RP][Kp]
+    float* partial;         // [splits][rows][RP]
+    int rows, chunk, splits;
+};
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+// 8 int8 codes (two dwords) -> 8 bfloat16: float(code) keeps only its upper 16 bits.
+__device__ __forceinline__ v8bf codes_to_bf16(uint32_t lo, uint32_t hi) {
+    union { uint32_t u[4]; v8bf v; } r;
+    const uint32_t w[2] = {lo, hi};
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const float f0 = (float)(int)(int8_t)(w[h] & 0xff), f1 = (float)(int)(int8_t)((w[h] >> 8) & 0xff);
+        const float f2 = (float)(int)(int8_t)((w[h] >> 16) & 0xff), f3 = (float)(int)(int8_t)(w[h] >> 24);
+        r.u[2 * h + 0] = (__float_as_uint(f0) >> 16) | (__float_as_uint(f1) & 0xffff0000u);
+        r.u[2 * h + 1] = (__float_as_uint(f2) >> 16) | (__float_as_uint(f3) & 0xffff0000u);
+    }
+    return r.v;
+}
+
+#define CB_KC 64
+template <int NT>
+__global__ __launch_bounds__(256) void codes_mul_bf16_kernel(CodesJobBf16 j0, CodesJobBf16 j1, int K, int Kp) {
+    constexpr int RP = NT * 16, LDK = CB_KC + 8;
+    constexpr int PIECES = 3 * RP * (CB_KC / 8);        // 16-byte pieces of a staged chunk
+    constexpr int PPT = (PIECES + 255) / 256;
+    __shared__ __align__(16) uint16_t bs[2][3 * RP * LDK];
+    const CodesJobBf16 job = blockIdx.z == 0 ? j0 : j1;
+    if ((int)blockIdx.x * 128 >= job.rows || (int)blockIdx.y >= job.splits) return;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int li = lane & 15, kq = lane >> 4;
+    const int r0 = blockIdx.x * 128 + wave * 32;
+    const int kb = blockIdx.y * job.chunk, ke = min(K, kb + job.chunk);
+    const int8_t* ap[2];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) ap[mt] = job.Cq + (size_t)min(r0 + 16 * mt + li, job.rows - 1) * K;
+    v4f acc[2][NT];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (v4f){0.f, 0.f, 0.f, 0.f};
+    uint4 ca[2], breg[PPT];
+    auto load_chunk = [&](int k0) {     // rows past the end re-read the last row (never stored)
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+            ca[mt] = *reinterpret_cast<const uint4*>(ap[mt] + min(k0 + 16 * kq, K - 16));
+#pragma unroll
+        for (int u = 0; u < PPT; ++u) {
+            const int p = min((int)threadIdx.x + 256 * u, PIECES - 1);
+            breg[u] = *reinterpret_cast<const uint4*>(job.Bp + (size_t)(p >> 3) * Kp + k0 + 8 * (p & 7));
+        }
+    };
+    auto store_chunk = [&](int buf) {
+#pragma unroll
+        for (int u = 0; u < PPT; ++u) {
+            const int p = threadIdx.x + 256 * u;
+            if (p < PIECES) *reinterpret_cast<uint4*>(&bs[buf][(p >> 3) * LDK + 8 * (p & 7)]) = breg[u];
+        }
+    };
+    if (kb < ke) load_chunk(kb);
+    int buf = 0;
+    for (int k0 = kb; k0 < ke; k0 += CB_KC, buf ^= 1) {
+        store_chunk(buf);
+        const uint4 c0 = ca[0], c1 = ca[1];
+        // a chunk cut by K: its codes beyond K meet zero planes (Kp padding), so no mask is needed
+        if (k0 + CB_KC < ke) load_chunk(k0 + CB_KC);
+        __syncthreads();                // bs[buf] complete; bs[buf ^ 1] no longer read
+#pragma unroll
+        for (int sidx = 0; sidx < 2; ++sidx) {
+            const v8bf a0 = sidx == 0 ? codes_to_bf16(c0.x, c0.y) : codes_to_bf16(c0.z, c0.w);
+            const v8bf a1 = sidx == 0 ? codes_to_bf16(c1.x, c1.y) : codes_to_bf16(c1.z, c1.w);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int pl = 0; pl < 3; ++pl) {
+                    union { uint4 u; v8bf v; } b;
+                    b.u = *reinterpret_cast<const uint4*>(&bs[buf][((pl * RP + 16 * nt + li) * LDK) + 16 * kq + 8 * sidx]);
+                    acc[0][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b.v, acc[0][nt], 0, 0, 0);
+                    acc[1][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b.v, acc[1][nt], 0, 0, 0);
+                }
+        }
+    }
+    float* out = job.partial + (size_t)blockIdx.y * job.rows * RP;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = r0 + 16 * mt + 4 * kq + v;
+                if (row < job.rows) out[(size_t)row * RP + 16 * nt + li] = acc[mt][nt][v];
+            }
+}
+
 // ---------------------------------------------------------------------------
 // T-type: partial[split][cols][LP] = R[i-range, :]^T . W[i-range, :]
 // grid (ceil(cols/64), splits); the 4 waves of a block share one 64-column strip,
@@ -425,9 +534,18 @@ int launch_resid_mul_t(const float* X, int rows, int cols, int axis, const float
     return LRQMM_OK;
 }
 
-int launch_codes_mul_n2(const int8_t* codesA, int rowsA, const float* WA, PassPlan planA, float* partialA,
-                        const int8_t* codesB, int rowsB, const float* WB, PassPlan planB, float* partialB,
-                        int K, int LP, hipStream_t st) {
+int launch_codes_mul_n2(const int8_t* codesA, int rowsA, const float* WA, const uint16_t* WA3, PassPlan planA,
+                        float* partialA, const int8_t* codesB, int rowsB, const float* WB, const uint16_t* WB3,
+                        PassPlan planB, float* partialB, int K, int Kp, int LP, hipStream_t st) {
+    const bool fast = (K % 16 == 0) && K >= 16 && ((uintptr_t)codesA % 16 == 0) && ((uintptr_t)codesB % 16 == 0);
+    if (fast) {
+        CodesJobBf16 j0 = {codesA, WA3, partialA, rowsA, planA.chunk, planA.splits};
+        CodesJobBf16 j1 = {codesB, WB3, partialB, rowsB, planB.chunk, planB.splits};
+        dim3 grid(ceil_div(max(rowsA, rowsB), 128), max(planA.splits, planB.splits), 2);
+        NT_SWITCH(LP / 16, hipLaunchKernelGGL((codes_mul_bf16_kernel<NT_>), grid, dim3(256), 0, st, j0, j1, K, Kp));
+        LRQ_CHECK_LAUNCH();
+        return LRQMM_OK;
+    }
     const bool vec = (K % 4 == 0) && ((uintptr_t)codesA % 4 == 0) && ((uintptr_t)codesB % 4 == 0);
     CodesJob j0 = {codesA, WA, partialA, rowsA, planA.chunk, planA.splits};
     CodesJob j1 = {codesB, WB, partialB, rowsB, planB.chunk, planB.splits};
