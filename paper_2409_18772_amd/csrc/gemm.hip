@@ -480,22 +480,25 @@ __device__ __forceinline__ float sum_slices(const float* __restrict__ p, int n, 
 struct BuildArgs {
     const float *U, *Sig, *sA, *partialA, *sB, *partialB, *Xp, *Gam, *Zt;
     float *Lp, *Rp;
-    int M, N, r, RP, R2P, splitsA, splitsB, nslices, nbL;
+    int M, N, r, RP, R2P, splitsA, splitsB, nslices, nbR;
 };
 
-#define BR_J 64     // columns j of C per workgroup of the right panel
-// Workgroups [0, nbL): left panel, one thread per entry:
+#define BR_J 16     // columns j of C per workgroup of the right panel: short strips, many workgroups --
+                    // a workgroup is a chain of three load latencies, so the strips run side by side
+// Workgroups [nbR, ...): left panel, one thread per entry:
 //   Lp[i][c] = U[i][c] Sig[c] (c < r),  sA[i] sum_sp partialA[sp][i][c-r] (r <= c < 2r), 0 beyond.
-// Then one workgroup per BR_J rows j of the right panel:
+// Workgroups [0, nbR) (the longer ones, dispatched first): BR_J rows j of the right panel each:
 //   Rp[j][c] = sB[j] sum_sp partialB[sp][j][c] + sum_u X[c][u] Gam[u] Zt[u][j]   (c < r),
 //              Gam[c-r] Zt[c-r][j] (r <= c < 2r), 0 beyond,
 // with X Gamma and the Zt strip staged in LDS so that global reads and writes stay coalesced.
 __global__ __launch_bounds__(256) void build_panels_kernel(BuildArgs a) {
-    __shared__ float xg[LRQMM_MAX_SKETCH * (LRQMM_MAX_SKETCH + 1)];
-    __shared__ float zt[LRQMM_MAX_SKETCH * (BR_J + 1)];
+    extern __shared__ float panel_lds[];        // sized by the launcher from r: xg | zt | pv
     const int r = a.r, RP = a.RP, R2P = a.R2P;
-    if ((int)blockIdx.x < a.nbL) {
-        const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    float* const xg = panel_lds;                 // r x (RP + 1): X Gamma
+    float* const zt = xg + r * (RP + 1);         // RP x (BR_J + 1): strip of Zt
+    float* const pv = zt + RP * (BR_J + 1);      // BR_J x RP: strip of (Vt B~)^T
+    if ((int)blockIdx.x >= a.nbR) {
+        const size_t idx = (size_t)(blockIdx.x - a.nbR) * 256 + threadIdx.x;
         if (idx >= (size_t)a.M * R2P) return;
         const int i = (int)(idx / R2P), c = (int)(idx % R2P);
         float v = 0.f;
@@ -508,25 +511,72 @@ __global__ __launch_bounds__(256) void build_panels_kernel(BuildArgs a) {
         a.Lp[idx] = v;
         return;
     }
-    const int j0 = ((int)blockIdx.x - a.nbL) * BR_J;
-    for (int e = threadIdx.x; e < r * r; e += 256) {
-        const int c = e / r, u = e - c * r;
-        xg[c * (r + 1) + u] = sum_slices<LRQ_VTW_MAX_SLICES>(a.Xp + e, a.nslices, (size_t)r * r) * a.Gam[u];
+    const int j0 = (int)blockIdx.x * BR_J;
+    for (int e0 = threadIdx.x; e0 < r * r; e0 += 4 * 256) {      // four entries' slice loads in flight
+        float x[4];
+#pragma unroll
+        for (int m = 0; m < 4; ++m)
+            x[m] = sum_slices<LRQ_VTW_MAX_SLICES>(a.Xp + min(e0 + 256 * m, r * r - 1), a.nslices, (size_t)r * r);
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const int e = e0 + 256 * m;
+            if (e < r * r) {
+                const int c = e / r, u = e - c * r;
+                xg[c * (RP + 1) + u] = x[m] * a.Gam[u];
+            }
+        }
     }
-    for (int e = threadIdx.x; e < r * BR_J; e += 256) {
-        const int u = e / BR_J, jl = e - u * BR_J;
-        zt[u * (BR_J + 1) + jl] = (j0 + jl < a.N) ? a.Zt[(size_t)u * a.N + j0 + jl] : 0.f;
+    for (int e0 = threadIdx.x; e0 < RP * BR_J; e0 += 4 * 256) {
+        float z[4];
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const int e = e0 + 256 * m;
+            const int u = min(e / BR_J, r - 1), j = min(j0 + e % BR_J, a.N - 1);
+            z[m] = a.Zt[(size_t)u * a.N + j];
+        }
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const int e = e0 + 256 * m;
+            const int u = e / BR_J, jl = e % BR_J;
+            if (e < RP * BR_J) zt[u * (BR_J + 1) + jl] = (u < r && j0 + jl < a.N) ? z[m] : 0.f;
+        }
+    }
+    for (int e = threadIdx.x; e < r * (RP - r); e += 256) {     // zero columns u >= r of X Gamma
+        const int c = e / (RP - r), u = r + e - c * (RP - r);
+        xg[c * (RP + 1) + u] = 0.f;
+    }
+    // sB[j] sum_sp partialB[sp][j][c] for the strip, four entries' split loads in flight
+    const size_t plane = (size_t)a.N * RP;
+    const int jn = min(BR_J, a.N - j0);
+    for (int e0 = threadIdx.x; e0 < jn * RP; e0 += 4 * 256) {
+        float x[4];
+#pragma unroll
+        for (int m = 0; m < 4; ++m)
+            x[m] = sum_slices<MAX_SPLITS>(a.partialB + (size_t)j0 * RP + min(e0 + 256 * m, jn * RP - 1), a.splitsB, plane);
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const int e = e0 + 256 * m;
+            if (e < jn * RP) pv[e] = x[m] * a.sB[j0 + e / RP];
+        }
     }
     __syncthreads();
-    const size_t plane = (size_t)a.N * RP;
     for (int e = threadIdx.x; e < BR_J * R2P; e += 256) {
         const int jl = e / R2P, c = e - jl * R2P;
         const int j = j0 + jl;
         if (j >= a.N) break;
         float v = 0.f;
         if (c < r) {
-            float acc = sum_slices<MAX_SPLITS>(a.partialB + (size_t)j * RP + c, a.splitsB, plane) * a.sB[j];
-            for (int u = 0; u < r; ++u) acc = fmaf(xg[c * (r + 1) + u], zt[u * (BR_J + 1) + jl], acc);
+            float acc = pv[jl * RP + c];
+            for (int u0 = 0; u0 < RP; u0 += 8) {       // rows u >= r of zt are zero
+                float xv[8], zv[8];
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    xv[t] = xg[c * (RP + 1) + u0 + t];
+                    zv[t] = zt[(u0 + t) * (BR_J + 1) + jl];
+                }
+#pragma unroll
+                for (int t = 0; t < 8; ++t) acc = fmaf(xv[t], zv[t], acc);
+            }
             v = acc;
         } else if (c < 2 * r) {
             v = a.Gam[c - r] * zt[(c - r) * (BR_J + 1) + jl];
@@ -572,9 +622,10 @@ int launch_build_panels(int M, int N, int K, int r, int RP, int R2P, const float
     a.Gam = Gam; a.Zt = Zt; a.Lp = Lp; a.Rp = Rp;
     a.M = M; a.N = N; a.r = r; a.RP = RP; a.R2P = R2P; a.splitsA = splitsA; a.splitsB = splitsB;
     a.nslices = ceil_div(K, ceil_div(K, vtw_slices(K)));
-    a.nbL = (int)(((size_t)M * R2P + 255) / 256);
-    const int total = a.nbL + ceil_div(N, BR_J);
-    hipLaunchKernelGGL(build_panels_kernel, dim3(total), dim3(256), 0, st, a);
+    a.nbR = ceil_div(N, BR_J);
+    const int total = a.nbR + (int)(((size_t)M * R2P + 255) / 256);
+    const size_t lds = sizeof(float) * ((size_t)r * (RP + 1) + (size_t)RP * (BR_J + 1) + (size_t)BR_J * RP);
+    hipLaunchKernelGGL(build_panels_kernel, dim3(total), dim3(256), lds, st, a);
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }

@@ -236,8 +236,7 @@ __global__ __launch_bounds__(256) void codes_mul_n_kernel(CodesJob j0, CodesJob 
 // visited in any order: in a 64-deep chunk lane group kq = l/16 owns k = 16 kq .. 16 kq + 15
 // (one 16-byte load of codes), first half in MFMA step 0, second half in step 1.
 // Bp: [3][RP][Kp] bfloat16 planes of the factor, k fastest, zero padded (Kp % 64 == 0).
-// grid (ceil(rows/128), splits, 2 jobs); a wave owns 32 rows, the 4 waves share the chunk of
-// Bp through double-buffered LDS.  Needs K % 16 == 0, K >= 16 and 16-byte aligned codes.
+// Needs K % 16 == 0, K >= 16 and 16-byte aligned codes.
 struct CodesJobBf16 {
     const int8_t* Cq;       // rows x K codes
     const uint16_t* Bp;     // [3][RP][Kp]
@@ -260,71 +259,98 @@ __device__ __forceinline__ v8bf codes_to_bf16(uint32_t lo, uint32_t hi) {
     return r.v;
 }
 
-#define CB_KC 64
+// Launch shape: grid (ceil(rows/256), splits, 2 jobs), one workgroup per CU.  A wave owns 64
+// rows; for each KB-deep slab of its split it issues ALL its code loads at once (KB bytes per
+// row, up to 128 registers), the four waves copy the slab of Bp into LDS meanwhile, and after
+// one barrier the matrix cores run through the slab without further waits: the HBM latency
+// is paid once per slab with the whole operand in flight.
 template <int NT>
-__global__ __launch_bounds__(256) void codes_mul_bf16_kernel(CodesJobBf16 j0, CodesJobBf16 j1, int K, int Kp) {
-    constexpr int RP = NT * 16, LDK = CB_KC + 8;
-    constexpr int PIECES = 3 * RP * (CB_KC / 8);        // 16-byte pieces of a staged chunk
-    constexpr int PPT = (PIECES + 255) / 256;
-    __shared__ __align__(16) uint16_t bs[2][3 * RP * LDK];
+struct CodesShape {
+    static constexpr int RP = NT * 16;
+    static constexpr int KB = NT <= 3 ? 512 : 256;      // slab depth: 3 RP (KB + 8) bf16 must fit LDS
+    static constexpr int LDK = KB + 8;
+    static constexpr int NC = KB / 64;                  // 64-deep chunks per slab
+    static constexpr int PIECES = 3 * RP * (KB / 8);    // 16-byte pieces of a slab of Bp
+    static constexpr int BATCH = 8;
+};
+
+template <int NT>
+__global__ __launch_bounds__(256, 1) void codes_mul_bf16_kernel(CodesJobBf16 j0, CodesJobBf16 j1, int K, int Kp) {
+    using S = CodesShape<NT>;
+    constexpr int RP = S::RP, KB = S::KB, LDK = S::LDK, NC = S::NC;
+    __shared__ __align__(16) uint16_t bs[3 * RP * LDK];
     const CodesJobBf16 job = blockIdx.z == 0 ? j0 : j1;
-    if ((int)blockIdx.x * 128 >= job.rows || (int)blockIdx.y >= job.splits) return;
+    if ((int)blockIdx.x * 256 >= job.rows || (int)blockIdx.y >= job.splits) return;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int li = lane & 15, kq = lane >> 4;
-    const int r0 = blockIdx.x * 128 + wave * 32;
+    const int r0 = blockIdx.x * 256 + wave * 64;
     const int kb = blockIdx.y * job.chunk, ke = min(K, kb + job.chunk);
-    const int8_t* ap[2];
+    const int8_t* ap[4];
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt) ap[mt] = job.Cq + (size_t)min(r0 + 16 * mt + li, job.rows - 1) * K;
-    v4f acc[2][NT];
+    for (int mt = 0; mt < 4; ++mt) ap[mt] = job.Cq + (size_t)min(r0 + 16 * mt + li, job.rows - 1) * K;
+    v4f acc[4][NT];
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
+    for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (v4f){0.f, 0.f, 0.f, 0.f};
-    uint4 ca[2], breg[PPT];
-    auto load_chunk = [&](int k0) {     // rows past the end re-read the last row (never stored)
+    for (int ks = kb; ks < ke; ks += KB) {
+        // codes of the whole slab; rows past the end re-read the last row (never stored), and
+        // codes past K meet zero planes, so clamped addresses need no mask
+        uint4 ca[4][NC];
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-            ca[mt] = *reinterpret_cast<const uint4*>(ap[mt] + min(k0 + 16 * kq, K - 16));
+        for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-        for (int u = 0; u < PPT; ++u) {
-            const int p = min((int)threadIdx.x + 256 * u, PIECES - 1);
-            breg[u] = *reinterpret_cast<const uint4*>(job.Bp + (size_t)(p >> 3) * Kp + k0 + 8 * (p & 7));
-        }
-    };
-    auto store_chunk = [&](int buf) {
+            for (int c = 0; c < NC; ++c)
+                ca[mt][c] = *reinterpret_cast<const uint4*>(ap[mt] + min(ks + 64 * c + 16 * kq, K - 16));
+        if (ks > kb) __syncthreads();       // previous slab no longer read
+        for (int p0 = threadIdx.x; p0 < S::PIECES; p0 += 256 * S::BATCH) {
+            uint4 t[S::BATCH];
 #pragma unroll
-        for (int u = 0; u < PPT; ++u) {
-            const int p = threadIdx.x + 256 * u;
-            if (p < PIECES) *reinterpret_cast<uint4*>(&bs[buf][(p >> 3) * LDK + 8 * (p & 7)]) = breg[u];
-        }
-    };
-    if (kb < ke) load_chunk(kb);
-    int buf = 0;
-    for (int k0 = kb; k0 < ke; k0 += CB_KC, buf ^= 1) {
-        store_chunk(buf);
-        const uint4 c0 = ca[0], c1 = ca[1];
-        // a chunk cut by K: its codes beyond K meet zero planes (Kp padding), so no mask is needed
-        if (k0 + CB_KC < ke) load_chunk(k0 + CB_KC);
-        __syncthreads();                // bs[buf] complete; bs[buf ^ 1] no longer read
+            for (int u = 0; u < S::BATCH; ++u) {
+                const int p = min(p0 + 256 * u, S::PIECES - 1);
+                const int rowp = p / (KB / 8), seg = p - rowp * (KB / 8);
+                const int k = ks + 8 * seg;
+                const uint4 v = *reinterpret_cast<const uint4*>(job.Bp + (size_t)rowp * Kp + min(k, Kp - 8));
+                t[u] = (k < Kp) ? v : make_uint4(0u, 0u, 0u, 0u);
+            }
 #pragma unroll
-        for (int sidx = 0; sidx < 2; ++sidx) {
-            const v8bf a0 = sidx == 0 ? codes_to_bf16(c0.x, c0.y) : codes_to_bf16(c0.z, c0.w);
-            const v8bf a1 = sidx == 0 ? codes_to_bf16(c1.x, c1.y) : codes_to_bf16(c1.z, c1.w);
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                for (int pl = 0; pl < 3; ++pl) {
-                    union { uint4 u; v8bf v; } b;
-                    b.u = *reinterpret_cast<const uint4*>(&bs[buf][((pl * RP + 16 * nt + li) * LDK) + 16 * kq + 8 * sidx]);
-                    acc[0][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b.v, acc[0][nt], 0, 0, 0);
-                    acc[1][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b.v, acc[1][nt], 0, 0, 0);
+            for (int u = 0; u < S::BATCH; ++u) {
+                const int p = p0 + 256 * u;
+                if (p < S::PIECES) {
+                    const int rowp = p / (KB / 8), seg = p - rowp * (KB / 8);
+                    *reinterpret_cast<uint4*>(&bs[rowp * LDK + 8 * seg]) = t[u];
                 }
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            if (ks + 64 * c < ke) {             // uniform
+#pragma unroll
+                for (int sidx = 0; sidx < 2; ++sidx) {
+                    v8bf af[4];
+#pragma unroll
+                    for (int mt = 0; mt < 4; ++mt)
+                        af[mt] = sidx == 0 ? codes_to_bf16(ca[mt][c].x, ca[mt][c].y)
+                                           : codes_to_bf16(ca[mt][c].z, ca[mt][c].w);
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                        for (int pl = 0; pl < 3; ++pl) {
+                            union { uint4 u; v8bf v; } b;
+                            b.u = *reinterpret_cast<const uint4*>(
+                                &bs[(pl * RP + 16 * nt + li) * LDK + 64 * c + 16 * kq + 8 * sidx]);
+#pragma unroll
+                            for (int mt = 0; mt < 4; ++mt)
+                                acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[mt], b.v, acc[mt][nt], 0, 0, 0);
+                        }
+                }
+            }
         }
     }
     float* out = job.partial + (size_t)blockIdx.y * job.rows * RP;
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
+    for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
@@ -541,7 +567,7 @@ int launch_codes_mul_n2(const int8_t* codesA, int rowsA, const float* WA, const 
     if (fast) {
         CodesJobBf16 j0 = {codesA, WA3, partialA, rowsA, planA.chunk, planA.splits};
         CodesJobBf16 j1 = {codesB, WB3, partialB, rowsB, planB.chunk, planB.splits};
-        dim3 grid(ceil_div(max(rowsA, rowsB), 128), max(planA.splits, planB.splits), 2);
+        dim3 grid(ceil_div(max(rowsA, rowsB), 256), max(planA.splits, planB.splits), 2);
         NT_SWITCH(LP / 16, hipLaunchKernelGGL((codes_mul_bf16_kernel<NT_>), grid, dim3(256), 0, st, j0, j1, K, Kp));
         LRQ_CHECK_LAUNCH();
         return LRQMM_OK;
