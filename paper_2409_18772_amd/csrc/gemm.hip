@@ -397,15 +397,20 @@ __device__ __forceinline__ void vtw_block(const float* __restrict__ Vt, const fl
     }
 }
 
-// x = hi + mid + lo with each term a bfloat16 (the upper 16 bits of a float32): every term
-// takes the next 8 significant bits by truncation and the subtractions are exact, so the sum
-// carries 24 bits (the remainder is below 2^-23 |x|, and exactly zero for most inputs).
+// x = hi + mid + lo with each term a bfloat16 (the upper 16 bits of a float32): every term is
+// the round-to-nearest-even bfloat16 of what is left and the subtractions are exact, so the
+// remainder is below 2^-27 |x| -- the three planes carry x to better than float32 precision.
+// (Finite inputs; rounding cannot overflow for |x| < 2^127.)
+__device__ __forceinline__ uint32_t bf16_rne_bits(float x) {
+    const uint32_t u = __float_as_uint(x);
+    return (u + 0x7fffu + ((u >> 16) & 1u)) & 0xffff0000u;
+}
 __device__ __forceinline__ void split_bf16x3(float x, uint16_t (&h)[3]) {
-    const uint32_t b0 = __float_as_uint(x) & 0xffff0000u;
+    const uint32_t b0 = bf16_rne_bits(x);
     const float r1 = x - __uint_as_float(b0);
-    const uint32_t b1 = __float_as_uint(r1) & 0xffff0000u;
+    const uint32_t b1 = bf16_rne_bits(r1);
     const float r2 = r1 - __uint_as_float(b1);
-    const uint32_t b2 = __float_as_uint(r2) & 0xffff0000u;
+    const uint32_t b2 = bf16_rne_bits(r2);
     h[0] = (uint16_t)(b0 >> 16);
     h[1] = (uint16_t)(b1 >> 16);
     h[2] = (uint16_t)(b2 >> 16);

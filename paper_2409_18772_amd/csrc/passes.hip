@@ -227,7 +227,7 @@ __global__ __launch_bounds__(256) void codes_mul_n_kernel(CodesJob j0, CodesJob 
 
 // The same code-matrix product on the bf16 matrix cores.  An int8 code is exact in bfloat16
 // (8 significant bits) and the float32 factor is supplied as three bfloat16 planes
-// hi + mid + lo (24 significant bits together, see split_bf16x3), so
+// hi + mid + lo (exact to 2^-27, see split_bf16x3), so
 //   code . w = code . hi + code . mid + code . lo
 // holds with every product exact and float32 accumulation in the matrix core: float32
 // accuracy at a fraction of the float32 MFMA cost (3 x 16 cycles instead of 8 x 32 per 32 k).
