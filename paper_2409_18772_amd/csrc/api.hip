@@ -211,9 +211,15 @@ static int rsvd_plan(LaunchList& ops, const float* X, const float* amax, int row
     if (carve_rsvd(a, rows, cols, axis, LP, rank, &w) > workspace_bytes) return LRQMM_ERR_WORKSPACE;
     const QuantParams q = make_quant_params(bits, round_mode);
     const int nscale = axis == LRQMM_AXIS_ROW ? rows : cols;
-    ops.push_back([=] { return launch_scales(amax, nscale, pad_to(nscale, 4), q.qmaxf, w.lam, w.s, st); });
-    if (omega_or_null) ops.push_back([=] { return launch_pad_copy(omega_or_null, cols, ell, LP, w.Wc, st); });
-    else ops.push_back([=] { return launch_fill_sketch(seed, axis, cols, ell, LP, w.Wc, st); });
+    if (omega_or_null) {
+        ops.push_back([=] { return launch_scales(amax, nscale, pad_to(nscale, 4), q.qmaxf, w.lam, w.s, st); });
+        ops.push_back([=] { return launch_pad_copy(omega_or_null, cols, ell, LP, w.Wc, st); });
+    } else {
+        ops.push_back([=] {
+            return launch_sketch_and_scales(seed, axis, cols, ell, LP, w.Wc, amax, nscale, pad_to(nscale, 4), q.qmaxf,
+                                            w.lam, w.s, st);
+        });
+    }
     const PassPlan pn = plan_pass_n(rows, cols), pt = plan_pass_t(rows, cols);
     // Q = orth(partial sums) in place: Gram (float64) -> Cholesky -> Q = Y T
     auto orth = [&](int splits, int n, float* buf) {
@@ -243,8 +249,10 @@ static int rsvd_plan(LaunchList& ops, const float* X, const float* amax, int row
     ops.push_back([=] { return launch_reduce_gram(w.partial, pt.splits, cols, LP, nullptr, w.Wc, w.gpart, st); });
     ops.push_back([=] { return launch_gram_sum(w.gpart, gram_blocks(cols), LP, w.gram, st); });
     ops.push_back([=] { return launch_small_svd(w.gram, ell, LP, rank, Sigma, w.Ur, w.Mv, st); });
-    ops.push_back([=] { return launch_apply(w.Yr, rows, LP, w.Ur, rank, rank, U, rank, 0, st); });
-    ops.push_back([=] { return launch_apply(w.Wc, cols, LP, w.Mv, rank, rank, Vt, cols, 1, st); });
+    ops.push_back([=] {
+        return launch_apply2(w.Yr, rows, w.Ur, rank, rank, U, rank, 0, w.Wc, cols, w.Mv, rank, rank, Vt, cols, 1, LP,
+                             st);
+    });
     return LRQMM_OK;
 }
 

@@ -18,6 +18,11 @@ int launch_scales(const float* amax, int n, int npad, float qmaxf, float* lam, f
 // omega[i*ld + j] for i < rows, j < ld; columns j >= cols are zero.
 int launch_fill_sketch(uint64_t seed, int stream_id, int rows, int cols, int ld, float* omega,
                        hipStream_t st);
+// The same plus, in the same launch, the step vectors of the operand: lam[i] = qmax/amax[i],
+// s[i] = amax[i]/qmax for i < n, zero up to npad (skipped when amax is null).
+int launch_sketch_and_scales(uint64_t seed, int stream_id, int rows, int cols, int ld, float* omega,
+                             const float* amax, int n, int npad, float qmaxf, float* lam, float* s,
+                             hipStream_t st);
 // dst[i*ld + j] = (j < cols) ? src[i*cols + j] : 0
 int launch_pad_copy(const float* src, int rows, int cols, int ld, float* dst, hipStream_t st);
 
@@ -59,6 +64,10 @@ int launch_chol_inverse(const double* gram, int ell, int LP, double* T, hipStrea
 // out = In[n x LP] . Mat[LP x cm]; normal: out[i*ldo + c]; transposed: out[c*ldo + i].
 int launch_apply(const float* In, int n, int LP, const double* Mat, int cm, int ldm, float* out,
                  int ldo, int transposed, hipStream_t st);
+// Two independent products of that kind in one launch.
+int launch_apply2(const float* In0, int n0, const double* Mat0, int cm0, int ldm0, float* out0, int ldo0,
+                  int transposed0, const float* In1, int n1, const double* Mat1, int cm1, int ldm1, float* out1,
+                  int ldo1, int transposed1, int LP, hipStream_t st);
 // Eigen-decomposition of the Gram matrix (l x l, leading dimension LP): Sigma[r] = sqrt of
 // the r largest eigenvalues, Ur (LP x r) their eigenvectors, Mv = Ur diag(1/Sigma).
 int launch_small_svd(const double* gram, int ell, int LP, int rank, float* Sigma, double* Ur,

@@ -247,14 +247,26 @@ __global__ __launch_bounds__(CHOL_THREADS) void chol_inverse_kernel(const double
 // loads KQ consecutive floats of its row (the wavefront's 16 rows form one contiguous block)
 // and, per step, one element of Mat.  Every wavefront reads all its rows before it writes any,
 // so `out` may alias `In` (same leading dimension).
+struct ApplyJob {
+    const float* In;
+    const double* Mat;
+    float* out;
+    int n, cm, ldm, ldo, transposed;
+};
+
+// Workgroups [0, nb0) work on job j0, the rest on j1.
 template <int NT>
-__global__ __launch_bounds__(64) void apply_kernel(const float* __restrict__ In, int n,
-                                                   const double* __restrict__ Mat, int cm, int ldm,
-                                                   float* __restrict__ out, int ldo, int transposed) {
+__global__ __launch_bounds__(64) void apply_kernel(ApplyJob j0, ApplyJob j1, int nb0) {
     constexpr int LP = NT * 16;
     constexpr int KQ = LP / 4;
+    const bool first = (int)blockIdx.x < nb0;
+    const ApplyJob job = first ? j0 : j1;
+    const float* __restrict__ In = job.In;
+    const double* __restrict__ Mat = job.Mat;
+    float* __restrict__ out = job.out;
+    const int n = job.n, cm = job.cm, ldm = job.ldm, ldo = job.ldo, transposed = job.transposed;
     const int l = threadIdx.x, li = l & 15, kq = l >> 4;
-    const int r0 = blockIdx.x * 16;
+    const int r0 = (first ? blockIdx.x : blockIdx.x - nb0) * 16;
     const int row = min(r0 + li, n - 1);
     const bool row_ok = r0 + li < n;
     float a[KQ];
@@ -589,14 +601,22 @@ int launch_chol_inverse(const double* gram, int ell, int LP, double* T, hipStrea
     return LRQMM_OK;
 }
 
-int launch_apply(const float* In, int n, int LP, const double* Mat, int cm, int ldm, float* out, int ldo,
-                 int transposed, hipStream_t st) {
-    if (n <= 0) return LRQMM_OK;
-    dim3 grid(ceil_div(n, 16));
-    NT_SWITCH(LP / 16, hipLaunchKernelGGL((apply_kernel<NT_>), grid, dim3(64), 0, st, In, n, Mat, cm, ldm, out,
-                                          ldo, transposed));
+int launch_apply2(const float* In0, int n0, const double* Mat0, int cm0, int ldm0, float* out0, int ldo0,
+                  int transposed0, const float* In1, int n1, const double* Mat1, int cm1, int ldm1, float* out1,
+                  int ldo1, int transposed1, int LP, hipStream_t st) {
+    const ApplyJob j0 = {In0, Mat0, out0, n0, cm0, ldm0, ldo0, transposed0};
+    const ApplyJob j1 = {In1, Mat1, out1, n1, cm1, ldm1, ldo1, transposed1};
+    const int nb0 = n0 > 0 ? ceil_div(n0, 16) : 0, nb1 = n1 > 0 ? ceil_div(n1, 16) : 0;
+    if (nb0 + nb1 == 0) return LRQMM_OK;
+    NT_SWITCH(LP / 16, hipLaunchKernelGGL((apply_kernel<NT_>), dim3(nb0 + nb1), dim3(64), 0, st, j0, j1, nb0));
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
+}
+
+int launch_apply(const float* In, int n, int LP, const double* Mat, int cm, int ldm, float* out, int ldo,
+                 int transposed, hipStream_t st) {
+    return launch_apply2(In, n, Mat, cm, ldm, out, ldo, transposed, nullptr, 0, nullptr, 0, 0, nullptr, 0, 0, LP,
+                         st);
 }
 
 int launch_small_svd(const double* gram, int ell, int LP, int rank, float* Sigma, double* Ur, double* Mv,

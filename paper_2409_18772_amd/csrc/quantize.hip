@@ -108,13 +108,17 @@ __global__ __launch_bounds__(256) void absmax_cols_kernel(const float* __restric
     const int r0 = blockIdx.y * rows_per_block;
     const int r1 = min(rows, r0 + rows_per_block);
     float4 m = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll 4
-    for (int r = r0; r < r1; ++r) {
-        float4 v = load4f<VEC>(X + (size_t)r * cols, c, cols, true);
-        m.x = fmaxf(m.x, fabsf(v.x));
-        m.y = fmaxf(m.y, fabsf(v.y));
-        m.z = fmaxf(m.z, fabsf(v.z));
-        m.w = fmaxf(m.w, fabsf(v.w));
+    for (int rb = r0; rb < r1; rb += 16) {      // 16 row loads in flight per thread (rows clamped, max is idempotent)
+        float4 v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) v[u] = load4f<VEC>(X + (size_t)min(rb + u, r1 - 1) * cols, c, cols, true);
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            m.x = fmaxf(m.x, fabsf(v[u].x));
+            m.y = fmaxf(m.y, fabsf(v[u].y));
+            m.z = fmaxf(m.z, fabsf(v[u].z));
+            m.w = fmaxf(m.w, fabsf(v[u].w));
+        }
     }
     if (c + 0 < cols) atomicMax(amax_bits + c + 0, __float_as_uint(m.x));
     if (c + 1 < cols) atomicMax(amax_bits + c + 1, __float_as_uint(m.y));

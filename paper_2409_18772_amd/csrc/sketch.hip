@@ -95,7 +95,21 @@ __device__ static float gaussian_at(uint64_t key, uint32_t i, uint32_t j) {
     return (float)(rad * t);
 }
 
-__global__ void fill_sketch_kernel(uint64_t key, int rows, int cols, int ld, float* __restrict__ omega) {
+// Workgroups [0, nb_sketch) fill the sketch; the following ones (if any) derive the step
+// vectors lambda = qmax/amax, s = amax/qmax of the operand the sketch is for, so that the
+// preparation of a factorization is one launch.
+__global__ void fill_sketch_kernel(uint64_t key, int rows, int cols, int ld, float* __restrict__ omega,
+                                   int nb_sketch, const float* __restrict__ amax, int n, int npad, float qmaxf,
+                                   float* __restrict__ lam, float* __restrict__ s) {
+    if ((int)blockIdx.x >= nb_sketch) {
+        const int i = ((int)blockIdx.x - nb_sketch) * blockDim.x + threadIdx.x;
+        if (i >= npad) return;
+        float l = 0.0f, st = 0.0f;
+        if (i < n) make_scales(amax[i], qmaxf, l, st);
+        lam[i] = l;
+        s[i] = st;
+        return;
+    }
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t total = (size_t)rows * ld;
     if (idx >= total) return;
@@ -121,11 +135,19 @@ static uint64_t host_mix64(uint64_t z) {
 
 int launch_fill_sketch(uint64_t seed, int stream_id, int rows, int cols, int ld, float* omega,
                        hipStream_t st) {
+    return launch_sketch_and_scales(seed, stream_id, rows, cols, ld, omega, nullptr, 0, 0, 0.f, nullptr, nullptr,
+                                    st);
+}
+
+int launch_sketch_and_scales(uint64_t seed, int stream_id, int rows, int cols, int ld, float* omega,
+                             const float* amax, int n, int npad, float qmaxf, float* lam, float* s,
+                             hipStream_t st) {
     const uint64_t key = host_mix64(seed + 0x9E3779B97F4A7C15ull * (uint64_t)(stream_id + 1));
     const size_t total = (size_t)rows * ld;
-    if (total == 0) return LRQMM_OK;
-    hipLaunchKernelGGL(fill_sketch_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, key,
-                       rows, cols, ld, omega);
+    const int nb_sketch = (int)((total + 255) / 256), nb_scale = amax ? (npad + 255) / 256 : 0;
+    if (nb_sketch + nb_scale == 0) return LRQMM_OK;
+    hipLaunchKernelGGL(fill_sketch_kernel, dim3(nb_sketch + nb_scale), dim3(256), 0, st, key, rows, cols, ld,
+                       omega, nb_sketch, amax, n, npad, qmaxf, lam, s);
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }
