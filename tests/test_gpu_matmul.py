@@ -140,3 +140,33 @@ def test_resnet_conv_shape_sampled_rows():
     ref = o.lrqmm(A, B, w.bits, w.rank, w.oversample, w.power_iters, seed=w.sketch_seed, row_sample=rows,
                   want_cint=False)
     assert rel_fro(ref["C"], C[rows]) < TOL
+
+
+def test_largest_config_properties():
+    """c4 (16384^3, l = 80, two power iterations) at full size: the oracle's factorization of two
+    16384^2 residuals does not fit a test's time budget, so this checks what must hold at any size:
+    finite output, bit-identical repeat, and on sampled rows an error against the exact float64
+    product far below that of direct (floor) quantization computed by the same library."""
+    import torch
+    import paper_2409_18772_amd as L
+    w = wl.CONFIGS["c4_16384_int4_r64"]
+    say("inputs", w.name)
+    A, B = wl.make_inputs(w)
+    dA, dB = to_dev(A), to_dev(B)
+    ws = L.Workspace.for_problem(w.M, w.N, w.K, w.rank, w.oversample)
+    say("matmul full", w.name)
+    C = L.lrqmm_matmul(dA, dB, w.bits, w.rank, w.oversample, w.power_iters, seed=w.sketch_seed, workspace=ws)
+    rows = np.random.default_rng(7).choice(w.M, size=12, replace=False)
+    ridx = torch.from_numpy(rows).cuda()
+    Cr = C[ridx].cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(Cr))
+    C2 = L.lrqmm_matmul(dA, dB, w.bits, w.rank, w.oversample, w.power_iters, seed=w.sketch_seed, workspace=ws)
+    assert torch.equal(C, C2)
+    del C2
+    C0 = L.lrqmm_matmul(dA, dB, w.bits, 0, workspace=ws)
+    C0r = C0[ridx].cpu().numpy().astype(np.float64)
+    say("exact product on", len(rows), "rows")
+    exact = A[rows].astype(np.float64) @ B.astype(np.float64)
+    e_lr, e_dq = o.rel_err(exact, Cr), o.rel_err(exact, C0r)
+    say(w.name, "err lrqmm", e_lr, "err direct quant", e_dq)
+    assert e_lr * 10.0 < e_dq
