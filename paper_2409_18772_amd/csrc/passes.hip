@@ -20,11 +20,11 @@ __device__ __forceinline__ v4f mfma16(float a, float b, v4f c) {
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
 
-// Register image of one thread's share of W[k0 .. k0+KCHUNK)[0..LP) (row-major, ld = LP).
-template <int NT>
+// Register image of one thread's share of W[k0 .. k0+KC)[0..LP) (row-major, ld = LP).
+template <int NT, int KC = KCHUNK>
 struct WStage {
     static constexpr int LP = NT * 16;
-    static constexpr int N4 = KCHUNK * LP / 4 / 256;   // float4 per thread (LP multiple of 16)
+    static constexpr int N4 = KC * LP / 4 / 256;   // float4 per thread (LP multiple of 16)
     float4 v[N4];
     __device__ __forceinline__ void load(const float* __restrict__ W, int k0, int kend) {
 #pragma unroll
@@ -59,8 +59,11 @@ __global__ __launch_bounds__(256) void resid_mul_n_kernel(
     const float* __restrict__ sc, QuantParams q, const float* __restrict__ W, int chunk,
     float* __restrict__ partial) {
     constexpr int LP = NT * 16;
-    __shared__ __align__(16) float wl[2][KCHUNK * (LP + 4)];
-    __shared__ __align__(16) float sl[2][2 * KCHUNK];   // per-column lambda | step of the chunk (AXIS 1)
+    // wide sketches stage 64-deep chunks: 128 x (LP + 4) floats twice would leave one workgroup per CU
+    constexpr int KC = NT <= 3 ? KCHUNK : KCHUNK / 2;
+    constexpr int KS = KC / 16;          // float4 loads per lane per chunk
+    __shared__ __align__(16) float wl[2][KC * (LP + 4)];
+    __shared__ __align__(16) float sl[2][2 * KC];   // per-column lambda | step of the chunk (AXIS 1)
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r = lane & 15, g = lane >> 4;
     const int row = blockIdx.x * 64 + wave * 16 + r;
@@ -77,16 +80,16 @@ __global__ __launch_bounds__(256) void resid_mul_n_kernel(
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) acc[nt] = (v4f){0.f, 0.f, 0.f, 0.f};
 
-    float4 xr[KSUB];
+    float4 xr[KS];
     float scale_reg = 0.f;     // this thread's element of the chunk's lambda (t < 128) or step vector
-    WStage<NT> ws;
+    WStage<NT, KC> ws;
     auto load_x = [&](int k0) {
 #pragma unroll
-        for (int j = 0; j < KSUB; ++j) xr[j] = load4f<VEC>(xp, k0 + 16 * j + 4 * g, ke, row_ok);
+        for (int j = 0; j < KS; ++j) xr[j] = load4f<VEC>(xp, k0 + 16 * j + 4 * g, ke, row_ok);
         if (AXIS == 1) {
-            const int t = threadIdx.x & (KCHUNK - 1);
+            const int t = threadIdx.x & (KC - 1);
             const int kc = min(k0 + t, ke - 1);
-            const float v = (threadIdx.x < KCHUNK) ? lam[kc] : sc[kc];
+            const float v = ((threadIdx.x & KC) == 0) ? lam[kc] : sc[kc];
             scale_reg = (k0 + t < ke) ? v : 0.f;
         }
     };
@@ -95,33 +98,33 @@ __global__ __launch_bounds__(256) void resid_mul_n_kernel(
         ws.load(W, kb, ke);
     }
     int buf = 0;
-    for (int k0 = kb; k0 < ke; k0 += KCHUNK, buf ^= 1) {
+    for (int k0 = kb; k0 < ke; k0 += KC, buf ^= 1) {
         ws.store(wl[buf]);
-        if (AXIS == 1) sl[buf][threadIdx.x] = scale_reg;
+        if (AXIS == 1 && threadIdx.x < 2 * KC) sl[buf][threadIdx.x] = scale_reg;
         __syncthreads();             // wl[buf], sl[buf] complete; the other buffers no longer read
-        float res[KSUB][4];
+        float res[KS][4];
 #pragma unroll
-        for (int j = 0; j < KSUB; ++j) {
+        for (int j = 0; j < KS; ++j) {
             float4 l4, s4;
             if (AXIS == 0) {
                 l4 = make_float4(lam_r, lam_r, lam_r, lam_r);
                 s4 = make_float4(s_r, s_r, s_r, s_r);
             } else {
                 l4 = *reinterpret_cast<const float4*>(&sl[buf][16 * j + 4 * g]);
-                s4 = *reinterpret_cast<const float4*>(&sl[buf][KCHUNK + 16 * j + 4 * g]);
+                s4 = *reinterpret_cast<const float4*>(&sl[buf][KC + 16 * j + 4 * g]);
             }
             res[j][0] = quant_residual(xr[j].x, l4.x, s4.x, q);
             res[j][1] = quant_residual(xr[j].y, l4.y, s4.y, q);
             res[j][2] = quant_residual(xr[j].z, l4.z, s4.z, q);
             res[j][3] = quant_residual(xr[j].w, l4.w, s4.w, q);
         }
-        if (k0 + KCHUNK < ke) {      // next chunk's loads fly during this chunk's MFMAs
-            load_x(k0 + KCHUNK);
-            ws.load(W, k0 + KCHUNK, ke);
+        if (k0 + KC < ke) {      // next chunk's loads fly during this chunk's MFMAs
+            load_x(k0 + KC);
+            ws.load(W, k0 + KC, ke);
         }
         const float* wb = wl[buf];
 #pragma unroll
-        for (int j = 0; j < KSUB; ++j) {
+        for (int j = 0; j < KS; ++j) {
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const float* wrow = wb + (16 * j + 4 * g + t) * (LP + 4) + r;
