@@ -130,8 +130,13 @@ LRQMM_API int lrqmm_gemm(int M, int N, int K, int bits, int rank,
  * With rank > 0 the work on B (quantization, factorization of R_B) is enqueued on
  * a second stream owned by the library (created on first use, default priority),
  * forked from and joined back into `stream` with events, so the call is still
- * ordered like a single-stream call from the caller's point of view.  Calls must
- * not be issued concurrently from several host threads.
+ * ordered like a single-stream call from the caller's point of view.  For large
+ * problems the integer product is enqueued on a third library stream while both
+ * factorizations are in their small SVD (the GPU is nearly idle then); it leaves
+ * raw int32 sums in C's memory, and the dequantizing rank-2r update runs after the
+ * panels as a kernel of its own with the arithmetic of the fused epilogue (same
+ * bits).  C must therefore not be read between the call and its completion on
+ * `stream`.  Calls must not be issued concurrently from several host threads.
  */
 LRQMM_API int lrqmm_matmul(int M, int N, int K, int bits, int rank, int oversample, int power_iters,
                  uint64_t seed, int round_mode, const float* A, const float* B, float* C,
@@ -148,9 +153,12 @@ LRQMM_API int lrqmm_matmul(int M, int N, int K, int bits, int rank, int oversamp
  * *ncalls (host pointer), then resets the call counter.  Not thread safe.
  *   stage 0 quantize A   stage 1 RSVD of R_A     (caller's stream)
  *   stage 2 quantize B   stage 3 RSVD of R_B     (library's second stream, concurrent with 0-1)
- *   stage 4 compensation panels   stage 5 int8 GEMM kernel with fused epilogue
+ *   stage 4 compensation panels
+ *   stage 5 int8 GEMM kernel with fused epilogue, or -- when the integer product ran early,
+ *           see lrqmm_matmul -- the dequantizing rank-2r update kernel alone
+ *   stage 6 the early integer product on the library's third stream (0 when fused)
  */
-#define LRQMM_PROF_STAGES 6
+#define LRQMM_PROF_STAGES 7
 LRQMM_API int lrqmm_profile_enable(int on);
 LRQMM_API int lrqmm_profile_read(float* stage_ms, int* ncalls);
 

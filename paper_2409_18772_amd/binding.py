@@ -16,7 +16,7 @@ _LIB = None
 
 EXPORTS = ("lrqmm_status_string", "lrqmm_workspace_bytes", "lrqmm_quantize", "lrqmm_fill_sketch",
            "lrqmm_rsvd", "lrqmm_gemm", "lrqmm_matmul", "lrqmm_profile_enable", "lrqmm_profile_read")
-PROF_STAGES = ("quantize_a", "rsvd_a", "quantize_b", "rsvd_b", "panels", "gemm")
+PROF_STAGES = ("quantize_a", "rsvd_a", "quantize_b", "rsvd_b", "panels", "gemm", "int_gemm")
 
 
 class LrqmmError(RuntimeError):

@@ -83,6 +83,7 @@ size_t carve_gemm(Arena& a, int M, int N, int K, int rank, GemmWs* w) {
 struct MatmulWs {
     int8_t *Aq, *BqT;
     float *amaxA, *amaxB, *U, *Sig, *Vt, *W, *Gam, *Zt;
+    uint32_t* tick;
     void *sub, *subA, *subB;          // gemm scratch aliases the two rsvd regions
     size_t sub_bytes, subA_bytes, subB_bytes;
 };
@@ -93,6 +94,7 @@ size_t carve_matmul(Arena& a, int M, int N, int K, int rank, int oversample, Mat
     t.BqT = a.take<int8_t>((size_t)N * K);
     t.amaxA = a.take<float>(M);
     t.amaxB = a.take<float>(N);
+    t.tick = a.take<uint32_t>(64);
     if (rank > 0) {
         t.U = a.take<float>((size_t)M * rank);
         t.Sig = a.take<float>(rank);
@@ -128,12 +130,14 @@ size_t carve_matmul(Arena& a, int M, int N, int K, int rank, int oversample, Mat
 
 // Optional stage timing of lrqmm_matmul with HIP events recorded on the caller's stream.
 constexpr int kProfStages = LRQMM_PROF_STAGES;
-constexpr int kProfEvents = 9;
+constexpr int kProfEvents = 11;
 constexpr int kProfMaxCalls = 512;
 // event indices: 0-2 main stream (quantize A, RSVD A), 3-5 side stream (quantize B, RSVD B),
-// 6-8 main stream after the join (panels, GEMM)
-constexpr int kStageBegin[kProfStages] = {0, 1, 3, 4, 6, 7};
-constexpr int kStageEnd[kProfStages] = {1, 2, 4, 5, 7, 8};
+// 6-8 main stream after the join (panels, GEMM or rank update), 9-10 the early integer GEMM on
+// the third stream (recorded back to back on the main stream when that schedule is not used)
+constexpr int kStageBegin[kProfStages] = {0, 1, 3, 4, 6, 7, 9};
+constexpr int kStageEnd[kProfStages] = {1, 2, 4, 5, 7, 8, 10};
+constexpr int kLastMainEvent = 8;
 struct Prof {
     bool on = false;
     int ncalls = 0;
@@ -143,14 +147,19 @@ struct Prof {
 
 // Second stream (default priority) on which the factorization of R_B runs next to R_A's.
 struct Side {
-    hipStream_t stream = nullptr;
+    hipStream_t stream = nullptr;        // factorization of R_B
+    hipStream_t gemm_stream = nullptr;   // early integer GEMM
     hipEvent_t fork = nullptr, join = nullptr;
+    hipEvent_t qa = nullptr, qb = nullptr, gate = nullptr, gate_b = nullptr, gdone = nullptr;
     bool ok = false;
 } g_side;
 
 bool side_ready() {
     if (g_side.ok) return true;
     if (hipStreamCreateWithFlags(&g_side.stream, hipStreamNonBlocking) != hipSuccess) return false;
+    if (hipStreamCreateWithFlags(&g_side.gemm_stream, hipStreamNonBlocking) != hipSuccess) return false;
+    for (hipEvent_t* e : {&g_side.qa, &g_side.qb, &g_side.gate, &g_side.gate_b, &g_side.gdone})
+        if (hipEventCreateWithFlags(e, hipEventDisableTiming) != hipSuccess) return false;
     if (hipEventCreateWithFlags(&g_side.fork, hipEventDisableTiming) != hipSuccess) return false;
     if (hipEventCreateWithFlags(&g_side.join, hipEventDisableTiming) != hipSuccess) return false;
     g_side.ok = true;
@@ -194,7 +203,8 @@ static int run_interleaved(const LaunchList& a, const LaunchList& b) {
 static int rsvd_plan(LaunchList& ops, const float* X, const float* amax, int rows, int cols, int axis, int bits,
                      int round_mode, int rank, int oversample, int power_iters, uint64_t seed,
                      const float* omega_or_null, float* U, float* Sigma, float* Vt, void* workspace,
-                     size_t workspace_bytes, hipStream_t st) {
+                     size_t workspace_bytes, hipStream_t st, const std::function<int()>& before_svd = nullptr,
+                     const std::function<int()>& after_svd = nullptr) {
     if (rows < 0 || cols < 0 || rank < 1 || oversample < 0 || power_iters < 0) return LRQMM_ERR_INVALID_ARG;
     if (axis != LRQMM_AXIS_ROW && axis != LRQMM_AXIS_COL) return LRQMM_ERR_INVALID_ARG;
     if (round_mode != LRQMM_ROUND_FLOOR && round_mode != LRQMM_ROUND_NEAREST) return LRQMM_ERR_INVALID_ARG;
@@ -248,7 +258,9 @@ static int rsvd_plan(LaunchList& ops, const float* X, const float* amax, int row
     pass_t();
     ops.push_back([=] { return launch_reduce_gram(w.partial, pt.splits, cols, LP, nullptr, w.Wc, w.gpart, st); });
     ops.push_back([=] { return launch_gram_sum(w.gpart, gram_blocks(cols), LP, w.gram, st); });
+    if (before_svd) ops.push_back(before_svd);      // the GPU is nearly idle from here to the end of the SVD
     ops.push_back([=] { return launch_small_svd(w.gram, ell, LP, rank, Sigma, w.Ur, w.Mv, st); });
+    if (after_svd) ops.push_back(after_svd);
     ops.push_back([=] {
         return launch_apply2(w.Yr, rows, w.Ur, rank, rank, U, rank, 0, w.Wc, cols, w.Mv, rank, rank, Vt, cols, 1, LP,
                              st);
@@ -318,7 +330,8 @@ int lrqmm_rsvd(const float* X, const float* amax, int rows, int cols, int axis, 
 static int gemm_impl(int M, int N, int K, int bits, int rank, const int8_t* Aq, const float* amaxA,
                      const int8_t* BqT, const float* amaxB, const float* U, const float* Sig, const float* Vt,
                      const float* W, const float* Gam, const float* Zt, float* C, int32_t* Cint_or_null,
-                     void* workspace, size_t workspace_bytes, void* stream, int prof_slot) {
+                     void* workspace, size_t workspace_bytes, void* stream, int prof_slot,
+                     hipEvent_t raw_sums_ready = nullptr) {
     if (M < 0 || N < 0 || K < 0 || rank < 0) return LRQMM_ERR_INVALID_ARG;
     if (!bits_ok(bits)) return LRQMM_ERR_UNSUPPORTED;
     if (!k_fits_int32(K, bits)) return LRQMM_ERR_UNSUPPORTED;
@@ -347,10 +360,20 @@ static int gemm_impl(int M, int N, int K, int bits, int rank, const int8_t* Aq, 
         LRQ_TRY(launch_build_panels(M, N, K, rank, RP, R2P, U, Sig, w.sA, w.partialA, pa.splits, w.sB,
                                     w.partialB, pb.splits, w.X, Gam, Zt, w.Lp, w.Rp, st));
     }
+    if (raw_sums_ready) {
+        // the integer product ran early on another stream and left its int32 sums in C
+        if (hipStreamWaitEvent(st, raw_sums_ready, 0) != hipSuccess) return LRQMM_ERR_HIP;
+        prof_mark(prof_slot, 7, st);
+        rc = launch_rank_update(M, N, C, w.sA, w.sB, w.Lp, w.Rp, R2P, st);
+        prof_mark(prof_slot, 8, st);
+        return rc;
+    }
     prof_mark(prof_slot, 7, st);
     rc = launch_int8_gemm(M, N, K, Aq, BqT, w.sA, w.sB, rank > 0 ? w.Lp : nullptr, rank > 0 ? w.Rp : nullptr,
                           R2P, C, Cint_or_null, st);
     prof_mark(prof_slot, 8, st);
+    prof_mark(prof_slot, 9, st);
+    prof_mark(prof_slot, 10, st);
     return rc;
 }
 
@@ -396,17 +419,55 @@ int lrqmm_matmul(int M, int N, int K, int bits, int rank, int oversample, int po
     if (K > 0) opsA.push_back([=] { return lrqmm_quantize(A, M, K, LRQMM_AXIS_ROW, bits, round_mode, w.Aq, w.amaxA, pst); });
     else opsA.push_back([=] { return launch_pad_copy(nullptr, M, 0, 1, w.amaxA, pst); });
     opsA.push_back([=] { prof_mark(slot, 1, pst); return LRQMM_OK; });
+    // Early integer GEMM: with both factorizations in their single-workgroup SVD the GPU is
+    // nearly idle, so the int8 product (which needs only the codes) runs there on a third
+    // stream, leaves raw int32 sums in C, and the epilogue follows the panels as a kernel of
+    // its own.  Used for problems on the large-tile kernel.
+    const bool early = overlap && int8_gemm_large_tiles(M, N);
+    hipStream_t gst = early ? g_side.gemm_stream : pst;
+    std::function<int()> before_svd = nullptr, before_svd_b = nullptr, after_svd_b = nullptr;
+    if (early) {
+        opsA.push_back([=] { return hipEventRecord(g_side.qa, pst) == hipSuccess ? LRQMM_OK : LRQMM_ERR_HIP; });
+        // The GEMM must not take the CUs before the two SVD workgroups have theirs: it waits
+        // for the kernels that precede both SVDs and then for a few minimal kernels, which
+        // gives the SVD launches (one dependent launch behind their events) a head start.
+        before_svd = [=] {
+            if (hipEventRecord(g_side.gate, pst) != hipSuccess) return LRQMM_ERR_HIP;
+            return LRQMM_OK;
+        };
+        before_svd_b = [=] {
+            if (hipEventRecord(g_side.gate_b, bst) != hipSuccess) return LRQMM_ERR_HIP;
+            return LRQMM_OK;
+        };
+        after_svd_b = [=] {     // issued by the host after both SVD launches
+            for (hipEvent_t e : {g_side.qa, g_side.qb, g_side.gate, g_side.gate_b})
+                if (hipStreamWaitEvent(gst, e, 0) != hipSuccess) return LRQMM_ERR_HIP;
+            for (int t = 0; t < 3; ++t) {
+                const int r = launch_tick(w.tick, gst);
+                if (r != LRQMM_OK) return r;
+            }
+            prof_mark(slot, 9, gst);
+            const int r = launch_int8_gemm(M, N, K, w.Aq, w.BqT, nullptr, nullptr, nullptr, nullptr, 0, nullptr,
+                                           reinterpret_cast<int32_t*>(C), gst);
+            prof_mark(slot, 10, gst);
+            if (r != LRQMM_OK) return r;
+            return hipEventRecord(g_side.gdone, gst) == hipSuccess ? LRQMM_OK : LRQMM_ERR_HIP;
+        };
+    }
     if (rank > 0)
         LRQ_TRY(rsvd_plan(opsA, A, w.amaxA, M, K, LRQMM_AXIS_ROW, bits, round_mode, rank, oversample, power_iters,
-                          seed, nullptr, w.U, w.Sig, w.Vt, w.subA, w.subA_bytes, pst));
+                          seed, nullptr, w.U, w.Sig, w.Vt, w.subA, w.subA_bytes, pst, before_svd));
     opsA.push_back([=] { prof_mark(slot, 2, pst); return LRQMM_OK; });
     opsB.push_back([=] { prof_mark(slot, 3, bst); return LRQMM_OK; });
     if (K > 0) opsB.push_back([=] { return lrqmm_quantize(B, K, N, LRQMM_AXIS_COL, bits, round_mode, w.BqT, w.amaxB, bst); });
     else opsB.push_back([=] { return launch_pad_copy(nullptr, N, 0, 1, w.amaxB, bst); });
     opsB.push_back([=] { prof_mark(slot, 4, bst); return LRQMM_OK; });
+    if (early)
+        opsB.push_back([=] { return hipEventRecord(g_side.qb, bst) == hipSuccess ? LRQMM_OK : LRQMM_ERR_HIP; });
     if (rank > 0)
         LRQ_TRY(rsvd_plan(opsB, B, w.amaxB, K, N, LRQMM_AXIS_COL, bits, round_mode, rank, oversample, power_iters,
-                          seed, nullptr, w.W, w.Gam, w.Zt, w.subB, w.subB_bytes, bst));
+                          seed, nullptr, w.W, w.Gam, w.Zt, w.subB, w.subB_bytes, bst, before_svd_b,
+                          after_svd_b));
     opsB.push_back([=] { prof_mark(slot, 5, bst); return LRQMM_OK; });
     LRQ_TRY(run_interleaved(opsA, opsB));
     if (overlap) {
@@ -415,7 +476,7 @@ int lrqmm_matmul(int M, int N, int K, int bits, int rank, int oversample, int po
     }
     prof_mark(slot, 6, pst);
     return gemm_impl(M, N, K, bits, rank, w.Aq, w.amaxA, w.BqT, w.amaxB, w.U, w.Sig, w.Vt, w.W, w.Gam, w.Zt, C,
-                     nullptr, w.sub, w.sub_bytes, stream, slot);
+                     nullptr, w.sub, w.sub_bytes, stream, slot, early ? g_side.gdone : nullptr);
 }
 
 int lrqmm_profile_enable(int on) {
@@ -436,7 +497,7 @@ int lrqmm_profile_read(float* stage_ms, int* ncalls) {
     *ncalls = n;
     for (int i = 0; i < kProfStages; ++i) stage_ms[i] = 0.f;
     if (n == 0) return LRQMM_OK;
-    if (hipEventSynchronize(g_prof.ev[n - 1][kProfEvents - 1]) != hipSuccess) return LRQMM_ERR_HIP;
+    if (hipEventSynchronize(g_prof.ev[n - 1][kLastMainEvent]) != hipSuccess) return LRQMM_ERR_HIP;
     for (int c = 0; c < n; ++c)
         for (int i = 0; i < kProfStages; ++i) {
             float ms = 0.f;

@@ -307,6 +307,9 @@ __global__ __launch_bounds__(512, 1) void int8_gemm256_kernel(int M, int N, int 
 #undef LRQ_SSTORE
 
     // ---- epilogue: dequantize, rank-2r update, store ----
+    // C == nullptr: only the raw int32 sums are wanted (the dequantization and the update then
+    // run later, in rank_update_kernel), and the step vectors are not read.
+    const bool want_c = C != nullptr;
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
         const int rbase = m0 + wm * 64 + mt * 32;
@@ -317,13 +320,13 @@ __global__ __launch_bounds__(512, 1) void int8_gemm256_kernel(int M, int N, int 
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int row = rbase + 8 * (v >> 2) + 4 * lh + (v & 3);
-            sa[v] = (row < M) ? sA[row] : 0.f;
+            sa[v] = (want_c && row < M) ? sA[row] : 0.f;
         }
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) {
             const int col = n0 + wn * 128 + nt * 32 + l32;
             const bool col_ok = col < N;
-            const float sb = col_ok ? sB[col] : 0.f;
+            const float sb = (want_c && col_ok) ? sB[col] : 0.f;
             v16f f;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
@@ -342,14 +345,107 @@ __global__ __launch_bounds__(512, 1) void int8_gemm256_kernel(int M, int N, int 
                     f = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.w, b4.w, f, 0, 0, 0);
                 }
             }
+            if (want_c) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = rbase + 8 * (v >> 2) + 4 * lh + (v & 3);
-                if (row < M && col_ok) C[(size_t)row * N + col] = f[v];
+                for (int v = 0; v < 16; ++v) {
+                    const int row = rbase + 8 * (v >> 2) + 4 * lh + (v & 3);
+                    if (row < M && col_ok) C[(size_t)row * N + col] = f[v];
+                }
             }
         }
     }
 }
+
+// The epilogue of the GEMM as a kernel of its own, for the schedule in which the integer
+// product runs early (next to the small kernels of the factorizations) and leaves its raw
+// int32 sums in C's memory: C <- float(Cint) sA_i sB_j + Lp . Rp^T in place, the same
+// arithmetic in the same order as the fused epilogue (bit-identical results).
+// 128x128 tile per workgroup, 4 waves of 64x64 (2x2 MFMA tiles).  A wave first issues all its
+// loads -- the four tiles of sums and, per 64 panel columns, the panel rows of both row tiles
+// and both column tiles -- and then runs the four accumulation chains interleaved, so neither
+// load latency nor the latency of dependent MFMAs is exposed.
+__global__ __launch_bounds__(256) void rank_update_kernel(int M, int N, float* __restrict__ C,
+                                                          const float* __restrict__ sA,
+                                                          const float* __restrict__ sB,
+                                                          const float* __restrict__ Lp,
+                                                          const float* __restrict__ Rp, int R2P, int tiles_n) {
+    const int m0 = (blockIdx.x / tiles_n) * 128, n0 = (blockIdx.x % tiles_n) * 128;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int32_t* Ci = reinterpret_cast<const int32_t*>(C);
+    const int rb0 = m0 + wm * 64, cb0 = n0 + wn * 64;
+    // branch-free loads (clamped addresses, results of rows / columns past the end are never
+    // stored): a load under a branch would make the wave wait for each of them in turn
+    v16f f[2][2];
+    int32_t raw[2][2][16];
+    float sa[2][16], sb[2];
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) sb[nt] = sB[min(cb0 + nt * 32 + l32, N - 1)];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = min(rb0 + mt * 32 + 8 * (v >> 2) + 4 * lh + (v & 3), M - 1);
+            sa[mt][v] = sA[row];
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) raw[mt][nt][v] = Ci[(size_t)row * N + min(cb0 + nt * 32 + l32, N - 1)];
+        }
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) f[mt][nt][v] = ((float)raw[mt][nt][v] * sa[mt][v]) * sb[nt];
+    const float* lp[2];
+    const float* rp[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {       // rows / columns past the end re-read the last one (never stored)
+        lp[t] = Lp + (size_t)min(rb0 + t * 32 + l32, M - 1) * R2P + 4 * lh;
+        rp[t] = Rp + (size_t)min(cb0 + t * 32 + l32, N - 1) * R2P + 4 * lh;
+    }
+    for (int t0 = 0; t0 < R2P; t0 += 64) {      // R2P % 8 == 0
+        // panel columns past R2P enter as zeros (clamped load, then select): the MFMAs below
+        // carry no guard, and adding exact zeros leaves the sums unchanged
+        float4 a4[2][8], b4[2][8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int tc = min(t0 + 8 * u, R2P - 8);
+            const bool in = t0 + 8 * u < R2P;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const float4 x = *reinterpret_cast<const float4*>(lp[t] + tc);
+                const float4 y = *reinterpret_cast<const float4*>(rp[t] + tc);
+                a4[t][u] = make_float4(in ? x.x : 0.f, in ? x.y : 0.f, in ? x.z : 0.f, in ? x.w : 0.f);
+                b4[t][u] = make_float4(in ? y.x : 0.f, in ? y.y : 0.f, in ? y.z : 0.f, in ? y.w : 0.f);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt) {
+                    f[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[mt][u].x, b4[nt][u].x, f[mt][nt], 0, 0, 0);
+                    f[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[mt][u].y, b4[nt][u].y, f[mt][nt], 0, 0, 0);
+                    f[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[mt][u].z, b4[nt][u].z, f[mt][nt], 0, 0, 0);
+                    f[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[mt][u].w, b4[nt][u].w, f[mt][nt], 0, 0, 0);
+                }
+        }
+    }
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            const int col = cb0 + nt * 32 + l32;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = rb0 + mt * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+                if (row < M && col < N) C[(size_t)row * N + col] = f[mt][nt][v];
+            }
+        }
+}
+
 // ---------------------------------------------------------------------------
 // Panels of the rank-2r update (compensation terms of Algorithm 2 regrouped):
 //   C = C0 + [U Sigma | A~ W] . [V^T B~ + (V^T W) Gamma Z^T ; Gamma Z^T]
@@ -673,6 +769,19 @@ static void dispatch_gemm(bool comp, bool wcint, dim3 grid, hipStream_t st, int 
 #undef LRQ_GEMM
 }
 
+bool int8_gemm_large_tiles(int M, int N) {
+    return M >= BTM && N >= BTN && ceil_div(M, BTM) * ceil_div(N, BTN) >= 128;
+}
+
+int launch_rank_update(int M, int N, float* C, const float* sA, const float* sB, const float* Lp, const float* Rp,
+                       int R2P, hipStream_t st) {
+    const int tiles_n = ceil_div(N, 128);
+    hipLaunchKernelGGL(rank_update_kernel, dim3(ceil_div(M, 128) * tiles_n), dim3(256), 0, st, M, N, C, sA, sB, Lp,
+                       Rp, R2P, tiles_n);
+    LRQ_CHECK_LAUNCH();
+    return LRQMM_OK;
+}
+
 int launch_int8_gemm(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, const float* sA,
                      const float* sB, const float* Lp, const float* Rp, int R2P, float* C, int32_t* Cint,
                      hipStream_t st) {
@@ -680,7 +789,7 @@ int launch_int8_gemm(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, c
     const bool comp = Lp != nullptr;
     // big problems: 256x256 tiles, one workgroup per CU
     const int btiles = ceil_div(M, BTM) * ceil_div(N, BTN);
-    if (M >= BTM && N >= BTN && btiles >= 128) {
+    if (int8_gemm_large_tiles(M, N)) {
         const int btn = ceil_div(N, BTN);
         dim3 bgrid(btiles);
         if (vec) dispatch_gemm256<true>(comp, Cint != nullptr, bgrid, st, M, N, K, Aq, BqT, sA, sB, Lp, Rp, R2P, C, Cint, btn, btiles);

@@ -11,6 +11,8 @@ int launch_quantize_rows(const float* X, int rows, int cols, QuantParams q, int8
 int launch_quantize_cols(const float* X, int rows, int cols, QuantParams q, int8_t* codesT,
                          float* amax, hipStream_t st);
 // lam[n], s[n] from amax[n]; entries n..npad-1 are zero-filled.
+// A minimal kernel (writes one zero word): used as a few microseconds of delay on a stream.
+int launch_tick(uint32_t* word, hipStream_t st);
 int launch_scales(const float* amax, int n, int npad, float qmaxf, float* lam, float* s,
                   hipStream_t st);
 
@@ -94,3 +96,9 @@ int launch_build_panels(int M, int N, int K, int r, int RP, int R2P, const float
 int launch_int8_gemm(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, const float* sA,
                      const float* sB, const float* Lp, const float* Rp, int R2P, float* C,
                      int32_t* Cint, hipStream_t st);
+// True when launch_int8_gemm uses the large-tile kernel, which accepts C == null together with
+// Cint != null (raw int32 sums only; sA, sB are then not read).
+bool int8_gemm_large_tiles(int M, int N);
+// C (holding raw int32 sums in its memory) <- float(Cint) sA_i sB_j + Lp . Rp^T, in place.
+int launch_rank_update(int M, int N, float* C, const float* sA, const float* sB, const float* Lp, const float* Rp,
+                       int R2P, hipStream_t st);

@@ -239,6 +239,12 @@ int launch_quantize_cols(const float* X, int rows, int cols, QuantParams q, int8
     return LRQMM_OK;
 }
 
+int launch_tick(uint32_t* word, hipStream_t st) {
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, st, word, 1, 0u);
+    LRQ_CHECK_LAUNCH();
+    return LRQMM_OK;
+}
+
 int launch_scales(const float* amax, int n, int npad, float qmaxf, float* lam, float* s,
                   hipStream_t st) {
     hipLaunchKernelGGL(scales_kernel, dim3(ceil_div(npad, 256)), dim3(256), 0, st, amax, n, npad, qmaxf, lam, s);
