@@ -423,7 +423,7 @@ int lrqmm_matmul(int M, int N, int K, int bits, int rank, int oversample, int po
     // nearly idle, so the int8 product (which needs only the codes) runs there on a third
     // stream, leaves raw int32 sums in C, and the epilogue follows the panels as a kernel of
     // its own.  Used for problems on the large-tile kernel.
-    const bool early = overlap && int8_gemm_large_tiles(M, N);
+    const bool early = overlap && rank_update_usable(M, N, C);
     hipStream_t gst = early ? g_side.gemm_stream : pst;
     std::function<int()> before_svd = nullptr, before_svd_b = nullptr, after_svd_b = nullptr;
     if (early) {

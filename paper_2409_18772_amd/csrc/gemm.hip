@@ -358,13 +358,16 @@ __global__ __launch_bounds__(512, 1) void int8_gemm256_kernel(int M, int N, int 
 
 // The epilogue of the GEMM as a kernel of its own, for the schedule in which the integer
 // product runs early (next to the small kernels of the factorizations) and leaves its raw
-// int32 sums in C's memory: C <- float(Cint) sA_i sB_j + Lp . Rp^T in place, the same
-// arithmetic in the same order as the fused epilogue (bit-identical results).
-// 128x128 tile per workgroup, 4 waves of 64x64 (2x2 MFMA tiles).  A wave first issues all its
-// loads -- the four tiles of sums and, per 64 panel columns, the panel rows of both row tiles
-// and both column tiles -- and then runs the four accumulation chains interleaved, so neither
-// load latency nor the latency of dependent MFMAs is exposed.
-__global__ __launch_bounds__(256) void rank_update_kernel(int M, int N, float* __restrict__ C,
+// int32 sums in C's memory: C <- float(Cint) sA_i sB_j + Lp . Rp^T in place, with the same
+// products accumulated in the same order as the fused epilogue (bit-identical results).
+// 128x128 tile per workgroup, 4 waves of 64x64 (2x2 MFMA tiles).  The MFMA runs on the
+// transposed tile (Rp rows as the A operand, Lp rows as B), so that a lane owns ONE row of C
+// and four groups of 4 consecutive columns: C is read and written with 16-byte accesses
+// (needs N % 4 == 0).  A wave first issues all its loads -- its four tiles of sums and, per 64
+// panel columns, the panel rows of both row tiles and both column tiles -- without branches,
+// and then runs the four accumulation chains interleaved, so neither load latency nor the
+// latency of dependent MFMAs is exposed.
+__global__ __launch_bounds__(256, 3) void rank_update_kernel(int M, int N, float* __restrict__ C,
                                                           const float* __restrict__ sA,
                                                           const float* __restrict__ sB,
                                                           const float* __restrict__ Lp,
@@ -373,35 +376,54 @@ __global__ __launch_bounds__(256) void rank_update_kernel(int M, int N, float* _
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, lh = lane >> 5;
-    const int32_t* Ci = reinterpret_cast<const int32_t*>(C);
     const int rb0 = m0 + wm * 64, cb0 = n0 + wn * 64;
-    // branch-free loads (clamped addresses, results of rows / columns past the end are never
-    // stored): a load under a branch would make the wave wait for each of them in turn
-    v16f f[2][2];
-    int32_t raw[2][2][16];
-    float sa[2][16], sb[2];
+    // D[i][j] of tile (mt, nt): j = l32 is the row of C, i = 8 g + 4 lh + e its column (v = 4 g + e)
+    int row[2], colb[2][4];         // this lane's C rows and first columns of its groups (clamped)
+    bool row_ok[2], col_ok[2][4];
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) sb[nt] = sB[min(cb0 + nt * 32 + l32, N - 1)];
+    for (int t = 0; t < 2; ++t) {
+        row_ok[t] = rb0 + t * 32 + l32 < M;
+        row[t] = min(rb0 + t * 32 + l32, M - 1);
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int row = min(rb0 + mt * 32 + 8 * (v >> 2) + 4 * lh + (v & 3), M - 1);
-            sa[mt][v] = sA[row];
-#pragma unroll
-            for (int nt = 0; nt < 2; ++nt) raw[mt][nt][v] = Ci[(size_t)row * N + min(cb0 + nt * 32 + l32, N - 1)];
+        for (int g = 0; g < 4; ++g) {
+            const int c = cb0 + t * 32 + 8 * g + 4 * lh;
+            col_ok[t][g] = c < N;
+            colb[t][g] = min(c, N - 4);
         }
+    }
+    v16f f[2][2];
+    int4 raw[2][2][4];
+    float4 sb[2][4];
+    float sa[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        sa[t] = sA[row[t]];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) sb[t][g] = *reinterpret_cast<const float4*>(sB + colb[t][g]);
+    }
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) f[mt][nt][v] = ((float)raw[mt][nt][v] * sa[mt][v]) * sb[nt];
+            for (int g = 0; g < 4; ++g)
+                raw[mt][nt][g] = *reinterpret_cast<const int4*>(C + (size_t)row[mt] * N + colb[nt][g]);
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                f[mt][nt][4 * g + 0] = ((float)raw[mt][nt][g].x * sa[mt]) * sb[nt][g].x;
+                f[mt][nt][4 * g + 1] = ((float)raw[mt][nt][g].y * sa[mt]) * sb[nt][g].y;
+                f[mt][nt][4 * g + 2] = ((float)raw[mt][nt][g].z * sa[mt]) * sb[nt][g].z;
+                f[mt][nt][4 * g + 3] = ((float)raw[mt][nt][g].w * sa[mt]) * sb[nt][g].w;
+            }
     const float* lp[2];
     const float* rp[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {       // rows / columns past the end re-read the last one (never stored)
-        lp[t] = Lp + (size_t)min(rb0 + t * 32 + l32, M - 1) * R2P + 4 * lh;
+        lp[t] = Lp + (size_t)row[t] * R2P + 4 * lh;
         rp[t] = Rp + (size_t)min(cb0 + t * 32 + l32, N - 1) * R2P + 4 * lh;
     }
     for (int t0 = 0; t0 < R2P; t0 += 64) {      // R2P % 8 == 0
@@ -425,25 +447,23 @@ __global__ __launch_bounds__(256) void rank_update_kernel(int M, int N, float* _
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt) {
-                    f[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[mt][u].x, b4[nt][u].x, f[mt][nt], 0, 0, 0);
-                    f[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[mt][u].y, b4[nt][u].y, f[mt][nt], 0, 0, 0);
-                    f[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[mt][u].z, b4[nt][u].z, f[mt][nt], 0, 0, 0);
-                    f[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[mt][u].w, b4[nt][u].w, f[mt][nt], 0, 0, 0);
+                for (int nt = 0; nt < 2; ++nt) {    // A operand: panel row of the column, B operand: of the row
+                    f[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(b4[nt][u].x, a4[mt][u].x, f[mt][nt], 0, 0, 0);
+                    f[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(b4[nt][u].y, a4[mt][u].y, f[mt][nt], 0, 0, 0);
+                    f[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(b4[nt][u].z, a4[mt][u].z, f[mt][nt], 0, 0, 0);
+                    f[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(b4[nt][u].w, a4[mt][u].w, f[mt][nt], 0, 0, 0);
                 }
         }
     }
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
-            const int col = cb0 + nt * 32 + l32;
+        for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = rb0 + mt * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
-                if (row < M && col < N) C[(size_t)row * N + col] = f[mt][nt][v];
-            }
-        }
+            for (int g = 0; g < 4; ++g)
+                if (row_ok[mt] && col_ok[nt][g])
+                    *reinterpret_cast<float4*>(C + (size_t)row[mt] * N + colb[nt][g]) =
+                        make_float4(f[mt][nt][4 * g + 0], f[mt][nt][4 * g + 1], f[mt][nt][4 * g + 2], f[mt][nt][4 * g + 3]);
 }
 
 // ---------------------------------------------------------------------------
@@ -771,6 +791,11 @@ static void dispatch_gemm(bool comp, bool wcint, dim3 grid, hipStream_t st, int 
 
 bool int8_gemm_large_tiles(int M, int N) {
     return M >= BTM && N >= BTN && ceil_div(M, BTM) * ceil_div(N, BTN) >= 128;
+}
+
+// The early-GEMM schedule needs the large-tile kernel and 16-byte accesses to the rows of C.
+bool rank_update_usable(int M, int N, const float* C) {
+    return int8_gemm_large_tiles(M, N) && N % 4 == 0 && ((uintptr_t)C & 15) == 0;
 }
 
 int launch_rank_update(int M, int N, float* C, const float* sA, const float* sB, const float* Lp, const float* Rp,

@@ -99,6 +99,9 @@ int launch_int8_gemm(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, c
 // True when launch_int8_gemm uses the large-tile kernel, which accepts C == null together with
 // Cint != null (raw int32 sums only; sA, sB are then not read).
 bool int8_gemm_large_tiles(int M, int N);
+// True when the integer product may run early and launch_rank_update finish the job: the
+// large-tile kernel applies, N % 4 == 0 and C is 16-byte aligned.
+bool rank_update_usable(int M, int N, const float* C);
 // C (holding raw int32 sums in its memory) <- float(Cint) sA_i sB_j + Lp . Rp^T, in place.
 int launch_rank_update(int M, int N, float* C, const float* sA, const float* sB, const float* Lp, const float* Rp,
                        int R2P, hipStream_t st);
