@@ -24,13 +24,13 @@ PEAK_INT8_TOPS = 5000.0     # MI355X dense int8 MFMA, TOP/s
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, GB/s
 
 
-def read_traffic(name: str):
-    """HBM bytes per launch measured offline with rocprofv3 --pmc (profiles/<name>), or None."""
+def read_traffic(name: str, key: str = "traffic_bytes_per_launch"):
+    """HBM bytes per launch measured offline with rocprofv3 --pmc (profiles/<name>, line `key: N`), or None."""
     path = os.path.join(ROOT, "profiles", name)
     try:
         with open(path) as f:
             for line in f:
-                if line.startswith("traffic_bytes_per_launch:"):
+                if line.startswith(key + ":"):
                     return float(line.split(":", 1)[1].split()[0])
     except OSError:
         pass
@@ -192,7 +192,8 @@ def main():
                                "int8_gemm256_kernel (int8 MFMA GEMM + fused dequant and rank-2r epilogue)",
                      "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                      "frac": round(achieved / PEAK_INT8_TOPS, 4),
-                     "traffic": read_traffic("int8_gemm_c3_pmc.txt"),
+                     "traffic": read_traffic("int8_gemm_c3_pmc.txt", "traffic_bytes_per_launch" if early
+                                             else "traffic_bytes_per_launch_fused"),
                      "launch_ms": round(stages[gemm_key], 4), "ops_per_launch": ops},
         "stages": stage_info,
         "direct_quant_ms": round(t_dq * 1e3, 4),
