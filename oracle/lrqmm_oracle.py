@@ -22,6 +22,9 @@ Pins (tests/test_oracle_*.py, no GPU):
   lrqmm          dense identity (A~ + R_Ar)(B~ + R_Br), full rank equals A.B,
                  err(LRQMM) <= err(direct quant), printed Table 3-4 values
                  (direct-quant column tight, LRQMM column order of magnitude)
+  scaled_update  hand-worked 2x2 example in exact fractions, alpha = 1 / beta = 0
+                 identity, beta = 0 ignoring NaNs in D, full-rank case equal to
+                 alpha A.B + beta D
 Parity unpinned: none of the functions below lacks a pin; the end-to-end
 tolerance between float32 GPU arithmetic and this float64 oracle is not fixed by
 the paper and is derived in the design notes.
@@ -375,6 +378,27 @@ def compensate(Aq, sa, Bq, sb, U, Sig, Vt, W, Gam, Zt) -> np.ndarray:
     Vt = np.asarray(Vt, np.float64)
     W = np.asarray(W, np.float64)
     return C0 + Ut @ (Vt @ Bf) + (Af @ W) @ Ztp + (Ut @ (Vt @ W)) @ Ztp
+
+
+def scaled_update(C_F: np.ndarray, alpha: float, beta: float, D: np.ndarray | None) -> np.ndarray:
+    """Last step of Algorithm 2: D <- alpha * C_F + beta * D, in float64.
+
+    alpha and beta are float32 scalars (the origin precision of the algorithm's
+    inputs).  With beta == 0 the old contents of D are not read at all, as in
+    the BLAS convention the algorithm's caption (D = alpha A.B + beta D) borrows,
+    so D may then be None or hold anything.
+    """
+    a = float(np.float32(alpha))
+    b = float(np.float32(beta))
+    out = a * np.asarray(C_F, dtype=np.float64)
+    if b != 0.0:
+        if D is None:
+            raise ValueError("beta != 0 needs D")
+        D = np.asarray(D, dtype=np.float32).astype(np.float64)
+        if D.shape != out.shape:
+            raise ValueError("shape")
+        out = out + b * D
+    return out
 
 
 def rel_err(C_ref: np.ndarray, X: np.ndarray) -> float:

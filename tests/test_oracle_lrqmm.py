@@ -149,3 +149,63 @@ def test_config_one_sanity_numbers():
     assert 0.04 < res["Sig"][1] < 0.08
     ref = o.exact_product(A, B)
     assert o.rel_err(ref, res["C"]) < 0.6 * o.rel_err(ref, res["C0"])
+
+
+# ---- last step of Algorithm 2: D <- alpha C_F + beta D ----------------------------------
+
+def test_scaled_update_hand_worked_example():
+    """2x2 case in exact fractions (all values are dyadic, so float64 is exact)."""
+    from fractions import Fraction as F
+    C = [[F(3, 2), F(-1, 4)], [F(5, 8), F(7)]]
+    D = [[F(1, 2), F(2)], [F(-3), F(1, 16)]]
+    alpha, beta = F(-3, 4), F(5, 2)
+    want = [[alpha * C[i][j] + beta * D[i][j] for j in range(2)] for i in range(2)]
+    got = o.scaled_update(np.array(C, dtype=np.float64), float(alpha), float(beta),
+                          np.array(D, dtype=np.float32))
+    assert got.dtype == np.float64
+    for i in range(2):
+        for j in range(2):
+            assert F(float(got[i, j])) == want[i][j]
+
+
+def test_scaled_update_special_cases():
+    rng = np.random.default_rng(3)
+    C = rng.standard_normal((5, 7))
+    D = rng.standard_normal((5, 7)).astype(np.float32)
+    # alpha = 1, beta = 0: the product itself
+    assert np.array_equal(o.scaled_update(C, 1.0, 0.0, None), C)
+    # beta = 0: D is not read, NaNs in it do not propagate
+    assert np.array_equal(o.scaled_update(C, 2.0, 0.0, np.full((5, 7), np.nan, np.float32)), 2.0 * C)
+    # alpha = 0: only the old D survives
+    assert np.array_equal(o.scaled_update(C, 0.0, 0.5, D), 0.5 * D.astype(np.float64))
+    # the two terms are not swapped: a transposed or exchanged operand changes the result
+    r = o.scaled_update(C, 0.25, -2.0, D)
+    assert np.allclose(r, 0.25 * C - 2.0 * D.astype(np.float64), rtol=1e-15, atol=0)
+    assert not np.allclose(r, -2.0 * C + 0.25 * D.astype(np.float64))
+    with pytest.raises(ValueError):
+        o.scaled_update(C, 1.0, 1.0, None)
+
+
+def test_full_rank_update_equals_blas_definition():
+    """With l = min(dims) the residual factors are exact, so D = alpha A.B + beta D to rounding
+    (the caption of Alg. 2)."""
+    M, K, N = 12, 10, 11
+    A = wl.random_matrix("normal", M, K, seed=4)
+    B = wl.random_matrix("normal", K, N, seed=5)
+    D0 = wl.random_matrix("uniform01", M, N, seed=6)
+    res = o.lrqmm(A, B, 4, 10, 0, 1, seed=2)
+    got = o.scaled_update(res["C"], 1.5, -0.75, D0)
+    want = 1.5 * o.exact_product(A, B) + (-0.75) * D0.astype(np.float64)
+    assert np.allclose(got, want, rtol=0, atol=1e-9 * np.abs(want).max())
+
+
+def test_strided_views_give_the_same_result():
+    """Operands that are windows of larger arrays (leading dimension > width) are the same matrices."""
+    M, K, N = 20, 17, 13
+    bigA = wl.random_matrix("normal", M, K + 7, seed=7)
+    bigB = wl.random_matrix("normal", K, N + 3, seed=8)
+    A, B = bigA[:, :K], bigB[:, :N]
+    r1 = o.lrqmm(A, B, 4, 3, 2, 1, seed=9)
+    r2 = o.lrqmm(np.ascontiguousarray(A), np.ascontiguousarray(B), 4, 3, 2, 1, seed=9)
+    assert np.array_equal(r1["Aq"], r2["Aq"]) and np.array_equal(r1["Bq"], r2["Bq"])
+    assert np.allclose(r1["C"], r2["C"], rtol=1e-12, atol=1e-12)
