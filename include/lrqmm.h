@@ -47,6 +47,9 @@ extern "C" {
 #define LRQMM_ROUND_FLOOR    0   /* round down: residual entries in [0, s)  (Eq. (get_ra2)) */
 #define LRQMM_ROUND_NEAREST  1   /* round to nearest, ties to even          (Eq. (quantAB)) */
 
+#define LRQMM_SCALE_VECTOR   0   /* one scale per row of A / per column of B (Background 2.2) */
+#define LRQMM_SCALE_TENSOR   1   /* one scale per matrix, as in the paper's own equations (Eq. (quantA)) */
+
 #define LRQMM_MAX_SKETCH  80     /* largest supported sketch width l = rank + oversample */
 
 /* Human-readable text for a status code (static storage). */
@@ -71,6 +74,19 @@ LRQMM_API size_t lrqmm_workspace_bytes(int M, int N, int K, int rank, int oversa
  */
 LRQMM_API int lrqmm_quantize(const float* X, int rows, int cols, int axis, int bits, int round_mode,
                    int8_t* codes, float* amax, void* stream);
+
+/*
+ * The same with a leading dimension and a choice of scale granularity.
+ *   ldx         row stride of X in elements, ldx >= cols (X is a window of a larger
+ *               row-major array; codes are always stored densely)
+ *   scale_mode  LRQMM_SCALE_VECTOR: as lrqmm_quantize;
+ *               LRQMM_SCALE_TENSOR: a single lambda = qmax / max|X| for the whole
+ *               matrix (Eq. (quantA) as printed); every entry of amax then holds that
+ *               global maximum, so all later stages take the array unchanged.
+ * Errors: LRQMM_ERR_INVALID_ARG for ldx < cols or an unknown scale_mode.
+ */
+LRQMM_API int lrqmm_quantize_ex(const float* X, int ldx, int rows, int cols, int axis, int bits,
+                      int round_mode, int scale_mode, int8_t* codes, float* amax, void* stream);
 
 /*
  * Gaussian test matrix of the randomized range finder (Background 2.1, stage 1).
@@ -100,6 +116,12 @@ LRQMM_API int lrqmm_rsvd(const float* X, const float* amax, int rows, int cols, 
                const float* omega_or_null, float* U, float* Sigma, float* Vt,
                void* workspace, size_t workspace_bytes, void* stream);
 
+/* lrqmm_rsvd for an X with row stride ldx >= cols (elements). */
+LRQMM_API int lrqmm_rsvd_ex(const float* X, int ldx, const float* amax, int rows, int cols, int axis, int bits,
+                  int round_mode, int rank, int oversample, int power_iters, uint64_t seed,
+                  const float* omega_or_null, float* U, float* Sigma, float* Vt,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
 /*
  * Quantized GEMM with fused dequantization and rank-2r compensation
  * (Eq. (INTGEMM), Eq. (QUANTGEMM); Algorithm 2, integer product, dequantization and compensation steps):
@@ -123,6 +145,23 @@ LRQMM_API int lrqmm_gemm(int M, int N, int K, int bits, int rank,
                void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * lrqmm_gemm followed by the last step of Algorithm 2, fused into the store phase of
+ * the GEMM:   D <- alpha * C_F + beta * D,   C_F being what lrqmm_gemm would write.
+ *   alpha, beta  float32 scalars, passed by value
+ *   D     M x N float32, row stride ldd >= N elements; input and output.  With
+ *         beta == 0 the old contents are never read (they may be uninitialised or NaN).
+ *   The products alpha * C_F and beta * D are rounded separately and then added
+ *   (no fused multiply-add).  Cint_or_null stays dense (row stride N).
+ * Errors: LRQMM_ERR_INVALID_ARG for ldd < N, otherwise as lrqmm_gemm.
+ */
+LRQMM_API int lrqmm_gemm_ex(int M, int N, int K, int bits, int rank,
+                  const int8_t* Aq, const float* amaxA, const int8_t* BqT, const float* amaxB,
+                  const float* U, const float* Sig, const float* Vt,
+                  const float* W, const float* Gam, const float* Zt,
+                  float alpha, float beta, float* D, int ldd, int32_t* Cint_or_null,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * The whole hot path, all of Algorithm 2 except its final alpha/beta update, from float32 A (M x K) and
  * B (K x N) to float32 C (M x N): quantize both operands, factor both residuals
  * (sketch seeds (seed, 0) and (seed, 1)), integer GEMM, fused compensation.
@@ -141,6 +180,27 @@ LRQMM_API int lrqmm_gemm(int M, int N, int K, int bits, int rank,
 LRQMM_API int lrqmm_matmul(int M, int N, int K, int bits, int rank, int oversample, int power_iters,
                  uint64_t seed, int round_mode, const float* A, const float* B, float* C,
                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * All of Algorithm 2 including its last step, D <- alpha * C_F + beta * D, for operands
+ * that are windows of larger row-major arrays:
+ *   A  M x K, row stride lda >= K;   B  K x N, row stride ldb >= N;
+ *   D  M x N, row stride ldd >= N, input (unless beta == 0) and output
+ *   scale_mode  LRQMM_SCALE_VECTOR or LRQMM_SCALE_TENSOR (see lrqmm_quantize_ex)
+ * lrqmm_matmul is this call with dense operands, alpha = 1, beta = 0 and vector
+ * scales.  Schedule and stream rules are those of lrqmm_matmul; the early integer
+ * product is used only when beta == 0 and ldd == N (it needs D's memory for the raw
+ * sums), otherwise the update is fused into the GEMM's store phase.  Strides that are
+ * not multiples of 4 elements (or bases that are not 16-byte aligned) select the
+ * scalar-load variants of the streaming kernels.
+ * Errors: LRQMM_ERR_INVALID_ARG for a stride below the row length or an unknown
+ * scale_mode, otherwise as lrqmm_matmul.
+ */
+LRQMM_API int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int power_iters,
+                    uint64_t seed, int round_mode, int scale_mode,
+                    const float* A, int lda, const float* B, int ldb,
+                    float alpha, float beta, float* D, int ldd,
+                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Stage timing of lrqmm_matmul for measurement (the split of Algorithm 2 into

@@ -9,13 +9,15 @@ import os
 
 AXIS_ROW, AXIS_COL = 0, 1
 ROUND_FLOOR, ROUND_NEAREST = 0, 1
+SCALE_VECTOR, SCALE_TENSOR = 0, 1
 MAX_SKETCH = 80
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
 EXPORTS = ("lrqmm_status_string", "lrqmm_workspace_bytes", "lrqmm_quantize", "lrqmm_fill_sketch",
-           "lrqmm_rsvd", "lrqmm_gemm", "lrqmm_matmul", "lrqmm_profile_enable", "lrqmm_profile_read")
+           "lrqmm_rsvd", "lrqmm_gemm", "lrqmm_matmul", "lrqmm_profile_enable", "lrqmm_profile_read",
+           "lrqmm_quantize_ex", "lrqmm_rsvd_ex", "lrqmm_gemm_ex", "lrqmm_matmul_ex")
 PROF_STAGES = ("quantize_a", "rsvd_a", "quantize_b", "rsvd_b", "panels", "gemm", "int_gemm")
 
 
@@ -55,6 +57,16 @@ def load_library() -> ctypes.CDLL:
     lib.lrqmm_gemm.argtypes = [c_int] * 5 + [c_vp] * 12 + [c_vp, c_sz, c_vp]
     lib.lrqmm_matmul.restype = c_int
     lib.lrqmm_matmul.argtypes = [c_int] * 7 + [c_u64, c_int, c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
+    c_f = ctypes.c_float
+    lib.lrqmm_quantize_ex.restype = c_int
+    lib.lrqmm_quantize_ex.argtypes = [c_vp] + [c_int] * 7 + [c_vp, c_vp, c_vp]
+    lib.lrqmm_rsvd_ex.restype = c_int
+    lib.lrqmm_rsvd_ex.argtypes = [c_vp, c_int, c_vp] + [c_int] * 8 + [c_u64, c_vp, c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
+    lib.lrqmm_gemm_ex.restype = c_int
+    lib.lrqmm_gemm_ex.argtypes = [c_int] * 5 + [c_vp] * 10 + [c_f, c_f, c_vp, c_int, c_vp, c_vp, c_sz, c_vp]
+    lib.lrqmm_matmul_ex.restype = c_int
+    lib.lrqmm_matmul_ex.argtypes = [c_int] * 7 + [c_u64, c_int, c_int, c_vp, c_int, c_vp, c_int, c_f, c_f, c_vp,
+                                    c_int, c_vp, c_sz, c_vp]
     lib.lrqmm_profile_enable.restype = c_int
     lib.lrqmm_profile_enable.argtypes = [c_int]
     lib.lrqmm_profile_read.restype = c_int
@@ -93,6 +105,20 @@ def _dev(t, dtype, name):
         raise TypeError(f"{name}: expected a contiguous CUDA tensor of dtype {dtype}")
 
 
+def _dev2d(t, dtype, name) -> int:
+    """A 2-D CUDA tensor whose rows are contiguous (a window of a row-major array); returns its row stride."""
+    import torch
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.dim() == 2):
+        raise TypeError(f"{name}: expected a 2-D CUDA tensor of dtype {dtype}")
+    rows, cols = t.shape
+    if cols > 1 and t.stride(1) != 1:
+        raise TypeError(f"{name}: elements of a row must be adjacent")
+    ld = t.stride(0) if rows > 1 else max(cols, t.stride(0))
+    if ld < cols:
+        raise TypeError(f"{name}: row stride below the row length")
+    return int(ld)
+
+
 class Workspace:
     """A 256-byte aligned device buffer (a torch uint8 tensor) handed to the library."""
 
@@ -126,6 +152,25 @@ def lrqmm_quantize(X, axis: int, bits: int, round_mode: int = ROUND_FLOOR, codes
     return codes, amax
 
 
+def lrqmm_quantize_ex(X, axis: int, bits: int, round_mode: int = ROUND_FLOOR, scale_mode: int = SCALE_VECTOR,
+                      codes=None, amax=None):
+    """lrqmm_quantize for a row-strided X and a choice of scale granularity."""
+    import torch
+    ldx = _dev2d(X, torch.float32, "X")
+    rows, cols = X.shape
+    if codes is None:
+        shape = (rows, cols) if axis == AXIS_ROW else (cols, rows)
+        codes = torch.empty(shape, dtype=torch.int8, device=X.device)
+    if amax is None:
+        amax = torch.empty(rows if axis == AXIS_ROW else cols, dtype=torch.float32, device=X.device)
+    _dev(codes, torch.int8, "codes")
+    _dev(amax, torch.float32, "amax")
+    st = load_library().lrqmm_quantize_ex(_ptr(X), ldx, rows, cols, axis, bits, round_mode, scale_mode,
+                                          _ptr(codes), _ptr(amax), _stream())
+    _check(st, "lrqmm_quantize_ex")
+    return codes, amax
+
+
 def lrqmm_fill_sketch(seed: int, stream_id: int, rows: int, cols: int, device="cuda"):
     import torch
     omega = torch.empty((rows, cols), dtype=torch.float32, device=device)
@@ -155,6 +200,66 @@ def lrqmm_rsvd(X, amax, axis: int, bits: int, rank: int, oversample: int = 0, po
                                    _ptr(Vt), ctypes.c_void_p(workspace.ptr), workspace.nbytes, _stream())
     _check(st, "lrqmm_rsvd")
     return U, Sigma, Vt
+
+
+def lrqmm_rsvd_ex(X, amax, axis: int, bits: int, rank: int, oversample: int = 0, power_iters: int = 0,
+                  seed: int = 0, round_mode: int = ROUND_FLOOR, omega=None, workspace: Workspace | None = None):
+    """lrqmm_rsvd for a row-strided X."""
+    import torch
+    ldx = _dev2d(X, torch.float32, "X")
+    _dev(amax, torch.float32, "amax")
+    _dev(omega, torch.float32, "omega")
+    rows, cols = X.shape
+    if omega is not None and tuple(omega.shape) != (cols, rank + oversample):
+        raise ValueError("omega must be cols x (rank + oversample)")
+    U = torch.empty((rows, rank), dtype=torch.float32, device=X.device)
+    Sigma = torch.empty((rank,), dtype=torch.float32, device=X.device)
+    Vt = torch.empty((rank, cols), dtype=torch.float32, device=X.device)
+    if workspace is None:
+        workspace = Workspace.for_problem(max(rows, cols), max(rows, cols), max(rows, cols), rank, oversample)
+    st = load_library().lrqmm_rsvd_ex(_ptr(X), ldx, _ptr(amax), rows, cols, axis, bits, round_mode, rank,
+                                      oversample, power_iters, seed & 0xFFFFFFFFFFFFFFFF, _ptr(omega), _ptr(U),
+                                      _ptr(Sigma), _ptr(Vt), ctypes.c_void_p(workspace.ptr), workspace.nbytes,
+                                      _stream())
+    _check(st, "lrqmm_rsvd_ex")
+    return U, Sigma, Vt
+
+
+def lrqmm_gemm_ex(Aq, amaxA, BqT, amaxB, bits: int, D, alpha: float = 1.0, beta: float = 0.0, factors_a=None,
+                  factors_b=None, want_cint: bool = False, workspace: Workspace | None = None):
+    """D <- alpha (deq(Aq . Bq) + compensation) + beta D, in place in the (row-strided) tensor D."""
+    import torch
+    _dev(Aq, torch.int8, "Aq")
+    _dev(BqT, torch.int8, "BqT")
+    _dev(amaxA, torch.float32, "amaxA")
+    _dev(amaxB, torch.float32, "amaxB")
+    M, K = Aq.shape
+    N, K2 = BqT.shape
+    if K != K2:
+        raise ValueError("Aq is M x K and BqT is N x K")
+    ldd = _dev2d(D, torch.float32, "D")
+    if tuple(D.shape) != (M, N):
+        raise ValueError("D must be M x N")
+    rank = 0
+    U = Sig = Vt = W = Gam = Zt = None
+    if factors_a is not None:
+        U, Sig, Vt = factors_a
+        W, Gam, Zt = factors_b
+        for n, t in (("U", U), ("Sig", Sig), ("Vt", Vt), ("W", W), ("Gam", Gam), ("Zt", Zt)):
+            _dev(t, torch.float32, n)
+        rank = Sig.numel()
+        if tuple(U.shape) != (M, rank) or tuple(Vt.shape) != (rank, K) or tuple(W.shape) != (K, rank) \
+                or tuple(Zt.shape) != (rank, N) or Gam.numel() != rank:
+            raise ValueError("factor shapes")
+    Cint = torch.empty((M, N), dtype=torch.int32, device=Aq.device) if want_cint else None
+    if workspace is None:
+        workspace = Workspace.for_problem(M, N, K, rank, 0)
+    st = load_library().lrqmm_gemm_ex(M, N, K, bits, rank, _ptr(Aq), _ptr(amaxA), _ptr(BqT), _ptr(amaxB),
+                                      _ptr(U), _ptr(Sig), _ptr(Vt), _ptr(W), _ptr(Gam), _ptr(Zt), float(alpha),
+                                      float(beta), _ptr(D), ldd, _ptr(Cint), ctypes.c_void_p(workspace.ptr),
+                                      workspace.nbytes, _stream())
+    _check(st, "lrqmm_gemm_ex")
+    return (D, Cint) if want_cint else D
 
 
 def lrqmm_gemm(Aq, amaxA, BqT, amaxB, bits: int, factors_a=None, factors_b=None, want_cint: bool = False,
@@ -211,6 +316,28 @@ def lrqmm_matmul(A, B, bits: int, rank: int, oversample: int = 0, power_iters: i
                                      workspace.nbytes, _stream())
     _check(st, "lrqmm_matmul")
     return C
+
+
+def lrqmm_matmul_ex(A, B, D, bits: int, rank: int, oversample: int = 0, power_iters: int = 0, seed: int = 0,
+                    round_mode: int = ROUND_FLOOR, scale_mode: int = SCALE_VECTOR, alpha: float = 1.0,
+                    beta: float = 0.0, workspace: Workspace | None = None):
+    """All of Algorithm 2: D <- alpha C_F + beta D in place; A, B, D may be row-strided windows."""
+    import torch
+    lda = _dev2d(A, torch.float32, "A")
+    ldb = _dev2d(B, torch.float32, "B")
+    ldd = _dev2d(D, torch.float32, "D")
+    M, K = A.shape
+    K2, N = B.shape
+    if K != K2 or tuple(D.shape) != (M, N):
+        raise ValueError("A is M x K, B is K x N, D is M x N")
+    if workspace is None:
+        workspace = Workspace.for_problem(M, N, K, rank, oversample)
+    st = load_library().lrqmm_matmul_ex(M, N, K, bits, rank, oversample, power_iters, seed & 0xFFFFFFFFFFFFFFFF,
+                                        round_mode, scale_mode, _ptr(A), lda, _ptr(B), ldb, float(alpha),
+                                        float(beta), _ptr(D), ldd, ctypes.c_void_p(workspace.ptr),
+                                        workspace.nbytes, _stream())
+    _check(st, "lrqmm_matmul_ex")
+    return D
 
 
 def lrqmm_profile_enable(on: bool):

@@ -200,12 +200,12 @@ static int run_interleaved(const LaunchList& a, const LaunchList& b) {
 }
 
 // Validates the arguments of lrqmm_rsvd and appends its launches to `ops`.
-static int rsvd_plan(LaunchList& ops, const float* X, const float* amax, int rows, int cols, int axis, int bits,
+static int rsvd_plan(LaunchList& ops, const float* X, int ldx, const float* amax, int rows, int cols, int axis, int bits,
                      int round_mode, int rank, int oversample, int power_iters, uint64_t seed,
                      const float* omega_or_null, float* U, float* Sigma, float* Vt, void* workspace,
                      size_t workspace_bytes, hipStream_t st, const std::function<int()>& before_svd = nullptr,
                      const std::function<int()>& after_svd = nullptr) {
-    if (rows < 0 || cols < 0 || rank < 1 || oversample < 0 || power_iters < 0) return LRQMM_ERR_INVALID_ARG;
+    if (rows < 0 || cols < 0 || rank < 1 || oversample < 0 || power_iters < 0 || ldx < cols) return LRQMM_ERR_INVALID_ARG;
     if (axis != LRQMM_AXIS_ROW && axis != LRQMM_AXIS_COL) return LRQMM_ERR_INVALID_ARG;
     if (round_mode != LRQMM_ROUND_FLOOR && round_mode != LRQMM_ROUND_NEAREST) return LRQMM_ERR_INVALID_ARG;
     if (!bits_ok(bits)) return LRQMM_ERR_UNSUPPORTED;
@@ -239,10 +239,10 @@ static int rsvd_plan(LaunchList& ops, const float* X, const float* amax, int row
         ops.push_back([=] { return launch_apply(buf, n, LP, w.T, LP, LP, buf, LP, 0, st); });
     };
     auto pass_n = [&] {
-        ops.push_back([=] { return launch_resid_mul_n(X, rows, cols, axis, w.lam, w.s, q, w.Wc, LP, pn, w.partial, st); });
+        ops.push_back([=] { return launch_resid_mul_n(X, ldx, rows, cols, axis, w.lam, w.s, q, w.Wc, LP, pn, w.partial, st); });
     };
     auto pass_t = [&] {
-        ops.push_back([=] { return launch_resid_mul_t(X, rows, cols, axis, w.lam, w.s, q, w.Yr, LP, pt, w.partial, st); });
+        ops.push_back([=] { return launch_resid_mul_t(X, ldx, rows, cols, axis, w.lam, w.s, q, w.Yr, LP, pt, w.partial, st); });
     };
     // Y = R Omega
     pass_n();
@@ -298,7 +298,13 @@ size_t lrqmm_workspace_bytes(int M, int N, int K, int rank, int oversample) {
 
 int lrqmm_quantize(const float* X, int rows, int cols, int axis, int bits, int round_mode, int8_t* codes,
                    float* amax, void* stream) {
-    if (rows < 0 || cols < 0) return LRQMM_ERR_INVALID_ARG;
+    return lrqmm_quantize_ex(X, cols, rows, cols, axis, bits, round_mode, LRQMM_SCALE_VECTOR, codes, amax, stream);
+}
+
+int lrqmm_quantize_ex(const float* X, int ldx, int rows, int cols, int axis, int bits, int round_mode,
+                      int scale_mode, int8_t* codes, float* amax, void* stream) {
+    if (rows < 0 || cols < 0 || ldx < cols) return LRQMM_ERR_INVALID_ARG;
+    if (scale_mode != LRQMM_SCALE_VECTOR && scale_mode != LRQMM_SCALE_TENSOR) return LRQMM_ERR_INVALID_ARG;
     if (axis != LRQMM_AXIS_ROW && axis != LRQMM_AXIS_COL) return LRQMM_ERR_INVALID_ARG;
     if (round_mode != LRQMM_ROUND_FLOOR && round_mode != LRQMM_ROUND_NEAREST) return LRQMM_ERR_INVALID_ARG;
     if (!bits_ok(bits)) return LRQMM_ERR_UNSUPPORTED;
@@ -306,8 +312,9 @@ int lrqmm_quantize(const float* X, int rows, int cols, int axis, int bits, int r
     if (!X || !codes || !amax) return LRQMM_ERR_INVALID_ARG;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const QuantParams q = make_quant_params(bits, round_mode);
-    if (axis == LRQMM_AXIS_ROW) return launch_quantize_rows(X, rows, cols, q, codes, amax, st);
-    return launch_quantize_cols(X, rows, cols, q, codes, amax, st);
+    const bool per_tensor = scale_mode == LRQMM_SCALE_TENSOR;
+    if (axis == LRQMM_AXIS_ROW) return launch_quantize_rows(X, ldx, rows, cols, q, per_tensor, codes, amax, st);
+    return launch_quantize_cols(X, ldx, rows, cols, q, per_tensor, codes, amax, st);
 }
 
 int lrqmm_fill_sketch(uint64_t seed, int stream_id, int rows, int cols, float* omega, void* stream) {
@@ -320,8 +327,15 @@ int lrqmm_fill_sketch(uint64_t seed, int stream_id, int rows, int cols, float* o
 int lrqmm_rsvd(const float* X, const float* amax, int rows, int cols, int axis, int bits, int round_mode,
                int rank, int oversample, int power_iters, uint64_t seed, const float* omega_or_null, float* U,
                float* Sigma, float* Vt, void* workspace, size_t workspace_bytes, void* stream) {
+    return lrqmm_rsvd_ex(X, cols, amax, rows, cols, axis, bits, round_mode, rank, oversample, power_iters, seed,
+                         omega_or_null, U, Sigma, Vt, workspace, workspace_bytes, stream);
+}
+
+int lrqmm_rsvd_ex(const float* X, int ldx, const float* amax, int rows, int cols, int axis, int bits, int round_mode,
+                  int rank, int oversample, int power_iters, uint64_t seed, const float* omega_or_null, float* U,
+                  float* Sigma, float* Vt, void* workspace, size_t workspace_bytes, void* stream) {
     LaunchList ops;
-    int rc = rsvd_plan(ops, X, amax, rows, cols, axis, bits, round_mode, rank, oversample, power_iters, seed,
+    int rc = rsvd_plan(ops, X, ldx, amax, rows, cols, axis, bits, round_mode, rank, oversample, power_iters, seed,
                        omega_or_null, U, Sigma, Vt, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
     if (rc != LRQMM_OK) return rc;
     return run_interleaved(ops, LaunchList());
@@ -329,10 +343,11 @@ int lrqmm_rsvd(const float* X, const float* amax, int rows, int cols, int axis, 
 
 static int gemm_impl(int M, int N, int K, int bits, int rank, const int8_t* Aq, const float* amaxA,
                      const int8_t* BqT, const float* amaxB, const float* U, const float* Sig, const float* Vt,
-                     const float* W, const float* Gam, const float* Zt, float* C, int32_t* Cint_or_null,
+                     const float* W, const float* Gam, const float* Zt, GemmOut out, int32_t* Cint_or_null,
                      void* workspace, size_t workspace_bytes, void* stream, int prof_slot,
                      hipEvent_t raw_sums_ready = nullptr) {
-    if (M < 0 || N < 0 || K < 0 || rank < 0) return LRQMM_ERR_INVALID_ARG;
+    float* const C = out.C;
+    if (M < 0 || N < 0 || K < 0 || rank < 0 || out.ldc < N) return LRQMM_ERR_INVALID_ARG;
     if (!bits_ok(bits)) return LRQMM_ERR_UNSUPPORTED;
     if (!k_fits_int32(K, bits)) return LRQMM_ERR_UNSUPPORTED;
     if (M == 0 || N == 0) return LRQMM_OK;
@@ -364,13 +379,13 @@ static int gemm_impl(int M, int N, int K, int bits, int rank, const int8_t* Aq, 
         // the integer product ran early on another stream and left its int32 sums in C
         if (hipStreamWaitEvent(st, raw_sums_ready, 0) != hipSuccess) return LRQMM_ERR_HIP;
         prof_mark(prof_slot, 7, st);
-        rc = launch_rank_update(M, N, C, w.sA, w.sB, w.Lp, w.Rp, R2P, st);
+        rc = launch_rank_update(M, N, C, w.sA, w.sB, w.Lp, w.Rp, R2P, out.alpha, st);
         prof_mark(prof_slot, 8, st);
         return rc;
     }
     prof_mark(prof_slot, 7, st);
     rc = launch_int8_gemm(M, N, K, Aq, BqT, w.sA, w.sB, rank > 0 ? w.Lp : nullptr, rank > 0 ? w.Rp : nullptr,
-                          R2P, C, Cint_or_null, st);
+                          R2P, out, Cint_or_null, st);
     prof_mark(prof_slot, 8, st);
     prof_mark(prof_slot, 9, st);
     prof_mark(prof_slot, 10, st);
@@ -381,14 +396,33 @@ int lrqmm_gemm(int M, int N, int K, int bits, int rank, const int8_t* Aq, const 
                const int8_t* BqT, const float* amaxB, const float* U, const float* Sig, const float* Vt,
                const float* W, const float* Gam, const float* Zt, float* C, int32_t* Cint_or_null,
                void* workspace, size_t workspace_bytes, void* stream) {
-    return gemm_impl(M, N, K, bits, rank, Aq, amaxA, BqT, amaxB, U, Sig, Vt, W, Gam, Zt, C, Cint_or_null,
+    return lrqmm_gemm_ex(M, N, K, bits, rank, Aq, amaxA, BqT, amaxB, U, Sig, Vt, W, Gam, Zt, 1.0f, 0.0f, C, N,
+                         Cint_or_null, workspace, workspace_bytes, stream);
+}
+
+int lrqmm_gemm_ex(int M, int N, int K, int bits, int rank, const int8_t* Aq, const float* amaxA,
+                  const int8_t* BqT, const float* amaxB, const float* U, const float* Sig, const float* Vt,
+                  const float* W, const float* Gam, const float* Zt, float alpha, float beta, float* D, int ldd,
+                  int32_t* Cint_or_null, void* workspace, size_t workspace_bytes, void* stream) {
+    const GemmOut out = {D, ldd, alpha, beta};
+    return gemm_impl(M, N, K, bits, rank, Aq, amaxA, BqT, amaxB, U, Sig, Vt, W, Gam, Zt, out, Cint_or_null,
                      workspace, workspace_bytes, stream, -1);
 }
 
 int lrqmm_matmul(int M, int N, int K, int bits, int rank, int oversample, int power_iters, uint64_t seed,
                  int round_mode, const float* A, const float* B, float* C, void* workspace,
                  size_t workspace_bytes, void* stream) {
+    return lrqmm_matmul_ex(M, N, K, bits, rank, oversample, power_iters, seed, round_mode, LRQMM_SCALE_VECTOR, A, K,
+                           B, N, 1.0f, 0.0f, C, N, workspace, workspace_bytes, stream);
+}
+
+int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int power_iters, uint64_t seed,
+                    int round_mode, int scale_mode, const float* A, int lda, const float* B, int ldb, float alpha,
+                    float beta, float* D, int ldd, void* workspace, size_t workspace_bytes, void* stream) {
+    float* const C = D;
     if (M < 0 || N < 0 || K < 0 || rank < 0 || oversample < 0 || power_iters < 0) return LRQMM_ERR_INVALID_ARG;
+    if (lda < K || ldb < N || ldd < N) return LRQMM_ERR_INVALID_ARG;
+    if (scale_mode != LRQMM_SCALE_VECTOR && scale_mode != LRQMM_SCALE_TENSOR) return LRQMM_ERR_INVALID_ARG;
     if (round_mode != LRQMM_ROUND_FLOOR && round_mode != LRQMM_ROUND_NEAREST) return LRQMM_ERR_INVALID_ARG;
     if (!bits_ok(bits)) return LRQMM_ERR_UNSUPPORTED;
     if (!k_fits_int32(K, bits)) return LRQMM_ERR_UNSUPPORTED;
@@ -416,14 +450,15 @@ int lrqmm_matmul(int M, int N, int K, int bits, int rank, int oversample, int po
     // the two sides are planned first and then issued alternately (see LaunchList)
     LaunchList opsA, opsB;
     opsA.push_back([=] { prof_mark(slot, 0, pst); return LRQMM_OK; });
-    if (K > 0) opsA.push_back([=] { return lrqmm_quantize(A, M, K, LRQMM_AXIS_ROW, bits, round_mode, w.Aq, w.amaxA, pst); });
+    if (K > 0) opsA.push_back([=] { return lrqmm_quantize_ex(A, lda, M, K, LRQMM_AXIS_ROW, bits, round_mode, scale_mode, w.Aq, w.amaxA, pst); });
     else opsA.push_back([=] { return launch_pad_copy(nullptr, M, 0, 1, w.amaxA, pst); });
     opsA.push_back([=] { prof_mark(slot, 1, pst); return LRQMM_OK; });
     // Early integer GEMM: with both factorizations in their single-workgroup SVD the GPU is
     // nearly idle, so the int8 product (which needs only the codes) runs there on a third
     // stream, leaves raw int32 sums in C, and the epilogue follows the panels as a kernel of
     // its own.  Used for problems on the large-tile kernel.
-    const bool early = overlap && rank_update_usable(M, N, C);
+    // (the raw sums need D's memory: only when its old contents are not an input and it is dense)
+    const bool early = overlap && rank_update_usable(M, N, C) && beta == 0.0f && ldd == N;
     hipStream_t gst = early ? g_side.gemm_stream : pst;
     std::function<int()> before_svd = nullptr, before_svd_b = nullptr, after_svd_b = nullptr;
     if (early) {
@@ -447,7 +482,7 @@ int lrqmm_matmul(int M, int N, int K, int bits, int rank, int oversample, int po
                 if (r != LRQMM_OK) return r;
             }
             prof_mark(slot, 9, gst);
-            const int r = launch_int8_gemm(M, N, K, w.Aq, w.BqT, nullptr, nullptr, nullptr, nullptr, 0, nullptr,
+            const int r = launch_int8_gemm(M, N, K, w.Aq, w.BqT, nullptr, nullptr, nullptr, nullptr, 0, GemmOut{nullptr, N, 1.0f, 0.0f},
                                            reinterpret_cast<int32_t*>(C), gst);
             prof_mark(slot, 10, gst);
             if (r != LRQMM_OK) return r;
@@ -455,17 +490,17 @@ int lrqmm_matmul(int M, int N, int K, int bits, int rank, int oversample, int po
         };
     }
     if (rank > 0)
-        LRQ_TRY(rsvd_plan(opsA, A, w.amaxA, M, K, LRQMM_AXIS_ROW, bits, round_mode, rank, oversample, power_iters,
+        LRQ_TRY(rsvd_plan(opsA, A, lda, w.amaxA, M, K, LRQMM_AXIS_ROW, bits, round_mode, rank, oversample, power_iters,
                           seed, nullptr, w.U, w.Sig, w.Vt, w.subA, w.subA_bytes, pst, before_svd));
     opsA.push_back([=] { prof_mark(slot, 2, pst); return LRQMM_OK; });
     opsB.push_back([=] { prof_mark(slot, 3, bst); return LRQMM_OK; });
-    if (K > 0) opsB.push_back([=] { return lrqmm_quantize(B, K, N, LRQMM_AXIS_COL, bits, round_mode, w.BqT, w.amaxB, bst); });
+    if (K > 0) opsB.push_back([=] { return lrqmm_quantize_ex(B, ldb, K, N, LRQMM_AXIS_COL, bits, round_mode, scale_mode, w.BqT, w.amaxB, bst); });
     else opsB.push_back([=] { return launch_pad_copy(nullptr, N, 0, 1, w.amaxB, bst); });
     opsB.push_back([=] { prof_mark(slot, 4, bst); return LRQMM_OK; });
     if (early)
         opsB.push_back([=] { return hipEventRecord(g_side.qb, bst) == hipSuccess ? LRQMM_OK : LRQMM_ERR_HIP; });
     if (rank > 0)
-        LRQ_TRY(rsvd_plan(opsB, B, w.amaxB, K, N, LRQMM_AXIS_COL, bits, round_mode, rank, oversample, power_iters,
+        LRQ_TRY(rsvd_plan(opsB, B, ldb, w.amaxB, K, N, LRQMM_AXIS_COL, bits, round_mode, rank, oversample, power_iters,
                           seed, nullptr, w.W, w.Gam, w.Zt, w.subB, w.subB_bytes, bst, before_svd_b,
                           after_svd_b));
     opsB.push_back([=] { prof_mark(slot, 5, bst); return LRQMM_OK; });
@@ -475,8 +510,8 @@ int lrqmm_matmul(int M, int N, int K, int bits, int rank, int oversample, int po
         if (hipStreamWaitEvent(pst, g_side.join, 0) != hipSuccess) return LRQMM_ERR_HIP;
     }
     prof_mark(slot, 6, pst);
-    return gemm_impl(M, N, K, bits, rank, w.Aq, w.amaxA, w.BqT, w.amaxB, w.U, w.Sig, w.Vt, w.W, w.Gam, w.Zt, C,
-                     nullptr, w.sub, w.sub_bytes, stream, slot, early ? g_side.gdone : nullptr);
+    return gemm_impl(M, N, K, bits, rank, w.Aq, w.amaxA, w.BqT, w.amaxB, w.U, w.Sig, w.Vt, w.W, w.Gam, w.Zt,
+                     GemmOut{D, ldd, alpha, beta}, nullptr, w.sub, w.sub_bytes, stream, slot, early ? g_side.gdone : nullptr);
 }
 
 int lrqmm_profile_enable(int on) {

@@ -51,6 +51,15 @@ __device__ __forceinline__ uint4 load16b(const int8_t* __restrict__ base, int ro
     return v;
 }
 
+// Last step of Algorithm 2 on one element: D <- alpha * value + beta * D (D is not read when
+// beta == 0, so it may then hold anything).
+__device__ __forceinline__ void store_out(const GemmOut& out, int row, int col, float value) {
+    float* p = out.C + (size_t)row * out.ldc + col;
+    float o = out.alpha * value;
+    if (out.beta != 0.f) o = o + out.beta * *p;
+    *p = o;
+}
+
 template <bool VEC, bool COMP, bool WCINT>
 __global__ __launch_bounds__(256) void int8_gemm_kernel(int M, int N, int K,
                                                         const int8_t* __restrict__ Aq,
@@ -59,7 +68,7 @@ __global__ __launch_bounds__(256) void int8_gemm_kernel(int M, int N, int K,
                                                         const float* __restrict__ sB,
                                                         const float* __restrict__ Lp,
                                                         const float* __restrict__ Rp, int R2P,
-                                                        float* __restrict__ C,
+                                                        GemmOut out,
                                                         int32_t* __restrict__ Cint, int tiles_n,
                                                         int ntiles) {
     __shared__ __align__(16) int8_t As[2][TM * LDS_STRIDE];
@@ -160,7 +169,7 @@ __global__ __launch_bounds__(256) void int8_gemm_kernel(int M, int N, int K,
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = rbase + 8 * (v >> 2) + 4 * lh + (v & 3);
-                if (row < M && col_ok) C[(size_t)row * N + col] = f[v];
+                if (row < M && col_ok) store_out(out, row, col, f[v]);
             }
         }
     }
@@ -209,9 +218,10 @@ __global__ __launch_bounds__(512, 1) void int8_gemm256_kernel(int M, int N, int 
                                                               const float* __restrict__ sB,
                                                               const float* __restrict__ Lp,
                                                               const float* __restrict__ Rp, int R2P,
-                                                              float* __restrict__ C,
+                                                              GemmOut out,
                                                               int32_t* __restrict__ Cint, int tiles_n,
                                                               int ntiles) {
+    float* __restrict__ C = out.C;
     __shared__ __align__(16) int8_t As[2][BTM * BSTRIDE];
     __shared__ __align__(16) int8_t Bs[2][BTN * BSTRIDE];
     int tile = blockIdx.x;
@@ -349,7 +359,7 @@ __global__ __launch_bounds__(512, 1) void int8_gemm256_kernel(int M, int N, int 
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int row = rbase + 8 * (v >> 2) + 4 * lh + (v & 3);
-                    if (row < M && col_ok) C[(size_t)row * N + col] = f[v];
+                    if (row < M && col_ok) store_out(out, row, col, f[v]);
                 }
             }
         }
@@ -371,7 +381,8 @@ __global__ __launch_bounds__(256, 3) void rank_update_kernel(int M, int N, float
                                                           const float* __restrict__ sA,
                                                           const float* __restrict__ sB,
                                                           const float* __restrict__ Lp,
-                                                          const float* __restrict__ Rp, int R2P, int tiles_n) {
+                                                          const float* __restrict__ Rp, int R2P, int tiles_n,
+                                                          float alpha) {
     const int m0 = (blockIdx.x / tiles_n) * 128, n0 = (blockIdx.x % tiles_n) * 128;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int wm = wave >> 1, wn = wave & 1;
@@ -463,7 +474,8 @@ __global__ __launch_bounds__(256, 3) void rank_update_kernel(int M, int N, float
             for (int g = 0; g < 4; ++g)
                 if (row_ok[mt] && col_ok[nt][g])
                     *reinterpret_cast<float4*>(C + (size_t)row[mt] * N + colb[nt][g]) =
-                        make_float4(f[mt][nt][4 * g + 0], f[mt][nt][4 * g + 1], f[mt][nt][4 * g + 2], f[mt][nt][4 * g + 3]);
+                        make_float4(alpha * f[mt][nt][4 * g + 0], alpha * f[mt][nt][4 * g + 1],
+                                    alpha * f[mt][nt][4 * g + 2], alpha * f[mt][nt][4 * g + 3]);
 }
 
 // ---------------------------------------------------------------------------
@@ -754,7 +766,7 @@ int launch_build_panels(int M, int N, int K, int r, int RP, int R2P, const float
 template <bool VEC>
 static void dispatch_gemm256(bool comp, bool wcint, dim3 grid, hipStream_t st, int M, int N, int K,
                              const int8_t* Aq, const int8_t* BqT, const float* sA, const float* sB,
-                             const float* Lp, const float* Rp, int R2P, float* C, int32_t* Cint, int tiles_n,
+                             const float* Lp, const float* Rp, int R2P, GemmOut C, int32_t* Cint, int tiles_n,
                              int ntiles) {
     const bool full = VEC && (M % BTM == 0) && (N % BTN == 0) && (K % BBK == 0) && K >= BBK;
 #define LRQ_GEMM(COMP, WC)                                                                                   \
@@ -777,7 +789,7 @@ static void dispatch_gemm256(bool comp, bool wcint, dim3 grid, hipStream_t st, i
 template <bool VEC>
 static void dispatch_gemm(bool comp, bool wcint, dim3 grid, hipStream_t st, int M, int N, int K,
                           const int8_t* Aq, const int8_t* BqT, const float* sA, const float* sB,
-                          const float* Lp, const float* Rp, int R2P, float* C, int32_t* Cint, int tiles_n,
+                          const float* Lp, const float* Rp, int R2P, GemmOut C, int32_t* Cint, int tiles_n,
                           int ntiles) {
 #define LRQ_GEMM(COMP, WC) \
     hipLaunchKernelGGL((int8_gemm_kernel<VEC, COMP, WC>), grid, dim3(256), 0, st, M, N, K, Aq, BqT, sA, sB, Lp, Rp, R2P, C, Cint, tiles_n, ntiles)
@@ -799,16 +811,16 @@ bool rank_update_usable(int M, int N, const float* C) {
 }
 
 int launch_rank_update(int M, int N, float* C, const float* sA, const float* sB, const float* Lp, const float* Rp,
-                       int R2P, hipStream_t st) {
+                       int R2P, float alpha, hipStream_t st) {
     const int tiles_n = ceil_div(N, 128);
     hipLaunchKernelGGL(rank_update_kernel, dim3(ceil_div(M, 128) * tiles_n), dim3(256), 0, st, M, N, C, sA, sB, Lp,
-                       Rp, R2P, tiles_n);
+                       Rp, R2P, tiles_n, alpha);
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }
 
 int launch_int8_gemm(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, const float* sA,
-                     const float* sB, const float* Lp, const float* Rp, int R2P, float* C, int32_t* Cint,
+                     const float* sB, const float* Lp, const float* Rp, int R2P, GemmOut C, int32_t* Cint,
                      hipStream_t st) {
     const bool vec = (K % 16 == 0) && (((uintptr_t)Aq | (uintptr_t)BqT) & 15) == 0;
     const bool comp = Lp != nullptr;

@@ -6,10 +6,12 @@
 #include "../../include/lrqmm.h"
 
 // ---- quantize.hip -------------------------------------------------------
-int launch_quantize_rows(const float* X, int rows, int cols, QuantParams q, int8_t* codes,
-                         float* amax, hipStream_t st);
-int launch_quantize_cols(const float* X, int rows, int cols, QuantParams q, int8_t* codesT,
-                         float* amax, hipStream_t st);
+// X is rows x cols with row stride ldx (>= cols).  per_tensor: one scale for the whole matrix,
+// i.e. every entry of amax holds the global maximum.
+int launch_quantize_rows(const float* X, int ldx, int rows, int cols, QuantParams q, bool per_tensor,
+                         int8_t* codes, float* amax, hipStream_t st);
+int launch_quantize_cols(const float* X, int ldx, int rows, int cols, QuantParams q, bool per_tensor,
+                         int8_t* codesT, float* amax, hipStream_t st);
 // lam[n], s[n] from amax[n]; entries n..npad-1 are zero-filled.
 // A minimal kernel (writes one zero word): used as a few microseconds of delay on a stream.
 int launch_tick(uint32_t* word, hipStream_t st);
@@ -36,12 +38,13 @@ struct PassPlan {
 };
 PassPlan plan_pass_n(int rows, int cols);
 PassPlan plan_pass_t(int rows, int cols);
+// X is rows x cols with row stride ldx (>= cols) in both passes.
 // partial[s][rows][LP] = R[:, chunk s] . W[chunk s, :]      (W is cols x LP)
-int launch_resid_mul_n(const float* X, int rows, int cols, int axis, const float* lam,
+int launch_resid_mul_n(const float* X, int ldx, int rows, int cols, int axis, const float* lam,
                        const float* s, QuantParams q, const float* W, int LP, PassPlan plan,
                        float* partial, hipStream_t st);
 // partial[s][cols][LP] = R[chunk s, :]^T . W[chunk s, :]    (W is rows x LP)
-int launch_resid_mul_t(const float* X, int rows, int cols, int axis, const float* lam,
+int launch_resid_mul_t(const float* X, int ldx, int rows, int cols, int axis, const float* lam,
                        const float* s, QuantParams q, const float* W, int LP, PassPlan plan,
                        float* partial, hipStream_t st);
 // Two independent products in one launch:
@@ -92,9 +95,16 @@ int launch_build_panels(int M, int N, int K, int r, int RP, int R2P, const float
                         const float* sA, const float* partialA, int splitsA, const float* sB,
                         const float* partialB, int splitsB, const float* Xp, const float* Gam, const float* Zt,
                         float* Lp, float* Rp, hipStream_t st);
-// C = diag(sA) (Aq . BqT^T) diag(sB) [+ Lp . Rp^T when Lp != null]; optional raw int32 output.
+// Destination of the GEMM: D (row stride ldc) <- alpha * result + beta * D; D is not read when beta == 0.
+struct GemmOut {
+    float* C;
+    int ldc;
+    float alpha, beta;
+};
+// result = diag(sA) (Aq . BqT^T) diag(sB) [+ Lp . Rp^T when Lp != null]; optional raw int32 output
+// (M x N, dense).
 int launch_int8_gemm(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, const float* sA,
-                     const float* sB, const float* Lp, const float* Rp, int R2P, float* C,
+                     const float* sB, const float* Lp, const float* Rp, int R2P, GemmOut C,
                      int32_t* Cint, hipStream_t st);
 // True when launch_int8_gemm uses the large-tile kernel, which accepts C == null together with
 // Cint != null (raw int32 sums only; sA, sB are then not read).
@@ -102,6 +112,6 @@ bool int8_gemm_large_tiles(int M, int N);
 // True when the integer product may run early and launch_rank_update finish the job: the
 // large-tile kernel applies, N % 4 == 0 and C is 16-byte aligned.
 bool rank_update_usable(int M, int N, const float* C);
-// C (holding raw int32 sums in its memory) <- float(Cint) sA_i sB_j + Lp . Rp^T, in place.
+// C (dense, holding raw int32 sums in its memory) <- alpha (float(Cint) sA_i sB_j + Lp . Rp^T), in place.
 int launch_rank_update(int M, int N, float* C, const float* sA, const float* sB, const float* Lp, const float* Rp,
-                       int R2P, hipStream_t st);
+                       int R2P, float alpha, hipStream_t st);

@@ -55,7 +55,7 @@ struct WStage {
 // ---------------------------------------------------------------------------
 template <int NT, int AXIS, bool VEC>
 __global__ __launch_bounds__(256) void resid_mul_n_kernel(
-    const float* __restrict__ X, int rows, int cols, const float* __restrict__ lam,
+    const float* __restrict__ X, int ldx, int rows, int cols, const float* __restrict__ lam,
     const float* __restrict__ sc, QuantParams q, const float* __restrict__ W, int chunk,
     float* __restrict__ partial) {
     constexpr int LP = NT * 16;
@@ -68,7 +68,7 @@ __global__ __launch_bounds__(256) void resid_mul_n_kernel(
     const int r = lane & 15, g = lane >> 4;
     const int row = blockIdx.x * 64 + wave * 16 + r;
     const bool row_ok = row < rows;
-    const float* xp = X + (size_t)(row_ok ? row : 0) * cols;
+    const float* xp = X + (size_t)(row_ok ? row : 0) * ldx;
     const int kb = blockIdx.y * chunk;
     const int ke = min(cols, kb + chunk);
     float lam_r = 0.f, s_r = 0.f;
@@ -375,7 +375,7 @@ __global__ __launch_bounds__(256, 1) void codes_mul_bf16_kernel(CodesJobBf16 j0,
 #define TUNR 4
 template <int NT, int AXIS, bool VEC>
 __global__ __launch_bounds__(256) void resid_mul_t_kernel(
-    const float* __restrict__ X, int rows, int cols, const float* __restrict__ lam,
+    const float* __restrict__ X, int ldx, int rows, int cols, const float* __restrict__ lam,
     const float* __restrict__ sc, QuantParams q, const float* __restrict__ W, int chunk,
     float* __restrict__ partial) {
     constexpr int LP = NT * 16;
@@ -406,7 +406,7 @@ __global__ __launch_bounds__(256) void resid_mul_t_kernel(
         const int i = i0 + g;
         const bool ok = i < ie;
         const size_t ii = ok ? (size_t)i : 0;
-        f.x = load4f<VEC>(X + ii * cols, kc, cols, ok);
+        f.x = load4f<VEC>(X + ii * ldx, kc, cols, ok);
         if (AXIS == 0) {            // unconditional loads from a valid row, then selects
             const float l = lam[ii], sv = sc[ii];
             f.lr = ok ? l : 0.f;
@@ -502,28 +502,28 @@ PassPlan plan_pass_t(int rows, int cols) {
 static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 template <int NT>
-static void dispatch_n(int axis, bool vec, dim3 grid, hipStream_t st, const float* X, int rows, int cols,
+static void dispatch_n(int axis, bool vec, dim3 grid, hipStream_t st, const float* X, int ldx, int rows, int cols,
                        const float* lam, const float* s, QuantParams q, const float* W, int chunk,
                        float* partial) {
     if (axis == 0) {
-        if (vec) hipLaunchKernelGGL((resid_mul_n_kernel<NT, 0, true>), grid, dim3(256), 0, st, X, rows, cols, lam, s, q, W, chunk, partial);
-        else     hipLaunchKernelGGL((resid_mul_n_kernel<NT, 0, false>), grid, dim3(256), 0, st, X, rows, cols, lam, s, q, W, chunk, partial);
+        if (vec) hipLaunchKernelGGL((resid_mul_n_kernel<NT, 0, true>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+        else     hipLaunchKernelGGL((resid_mul_n_kernel<NT, 0, false>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
     } else {
-        if (vec) hipLaunchKernelGGL((resid_mul_n_kernel<NT, 1, true>), grid, dim3(256), 0, st, X, rows, cols, lam, s, q, W, chunk, partial);
-        else     hipLaunchKernelGGL((resid_mul_n_kernel<NT, 1, false>), grid, dim3(256), 0, st, X, rows, cols, lam, s, q, W, chunk, partial);
+        if (vec) hipLaunchKernelGGL((resid_mul_n_kernel<NT, 1, true>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+        else     hipLaunchKernelGGL((resid_mul_n_kernel<NT, 1, false>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
     }
 }
 
 template <int NT>
-static void dispatch_t(int axis, bool vec, dim3 grid, hipStream_t st, const float* X, int rows, int cols,
+static void dispatch_t(int axis, bool vec, dim3 grid, hipStream_t st, const float* X, int ldx, int rows, int cols,
                        const float* lam, const float* s, QuantParams q, const float* W, int chunk,
                        float* partial) {
     if (axis == 0) {
-        if (vec) hipLaunchKernelGGL((resid_mul_t_kernel<NT, 0, true>), grid, dim3(256), 0, st, X, rows, cols, lam, s, q, W, chunk, partial);
-        else     hipLaunchKernelGGL((resid_mul_t_kernel<NT, 0, false>), grid, dim3(256), 0, st, X, rows, cols, lam, s, q, W, chunk, partial);
+        if (vec) hipLaunchKernelGGL((resid_mul_t_kernel<NT, 0, true>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+        else     hipLaunchKernelGGL((resid_mul_t_kernel<NT, 0, false>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
     } else {
-        if (vec) hipLaunchKernelGGL((resid_mul_t_kernel<NT, 1, true>), grid, dim3(256), 0, st, X, rows, cols, lam, s, q, W, chunk, partial);
-        else     hipLaunchKernelGGL((resid_mul_t_kernel<NT, 1, false>), grid, dim3(256), 0, st, X, rows, cols, lam, s, q, W, chunk, partial);
+        if (vec) hipLaunchKernelGGL((resid_mul_t_kernel<NT, 1, true>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+        else     hipLaunchKernelGGL((resid_mul_t_kernel<NT, 1, false>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
     }
 }
 
@@ -543,22 +543,22 @@ static void dispatch_c(bool vec, dim3 grid, hipStream_t st, CodesJob j0, CodesJo
         default: return LRQMM_ERR_UNSUPPORTED;          \
     }
 
-int launch_resid_mul_n(const float* X, int rows, int cols, int axis, const float* lam, const float* s,
+int launch_resid_mul_n(const float* X, int ldx, int rows, int cols, int axis, const float* lam, const float* s,
                        QuantParams q, const float* W, int LP, PassPlan plan, float* partial,
                        hipStream_t st) {
-    const bool vec = (cols % 4 == 0) && aligned16(X);
+    const bool vec = (cols % 4 == 0) && (ldx % 4 == 0) && aligned16(X);
     dim3 grid(ceil_div(rows, 64), plan.splits);
-    NT_SWITCH(LP / 16, (dispatch_n<NT_>(axis, vec, grid, st, X, rows, cols, lam, s, q, W, plan.chunk, partial)));
+    NT_SWITCH(LP / 16, (dispatch_n<NT_>(axis, vec, grid, st, X, ldx, rows, cols, lam, s, q, W, plan.chunk, partial)));
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }
 
-int launch_resid_mul_t(const float* X, int rows, int cols, int axis, const float* lam, const float* s,
+int launch_resid_mul_t(const float* X, int ldx, int rows, int cols, int axis, const float* lam, const float* s,
                        QuantParams q, const float* W, int LP, PassPlan plan, float* partial,
                        hipStream_t st) {
-    const bool vec = (cols % 4 == 0) && aligned16(X);
+    const bool vec = (cols % 4 == 0) && (ldx % 4 == 0) && aligned16(X);
     dim3 grid(ceil_div(cols, 64), plan.splits);
-    NT_SWITCH(LP / 16, (dispatch_t<NT_>(axis, vec, grid, st, X, rows, cols, lam, s, q, W, plan.chunk, partial)));
+    NT_SWITCH(LP / 16, (dispatch_t<NT_>(axis, vec, grid, st, X, ldx, rows, cols, lam, s, q, W, plan.chunk, partial)));
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }

@@ -4,24 +4,32 @@
 #include "kernels.h"
 
 // One wavefront per row: absmax by wave reduction, then codes with 4-byte packed stores.
+// mode (all row kernels): ROWS_FULL computes amax and codes; ROWS_AMAX_ONLY stops after amax;
+// ROWS_GIVEN_AMAX reads amax[row] (written by an earlier launch) instead of the row's own maximum.
+enum { ROWS_FULL = 0, ROWS_AMAX_ONLY = 1, ROWS_GIVEN_AMAX = 2 };
 template <bool VEC>
-__global__ __launch_bounds__(256) void quant_rows_kernel(const float* __restrict__ X, int rows,
+__global__ __launch_bounds__(256) void quant_rows_kernel(const float* __restrict__ X, int ldx, int rows,
                                                          int cols, QuantParams q,
                                                          int8_t* __restrict__ codes,
-                                                         float* __restrict__ amax) {
+                                                         float* __restrict__ amax, int mode) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + wave;
     if (row >= rows) return;
-    const float* xp = X + (size_t)row * cols;
+    const float* xp = X + (size_t)row * ldx;
     float m = 0.0f;
-    for (int k = lane * 4; k < cols; k += 256) {
-        float4 v = load4f<VEC>(xp, k, cols, true);
-        m = fmaxf(fmaxf(m, fabsf(v.x)), fmaxf(fabsf(v.y), fmaxf(fabsf(v.z), fabsf(v.w))));
+    if (mode == ROWS_GIVEN_AMAX) {
+        m = amax[row];
+    } else {
+        for (int k = lane * 4; k < cols; k += 256) {
+            float4 v = load4f<VEC>(xp, k, cols, true);
+            m = fmaxf(fmaxf(m, fabsf(v.x)), fmaxf(fabsf(v.y), fmaxf(fabsf(v.z), fabsf(v.w))));
+        }
+        m = wave_max(m);
+        if (lane == 0) amax[row] = m;
+        if (mode == ROWS_AMAX_ONLY) return;
     }
-    m = wave_max(m);
     float lam, s;
     make_scales(m, q.qmaxf, lam, s);
-    if (lane == 0) amax[row] = m;
     int8_t* cp = codes + (size_t)row * cols;
     for (int k = lane * 4; k < cols; k += 256) {
         float4 v = load4f<VEC>(xp, k, cols, true);
@@ -44,15 +52,15 @@ __global__ __launch_bounds__(256) void quant_rows_kernel(const float* __restrict
 // code computation (NV float4 per thread, NV <= 16), so A is fetched from HBM once.  TPR threads
 // cooperate on a row: 64 (one wavefront, cols <= 4096) or 256 (a workgroup, cols <= 16384).
 template <bool VEC, int TPR, int NV>
-__global__ __launch_bounds__(256) void quant_rows_cached_kernel(const float* __restrict__ X, int rows,
+__global__ __launch_bounds__(256) void quant_rows_cached_kernel(const float* __restrict__ X, int ldx, int rows,
                                                                 int cols, QuantParams q,
                                                                 int8_t* __restrict__ codes,
-                                                                float* __restrict__ amax) {
+                                                                float* __restrict__ amax, int mode) {
     __shared__ float wmax[4];
     const int t = threadIdx.x % TPR;
     const int row = blockIdx.x * (256 / TPR) + threadIdx.x / TPR;
     const bool row_ok = row < rows;
-    const float* xp = X + (size_t)(row_ok ? row : 0) * cols;
+    const float* xp = X + (size_t)(row_ok ? row : 0) * ldx;
     float4 v[NV];
     float m = 0.0f;
 #pragma unroll
@@ -68,9 +76,11 @@ __global__ __launch_bounds__(256) void quant_rows_cached_kernel(const float* __r
         m = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
     }
     if (!row_ok) return;
+    if (mode == ROWS_GIVEN_AMAX) m = amax[row];
+    else if (t == 0) amax[row] = m;
+    if (mode == ROWS_AMAX_ONLY) return;
     float lam, s;
     make_scales(m, q.qmaxf, lam, s);
-    if (t == 0) amax[row] = m;
     int8_t* cp = codes + (size_t)row * cols;
 #pragma unroll
     for (int u = 0; u < NV; ++u) {
@@ -100,7 +110,7 @@ __global__ void fill_u32_kernel(uint32_t* p, int n, uint32_t v) {
 // slab of rows (coalesced 4 KB per row per block); slabs are merged with an unsigned
 // atomic max on the bit pattern of |x| (exact and order independent for x >= 0).
 template <bool VEC>
-__global__ __launch_bounds__(256) void absmax_cols_kernel(const float* __restrict__ X, int rows,
+__global__ __launch_bounds__(256) void absmax_cols_kernel(const float* __restrict__ X, int ldx, int rows,
                                                           int cols, int rows_per_block,
                                                           uint32_t* __restrict__ amax_bits) {
     const int c = (blockIdx.x * 256 + threadIdx.x) * 4;
@@ -111,7 +121,7 @@ __global__ __launch_bounds__(256) void absmax_cols_kernel(const float* __restric
     for (int rb = r0; rb < r1; rb += 16) {      // 16 row loads in flight per thread (rows clamped, max is idempotent)
         float4 v[16];
 #pragma unroll
-        for (int u = 0; u < 16; ++u) v[u] = load4f<VEC>(X + (size_t)min(rb + u, r1 - 1) * cols, c, cols, true);
+        for (int u = 0; u < 16; ++u) v[u] = load4f<VEC>(X + (size_t)min(rb + u, r1 - 1) * ldx, c, cols, true);
 #pragma unroll
         for (int u = 0; u < 16; ++u) {
             m.x = fmaxf(m.x, fabsf(v[u].x));
@@ -129,7 +139,7 @@ __global__ __launch_bounds__(256) void absmax_cols_kernel(const float* __restric
 // Quantize a 64(k) x 64(n) tile with per-column scales and store it transposed
 // (codesT is cols x rows, contiguous along the original row index k).
 template <bool VEC, bool VECOUT>
-__global__ __launch_bounds__(256) void quant_cols_kernel(const float* __restrict__ X, int rows,
+__global__ __launch_bounds__(256) void quant_cols_kernel(const float* __restrict__ X, int ldx, int rows,
                                                          int cols, const float* __restrict__ amax,
                                                          QuantParams q,
                                                          int8_t* __restrict__ codesT) {
@@ -148,7 +158,7 @@ __global__ __launch_bounds__(256) void quant_cols_kernel(const float* __restrict
     for (int rr = 0; rr < 4; ++rr) {
         const int kl = ty + 16 * rr;
         const int k = k0 + kl;
-        float4 v = load4f<VEC>(X + (size_t)min(k, rows - 1) * cols, n, cols, k < rows);
+        float4 v = load4f<VEC>(X + (size_t)min(k, rows - 1) * ldx, n, cols, k < rows);
         tile[tx * 4 + 0][kl] = (int8_t)(int)quant_code(v.x, lam[0], q);
         tile[tx * 4 + 1][kl] = (int8_t)(int)quant_code(v.y, lam[1], q);
         tile[tx * 4 + 2][kl] = (int8_t)(int)quant_code(v.z, lam[2], q);
@@ -179,18 +189,47 @@ __global__ void scales_kernel(const float* __restrict__ amax, int n, int npad, f
     s[i] = st;
 }
 
+// One scale for the whole matrix (the paper's own Eq. (quantA)): every entry of amax[n] is
+// replaced by the maximum of all of them.  One workgroup; max is exact and order independent.
+__global__ __launch_bounds__(1024) void tensor_max_kernel(float* __restrict__ amax, int n) {
+    __shared__ float wm[16];
+    float m = 0.0f;
+    for (int i = threadIdx.x; i < n; i += 1024) m = fmaxf(m, amax[i]);
+    m = wave_max(m);
+    if ((threadIdx.x & 63) == 0) wm[threadIdx.x >> 6] = m;
+    __syncthreads();
+    m = wm[0];
+#pragma unroll
+    for (int w = 1; w < 16; ++w) m = fmaxf(m, wm[w]);
+    for (int i = threadIdx.x; i < n; i += 1024) amax[i] = m;
+}
+
 static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
-int launch_quantize_rows(const float* X, int rows, int cols, QuantParams q, int8_t* codes,
-                         float* amax, hipStream_t st) {
-    const bool vec = (cols % 4 == 0) && aligned16(X) && (((uintptr_t)codes & 3) == 0);
+static int rows_launch(const float* X, int ldx, int rows, int cols, QuantParams q, int8_t* codes, float* amax,
+                       int mode, hipStream_t st);
+
+int launch_quantize_rows(const float* X, int ldx, int rows, int cols, QuantParams q, bool per_tensor,
+                         int8_t* codes, float* amax, hipStream_t st) {
+    if (!per_tensor) return rows_launch(X, ldx, rows, cols, q, codes, amax, ROWS_FULL, st);
+    // one scale per matrix: row maxima, their maximum broadcast to every row, then the codes
+    int rc = rows_launch(X, ldx, rows, cols, q, codes, amax, ROWS_AMAX_ONLY, st);
+    if (rc != LRQMM_OK) return rc;
+    hipLaunchKernelGGL(tensor_max_kernel, dim3(1), dim3(1024), 0, st, amax, rows);
+    LRQ_CHECK_LAUNCH();
+    return rows_launch(X, ldx, rows, cols, q, codes, amax, ROWS_GIVEN_AMAX, st);
+}
+
+static int rows_launch(const float* X, int ldx, int rows, int cols, QuantParams q, int8_t* codes, float* amax,
+                       int mode, hipStream_t st) {
+    const bool vec = (cols % 4 == 0) && (ldx % 4 == 0) && aligned16(X) && (((uintptr_t)codes & 3) == 0);
     if (cols <= 256 * 4 * 16) {
         // Row cached in registers: one wavefront per row up to 4096 columns, else one workgroup.
         const bool wave = cols <= 64 * 4 * 16;
         const int per = wave ? 256 : 1024;
         const int need = ceil_div(cols, per);
         dim3 grid(wave ? ceil_div(rows, 4) : rows);
-#define LRQ_QR(V, T, N) hipLaunchKernelGGL((quant_rows_cached_kernel<V, T, N>), grid, dim3(256), 0, st, X, rows, cols, q, codes, amax)
+#define LRQ_QR(V, T, N) hipLaunchKernelGGL((quant_rows_cached_kernel<V, T, N>), grid, dim3(256), 0, st, X, ldx, rows, cols, q, codes, amax, mode)
 #define LRQ_QR_NV(V, T) do { if (need <= 1) LRQ_QR(V, T, 1); else if (need <= 2) LRQ_QR(V, T, 2); \
         else if (need <= 4) LRQ_QR(V, T, 4); else if (need <= 8) LRQ_QR(V, T, 8); else LRQ_QR(V, T, 16); } while (0)
         if (wave) { if (vec) LRQ_QR_NV(true, 64); else LRQ_QR_NV(false, 64); }
@@ -199,16 +238,16 @@ int launch_quantize_rows(const float* X, int rows, int cols, QuantParams q, int8
 #undef LRQ_QR
     } else {                              // very long rows: two passes over the row
         dim3 grid(ceil_div(rows, 4));
-        if (vec) hipLaunchKernelGGL(quant_rows_kernel<true>, grid, dim3(256), 0, st, X, rows, cols, q, codes, amax);
-        else     hipLaunchKernelGGL(quant_rows_kernel<false>, grid, dim3(256), 0, st, X, rows, cols, q, codes, amax);
+        if (vec) hipLaunchKernelGGL(quant_rows_kernel<true>, grid, dim3(256), 0, st, X, ldx, rows, cols, q, codes, amax, mode);
+        else     hipLaunchKernelGGL(quant_rows_kernel<false>, grid, dim3(256), 0, st, X, ldx, rows, cols, q, codes, amax, mode);
     }
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }
 
-int launch_quantize_cols(const float* X, int rows, int cols, QuantParams q, int8_t* codesT,
-                         float* amax, hipStream_t st) {
-    const bool vec = (cols % 4 == 0) && aligned16(X);
+int launch_quantize_cols(const float* X, int ldx, int rows, int cols, QuantParams q, bool per_tensor,
+                         int8_t* codesT, float* amax, hipStream_t st) {
+    const bool vec = (cols % 4 == 0) && (ldx % 4 == 0) && aligned16(X);
     const bool vecout = (rows % 16 == 0) && aligned16(codesT);
     hipLaunchKernelGGL(fill_u32_kernel, dim3(ceil_div(cols, 256)), dim3(256), 0, st,
                        reinterpret_cast<uint32_t*>(amax), cols, 0u);
@@ -220,21 +259,25 @@ int launch_quantize_cols(const float* X, int rows, int cols, QuantParams q, int8
     slabs = ceil_div(rows, rows_per_block);
     dim3 g1(col_blocks, slabs);
     if (vec)
-        hipLaunchKernelGGL(absmax_cols_kernel<true>, g1, dim3(256), 0, st, X, rows, cols, rows_per_block,
+        hipLaunchKernelGGL(absmax_cols_kernel<true>, g1, dim3(256), 0, st, X, ldx, rows, cols, rows_per_block,
                            reinterpret_cast<uint32_t*>(amax));
     else
-        hipLaunchKernelGGL(absmax_cols_kernel<false>, g1, dim3(256), 0, st, X, rows, cols, rows_per_block,
+        hipLaunchKernelGGL(absmax_cols_kernel<false>, g1, dim3(256), 0, st, X, ldx, rows, cols, rows_per_block,
                            reinterpret_cast<uint32_t*>(amax));
     LRQ_CHECK_LAUNCH();
+    if (per_tensor) {
+        hipLaunchKernelGGL(tensor_max_kernel, dim3(1), dim3(1024), 0, st, amax, cols);
+        LRQ_CHECK_LAUNCH();
+    }
     dim3 g2(ceil_div(cols, 64), ceil_div(rows, 64));
     if (vec && vecout)
-        hipLaunchKernelGGL((quant_cols_kernel<true, true>), g2, dim3(256), 0, st, X, rows, cols, amax, q, codesT);
+        hipLaunchKernelGGL((quant_cols_kernel<true, true>), g2, dim3(256), 0, st, X, ldx, rows, cols, amax, q, codesT);
     else if (vec)
-        hipLaunchKernelGGL((quant_cols_kernel<true, false>), g2, dim3(256), 0, st, X, rows, cols, amax, q, codesT);
+        hipLaunchKernelGGL((quant_cols_kernel<true, false>), g2, dim3(256), 0, st, X, ldx, rows, cols, amax, q, codesT);
     else if (vecout)
-        hipLaunchKernelGGL((quant_cols_kernel<false, true>), g2, dim3(256), 0, st, X, rows, cols, amax, q, codesT);
+        hipLaunchKernelGGL((quant_cols_kernel<false, true>), g2, dim3(256), 0, st, X, ldx, rows, cols, amax, q, codesT);
     else
-        hipLaunchKernelGGL((quant_cols_kernel<false, false>), g2, dim3(256), 0, st, X, rows, cols, amax, q, codesT);
+        hipLaunchKernelGGL((quant_cols_kernel<false, false>), g2, dim3(256), 0, st, X, ldx, rows, cols, amax, q, codesT);
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }

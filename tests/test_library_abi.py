@@ -53,6 +53,13 @@ def test_host_side_validation_without_a_gpu():
     assert lib.lrqmm_gemm(4, 4, 1 << 20, 8, 0, *([None] * 12), None, 0, None) == -2
     assert lib.lrqmm_matmul(4, 4, 4, 8, 5, 0, 0, 0, 0, None, None, None, None, 0, None) == -1
     assert lib.lrqmm_fill_sketch(1, -1, 4, 4, None, None) == -1
+    # strides below the row length, unknown scale granularity
+    assert lib.lrqmm_quantize_ex(None, 3, 4, 4, 0, 8, 0, 0, None, None, None) == -1
+    assert lib.lrqmm_quantize_ex(None, 4, 4, 4, 0, 8, 0, 7, None, None, None) == -1
+    assert lib.lrqmm_rsvd_ex(None, 7, None, 8, 8, 0, 8, 0, 2, 0, 0, 0, None, None, None, None, None, 0, None) == -1
+    assert lib.lrqmm_gemm_ex(4, 4, 4, 8, 0, *([None] * 10), 1.0, 0.0, None, 3, None, None, 0, None) == -1
+    assert lib.lrqmm_matmul_ex(4, 4, 4, 8, 0, 0, 0, 0, 0, 0, None, 3, None, 4, 1.0, 0.0, None, 4, None, 0, None) == -1
+    assert lib.lrqmm_matmul_ex(4, 4, 4, 8, 0, 0, 0, 0, 0, 3, None, 4, None, 4, 1.0, 0.0, None, 4, None, 0, None) == -1
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
