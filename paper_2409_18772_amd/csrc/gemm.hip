@@ -179,26 +179,6 @@ __global__ __launch_bounds__(256) void int8_gemm_kernel(int M, int N, int K,
 // CU (two waves per SIMD, so one wave's LDS/global waits and barrier stalls are covered by
 // the other's MFMAs).  Waves form a 4x2 grid, each 64x128 = 2x4 MFMA tiles (128 accumulator
 // registers); per 32-deep MFMA step a wave reads 6 KB of operands from LDS for 8 MFMAs.
-#ifdef LRQ_ABLATE_LDS_BROADCAST   // timing experiment only: every lane reads row 0 (wrong results)
-#define LRQ_ABL_ROW(x) 0
-#else
-#define LRQ_ABL_ROW(x) (x)
-#endif
-#ifdef LRQ_ABLATE_GLOAD
-#define LRQ_ABL_GLOAD(x)
-#else
-#define LRQ_ABL_GLOAD(x) x
-#endif
-#ifdef LRQ_ABLATE_SSTORE
-#define LRQ_ABL_SSTORE(x)
-#else
-#define LRQ_ABL_SSTORE(x) x
-#endif
-#ifdef LRQ_ABLATE_SYNC
-#define LRQ_ABL_SYNC(x)
-#else
-#define LRQ_ABL_SYNC(x) x
-#endif
 #define BTM 256
 #define BTN 256
 #ifndef BBK
@@ -279,11 +259,11 @@ __global__ __launch_bounds__(512, 1) void int8_gemm256_kernel(int M, int N, int 
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
                 af[mt] = *reinterpret_cast<const v4i*>(
-                    &As[buf][(wm * 64 + mt * 32 + LRQ_ABL_ROW(l32)) * BSTRIDE + kk * 32 + LRQ_ABL_ROW(lh) * 16]);
+                    &As[buf][(wm * 64 + mt * 32 + l32) * BSTRIDE + kk * 32 + lh * 16]);
 #pragma unroll
             for (int nt = 0; nt < 4; ++nt)
                 bf[nt] = *reinterpret_cast<const v4i*>(
-                    &Bs[buf][(wn * 128 + nt * 32 + LRQ_ABL_ROW(l32)) * BSTRIDE + kk * 32 + LRQ_ABL_ROW(lh) * 16]);
+                    &Bs[buf][(wn * 128 + nt * 32 + l32) * BSTRIDE + kk * 32 + lh * 16]);
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
@@ -301,10 +281,10 @@ __global__ __launch_bounds__(512, 1) void int8_gemm256_kernel(int M, int N, int 
 #define LRQ_GEMM_STEP(J, SCUR, SNEXT)                  \
     if (kt + J < nk) {                                 \
         const int i = kt + J;                          \
-        LRQ_ABL_GLOAD(LRQ_GLOAD(SCUR, (i + 3) * BBK));  \
+        LRQ_GLOAD(SCUR, (i + 3) * BBK);             \
         compute(i & 1);                                \
-        if (i + 1 < nk) { LRQ_ABL_SSTORE(LRQ_SSTORE(SNEXT, (i + 1) & 1)); } \
-        LRQ_ABL_SYNC(__syncthreads());                 \
+        if (i + 1 < nk) { LRQ_SSTORE(SNEXT, (i + 1) & 1); } \
+        __syncthreads();                               \
     }
     for (int kt = 0; kt < nk; kt += 3) {
         LRQ_GEMM_STEP(0, r0, r1)
