@@ -22,6 +22,9 @@ Pins (tests/test_oracle_*.py, no GPU):
   lrqmm          dense identity (A~ + R_Ar)(B~ + R_Br), full rank equals A.B,
                  err(LRQMM) <= err(direct quant), printed Table 3-4 values
                  (direct-quant column tight, LRQMM column order of magnitude)
+  residual_compensation  dense identity (A~ + R~_A)(B~ + R~_B) for four terms, second-level
+                 residual inside [0, s_R), first term equal to direct quantization,
+                 printed QT-110 / QT-111 columns of Tables 3-4
   scaled_update  hand-worked 2x2 example in exact fractions, alpha = 1 / beta = 0
                  identity, beta = 0 ignoring NaNs in D, full-rank case equal to
                  alpha A.B + beta D
@@ -378,6 +381,55 @@ def compensate(Aq, sa, Bq, sb, U, Sig, Vt, W, Gam, Zt) -> np.ndarray:
     Vt = np.asarray(Vt, np.float64)
     W = np.asarray(W, np.float64)
     return C0 + Ut @ (Vt @ Bf) + (Af @ W) @ Ztp + (Ut @ (Vt @ W)) @ Ztp
+
+
+def residual_compensation(A: np.ndarray, B: np.ndarray, bits: int, terms: int, round_mode: int = FLOOR,
+                          per_tensor: bool = False, row_sample: np.ndarray | None = None) -> dict:
+    """Complete residual compensation, Eq. (gemm_r_split): the residuals are quantized a second
+    time, with scales of their own, and the product is the sum of the first `terms` of
+
+        A~ B~  +  A~ R~_B  +  R~_A B~  +  R~_A R~_B
+
+    (terms = 1: direct quantization; 3: the three terms called QT(1,1,0) in the Evaluation;
+    4: all four, QT(1,1,1)).  Each term is an integer product dequantized with the two scales of
+    its operands.  The residual that is quantized is the float32 value fl32(x - code * s) (the
+    exact difference rounded once), so that its codes are defined by float32 operations only.
+    """
+    if terms not in (1, 3, 4):
+        raise ValueError("terms must be 1, 3 or 4")
+    A = np.asarray(A, dtype=np.float32)
+    B = np.asarray(B, dtype=np.float32)
+    ax_a, ax_b = (TENSOR, TENSOR) if per_tensor else (ROWWISE, COLWISE)
+    out = {}
+
+    def two_levels(X, axis):
+        amax = absmax(X, axis)
+        _, s = scales(amax, bits)
+        q = quantize(X, amax, axis, bits, round_mode)
+        r = residual(X, q, s, axis).astype(np.float32)
+        amax_r = absmax(r, axis)
+        _, s_r = scales(amax_r, bits)
+        q_r = quantize(r, amax_r, axis, bits, round_mode)
+        return amax, s, q, r, amax_r, s_r, q_r
+
+    amax_a, sa, Aq, Ra, amax_ra, sra, RAq = two_levels(A, ax_a)
+    amax_b, sb, Bq, Rb, amax_rb, srb, RBq = two_levels(B, ax_b)
+    M, N = A.shape[0], B.shape[1]
+    bc = lambda v, n: np.broadcast_to(np.asarray(v, dtype=np.float32), (n,))
+    sa_r, sra_r, sb_c, srb_c = bc(sa, M), bc(sra, M), bc(sb, N), bc(srb, N)
+    sel = slice(None) if row_sample is None else np.asarray(row_sample, dtype=np.int64)
+    T = [dequant(int_gemm(Aq[sel], Bq), sa_r[sel], sb_c)]
+    if terms >= 3:
+        T.append(dequant(int_gemm(Aq[sel], RBq), sa_r[sel], srb_c))
+        T.append(dequant(int_gemm(RAq[sel], Bq), sra_r[sel], sb_c))
+    if terms == 4:
+        T.append(dequant(int_gemm(RAq[sel], RBq), sra_r[sel], srb_c))
+    C = T[0]
+    for t in T[1:]:
+        C = C + t
+    out.update(amax_a=amax_a, amax_b=amax_b, amax_ra=amax_ra, amax_rb=amax_rb, sa=sa, sb=sb, sra=sra, srb=srb,
+               Aq=Aq, Bq=Bq, RAq=RAq, RBq=RBq, Ra=Ra, Rb=Rb, terms=T, C0=T[0], C=C)
+    return out
 
 
 def scaled_update(C_F: np.ndarray, alpha: float, beta: float, D: np.ndarray | None) -> np.ndarray:

@@ -18,7 +18,11 @@ def _tables():
             if not line or line.startswith("#"):
                 continue
             name, *vals = [p.strip() for p in line.split(";")]
-            t[name] = dict(zip(("dq4", "lr4", "dq8", "lr8"), map(float, vals)))
+            if name.startswith("qt "):
+                t.setdefault(name[3:].strip(), {}).update(zip(("qt110_4", "qt111_4", "qt110_8", "qt111_8"),
+                                                              map(float, vals)))
+            else:
+                t.setdefault(name, {}).update(zip(("dq4", "lr4", "dq8", "lr8"), map(float, vals)))
     return t
 
 
@@ -209,3 +213,64 @@ def test_strided_views_give_the_same_result():
     r2 = o.lrqmm(np.ascontiguousarray(A), np.ascontiguousarray(B), 4, 3, 2, 1, seed=9)
     assert np.array_equal(r1["Aq"], r2["Aq"]) and np.array_equal(r1["Bq"], r2["Bq"])
     assert np.allclose(r1["C"], r2["C"], rtol=1e-12, atol=1e-12)
+
+
+# ---- complete residual compensation, Eq. (gemm_r_split) ---------------------------------
+
+@pytest.mark.parametrize("per_tensor", [False, True])
+def test_residual_compensation_identities(per_tensor):
+    M, K, N, bits = 23, 31, 19, 4
+    A = wl.random_matrix("normal", M, K, seed=1)
+    B = wl.random_matrix("uniform01", K, N, seed=2)
+    ax_a, ax_b = (o.TENSOR, o.TENSOR) if per_tensor else (o.ROWWISE, o.COLWISE)
+    r4 = o.residual_compensation(A, B, bits, 4, per_tensor=per_tensor)
+    At = o.dequant_matrix(r4["Aq"], r4["sa"], ax_a)
+    Bt = o.dequant_matrix(r4["Bq"], r4["sb"], ax_b)
+    RAt = o.dequant_matrix(r4["RAq"], r4["sra"], ax_a)
+    RBt = o.dequant_matrix(r4["RBq"], r4["srb"], ax_b)
+    # all four terms: the product of the twice-quantized operands
+    dense = (At + RAt) @ (Bt + RBt)
+    assert np.allclose(r4["C"], dense, rtol=0, atol=1e-12 * np.abs(dense).max())
+    # three terms: the same without R~_A R~_B, in the order of the equation
+    r3 = o.residual_compensation(A, B, bits, 3, per_tensor=per_tensor)
+    assert np.allclose(r3["C"], dense - RAt @ RBt, rtol=0, atol=1e-12 * np.abs(dense).max())
+    assert np.allclose(r3["terms"][1], At @ RBt, rtol=1e-12, atol=1e-15)
+    assert np.allclose(r3["terms"][2], RAt @ Bt, rtol=1e-12, atol=1e-15)
+    # one term: direct quantization
+    r1 = o.residual_compensation(A, B, bits, 1, per_tensor=per_tensor)
+    assert np.array_equal(r1["C"], o.lrqmm(A, B, bits, 0, per_tensor=per_tensor)["C"])
+    # floor at both levels: first residual in [0, s), second-level residual in [0, s_R)
+    bcast = lambda v, ax, shape: o._broadcast(np.asarray(v, np.float64), ax, shape)
+    for X, Xt, R, Rt, s1, s2, ax in ((A, At, r4["Ra"], RAt, r4["sa"], r4["sra"], ax_a),
+                                     (B, Bt, r4["Rb"], RBt, r4["sb"], r4["srb"], ax_b)):
+        assert np.array_equal(R.astype(np.float64), (X.astype(np.float64) - Xt).astype(np.float32).astype(np.float64))
+        S1, S2 = bcast(s1, ax, X.shape), bcast(s2, ax, X.shape)
+        assert np.all(R >= -1e-6 * S1) and np.all(R < S1 * (1 + 1e-6))     # up to the rounding of lambda * x
+        R2 = R.astype(np.float64) - Rt
+        assert np.all(R2 >= -1e-6 * S2) and np.all(R2 < S2 * (1 + 1e-6))
+        # the second scale is the first divided by about qmax: max of R is just below s
+        assert np.all(np.asarray(s2) <= np.asarray(s1) / o.qmax_of(bits) * (1 + 1e-6))
+    # more terms, less error (floor: every dropped term is a non-negative matrix here only for B >= 0)
+    exact = o.exact_product(A, B)
+    assert o.rel_err(exact, r4["C"]) < o.rel_err(exact, r3["C"]) < o.rel_err(exact, r1["C"])
+    with pytest.raises(ValueError):
+        o.residual_compensation(A, B, bits, 2)
+
+
+def test_residual_compensation_reproduces_printed_columns():
+    """QT-110 / QT-111 columns of Tables 3-4 (size 2000, one scale per matrix), on fresh draws of the
+    same distributions and a sample of rows: continuous uniform inputs to 10 %, Poisson (whose maximum
+    varies from draw to draw) to 30 %."""
+    t = _tables()
+    n = 2000
+    rows = np.arange(0, n, 25)
+    for kind, band in (("uniform01", 1.10), ("poisson", 1.30)):
+        A = wl.random_matrix(kind, n, n, seed=0)
+        B = wl.random_matrix(kind, n, n, seed=1)
+        ref = o.exact_product(A[rows], B)
+        for bits in (4, 8):
+            res = o.residual_compensation(A, B, bits, 4, per_tensor=True, row_sample=rows)
+            three = res["terms"][0] + res["terms"][1] + res["terms"][2]
+            for C, key in ((three, "qt110_%d" % bits), (res["C"], "qt111_%d" % bits)):
+                e = o.rel_err(ref, C)
+                assert t[kind][key] / band < e < t[kind][key] * band, (kind, bits, key, e, t[kind][key])
