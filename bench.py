@@ -179,6 +179,16 @@ def main():
     near = o.lrqmm(A, B, w.bits, 0, round_mode=o.NEAREST, row_sample=rows, want_cint=False)
     err_dq_near = o.rel_err(exact, near["C"])
 
+    # complete residual compensation (Eq. (gemm_r_split) with three / four full-size integer GEMMs): the
+    # alternative that the low-rank terms replace, on the same inputs and by the same library
+    rws = L.Workspace(L.lrqmm_residual_workspace_bytes(w.M, w.N, w.K))
+    full_residual = {}
+    for terms, name in ((3, "three_terms_QT110"), (4, "four_terms_QT111")):
+        fn = lambda: L.lrqmm_residual_matmul(dA, dB, C, w.bits, terms, workspace=rws)
+        t_r = timed(fn, max(5, args.steps // 2), 2)
+        full_residual[name] = {"ms": round(t_r * 1e3, 4), "rel_error": o.rel_err(exact, C.cpu().numpy()[rows])}
+    del rws
+
     out = {
         "metric": "LRQMM effective TOPS (2MNK/t) at 4096^3 int4 r=32; rel. error vs direct quant",
         "value": round(tops, 3), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -200,6 +210,7 @@ def main():
         "overhead_vs_direct_quant": round((t_step - t_dq) / t_dq, 4),
         "rel_error": {"lrqmm": err_lr, "direct_quant_floor": err_dq, "direct_quant_nearest": err_dq_near,
                       "gain_vs_floor": err_dq / err_lr, "rows_sampled": int(len(rows))},
+        "full_residual_baselines": full_residual,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, A, B, args.cpu_rows)

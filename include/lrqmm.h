@@ -203,6 +203,35 @@ LRQMM_API int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int overs
                     void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Complete residual compensation (Methodology, Eq. (gemm_r_split)) -- the full-size
+ * alternative that LRQMM replaces by low-rank terms, kept as a measured baseline:
+ * the residual of each operand is quantized a second time with scales of its own and
+ *     D <- alpha * (A~ B~ + A~ R~_B + R~_A B~ + R~_A R~_B) + beta * D
+ * is evaluated with one integer GEMM per term, taking the first `terms` terms:
+ *   terms = 1  direct quantization;  3  the variant the Evaluation calls QT(1,1,0);
+ *   terms = 4  all four, QT(1,1,1).
+ *
+ * lrqmm_quantize_residual: second-level quantization of X (layout, axis, bits, round
+ * and scale modes as lrqmm_quantize_ex).  amax0 (device, read only) holds the group
+ * maxima that the first quantization of X returned; the value quantized is the
+ * float32 residual fl32(x - code0 * s0).  Outputs: codesR (int8, layout as
+ * lrqmm_quantize), amaxR (the residual's own group maxima; must not alias amax0).
+ *
+ * lrqmm_residual_matmul: A (M x K, stride lda), B (K x N, stride ldb), D (M x N, stride
+ * ldd) as in lrqmm_matmul_ex; every kernel runs on `stream`.  The workspace (256-byte
+ * aligned, lrqmm_residual_workspace_bytes(M, N, K) bytes) holds both levels of codes.
+ * Errors: LRQMM_ERR_INVALID_ARG for terms outside {1, 3, 4}, otherwise as lrqmm_matmul_ex.
+ */
+LRQMM_API int lrqmm_quantize_residual(const float* X, int ldx, const float* amax0, int rows, int cols,
+                            int axis, int bits, int round_mode, int scale_mode,
+                            int8_t* codesR, float* amaxR, void* stream);
+LRQMM_API size_t lrqmm_residual_workspace_bytes(int M, int N, int K);
+LRQMM_API int lrqmm_residual_matmul(int M, int N, int K, int bits, int terms, int round_mode, int scale_mode,
+                          const float* A, int lda, const float* B, int ldb,
+                          float alpha, float beta, float* D, int ldd,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Stage timing of lrqmm_matmul for measurement (the split of Algorithm 2 into
  * quantization, the two residual factorizations, panel preparation and the
  * integer GEMM with its fused epilogue).  While enabled, each lrqmm_matmul call

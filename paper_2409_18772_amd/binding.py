@@ -17,7 +17,8 @@ _LIB = None
 
 EXPORTS = ("lrqmm_status_string", "lrqmm_workspace_bytes", "lrqmm_quantize", "lrqmm_fill_sketch",
            "lrqmm_rsvd", "lrqmm_gemm", "lrqmm_matmul", "lrqmm_profile_enable", "lrqmm_profile_read",
-           "lrqmm_quantize_ex", "lrqmm_rsvd_ex", "lrqmm_gemm_ex", "lrqmm_matmul_ex")
+           "lrqmm_quantize_ex", "lrqmm_rsvd_ex", "lrqmm_gemm_ex", "lrqmm_matmul_ex",
+           "lrqmm_quantize_residual", "lrqmm_residual_workspace_bytes", "lrqmm_residual_matmul")
 PROF_STAGES = ("quantize_a", "rsvd_a", "quantize_b", "rsvd_b", "panels", "gemm", "int_gemm")
 
 
@@ -67,6 +68,13 @@ def load_library() -> ctypes.CDLL:
     lib.lrqmm_matmul_ex.restype = c_int
     lib.lrqmm_matmul_ex.argtypes = [c_int] * 7 + [c_u64, c_int, c_int, c_vp, c_int, c_vp, c_int, c_f, c_f, c_vp,
                                     c_int, c_vp, c_sz, c_vp]
+    lib.lrqmm_quantize_residual.restype = c_int
+    lib.lrqmm_quantize_residual.argtypes = [c_vp, c_int, c_vp] + [c_int] * 6 + [c_vp, c_vp, c_vp]
+    lib.lrqmm_residual_workspace_bytes.restype = c_sz
+    lib.lrqmm_residual_workspace_bytes.argtypes = [c_int] * 3
+    lib.lrqmm_residual_matmul.restype = c_int
+    lib.lrqmm_residual_matmul.argtypes = [c_int] * 7 + [c_vp, c_int, c_vp, c_int, c_f, c_f, c_vp, c_int, c_vp, c_sz,
+                                          c_vp]
     lib.lrqmm_profile_enable.restype = c_int
     lib.lrqmm_profile_enable.argtypes = [c_int]
     lib.lrqmm_profile_read.restype = c_int
@@ -169,6 +177,49 @@ def lrqmm_quantize_ex(X, axis: int, bits: int, round_mode: int = ROUND_FLOOR, sc
                                           _ptr(codes), _ptr(amax), _stream())
     _check(st, "lrqmm_quantize_ex")
     return codes, amax
+
+
+def lrqmm_quantize_residual(X, amax0, axis: int, bits: int, round_mode: int = ROUND_FLOOR,
+                            scale_mode: int = SCALE_VECTOR):
+    """Second-level codes and maxima of X's quantization residual (amax0: first-level maxima)."""
+    import torch
+    ldx = _dev2d(X, torch.float32, "X")
+    _dev(amax0, torch.float32, "amax0")
+    rows, cols = X.shape
+    if amax0.numel() != (rows if axis == AXIS_ROW else cols):
+        raise ValueError("amax0 must hold one maximum per scale group")
+    shape = (rows, cols) if axis == AXIS_ROW else (cols, rows)
+    codes = torch.empty(shape, dtype=torch.int8, device=X.device)
+    amax = torch.empty_like(amax0)
+    st = load_library().lrqmm_quantize_residual(_ptr(X), ldx, _ptr(amax0), rows, cols, axis, bits, round_mode,
+                                                scale_mode, _ptr(codes), _ptr(amax), _stream())
+    _check(st, "lrqmm_quantize_residual")
+    return codes, amax
+
+
+def lrqmm_residual_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(load_library().lrqmm_residual_workspace_bytes(M, N, K))
+
+
+def lrqmm_residual_matmul(A, B, D, bits: int, terms: int, round_mode: int = ROUND_FLOOR,
+                          scale_mode: int = SCALE_VECTOR, alpha: float = 1.0, beta: float = 0.0,
+                          workspace: Workspace | None = None):
+    """Complete residual compensation: D <- alpha (first `terms` terms of Eq. (gemm_r_split)) + beta D."""
+    import torch
+    lda = _dev2d(A, torch.float32, "A")
+    ldb = _dev2d(B, torch.float32, "B")
+    ldd = _dev2d(D, torch.float32, "D")
+    M, K = A.shape
+    K2, N = B.shape
+    if K != K2 or tuple(D.shape) != (M, N):
+        raise ValueError("A is M x K, B is K x N, D is M x N")
+    if workspace is None:
+        workspace = Workspace(lrqmm_residual_workspace_bytes(M, N, K), A.device)
+    st = load_library().lrqmm_residual_matmul(M, N, K, bits, terms, round_mode, scale_mode, _ptr(A), lda, _ptr(B),
+                                              ldb, float(alpha), float(beta), _ptr(D), ldd,
+                                              ctypes.c_void_p(workspace.ptr), workspace.nbytes, _stream())
+    _check(st, "lrqmm_residual_matmul")
+    return D
 
 
 def lrqmm_fill_sketch(seed: int, stream_id: int, rows: int, cols: int, device="cuda"):

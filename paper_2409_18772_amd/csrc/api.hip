@@ -313,8 +313,24 @@ int lrqmm_quantize_ex(const float* X, int ldx, int rows, int cols, int axis, int
     hipStream_t st = static_cast<hipStream_t>(stream);
     const QuantParams q = make_quant_params(bits, round_mode);
     const bool per_tensor = scale_mode == LRQMM_SCALE_TENSOR;
-    if (axis == LRQMM_AXIS_ROW) return launch_quantize_rows(X, ldx, rows, cols, q, per_tensor, codes, amax, st);
-    return launch_quantize_cols(X, ldx, rows, cols, q, per_tensor, codes, amax, st);
+    if (axis == LRQMM_AXIS_ROW) return launch_quantize_rows(X, ldx, rows, cols, q, per_tensor, nullptr, codes, amax, st);
+    return launch_quantize_cols(X, ldx, rows, cols, q, per_tensor, nullptr, codes, amax, st);
+}
+
+int lrqmm_quantize_residual(const float* X, int ldx, const float* amax0, int rows, int cols, int axis, int bits,
+                            int round_mode, int scale_mode, int8_t* codesR, float* amaxR, void* stream) {
+    if (rows < 0 || cols < 0 || ldx < cols) return LRQMM_ERR_INVALID_ARG;
+    if (scale_mode != LRQMM_SCALE_VECTOR && scale_mode != LRQMM_SCALE_TENSOR) return LRQMM_ERR_INVALID_ARG;
+    if (axis != LRQMM_AXIS_ROW && axis != LRQMM_AXIS_COL) return LRQMM_ERR_INVALID_ARG;
+    if (round_mode != LRQMM_ROUND_FLOOR && round_mode != LRQMM_ROUND_NEAREST) return LRQMM_ERR_INVALID_ARG;
+    if (!bits_ok(bits)) return LRQMM_ERR_UNSUPPORTED;
+    if (rows == 0 || cols == 0) return LRQMM_OK;
+    if (!X || !amax0 || !codesR || !amaxR || amax0 == amaxR) return LRQMM_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const QuantParams q = make_quant_params(bits, round_mode);
+    const bool per_tensor = scale_mode == LRQMM_SCALE_TENSOR;
+    if (axis == LRQMM_AXIS_ROW) return launch_quantize_rows(X, ldx, rows, cols, q, per_tensor, amax0, codesR, amaxR, st);
+    return launch_quantize_cols(X, ldx, rows, cols, q, per_tensor, amax0, codesR, amaxR, st);
 }
 
 int lrqmm_fill_sketch(uint64_t seed, int stream_id, int rows, int cols, float* omega, void* stream) {
@@ -512,6 +528,85 @@ int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int
     prof_mark(slot, 6, pst);
     return gemm_impl(M, N, K, bits, rank, w.Aq, w.amaxA, w.BqT, w.amaxB, w.U, w.Sig, w.Vt, w.W, w.Gam, w.Zt,
                      GemmOut{D, ldd, alpha, beta}, nullptr, w.sub, w.sub_bytes, stream, slot, early ? g_side.gdone : nullptr);
+}
+
+namespace {
+struct ResidualWs {
+    int8_t *Aq, *RAq, *BqT, *RBqT;
+    float *amaxA, *amaxRA, *amaxB, *amaxRB;
+    void* sub;
+    size_t sub_bytes;
+};
+size_t carve_residual(Arena& a, int M, int N, int K, ResidualWs* w) {
+    ResidualWs t = {};
+    t.Aq = a.take<int8_t>((size_t)M * K);
+    t.RAq = a.take<int8_t>((size_t)M * K);
+    t.BqT = a.take<int8_t>((size_t)N * K);
+    t.RBqT = a.take<int8_t>((size_t)N * K);
+    t.amaxA = a.take<float>(M);
+    t.amaxRA = a.take<float>(M);
+    t.amaxB = a.take<float>(N);
+    t.amaxRB = a.take<float>(N);
+    a.off = align_up(a.off, 256);
+    Arena g(nullptr);
+    t.sub_bytes = carve_gemm(g, M, N, K, 0, nullptr);
+    t.sub = a.base ? a.base + a.off : nullptr;
+    a.off += t.sub_bytes;
+    if (w) *w = t;
+    return a.off;
+}
+}  // namespace
+
+size_t lrqmm_residual_workspace_bytes(int M, int N, int K) {
+    if (M < 0 || N < 0 || K < 0) return 0;
+    Arena a(nullptr);
+    return carve_residual(a, M, N, K, nullptr) + 256;
+}
+
+int lrqmm_residual_matmul(int M, int N, int K, int bits, int terms, int round_mode, int scale_mode, const float* A,
+                          int lda, const float* B, int ldb, float alpha, float beta, float* D, int ldd,
+                          void* workspace, size_t workspace_bytes, void* stream) {
+    if (M < 0 || N < 0 || K < 0 || lda < K || ldb < N || ldd < N) return LRQMM_ERR_INVALID_ARG;
+    if (terms != 1 && terms != 3 && terms != 4) return LRQMM_ERR_INVALID_ARG;
+    if (round_mode != LRQMM_ROUND_FLOOR && round_mode != LRQMM_ROUND_NEAREST) return LRQMM_ERR_INVALID_ARG;
+    if (scale_mode != LRQMM_SCALE_VECTOR && scale_mode != LRQMM_SCALE_TENSOR) return LRQMM_ERR_INVALID_ARG;
+    if (!bits_ok(bits)) return LRQMM_ERR_UNSUPPORTED;
+    if (!k_fits_int32(K, bits)) return LRQMM_ERR_UNSUPPORTED;
+    if (M == 0 || N == 0) return LRQMM_OK;
+    if (!D || (K > 0 && (!A || !B))) return LRQMM_ERR_INVALID_ARG;
+    if (!workspace || ((uintptr_t)workspace & 255)) return LRQMM_ERR_WORKSPACE;
+    ResidualWs w;
+    Arena a(workspace);
+    if (carve_residual(a, M, N, K, &w) > workspace_bytes) return LRQMM_ERR_WORKSPACE;
+    if (K == 0) terms = 1;
+    int rc;
+    if (K > 0) {
+        LRQ_TRY(lrqmm_quantize_ex(A, lda, M, K, LRQMM_AXIS_ROW, bits, round_mode, scale_mode, w.Aq, w.amaxA, stream));
+        LRQ_TRY(lrqmm_quantize_ex(B, ldb, K, N, LRQMM_AXIS_COL, bits, round_mode, scale_mode, w.BqT, w.amaxB, stream));
+        if (terms >= 3) {
+            LRQ_TRY(lrqmm_quantize_residual(A, lda, w.amaxA, M, K, LRQMM_AXIS_ROW, bits, round_mode, scale_mode, w.RAq,
+                                            w.amaxRA, stream));
+            LRQ_TRY(lrqmm_quantize_residual(B, ldb, w.amaxB, K, N, LRQMM_AXIS_COL, bits, round_mode, scale_mode, w.RBqT,
+                                            w.amaxRB, stream));
+        }
+    } else {
+        LRQ_TRY(launch_pad_copy(nullptr, M, 0, 1, w.amaxA, static_cast<hipStream_t>(stream)));
+        LRQ_TRY(launch_pad_copy(nullptr, N, 0, 1, w.amaxB, static_cast<hipStream_t>(stream)));
+    }
+    // one integer GEMM per term of Eq. (gemm_r_split), each dequantized with the scales of its two
+    // operands and accumulated into D through the GEMM's own alpha/beta update
+    auto term = [&](const int8_t* Lq, const float* amaxL, const int8_t* RqT, const float* amaxR, float b) {
+        return gemm_impl(M, N, K, bits, 0, Lq, amaxL, RqT, amaxR, nullptr, nullptr, nullptr, nullptr, nullptr,
+                         nullptr, GemmOut{D, ldd, alpha, b}, nullptr, w.sub, w.sub_bytes, stream, -1);
+    };
+    LRQ_TRY(term(w.Aq, w.amaxA, w.BqT, w.amaxB, beta));
+    if (terms >= 3) {
+        // alpha * term is added to what D holds now: beta = 1 from here on
+        LRQ_TRY(term(w.Aq, w.amaxA, w.RBqT, w.amaxRB, 1.0f));
+        LRQ_TRY(term(w.RAq, w.amaxRA, w.BqT, w.amaxB, 1.0f));
+    }
+    if (terms == 4) LRQ_TRY(term(w.RAq, w.amaxRA, w.RBqT, w.amaxRB, 1.0f));
+    return LRQMM_OK;
 }
 
 int lrqmm_profile_enable(int on) {

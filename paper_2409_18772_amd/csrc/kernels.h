@@ -7,11 +7,12 @@
 
 // ---- quantize.hip -------------------------------------------------------
 // X is rows x cols with row stride ldx (>= cols).  per_tensor: one scale for the whole matrix,
-// i.e. every entry of amax holds the global maximum.
+// i.e. every entry of amax holds the global maximum.  amax0 != null: quantize the residual of a
+// first quantization whose group maxima are amax0 (second level of Eq. (gemm_r_split)).
 int launch_quantize_rows(const float* X, int ldx, int rows, int cols, QuantParams q, bool per_tensor,
-                         int8_t* codes, float* amax, hipStream_t st);
+                         const float* amax0, int8_t* codes, float* amax, hipStream_t st);
 int launch_quantize_cols(const float* X, int ldx, int rows, int cols, QuantParams q, bool per_tensor,
-                         int8_t* codesT, float* amax, hipStream_t st);
+                         const float* amax0, int8_t* codesT, float* amax, hipStream_t st);
 // lam[n], s[n] from amax[n]; entries n..npad-1 are zero-filled.
 // A minimal kernel (writes one zero word): used as a few microseconds of delay on a stream.
 int launch_tick(uint32_t* word, hipStream_t st);

@@ -134,45 +134,43 @@ __global__ __launch_bounds__(64) void gram_sum_kernel(const double* __restrict__
 // one workgroup barrier per step is enough).  The serial chain per step is LDS write ->
 // barrier -> LDS read -> reciprocal -> FMA; the square roots are taken once at the end.
 // A pivot below 1e-10 of its original diagonal (rank-deficient sketch) is dead: it
-// eliminates nothing and its row and column of T are zero.  All 1024 threads stage the Gram
-// matrix in LDS; the waves that own no tile then leave.
+// eliminates nothing and its row and column of T are zero.  The workgroup holds only the
+// workers (rounded up to whole waves) and 4 KB of LDS, and every worker loads its tile
+// straight from global memory: a small footprint lets the workgroup start at once on a chip
+// that another stream keeps full (with 1024 threads and the matrix staged in LDS it waited
+// hundreds of microseconds for a free CU at l = 80).
 template <int NT>
 struct CholShape {
     static constexpr int LP = 16 * NT;
     static constexpr int KR = 4, KC = 8;            // register tile per worker
     static constexpr int NTI = LP / KR;             // workers per row and per column
     static constexpr int WORKERS = NTI * NTI;
+    static constexpr int THREADS = (WORKERS + 63) / 64 * 64;
 };
-#define CHOL_THREADS 1024
 
 template <int NT>
-__global__ __launch_bounds__(CHOL_THREADS) void chol_inverse_kernel(const double* __restrict__ gram, int ell,
+__global__ __launch_bounds__(CholShape<NT>::THREADS) void chol_inverse_kernel(const double* __restrict__ gram, int ell,
                                                                     double* __restrict__ T) {
     using S = CholShape<NT>;
     constexpr int LP = S::LP, KR = S::KR, KC = S::KC, NTI = S::NTI;
-    __shared__ double Gs[LP * (LP + 1)];
     __shared__ double rowb[2][2 * LP];
     __shared__ double colb[2][LP];
     __shared__ __align__(16) double2 pivb[2];
     const int tid = threadIdx.x;
-    for (int idx = tid; idx < LP * LP; idx += CHOL_THREADS) {
-        const int a = idx / LP, b = idx - a * LP;
-        Gs[a * (LP + 1) + b] = (a < ell && b < ell) ? gram[idx] : 0.0;
-    }
-    __syncthreads();
-    if (tid >= (S::WORKERS + 63) / 64 * 64) return;      // whole waves without a tile
     const bool worker = tid < S::WORKERS;
     const int ti = worker ? tid / NTI : 0, tg = worker ? tid - ti * NTI : 0;
     double mreg[KR][KC];
     double thr[KR];             // 1e-10 * original diagonal of the thread's rows
 #pragma unroll
     for (int ir = 0; ir < KR; ++ir) {
-        const int i = ti + NTI * ir;
-        thr[ir] = 1e-10 * Gs[i * (LP + 1) + i];
+        const int i = ti + NTI * ir;        // < LP; rows and columns >= ell enter as zeros
+        const double gd = gram[i * LP + i];
+        thr[ir] = i < ell ? 1e-10 * gd : 0.0;
 #pragma unroll
         for (int kc = 0; kc < KC; ++kc) {
-            const int c = tg + NTI * kc;
-            mreg[ir][kc] = (c < LP) ? Gs[i * (LP + 1) + c] : ((c - LP == i && i < ell) ? 1.0 : 0.0);
+            const int c = tg + NTI * kc;        // < 2 LP
+            const double g = gram[i * LP + (c < LP ? c : c - LP)];     // always inside the LP x LP array
+            mreg[ir][kc] = (c < LP) ? ((i < ell && c < ell) ? g : 0.0) : ((c - LP == i && i < ell) ? 1.0 : 0.0);
         }
     }
     double pivot[KR];           // pivots of the thread's rows, 0 when dead
@@ -595,7 +593,7 @@ int launch_gram_sum(const double* gpart, int nb, int LP, double* gram, hipStream
 }
 
 int launch_chol_inverse(const double* gram, int ell, int LP, double* T, hipStream_t st) {
-    NT_SWITCH(LP / 16, hipLaunchKernelGGL((chol_inverse_kernel<NT_>), dim3(1), dim3(CHOL_THREADS), 0, st, gram, ell,
+    NT_SWITCH(LP / 16, hipLaunchKernelGGL((chol_inverse_kernel<NT_>), dim3(1), dim3(CholShape<NT_>::THREADS), 0, st, gram, ell,
                                           T));
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;

@@ -4,6 +4,14 @@
 #include "kernels.h"
 
 // One wavefront per row: absmax by wave reduction, then codes with 4-byte packed stores.
+// Second quantization level (complete residual compensation, Eq. (gemm_r_split)): when amax0 is
+// given, the value that is quantized is the residual fl32(x - code0 * s0) of the first level, whose
+// scales come from amax0 (the first level's maxima of the same groups).
+__device__ __forceinline__ float4 first_level_residual(float4 v, float lam0, float s0, const QuantParams& q) {
+    return make_float4(quant_residual(v.x, lam0, s0, q), quant_residual(v.y, lam0, s0, q),
+                       quant_residual(v.z, lam0, s0, q), quant_residual(v.w, lam0, s0, q));
+}
+
 // mode (all row kernels): ROWS_FULL computes amax and codes; ROWS_AMAX_ONLY stops after amax;
 // ROWS_GIVEN_AMAX reads amax[row] (written by an earlier launch) instead of the row's own maximum.
 enum { ROWS_FULL = 0, ROWS_AMAX_ONLY = 1, ROWS_GIVEN_AMAX = 2 };
@@ -11,17 +19,21 @@ template <bool VEC>
 __global__ __launch_bounds__(256) void quant_rows_kernel(const float* __restrict__ X, int ldx, int rows,
                                                          int cols, QuantParams q,
                                                          int8_t* __restrict__ codes,
-                                                         float* __restrict__ amax, int mode) {
+                                                         float* __restrict__ amax, int mode,
+                                                         const float* __restrict__ amax0) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + wave;
     if (row >= rows) return;
     const float* xp = X + (size_t)row * ldx;
+    float lam0 = 0.f, s0 = 0.f;
+    if (amax0) make_scales(amax0[row], q.qmaxf, lam0, s0);
     float m = 0.0f;
     if (mode == ROWS_GIVEN_AMAX) {
         m = amax[row];
     } else {
         for (int k = lane * 4; k < cols; k += 256) {
             float4 v = load4f<VEC>(xp, k, cols, true);
+            if (amax0) v = first_level_residual(v, lam0, s0, q);
             m = fmaxf(fmaxf(m, fabsf(v.x)), fmaxf(fabsf(v.y), fmaxf(fabsf(v.z), fabsf(v.w))));
         }
         m = wave_max(m);
@@ -33,6 +45,7 @@ __global__ __launch_bounds__(256) void quant_rows_kernel(const float* __restrict
     int8_t* cp = codes + (size_t)row * cols;
     for (int k = lane * 4; k < cols; k += 256) {
         float4 v = load4f<VEC>(xp, k, cols, true);
+        if (amax0) v = first_level_residual(v, lam0, s0, q);
         int c0 = (int)quant_code(v.x, lam, q), c1 = (int)quant_code(v.y, lam, q);
         int c2 = (int)quant_code(v.z, lam, q), c3 = (int)quant_code(v.w, lam, q);
         if (VEC) {
@@ -55,7 +68,8 @@ template <bool VEC, int TPR, int NV>
 __global__ __launch_bounds__(256) void quant_rows_cached_kernel(const float* __restrict__ X, int ldx, int rows,
                                                                 int cols, QuantParams q,
                                                                 int8_t* __restrict__ codes,
-                                                                float* __restrict__ amax, int mode) {
+                                                                float* __restrict__ amax, int mode,
+                                                                const float* __restrict__ amax0) {
     __shared__ float wmax[4];
     const int t = threadIdx.x % TPR;
     const int row = blockIdx.x * (256 / TPR) + threadIdx.x / TPR;
@@ -63,10 +77,13 @@ __global__ __launch_bounds__(256) void quant_rows_cached_kernel(const float* __r
     const float* xp = X + (size_t)(row_ok ? row : 0) * ldx;
     float4 v[NV];
     float m = 0.0f;
+    float lam0 = 0.f, s0 = 0.f;
+    if (amax0) make_scales(amax0[row_ok ? row : 0], q.qmaxf, lam0, s0);
 #pragma unroll
     for (int u = 0; u < NV; ++u) {
         const int k = (t + TPR * u) * 4;
         v[u] = load4f<VEC>(xp, k, cols, row_ok);
+        if (amax0) v[u] = first_level_residual(v[u], lam0, s0, q);     // zeros stay zeros
         m = fmaxf(fmaxf(m, fabsf(v[u].x)), fmaxf(fabsf(v[u].y), fmaxf(fabsf(v[u].z), fabsf(v[u].w))));
     }
     m = wave_max(m);
@@ -112,9 +129,15 @@ __global__ void fill_u32_kernel(uint32_t* p, int n, uint32_t v) {
 template <bool VEC>
 __global__ __launch_bounds__(256) void absmax_cols_kernel(const float* __restrict__ X, int ldx, int rows,
                                                           int cols, int rows_per_block,
-                                                          uint32_t* __restrict__ amax_bits) {
+                                                          uint32_t* __restrict__ amax_bits, QuantParams q,
+                                                          const float* __restrict__ amax0) {
     const int c = (blockIdx.x * 256 + threadIdx.x) * 4;
     if (c >= cols) return;
+    float lam0[4] = {0.f, 0.f, 0.f, 0.f}, s0[4] = {0.f, 0.f, 0.f, 0.f};
+    if (amax0) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) make_scales(c + t < cols ? amax0[c + t] : 0.f, q.qmaxf, lam0[t], s0[t]);
+    }
     const int r0 = blockIdx.y * rows_per_block;
     const int r1 = min(rows, r0 + rows_per_block);
     float4 m = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -124,6 +147,9 @@ __global__ __launch_bounds__(256) void absmax_cols_kernel(const float* __restric
         for (int u = 0; u < 16; ++u) v[u] = load4f<VEC>(X + (size_t)min(rb + u, r1 - 1) * ldx, c, cols, true);
 #pragma unroll
         for (int u = 0; u < 16; ++u) {
+            if (amax0)
+                v[u] = make_float4(quant_residual(v[u].x, lam0[0], s0[0], q), quant_residual(v[u].y, lam0[1], s0[1], q),
+                                   quant_residual(v[u].z, lam0[2], s0[2], q), quant_residual(v[u].w, lam0[3], s0[3], q));
             m.x = fmaxf(m.x, fabsf(v[u].x));
             m.y = fmaxf(m.y, fabsf(v[u].y));
             m.z = fmaxf(m.z, fabsf(v[u].z));
@@ -142,7 +168,8 @@ template <bool VEC, bool VECOUT>
 __global__ __launch_bounds__(256) void quant_cols_kernel(const float* __restrict__ X, int ldx, int rows,
                                                          int cols, const float* __restrict__ amax,
                                                          QuantParams q,
-                                                         int8_t* __restrict__ codesT) {
+                                                         int8_t* __restrict__ codesT,
+                                                         const float* __restrict__ amax0) {
     __shared__ __align__(16) int8_t tile[64][80];
     const int n0 = blockIdx.x * 64, k0 = blockIdx.y * 64;
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
@@ -154,11 +181,19 @@ __global__ __launch_bounds__(256) void quant_cols_kernel(const float* __restrict
         float s_unused;
         make_scales(a, q.qmaxf, lam[t], s_unused);
     }
+    float lam0[4] = {0.f, 0.f, 0.f, 0.f}, s0[4] = {0.f, 0.f, 0.f, 0.f};
+    if (amax0) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) make_scales(n + t < cols ? amax0[n + t] : 0.f, q.qmaxf, lam0[t], s0[t]);
+    }
 #pragma unroll
     for (int rr = 0; rr < 4; ++rr) {
         const int kl = ty + 16 * rr;
         const int k = k0 + kl;
         float4 v = load4f<VEC>(X + (size_t)min(k, rows - 1) * ldx, n, cols, k < rows);
+        if (amax0)
+            v = make_float4(quant_residual(v.x, lam0[0], s0[0], q), quant_residual(v.y, lam0[1], s0[1], q),
+                            quant_residual(v.z, lam0[2], s0[2], q), quant_residual(v.w, lam0[3], s0[3], q));
         tile[tx * 4 + 0][kl] = (int8_t)(int)quant_code(v.x, lam[0], q);
         tile[tx * 4 + 1][kl] = (int8_t)(int)quant_code(v.y, lam[1], q);
         tile[tx * 4 + 2][kl] = (int8_t)(int)quant_code(v.z, lam[2], q);
@@ -207,21 +242,21 @@ __global__ __launch_bounds__(1024) void tensor_max_kernel(float* __restrict__ am
 static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 static int rows_launch(const float* X, int ldx, int rows, int cols, QuantParams q, int8_t* codes, float* amax,
-                       int mode, hipStream_t st);
+                       int mode, const float* amax0, hipStream_t st);
 
 int launch_quantize_rows(const float* X, int ldx, int rows, int cols, QuantParams q, bool per_tensor,
-                         int8_t* codes, float* amax, hipStream_t st) {
-    if (!per_tensor) return rows_launch(X, ldx, rows, cols, q, codes, amax, ROWS_FULL, st);
+                         const float* amax0, int8_t* codes, float* amax, hipStream_t st) {
+    if (!per_tensor) return rows_launch(X, ldx, rows, cols, q, codes, amax, ROWS_FULL, amax0, st);
     // one scale per matrix: row maxima, their maximum broadcast to every row, then the codes
-    int rc = rows_launch(X, ldx, rows, cols, q, codes, amax, ROWS_AMAX_ONLY, st);
+    int rc = rows_launch(X, ldx, rows, cols, q, codes, amax, ROWS_AMAX_ONLY, amax0, st);
     if (rc != LRQMM_OK) return rc;
     hipLaunchKernelGGL(tensor_max_kernel, dim3(1), dim3(1024), 0, st, amax, rows);
     LRQ_CHECK_LAUNCH();
-    return rows_launch(X, ldx, rows, cols, q, codes, amax, ROWS_GIVEN_AMAX, st);
+    return rows_launch(X, ldx, rows, cols, q, codes, amax, ROWS_GIVEN_AMAX, amax0, st);
 }
 
 static int rows_launch(const float* X, int ldx, int rows, int cols, QuantParams q, int8_t* codes, float* amax,
-                       int mode, hipStream_t st) {
+                       int mode, const float* amax0, hipStream_t st) {
     const bool vec = (cols % 4 == 0) && (ldx % 4 == 0) && aligned16(X) && (((uintptr_t)codes & 3) == 0);
     if (cols <= 256 * 4 * 16) {
         // Row cached in registers: one wavefront per row up to 4096 columns, else one workgroup.
@@ -229,7 +264,7 @@ static int rows_launch(const float* X, int ldx, int rows, int cols, QuantParams 
         const int per = wave ? 256 : 1024;
         const int need = ceil_div(cols, per);
         dim3 grid(wave ? ceil_div(rows, 4) : rows);
-#define LRQ_QR(V, T, N) hipLaunchKernelGGL((quant_rows_cached_kernel<V, T, N>), grid, dim3(256), 0, st, X, ldx, rows, cols, q, codes, amax, mode)
+#define LRQ_QR(V, T, N) hipLaunchKernelGGL((quant_rows_cached_kernel<V, T, N>), grid, dim3(256), 0, st, X, ldx, rows, cols, q, codes, amax, mode, amax0)
 #define LRQ_QR_NV(V, T) do { if (need <= 1) LRQ_QR(V, T, 1); else if (need <= 2) LRQ_QR(V, T, 2); \
         else if (need <= 4) LRQ_QR(V, T, 4); else if (need <= 8) LRQ_QR(V, T, 8); else LRQ_QR(V, T, 16); } while (0)
         if (wave) { if (vec) LRQ_QR_NV(true, 64); else LRQ_QR_NV(false, 64); }
@@ -238,15 +273,15 @@ static int rows_launch(const float* X, int ldx, int rows, int cols, QuantParams 
 #undef LRQ_QR
     } else {                              // very long rows: two passes over the row
         dim3 grid(ceil_div(rows, 4));
-        if (vec) hipLaunchKernelGGL(quant_rows_kernel<true>, grid, dim3(256), 0, st, X, ldx, rows, cols, q, codes, amax, mode);
-        else     hipLaunchKernelGGL(quant_rows_kernel<false>, grid, dim3(256), 0, st, X, ldx, rows, cols, q, codes, amax, mode);
+        if (vec) hipLaunchKernelGGL(quant_rows_kernel<true>, grid, dim3(256), 0, st, X, ldx, rows, cols, q, codes, amax, mode, amax0);
+        else     hipLaunchKernelGGL(quant_rows_kernel<false>, grid, dim3(256), 0, st, X, ldx, rows, cols, q, codes, amax, mode, amax0);
     }
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }
 
 int launch_quantize_cols(const float* X, int ldx, int rows, int cols, QuantParams q, bool per_tensor,
-                         int8_t* codesT, float* amax, hipStream_t st) {
+                         const float* amax0, int8_t* codesT, float* amax, hipStream_t st) {
     const bool vec = (cols % 4 == 0) && (ldx % 4 == 0) && aligned16(X);
     const bool vecout = (rows % 16 == 0) && aligned16(codesT);
     hipLaunchKernelGGL(fill_u32_kernel, dim3(ceil_div(cols, 256)), dim3(256), 0, st,
@@ -260,10 +295,10 @@ int launch_quantize_cols(const float* X, int ldx, int rows, int cols, QuantParam
     dim3 g1(col_blocks, slabs);
     if (vec)
         hipLaunchKernelGGL(absmax_cols_kernel<true>, g1, dim3(256), 0, st, X, ldx, rows, cols, rows_per_block,
-                           reinterpret_cast<uint32_t*>(amax));
+                           reinterpret_cast<uint32_t*>(amax), q, amax0);
     else
         hipLaunchKernelGGL(absmax_cols_kernel<false>, g1, dim3(256), 0, st, X, ldx, rows, cols, rows_per_block,
-                           reinterpret_cast<uint32_t*>(amax));
+                           reinterpret_cast<uint32_t*>(amax), q, amax0);
     LRQ_CHECK_LAUNCH();
     if (per_tensor) {
         hipLaunchKernelGGL(tensor_max_kernel, dim3(1), dim3(1024), 0, st, amax, cols);
@@ -271,13 +306,13 @@ int launch_quantize_cols(const float* X, int ldx, int rows, int cols, QuantParam
     }
     dim3 g2(ceil_div(cols, 64), ceil_div(rows, 64));
     if (vec && vecout)
-        hipLaunchKernelGGL((quant_cols_kernel<true, true>), g2, dim3(256), 0, st, X, ldx, rows, cols, amax, q, codesT);
+        hipLaunchKernelGGL((quant_cols_kernel<true, true>), g2, dim3(256), 0, st, X, ldx, rows, cols, amax, q, codesT, amax0);
     else if (vec)
-        hipLaunchKernelGGL((quant_cols_kernel<true, false>), g2, dim3(256), 0, st, X, ldx, rows, cols, amax, q, codesT);
+        hipLaunchKernelGGL((quant_cols_kernel<true, false>), g2, dim3(256), 0, st, X, ldx, rows, cols, amax, q, codesT, amax0);
     else if (vecout)
-        hipLaunchKernelGGL((quant_cols_kernel<false, true>), g2, dim3(256), 0, st, X, ldx, rows, cols, amax, q, codesT);
+        hipLaunchKernelGGL((quant_cols_kernel<false, true>), g2, dim3(256), 0, st, X, ldx, rows, cols, amax, q, codesT, amax0);
     else
-        hipLaunchKernelGGL((quant_cols_kernel<false, false>), g2, dim3(256), 0, st, X, ldx, rows, cols, amax, q, codesT);
+        hipLaunchKernelGGL((quant_cols_kernel<false, false>), g2, dim3(256), 0, st, X, ldx, rows, cols, amax, q, codesT, amax0);
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }
