@@ -118,8 +118,10 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps
 
-    # headline: K steps of the whole path; stage boundaries marked with HIP events on the same stream
-    L.lrqmm_profile_enable(True)
+    # headline: K steps of the whole path.  In the timed region only the integer GEMM is bracketed by
+    # HIP events (on the stream it is launched on); the full stage split is taken in a second,
+    # untimed pass, because its eleven event records per step lengthen a step by ~4 %.
+    L.lrqmm_profile_enable(L.PROF_GEMM_ONLY)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -130,8 +132,16 @@ def main():
         step()
     torch.cuda.synchronize()
     t_step = (time.perf_counter() - t0) / args.steps
-    stages, ncalls = L.lrqmm_profile_read()
+    gemm_stages, ncalls = L.lrqmm_profile_read()
+    L.lrqmm_profile_enable(True)
+    for _ in range(min(args.steps, 20)):
+        step()
+    torch.cuda.synchronize()
+    stages, _ = L.lrqmm_profile_read()
     L.lrqmm_profile_enable(False)
+    early = gemm_stages.get("int_gemm", 0.0) > 1e-3
+    # the GEMM's launch time is the one measured inside the timed region
+    stages["int_gemm" if early else "gemm"] = gemm_stages["int_gemm" if early else "gemm"]
 
     # direct-quantization pipeline alone (rank 0) for the overhead figure
     t_dq = timed(lambda: step(0), max(5, args.steps // 2), 2)
@@ -144,7 +154,6 @@ def main():
     # dominant kernel: the int8 MFMA GEMM.  For large problems lrqmm_matmul runs it early on its
     # third stream (stage "int_gemm", raw int32 sums) and the epilogue separately (stage "gemm");
     # otherwise stage "gemm" is the GEMM with its fused epilogue.
-    early = stages.get("int_gemm", 0.0) > 1e-3
     gemm_key = "int_gemm" if early else "gemm"
     gemm_s = stages[gemm_key] * 1e-3
     achieved = ops / gemm_s / 1e12 if gemm_s > 0 else 0.0
@@ -206,6 +215,8 @@ def main():
                                              else "traffic_bytes_per_launch_fused"),
                      "launch_ms": round(stages[gemm_key], 4), "ops_per_launch": ops},
         "stages": stage_info,
+        "stages_note": "GEMM launch time from HIP events inside the timed region; the other stages from a "
+                       "separate fully instrumented pass of the same step",
         "direct_quant_ms": round(t_dq * 1e3, 4),
         "overhead_vs_direct_quant": round((t_step - t_dq) / t_dq, 4),
         "rel_error": {"lrqmm": err_lr, "direct_quant_floor": err_dq, "direct_quant_nearest": err_dq_near,

@@ -176,6 +176,10 @@ LRQMM_API int lrqmm_gemm_ex(int M, int N, int K, int bits, int rank,
  * panels as a kernel of its own with the arithmetic of the fused epilogue (same
  * bits).  C must therefore not be read between the call and its completion on
  * `stream`.  Calls must not be issued concurrently from several host threads.
+ * The call enqueues only kernels and event waits (memory is cleared by fill kernels), so it may be
+ * recorded into a HIP graph by stream capture on `stream`; the library's own streams join the
+ * capture through their fork event.  Call it once outside a capture first (its streams and
+ * events are created on first use), and keep profiling off while capturing.
  */
 LRQMM_API int lrqmm_matmul(int M, int N, int K, int bits, int rank, int oversample, int power_iters,
                  uint64_t seed, int round_mode, const float* A, const float* B, float* C,
@@ -246,8 +250,14 @@ LRQMM_API int lrqmm_residual_matmul(int M, int N, int K, int bits, int terms, in
  *   stage 5 int8 GEMM kernel with fused epilogue, or -- when the integer product ran early,
  *           see lrqmm_matmul -- the dequantizing rank-2r update kernel alone
  *   stage 6 the early integer product on the library's third stream (0 when fused)
+ *
+ * lrqmm_profile_enable(LRQMM_PROF_GEMM_ONLY) records only the two events around the integer
+ * GEMM kernel, on the stream that kernel is launched on (for the early product that is the
+ * library's third stream, off the critical path), so a timed run is not lengthened by the other
+ * nine records; lrqmm_profile_read then fills stage 5 or 6 only.  1 = all stages, 0 = off.
  */
 #define LRQMM_PROF_STAGES 7
+#define LRQMM_PROF_GEMM_ONLY 2
 LRQMM_API int lrqmm_profile_enable(int on);
 LRQMM_API int lrqmm_profile_read(float* stage_ms, int* ncalls);
 

@@ -391,8 +391,12 @@ def lrqmm_matmul_ex(A, B, D, bits: int, rank: int, oversample: int = 0, power_it
     return D
 
 
-def lrqmm_profile_enable(on: bool):
-    _check(load_library().lrqmm_profile_enable(1 if on else 0), "lrqmm_profile_enable")
+PROF_GEMM_ONLY = 2
+
+
+def lrqmm_profile_enable(on):
+    """False/0 off, True/1 all stages, PROF_GEMM_ONLY: only the events around the integer GEMM."""
+    _check(load_library().lrqmm_profile_enable(int(on)), "lrqmm_profile_enable")
 
 
 def lrqmm_profile_read():

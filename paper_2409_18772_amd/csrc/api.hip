@@ -140,6 +140,8 @@ constexpr int kStageEnd[kProfStages] = {1, 2, 4, 5, 7, 8, 10};
 constexpr int kLastMainEvent = 8;
 struct Prof {
     bool on = false;
+    bool gemm_only = false;             // record only the pair of events around the integer GEMM
+    bool early[kProfMaxCalls] = {};     // per recorded call: the GEMM ran on the third stream
     int ncalls = 0;
     hipEvent_t ev[kProfMaxCalls][kProfEvents];
     bool created = false;
@@ -167,7 +169,12 @@ bool side_ready() {
 }
 
 inline void prof_mark(int slot, int i, hipStream_t st) {
-    if (slot >= 0) (void)hipEventRecord(g_prof.ev[slot][i], st);
+    if (slot < 0) return;
+    if (g_prof.gemm_only) {     // events 9, 10 bracket the early product, 7, 8 the fused kernel
+        const bool early = g_prof.early[slot];
+        if (!(early ? (i == 9 || i == 10) : (i == 7 || i == 8))) return;
+    }
+    (void)hipEventRecord(g_prof.ev[slot][i], st);
 }
 
 bool bits_ok(int bits) { return bits >= 2 && bits <= 8; }
@@ -475,6 +482,7 @@ int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int
     // its own.  Used for problems on the large-tile kernel.
     // (the raw sums need D's memory: only when its old contents are not an input and it is dense)
     const bool early = overlap && rank_update_usable(M, N, C) && beta == 0.0f && ldd == N;
+    if (slot >= 0) g_prof.early[slot] = early;
     hipStream_t gst = early ? g_side.gemm_stream : pst;
     std::function<int()> before_svd = nullptr, before_svd_b = nullptr, after_svd_b = nullptr;
     if (early) {
@@ -617,6 +625,7 @@ int lrqmm_profile_enable(int on) {
         g_prof.created = true;
     }
     g_prof.on = on != 0;
+    g_prof.gemm_only = on == LRQMM_PROF_GEMM_ONLY;
     g_prof.ncalls = 0;
     return LRQMM_OK;
 }
@@ -627,6 +636,19 @@ int lrqmm_profile_read(float* stage_ms, int* ncalls) {
     *ncalls = n;
     for (int i = 0; i < kProfStages; ++i) stage_ms[i] = 0.f;
     if (n == 0) return LRQMM_OK;
+    if (g_prof.gemm_only) {
+        // the caller has synchronized the stream of the calls (see the header); each call
+        // contributes its GEMM to stage 6 (early product) or 5 (fused kernel)
+        for (int c = 0; c < n; ++c) {
+            const int b = g_prof.early[c] ? 9 : 7, stage = g_prof.early[c] ? 6 : 5;
+            float ms = 0.f;
+            if (hipEventSynchronize(g_prof.ev[c][b + 1]) != hipSuccess) return LRQMM_ERR_HIP;
+            if (hipEventElapsedTime(&ms, g_prof.ev[c][b], g_prof.ev[c][b + 1]) != hipSuccess) return LRQMM_ERR_HIP;
+            stage_ms[stage] += ms / (float)n;
+        }
+        g_prof.ncalls = 0;
+        return LRQMM_OK;
+    }
     if (hipEventSynchronize(g_prof.ev[n - 1][kLastMainEvent]) != hipSuccess) return LRQMM_ERR_HIP;
     for (int c = 0; c < n; ++c)
         for (int i = 0; i < kProfStages; ++i) {

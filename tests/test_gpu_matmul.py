@@ -170,3 +170,65 @@ def test_largest_config_properties():
     e_lr, e_dq = o.rel_err(exact, Cr), o.rel_err(exact, C0r)
     say(w.name, "err lrqmm", e_lr, "err direct quant", e_dq)
     assert e_lr * 10.0 < e_dq
+
+
+@pytest.mark.parametrize("shape", [(4096, 2048, 512), (300, 200, 260)])
+def test_call_can_be_captured_in_a_graph(shape):
+    """The call only enqueues kernels and event waits (its clears are fill kernels), so it may be recorded
+    into a HIP graph, side streams included; every replay must reproduce the eager result, with eager work
+    and synchronizations between the replays.  The first shape takes the three-stream schedule."""
+    import torch
+    import paper_2409_18772_amd as L
+    M, N, K = shape
+    A = to_dev(wl.random_matrix("normal", M, K, seed=31))
+    B = to_dev(wl.random_matrix("normal", K, N, seed=32))
+    ws = L.Workspace.for_problem(M, N, K, 8, 4)
+    C = torch.empty((M, N), dtype=torch.float32, device="cuda")
+
+    def step():
+        L.lrqmm_matmul(A, B, 4, 8, 4, 1, seed=7, workspace=ws, C=C)
+
+    step()
+    torch.cuda.synchronize()
+    ref = C.clone()
+    say("capture", shape)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        step()                       # first use of the library's streams and events outside the capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        step()
+    torch.cuda.synchronize()
+    for i in range(3):
+        C.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(C, ref), i
+        step()                       # eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(C, ref), i
+
+
+def test_gemm_only_profiling_mode():
+    import torch
+    import paper_2409_18772_amd as L
+    M, N, K = 4096, 2048, 512
+    A = to_dev(wl.random_matrix("normal", M, K, seed=33))
+    B = to_dev(wl.random_matrix("normal", K, N, seed=34))
+    ws = L.Workspace.for_problem(M, N, K, 8, 4)
+    L.lrqmm_profile_enable(L.PROF_GEMM_ONLY)
+    try:
+        for _ in range(3):
+            L.lrqmm_matmul(A, B, 4, 8, 4, 1, workspace=ws)          # early product: stage int_gemm
+        torch.cuda.synchronize()
+        st, n = L.lrqmm_profile_read()
+        assert n == 3 and st["int_gemm"] > 0 and st["gemm"] == 0 and st["rsvd_a"] == 0
+        L.lrqmm_matmul(A, B, 4, 0, workspace=ws)                    # rank 0: fused kernel, stage gemm
+        torch.cuda.synchronize()
+        st, n = L.lrqmm_profile_read()
+        assert n == 1 and st["gemm"] > 0 and st["int_gemm"] == 0
+    finally:
+        L.lrqmm_profile_enable(False)
