@@ -152,7 +152,7 @@ struct Side {
     hipStream_t stream = nullptr;        // factorization of R_B
     hipStream_t gemm_stream = nullptr;   // early integer GEMM
     hipEvent_t fork = nullptr, join = nullptr;
-    hipEvent_t qa = nullptr, qb = nullptr, gate = nullptr, gate_b = nullptr, gdone = nullptr;
+    hipEvent_t gate = nullptr, gate_b = nullptr, gdone = nullptr;
     bool ok = false;
 } g_side;
 
@@ -160,7 +160,7 @@ bool side_ready() {
     if (g_side.ok) return true;
     if (hipStreamCreateWithFlags(&g_side.stream, hipStreamNonBlocking) != hipSuccess) return false;
     if (hipStreamCreateWithFlags(&g_side.gemm_stream, hipStreamNonBlocking) != hipSuccess) return false;
-    for (hipEvent_t* e : {&g_side.qa, &g_side.qb, &g_side.gate, &g_side.gate_b, &g_side.gdone})
+    for (hipEvent_t* e : {&g_side.gate, &g_side.gate_b, &g_side.gdone})
         if (hipEventCreateWithFlags(e, hipEventDisableTiming) != hipSuccess) return false;
     if (hipEventCreateWithFlags(&g_side.fork, hipEventDisableTiming) != hipSuccess) return false;
     if (hipEventCreateWithFlags(&g_side.join, hipEventDisableTiming) != hipSuccess) return false;
@@ -486,7 +486,6 @@ int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int
     hipStream_t gst = early ? g_side.gemm_stream : pst;
     std::function<int()> before_svd = nullptr, before_svd_b = nullptr, after_svd_b = nullptr;
     if (early) {
-        opsA.push_back([=] { return hipEventRecord(g_side.qa, pst) == hipSuccess ? LRQMM_OK : LRQMM_ERR_HIP; });
         // The GEMM must not take the CUs before the two SVD workgroups have theirs: it waits
         // for the kernels that precede both SVDs and then for a few minimal kernels, which
         // gives the SVD launches (one dependent launch behind their events) a head start.
@@ -499,7 +498,7 @@ int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int
             return LRQMM_OK;
         };
         after_svd_b = [=] {     // issued by the host after both SVD launches
-            for (hipEvent_t e : {g_side.qa, g_side.qb, g_side.gate, g_side.gate_b})
+            for (hipEvent_t e : {g_side.gate, g_side.gate_b})    // recorded after both quantizations
                 if (hipStreamWaitEvent(gst, e, 0) != hipSuccess) return LRQMM_ERR_HIP;
             for (int t = 0; t < 3; ++t) {
                 const int r = launch_tick(w.tick, gst);
@@ -521,8 +520,6 @@ int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int
     if (K > 0) opsB.push_back([=] { return lrqmm_quantize_ex(B, ldb, K, N, LRQMM_AXIS_COL, bits, round_mode, scale_mode, w.BqT, w.amaxB, bst); });
     else opsB.push_back([=] { return launch_pad_copy(nullptr, N, 0, 1, w.amaxB, bst); });
     opsB.push_back([=] { prof_mark(slot, 4, bst); return LRQMM_OK; });
-    if (early)
-        opsB.push_back([=] { return hipEventRecord(g_side.qb, bst) == hipSuccess ? LRQMM_OK : LRQMM_ERR_HIP; });
     if (rank > 0)
         LRQ_TRY(rsvd_plan(opsB, B, ldb, w.amaxB, K, N, LRQMM_AXIS_COL, bits, round_mode, rank, oversample, power_iters,
                           seed, nullptr, w.W, w.Gam, w.Zt, w.subB, w.subB_bytes, bst, before_svd_b,
