@@ -166,7 +166,7 @@ LRQMM_API int lrqmm_gemm_ex(int M, int N, int K, int bits, int rank,
  * B (K x N) to float32 C (M x N): quantize both operands, factor both residuals
  * (sketch seeds (seed, 0) and (seed, 1)), integer GEMM, fused compensation.
  * rank == 0 runs the direct-quantization pipeline only.
- * With rank > 0 the work on B (quantization, factorization of R_B) is enqueued on
+ * With rank > 0 the work on A (quantization, factorization of R_A) is enqueued on
  * a second stream owned by the library (created on first use, default priority),
  * forked from and joined back into `stream` with events, so the call is still
  * ordered like a single-stream call from the caller's point of view.  For large
@@ -244,8 +244,8 @@ LRQMM_API int lrqmm_residual_matmul(int M, int N, int K, int bits, int terms, in
  * synchronisation), writes the per-stage mean duration in milliseconds to
  * stage_ms[LRQMM_PROF_STAGES] (host pointer) and the number of calls averaged to
  * *ncalls (host pointer), then resets the call counter.  Not thread safe.
- *   stage 0 quantize A   stage 1 RSVD of R_A     (caller's stream)
- *   stage 2 quantize B   stage 3 RSVD of R_B     (library's second stream, concurrent with 0-1)
+ *   stage 0 quantize A   stage 1 RSVD of R_A     (library's second stream, concurrent with 2-3)
+ *   stage 2 quantize B   stage 3 RSVD of R_B     (caller's stream)
  *   stage 4 compensation panels
  *   stage 5 int8 GEMM kernel with fused epilogue, or -- when the integer product ran early,
  *           see lrqmm_matmul -- the dequantizing rank-2r update kernel alone

@@ -463,19 +463,23 @@ int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int
     int rc;
     hipStream_t pst = static_cast<hipStream_t>(stream);
     const int slot = (g_prof.on && g_prof.ncalls < kProfMaxCalls) ? g_prof.ncalls++ : -1;
-    // B's quantization and factorization run on a second stream next to A's; rank 0 stays on one stream
+    // the two operands' quantization and factorization run on two streams; rank 0 stays on one stream
     const bool overlap = rank > 0 && K > 0 && side_ready();
-    hipStream_t bst = overlap ? g_side.stream : pst;
+    // B's chain is the longer one (its quantization needs two passes over B), so it stays on the
+    // caller's stream and starts at once; A's chain takes the side stream and absorbs the latency of
+    // the fork event, and has normally finished when the caller's stream reaches the join.
+    hipStream_t bst = pst;
+    hipStream_t ast = overlap ? g_side.stream : pst;
     if (overlap) {
         if (hipEventRecord(g_side.fork, pst) != hipSuccess) return LRQMM_ERR_HIP;
-        if (hipStreamWaitEvent(bst, g_side.fork, 0) != hipSuccess) return LRQMM_ERR_HIP;
+        if (hipStreamWaitEvent(ast, g_side.fork, 0) != hipSuccess) return LRQMM_ERR_HIP;
     }
     // the two sides are planned first and then issued alternately (see LaunchList)
     LaunchList opsA, opsB;
-    opsA.push_back([=] { prof_mark(slot, 0, pst); return LRQMM_OK; });
-    if (K > 0) opsA.push_back([=] { return lrqmm_quantize_ex(A, lda, M, K, LRQMM_AXIS_ROW, bits, round_mode, scale_mode, w.Aq, w.amaxA, pst); });
-    else opsA.push_back([=] { return launch_pad_copy(nullptr, M, 0, 1, w.amaxA, pst); });
-    opsA.push_back([=] { prof_mark(slot, 1, pst); return LRQMM_OK; });
+    opsA.push_back([=] { prof_mark(slot, 0, ast); return LRQMM_OK; });
+    if (K > 0) opsA.push_back([=] { return lrqmm_quantize_ex(A, lda, M, K, LRQMM_AXIS_ROW, bits, round_mode, scale_mode, w.Aq, w.amaxA, ast); });
+    else opsA.push_back([=] { return launch_pad_copy(nullptr, M, 0, 1, w.amaxA, ast); });
+    opsA.push_back([=] { prof_mark(slot, 1, ast); return LRQMM_OK; });
     // Early integer GEMM: with both factorizations in their single-workgroup SVD the GPU is
     // nearly idle, so the int8 product (which needs only the codes) runs there on a third
     // stream, leaves raw int32 sums in C, and the epilogue follows the panels as a kernel of
@@ -490,7 +494,7 @@ int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int
         // for the kernels that precede both SVDs and then for a few minimal kernels, which
         // gives the SVD launches (one dependent launch behind their events) a head start.
         before_svd = [=] {
-            if (hipEventRecord(g_side.gate, pst) != hipSuccess) return LRQMM_ERR_HIP;
+            if (hipEventRecord(g_side.gate, ast) != hipSuccess) return LRQMM_ERR_HIP;
             return LRQMM_OK;
         };
         before_svd_b = [=] {
@@ -514,8 +518,8 @@ int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int
     }
     if (rank > 0)
         LRQ_TRY(rsvd_plan(opsA, A, lda, w.amaxA, M, K, LRQMM_AXIS_ROW, bits, round_mode, rank, oversample, power_iters,
-                          seed, nullptr, w.U, w.Sig, w.Vt, w.subA, w.subA_bytes, pst, before_svd));
-    opsA.push_back([=] { prof_mark(slot, 2, pst); return LRQMM_OK; });
+                          seed, nullptr, w.U, w.Sig, w.Vt, w.subA, w.subA_bytes, ast, before_svd));
+    opsA.push_back([=] { prof_mark(slot, 2, ast); return LRQMM_OK; });
     opsB.push_back([=] { prof_mark(slot, 3, bst); return LRQMM_OK; });
     if (K > 0) opsB.push_back([=] { return lrqmm_quantize_ex(B, ldb, K, N, LRQMM_AXIS_COL, bits, round_mode, scale_mode, w.BqT, w.amaxB, bst); });
     else opsB.push_back([=] { return launch_pad_copy(nullptr, N, 0, 1, w.amaxB, bst); });
@@ -525,9 +529,9 @@ int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int
                           seed, nullptr, w.W, w.Gam, w.Zt, w.subB, w.subB_bytes, bst, before_svd_b,
                           after_svd_b));
     opsB.push_back([=] { prof_mark(slot, 5, bst); return LRQMM_OK; });
-    LRQ_TRY(run_interleaved(opsA, opsB));
+    LRQ_TRY(run_interleaved(opsB, opsA));
     if (overlap) {
-        if (hipEventRecord(g_side.join, bst) != hipSuccess) return LRQMM_ERR_HIP;
+        if (hipEventRecord(g_side.join, ast) != hipSuccess) return LRQMM_ERR_HIP;
         if (hipStreamWaitEvent(pst, g_side.join, 0) != hipSuccess) return LRQMM_ERR_HIP;
     }
     prof_mark(slot, 6, pst);
