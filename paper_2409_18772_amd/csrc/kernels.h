@@ -32,7 +32,8 @@ int launch_sketch_and_scales(uint64_t seed, int stream_id, int rows, int cols, i
 int launch_pad_copy(const float* src, int rows, int cols, int ld, float* dst, hipStream_t st);
 
 // ---- passes.hip ---------------------------------------------------------
-#define MAX_SPLITS 8    // upper bound on PassPlan::splits
+#define MAX_SPLITS 8      // upper bound on the splits of plan_pass_n (its partials are summed in one batch)
+#define MAX_SPLITS_T 64   // upper bound for plan_pass_t (only launch_reduce_gram sums those, in batches)
 struct PassPlan {
     int splits;   // number of partial results
     int chunk;    // reduction-index range per split (multiple of 64)

@@ -55,15 +55,19 @@ __global__ __launch_bounds__(256) void reduce_gram_kernel(const float* __restric
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
             if (row < re) {
                 const size_t off = (size_t)row * LP + c;
-                // every split's load is issued before the first add (splits <= MAX_SPLITS)
-                float4 p[MAX_SPLITS];
+                // splits are summed in order, MAX_SPLITS at a time: the loads of a batch are all
+                // issued before its first add (tall operands use more than one batch)
+                for (int s0 = 0; s0 < splits; s0 += MAX_SPLITS) {
+                    float4 p[MAX_SPLITS];
 #pragma unroll
-                for (int sp = 0; sp < MAX_SPLITS; ++sp)
-                    p[sp] = (sp < splits) ? *reinterpret_cast<const float4*>(partial + sp * plane + off)
-                                          : make_float4(0.f, 0.f, 0.f, 0.f);
+                    for (int sp = 0; sp < MAX_SPLITS; ++sp)
+                        p[sp] = (s0 + sp < splits)
+                                    ? *reinterpret_cast<const float4*>(partial + (size_t)(s0 + sp) * plane + off)
+                                    : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-                for (int sp = 0; sp < MAX_SPLITS; ++sp) {
-                    v.x += p[sp].x; v.y += p[sp].y; v.z += p[sp].z; v.w += p[sp].w;
+                    for (int sp = 0; sp < MAX_SPLITS; ++sp) {
+                        v.x += p[sp].x; v.y += p[sp].y; v.z += p[sp].z; v.w += p[sp].w;
+                    }
                 }
                 if (rowscale) {
                     const float rs = rowscale[row];

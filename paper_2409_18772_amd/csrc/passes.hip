@@ -475,17 +475,17 @@ __global__ __launch_bounds__(256) void resid_mul_t_kernel(
 // ---------------------------------------------------------------------------
 // launch plans and dispatch
 // ---------------------------------------------------------------------------
-static int pick_splits(int blocks_one_split, int reduce_len, int unit) {
+static int pick_splits(int blocks_one_split, int reduce_len, int unit, int limit) {
     // aim for ~512 workgroups (2 per CU) but keep >= 4 `unit`-sized steps per split
     int want = ceil_div(512, max(1, blocks_one_split));
     int max_splits = max(1, reduce_len / (4 * unit));
-    int s = max(1, min(want, min(max_splits, MAX_SPLITS)));
+    int s = max(1, min(want, min(max_splits, limit)));
     return s;
 }
 
 PassPlan plan_pass_n(int rows, int cols) {
     PassPlan p;
-    int s = pick_splits(ceil_div(rows, 64), cols, KCHUNK);
+    int s = pick_splits(ceil_div(rows, 64), cols, KCHUNK, MAX_SPLITS);
     p.chunk = ceil_div(ceil_div(cols, s), KCHUNK) * KCHUNK;
     p.splits = ceil_div(cols, p.chunk);
     return p;
@@ -493,7 +493,7 @@ PassPlan plan_pass_n(int rows, int cols) {
 
 PassPlan plan_pass_t(int rows, int cols) {
     PassPlan p;
-    int s = pick_splits(ceil_div(cols, 64), rows, 16);
+    int s = pick_splits(ceil_div(cols, 64), rows, 16, MAX_SPLITS_T);     // few column strips: many row chunks
     p.chunk = ceil_div(ceil_div(rows, s), 16) * 16;
     p.splits = ceil_div(rows, p.chunk);
     return p;
