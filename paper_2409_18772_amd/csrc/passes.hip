@@ -142,6 +142,194 @@ __global__ __launch_bounds__(256) void resid_mul_n_kernel(
             if (orow0 + v < rows) out[(size_t)(orow0 + v) * LP + 16 * nt + r] = acc[nt][v];
 }
 
+// ---------------------------------------------------------------------------
+// The same product on the bf16 matrix cores.  A float32 value is the exact sum of three
+// bfloat16 planes (8 + 8 + 8 significant bits: round to nearest, subtract, repeat), and the
+// product of two such sums is evaluated with the six plane products whose weight is at least
+// 2^-16 of the leading one (r1 w1, r1 w2, r2 w1, r1 w3, r2 w2, r3 w1), each exact, accumulated
+// in float32 by the matrix core: the dropped products are below 2^-24 of the leading one,
+// the size of the float32 accumulation rounding itself.  Six v_mfma_f32_16x16x32_bf16 take
+// 96 cycles per 32 k against 256 for eight v_mfma_f32_16x16x4_f32, and these kernels are
+// bound by the matrix cores as soon as two of them share the chip.
+// Operand layout (lane l): A[i = l%16][k = 8(l/16) .. +8], B[k = 8(l/16) .. +8][j = l%16],
+// D[i = 4(l/16)+v][j = l%16].  The 8 k-slots of lane group g in a 32-deep step are the
+// columns 4g .. 4g+3 and 16+4g .. 16+4g+3 of that step (two 16-byte loads of X); W is staged
+// in LDS as three planes [plane][n][k] with k in that slot order, so a B operand is one
+// 16-byte LDS read.
+// ---------------------------------------------------------------------------
+typedef __bf16 v8bf16 __attribute__((ext_vector_type(8)));
+struct Planes3 {
+    v8bf16 p1, p2, p3;
+};
+__device__ __forceinline__ Planes3 split_planes(const float (&r)[8]) {
+    Planes3 o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const __bf16 h = (__bf16)r[e];
+        const float rem = r[e] - (float)h;          // exact
+        const __bf16 m = (__bf16)rem;
+        const float rem2 = rem - (float)m;          // exact
+        o.p1[e] = h;
+        o.p2[e] = m;
+        o.p3[e] = (__bf16)rem2;
+    }
+    return o;
+}
+// acc[m][n] += a[m] . b[n] for NA x NB independent accumulators: the six plane products are
+// the outer loop (smallest terms first), so consecutive matrix instructions never depend on
+// each other.
+template <int NA, int NB>
+__device__ __forceinline__ void mfma_planes(const Planes3 (&a)[NA], const Planes3 (&b)[NB], v4f (&acc)[NA][NB]) {
+#define LRQ_PP(PA, PB)                                                                               \
+    _Pragma("unroll") for (int m = 0; m < NA; ++m) _Pragma("unroll") for (int n = 0; n < NB; ++n)     \
+        acc[m][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m].PA, b[n].PB, acc[m][n], 0, 0, 0);
+    LRQ_PP(p3, p1)
+    LRQ_PP(p2, p2)
+    LRQ_PP(p1, p3)
+    LRQ_PP(p2, p1)
+    LRQ_PP(p1, p2)
+    LRQ_PP(p1, p1)
+#undef LRQ_PP
+}
+
+// One thread's share of the chunk W[k0 .. k0+KC)[0..LP): units (n, group), a unit being the 8
+// rows of W that form one lane group's k-slots of one 32-deep step, for one column n.
+template <int NT, int KC>
+struct WStageBf16 {
+    static constexpr int LP = NT * 16;
+    static constexpr int LDK = KC + 8;                      // plane row stride in bfloat16
+    static constexpr int UNITS = LP * (KC / 8);
+    static constexpr int NU = (UNITS + 255) / 256;
+    float v[NU][8];
+    __device__ __forceinline__ void load(const float* __restrict__ W, int k0, int kend) {
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+            const int unit = min((int)threadIdx.x + 256 * u, UNITS - 1);
+            const int n = unit % LP, grp = unit / LP;        // grp = 4 (step in chunk) + lane group
+            const int kbase = k0 + 32 * (grp >> 2) + 4 * (grp & 3);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int k = kbase + (e & 3) + 16 * (e >> 2);
+                const float t = W[(size_t)min(k, kend - 1) * LP + n];   // branch free: clamp, then select
+                v[u][e] = k < kend ? t : 0.f;
+            }
+        }
+    }
+    __device__ __forceinline__ void store(uint16_t* __restrict__ wl) const {
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+            const int unit = (int)threadIdx.x + 256 * u;
+            if (unit < UNITS) {
+                const int n = unit % LP, grp = unit / LP;
+                const Planes3 pl = split_planes(v[u]);
+                uint16_t* dst = wl + n * LDK + 8 * grp;
+                *reinterpret_cast<v8bf16*>(dst) = pl.p1;
+                *reinterpret_cast<v8bf16*>(dst + LP * LDK) = pl.p2;
+                *reinterpret_cast<v8bf16*>(dst + 2 * LP * LDK) = pl.p3;
+            }
+        }
+    }
+};
+
+template <int NT, int AXIS, bool VEC>
+__global__ __launch_bounds__(256) void resid_mul_n_bf16_kernel(
+    const float* __restrict__ X, int ldx, int rows, int cols, const float* __restrict__ lam,
+    const float* __restrict__ sc, QuantParams q, const float* __restrict__ W, int chunk,
+    float* __restrict__ partial) {
+    constexpr int LP = NT * 16;
+    constexpr int KC = 64;      // two 32-deep steps per chunk; 41 KB of LDS at l <= 48 (three workgroups per CU)
+    constexpr int KS = KC / 16;                             // float4 loads per lane per chunk
+    using WS = WStageBf16<NT, KC>;
+    constexpr int LDK = WS::LDK;
+    __shared__ __align__(16) uint16_t wl[2][3 * LP * LDK];
+    __shared__ __align__(16) float sl[2][2 * KC];   // per-column lambda | step of the chunk (AXIS 1)
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int r = lane & 15, g = lane >> 4;
+    const int row = blockIdx.x * 64 + wave * 16 + r;
+    const bool row_ok = row < rows;
+    const float* xp = X + (size_t)(row_ok ? row : 0) * ldx;
+    const int kb = blockIdx.y * chunk;
+    const int ke = min(cols, kb + chunk);
+    float lam_r = 0.f, s_r = 0.f;
+    if (AXIS == 0 && row_ok) {
+        lam_r = lam[row];
+        s_r = sc[row];
+    }
+    v4f acc[1][NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[0][nt] = (v4f){0.f, 0.f, 0.f, 0.f};
+
+    float4 xr[KS];
+    float scale_reg = 0.f;     // this thread's element of the chunk's lambda (t < KC) or step vector
+    WS ws;
+    auto load_x = [&](int k0) {
+#pragma unroll
+        for (int j = 0; j < KS; ++j) xr[j] = load4f<VEC>(xp, k0 + 16 * j + 4 * g, ke, row_ok);
+        if (AXIS == 1) {
+            const int t = threadIdx.x & (KC - 1);
+            const int kc = min(k0 + t, ke - 1);
+            const float v = ((threadIdx.x & KC) == 0) ? lam[kc] : sc[kc];
+            scale_reg = (k0 + t < ke) ? v : 0.f;
+        }
+    };
+    if (kb < ke) {
+        load_x(kb);
+        ws.load(W, kb, ke);
+    }
+    int buf = 0;
+    for (int k0 = kb; k0 < ke; k0 += KC, buf ^= 1) {
+        ws.store(wl[buf]);
+        if (AXIS == 1 && threadIdx.x < 2 * KC) sl[buf][threadIdx.x] = scale_reg;
+        __syncthreads();             // wl[buf], sl[buf] complete; the other buffers no longer read
+        Planes3 ap[KC / 32][1];
+#pragma unroll
+        for (int jj = 0; jj < KC / 32; ++jj) {
+            float res[8];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int j = 2 * jj + h;
+                float4 l4, s4;
+                if (AXIS == 0) {
+                    l4 = make_float4(lam_r, lam_r, lam_r, lam_r);
+                    s4 = make_float4(s_r, s_r, s_r, s_r);
+                } else {
+                    l4 = *reinterpret_cast<const float4*>(&sl[buf][16 * j + 4 * g]);
+                    s4 = *reinterpret_cast<const float4*>(&sl[buf][KC + 16 * j + 4 * g]);
+                }
+                res[4 * h + 0] = quant_residual(xr[j].x, l4.x, s4.x, q);
+                res[4 * h + 1] = quant_residual(xr[j].y, l4.y, s4.y, q);
+                res[4 * h + 2] = quant_residual(xr[j].z, l4.z, s4.z, q);
+                res[4 * h + 3] = quant_residual(xr[j].w, l4.w, s4.w, q);
+            }
+            ap[jj][0] = split_planes(res);
+        }
+        if (k0 + KC < ke) {      // next chunk's loads fly during this chunk's MFMAs
+            load_x(k0 + KC);
+            ws.load(W, k0 + KC, ke);
+        }
+        const uint16_t* wb = wl[buf];
+#pragma unroll
+        for (int jj = 0; jj < KC / 32; ++jj) {
+            Planes3 bp[NT];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const uint16_t* src = wb + (16 * nt + r) * LDK + 32 * jj + 8 * g;
+                bp[nt].p1 = *reinterpret_cast<const v8bf16*>(src);
+                bp[nt].p2 = *reinterpret_cast<const v8bf16*>(src + LP * LDK);
+                bp[nt].p3 = *reinterpret_cast<const v8bf16*>(src + 2 * LP * LDK);
+            }
+            mfma_planes<1, NT>(ap[jj], bp, acc);
+        }
+    }
+    float* out = partial + (size_t)blockIdx.y * rows * LP;
+    const int orow0 = blockIdx.x * 64 + wave * 16 + 4 * g;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            if (orow0 + v < rows) out[(size_t)(orow0 + v) * LP + 16 * nt + r] = acc[0][nt][v];
+}
+
 // Same contraction with an int8 code matrix as the streamed operand (no scales).
 // blockIdx.z selects one of two independent jobs (A~ W and (V^T B~)^T share one launch).
 struct CodesJob {
@@ -472,6 +660,119 @@ __global__ __launch_bounds__(256) void resid_mul_t_kernel(
     }
 }
 
+// The T-type product on the bf16 matrix cores (see resid_mul_n_bf16_kernel for the plane
+// arithmetic).  A wave takes 32 rows per step: lane group g loads rows base + 4e + g (e < 8),
+// which are its 8 k-slots; both operands come straight from global memory in that order (a
+// float4 of X and NT floats of W per row), so no LDS is needed before the final merge.
+template <int NT, int AXIS, bool VEC>
+__global__ __launch_bounds__(256) void resid_mul_t_bf16_kernel(
+    const float* __restrict__ X, int ldx, int rows, int cols, const float* __restrict__ lam,
+    const float* __restrict__ sc, QuantParams q, const float* __restrict__ W, int chunk,
+    float* __restrict__ partial) {
+    constexpr int LP = NT * 16;
+    __shared__ __align__(16) float red[64 * LP];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int c = lane & 15, g = lane >> 4;
+    const int c0 = blockIdx.x * 64;
+    const int kc = c0 + 4 * c;
+    const int ib = blockIdx.y * chunk;
+    const int ie = min(rows, ib + chunk);
+    float lcol[4] = {0.f, 0.f, 0.f, 0.f}, scol[4] = {0.f, 0.f, 0.f, 0.f};
+    if (AXIS == 1 && kc < cols) {   // padded with zeros to a multiple of 4
+        const float4 l4 = *reinterpret_cast<const float4*>(lam + kc);
+        const float4 s4 = *reinterpret_cast<const float4*>(sc + kc);
+        lcol[0] = l4.x; lcol[1] = l4.y; lcol[2] = l4.z; lcol[3] = l4.w;
+        scol[0] = s4.x; scol[1] = s4.y; scol[2] = s4.z; scol[3] = s4.w;
+    }
+    v4f acc[4][NT];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[t][nt] = (v4f){0.f, 0.f, 0.f, 0.f};
+
+    struct Group {
+        float x[8][4];
+        float lr[8], sr[8];
+        float w[8][NT];
+    };
+    auto load_group = [&](int i0, Group& f) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int i = i0 + 4 * e + g;
+            const bool ok = i < ie;
+            const size_t ii = ok ? (size_t)i : 0;      // unconditional loads from a valid row, then selects
+            const float4 xv = load4f<VEC>(X + ii * ldx, kc, cols, ok);
+            f.x[e][0] = xv.x; f.x[e][1] = xv.y; f.x[e][2] = xv.z; f.x[e][3] = xv.w;
+            if (AXIS == 0) {
+                const float l = lam[ii], sv = sc[ii];
+                f.lr[e] = ok ? l : 0.f;
+                f.sr[e] = ok ? sv : 0.f;
+            }
+            const float* wp = W + ii * LP + NT * c;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const float wv = wp[nt];
+                f.w[e][nt] = ok ? wv : 0.f;
+            }
+        }
+    };
+    Group cur, nxt;
+    const int istart = ib + 32 * wave;
+    load_group(istart, cur);
+    for (int i0 = istart; i0 < ie; i0 += 128) {
+        load_group(i0 + 128, nxt);      // past the end: every row masked
+        Planes3 bp[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            float wv[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) wv[e] = cur.w[e][nt];
+            bp[nt] = split_planes(wv);
+        }
+#pragma unroll
+        for (int th = 0; th < 2; ++th) {        // two column components at a time: 2 NT independent chains
+            Planes3 ap[2];
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt) {
+                const int t = 2 * th + tt;
+                float res[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    res[e] = quant_residual(cur.x[e][t], AXIS == 0 ? cur.lr[e] : lcol[t],
+                                            AXIS == 0 ? cur.sr[e] : scol[t], q);
+                ap[tt] = split_planes(res);
+            }
+            v4f (&a2)[2][NT] = *reinterpret_cast<v4f (*)[2][NT]>(&acc[2 * th]);
+            mfma_planes<2, NT>(ap, bp, a2);
+        }
+        cur = nxt;
+    }
+    // merge the four waves (fixed order: deterministic)
+    for (int wv = 0; wv < 4; ++wv) {
+        if (wave == wv) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int cl = 16 * g + 4 * v + t;   // local column of D row 4g+v in M-tile t
+                        float* p = red + cl * LP + NT * c + nt;
+                        *p = (wv == 0) ? acc[t][nt][v] : (*p + acc[t][nt][v]);
+                    }
+        }
+        __syncthreads();
+    }
+    float* out = partial + (size_t)blockIdx.y * cols * LP;
+    for (int idx = threadIdx.x; idx < 64 * LP / 4; idx += 256) {
+        const int e = idx * 4;
+        const int cl = e / LP, n = e % LP;
+        if (c0 + cl < cols)
+            *reinterpret_cast<float4*>(out + (size_t)(c0 + cl) * LP + n) =
+                *reinterpret_cast<const float4*>(red + cl * LP + n);
+    }
+}
+
 // ---------------------------------------------------------------------------
 // launch plans and dispatch
 // ---------------------------------------------------------------------------
@@ -501,16 +802,23 @@ PassPlan plan_pass_t(int rows, int cols) {
 
 static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
+#ifdef LRQ_PASS_FP32
+#define LRQ_PASS_N resid_mul_n_kernel
+#define LRQ_PASS_T resid_mul_t_kernel
+#else
+#define LRQ_PASS_N resid_mul_n_bf16_kernel
+#define LRQ_PASS_T resid_mul_t_bf16_kernel
+#endif
 template <int NT>
 static void dispatch_n(int axis, bool vec, dim3 grid, hipStream_t st, const float* X, int ldx, int rows, int cols,
                        const float* lam, const float* s, QuantParams q, const float* W, int chunk,
                        float* partial) {
     if (axis == 0) {
-        if (vec) hipLaunchKernelGGL((resid_mul_n_kernel<NT, 0, true>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
-        else     hipLaunchKernelGGL((resid_mul_n_kernel<NT, 0, false>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+        if (vec) hipLaunchKernelGGL((LRQ_PASS_N<NT, 0, true>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+        else     hipLaunchKernelGGL((LRQ_PASS_N<NT, 0, false>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
     } else {
-        if (vec) hipLaunchKernelGGL((resid_mul_n_kernel<NT, 1, true>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
-        else     hipLaunchKernelGGL((resid_mul_n_kernel<NT, 1, false>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+        if (vec) hipLaunchKernelGGL((LRQ_PASS_N<NT, 1, true>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+        else     hipLaunchKernelGGL((LRQ_PASS_N<NT, 1, false>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
     }
 }
 
@@ -519,11 +827,11 @@ static void dispatch_t(int axis, bool vec, dim3 grid, hipStream_t st, const floa
                        const float* lam, const float* s, QuantParams q, const float* W, int chunk,
                        float* partial) {
     if (axis == 0) {
-        if (vec) hipLaunchKernelGGL((resid_mul_t_kernel<NT, 0, true>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
-        else     hipLaunchKernelGGL((resid_mul_t_kernel<NT, 0, false>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+        if (vec) hipLaunchKernelGGL((LRQ_PASS_T<NT, 0, true>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+        else     hipLaunchKernelGGL((LRQ_PASS_T<NT, 0, false>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
     } else {
-        if (vec) hipLaunchKernelGGL((resid_mul_t_kernel<NT, 1, true>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
-        else     hipLaunchKernelGGL((resid_mul_t_kernel<NT, 1, false>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+        if (vec) hipLaunchKernelGGL((LRQ_PASS_T<NT, 1, true>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+        else     hipLaunchKernelGGL((LRQ_PASS_T<NT, 1, false>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
     }
 }
 
