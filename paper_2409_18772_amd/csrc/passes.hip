@@ -664,8 +664,9 @@ __global__ __launch_bounds__(256) void resid_mul_t_kernel(
 // arithmetic).  A wave takes 32 rows per step: lane group g loads rows base + 4e + g (e < 8),
 // which are its 8 k-slots; both operands come straight from global memory in that order (a
 // float4 of X and NT floats of W per row), so no LDS is needed before the final merge.
+// (two workgroups per CU up to l = 64: the register cap costs no spills there and hides the loads better)
 template <int NT, int AXIS, bool VEC>
-__global__ __launch_bounds__(256) void resid_mul_t_bf16_kernel(
+__global__ __launch_bounds__(256, NT <= 4 ? 2 : 1) void resid_mul_t_bf16_kernel(
     const float* __restrict__ X, int ldx, int rows, int cols, const float* __restrict__ lam,
     const float* __restrict__ sc, QuantParams q, const float* __restrict__ W, int chunk,
     float* __restrict__ partial) {
@@ -802,23 +803,24 @@ PassPlan plan_pass_t(int rows, int cols) {
 
 static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
-#ifdef LRQ_PASS_FP32
-#define LRQ_PASS_N resid_mul_n_kernel
-#define LRQ_PASS_T resid_mul_t_kernel
-#else
-#define LRQ_PASS_N resid_mul_n_bf16_kernel
-#define LRQ_PASS_T resid_mul_t_bf16_kernel
-#endif
+// Sketches of up to 16 columns keep the float32 matrix-core kernels (one tile of W columns: the
+// matrix cores are nowhere near busy and splitting operands into planes only adds work; the
+// conv-shaped workload with l = 8 measures 0.37 ms against 0.39 ms); wider ones use the bf16 kernels.
+template <int NT, int AXIS, bool VEC>
+struct PassKernels {
+    static constexpr auto n = NT == 1 ? resid_mul_n_kernel<NT, AXIS, VEC> : resid_mul_n_bf16_kernel<NT, AXIS, VEC>;
+    static constexpr auto t = NT == 1 ? resid_mul_t_kernel<NT, AXIS, VEC> : resid_mul_t_bf16_kernel<NT, AXIS, VEC>;
+};
 template <int NT>
 static void dispatch_n(int axis, bool vec, dim3 grid, hipStream_t st, const float* X, int ldx, int rows, int cols,
                        const float* lam, const float* s, QuantParams q, const float* W, int chunk,
                        float* partial) {
     if (axis == 0) {
-        if (vec) hipLaunchKernelGGL((LRQ_PASS_N<NT, 0, true>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
-        else     hipLaunchKernelGGL((LRQ_PASS_N<NT, 0, false>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+        if (vec) hipLaunchKernelGGL((PassKernels<NT, 0, true>::n), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+        else     hipLaunchKernelGGL((PassKernels<NT, 0, false>::n), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
     } else {
-        if (vec) hipLaunchKernelGGL((LRQ_PASS_N<NT, 1, true>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
-        else     hipLaunchKernelGGL((LRQ_PASS_N<NT, 1, false>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+        if (vec) hipLaunchKernelGGL((PassKernels<NT, 1, true>::n), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+        else     hipLaunchKernelGGL((PassKernels<NT, 1, false>::n), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
     }
 }
 
@@ -827,11 +829,11 @@ static void dispatch_t(int axis, bool vec, dim3 grid, hipStream_t st, const floa
                        const float* lam, const float* s, QuantParams q, const float* W, int chunk,
                        float* partial) {
     if (axis == 0) {
-        if (vec) hipLaunchKernelGGL((LRQ_PASS_T<NT, 0, true>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
-        else     hipLaunchKernelGGL((LRQ_PASS_T<NT, 0, false>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+        if (vec) hipLaunchKernelGGL((PassKernels<NT, 0, true>::t), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+        else     hipLaunchKernelGGL((PassKernels<NT, 0, false>::t), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
     } else {
-        if (vec) hipLaunchKernelGGL((LRQ_PASS_T<NT, 1, true>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
-        else     hipLaunchKernelGGL((LRQ_PASS_T<NT, 1, false>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+        if (vec) hipLaunchKernelGGL((PassKernels<NT, 1, true>::t), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+        else     hipLaunchKernelGGL((PassKernels<NT, 1, false>::t), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
     }
 }
 
