@@ -211,8 +211,7 @@ def main():
                                "int8_gemm256_kernel (int8 MFMA GEMM + fused dequant and rank-2r epilogue)",
                      "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                      "frac": round(achieved / PEAK_INT8_TOPS, 4),
-                     "traffic": read_traffic("int8_gemm_c3_pmc.txt", "traffic_bytes_per_launch" if early
-                                             else "traffic_bytes_per_launch_fused"),
+                     "traffic": read_traffic("int8_gemm_c3_pmc.txt") if early else None,
                      "launch_ms": round(stages[gemm_key], 4), "ops_per_launch": ops},
         "stages": stage_info,
         "stages_note": "GEMM launch time from HIP events inside the timed region; the other stages from a "

@@ -60,6 +60,29 @@ __device__ __forceinline__ void store_out(const GemmOut& out, int row, int col, 
     *p = o;
 }
 
+// Workgroup ids are dealt round-robin to the 8 XCDs, each with an L2 of its own.  The tile grid
+// is cut into gm x gn = 8 rectangles, one per XCD, as square as the tile counts allow, so that an
+// XCD fetches tiles_m/gm row panels of A and tiles_n/gn of B instead of whole bands (at 16 x 16
+// tiles: 8 + 4 panels per XCD instead of 2 + 16).  Tile counts that are no multiple of 8 keep
+// the launch order.
+__device__ __forceinline__ int xcd_tile(int id, int tiles_n, int ntiles) {
+    if (ntiles & 7) return id;
+    const int tiles_m = ntiles / tiles_n;
+    int gm = 0, best = 0x7fffffff;
+#pragma unroll
+    for (int g = 1; g <= 8; g *= 2) {
+        const int h = 8 / g;
+        if (tiles_m % g == 0 && tiles_n % h == 0) {
+            const int cost = tiles_m / g + tiles_n / h;
+            if (cost < best) { best = cost; gm = g; }
+        }
+    }
+    // ntiles % 8 == 0 guarantees that one of the four cuts divides both tile counts
+    const int gn = 8 / gm, bn = tiles_n / gn, bm = tiles_m / gm;
+    const int x = id & 7, j = id >> 3;
+    return ((x / gn) * bm + j / bn) * tiles_n + (x % gn) * bn + j % bn;
+}
+
 template <bool VEC, bool COMP, bool WCINT>
 __global__ __launch_bounds__(256) void int8_gemm_kernel(int M, int N, int K,
                                                         const int8_t* __restrict__ Aq,
@@ -73,10 +96,7 @@ __global__ __launch_bounds__(256) void int8_gemm_kernel(int M, int N, int K,
                                                         int ntiles) {
     __shared__ __align__(16) int8_t As[2][TM * LDS_STRIDE];
     __shared__ __align__(16) int8_t Bs[2][TN * LDS_STRIDE];
-    // Workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a contiguous
-    // band of tiles so operand panels are shared inside its L2.
-    int tile = blockIdx.x;
-    if ((ntiles & 7) == 0) tile = (tile & 7) * (ntiles >> 3) + (tile >> 3);
+    const int tile = xcd_tile(blockIdx.x, tiles_n, ntiles);
     const int m0 = (tile / tiles_n) * TM, n0 = (tile % tiles_n) * TN;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int wm = wave >> 1, wn = wave & 1;
@@ -204,8 +224,7 @@ __global__ __launch_bounds__(512, 1) void int8_gemm256_kernel(int M, int N, int 
     float* __restrict__ C = out.C;
     __shared__ __align__(16) int8_t As[2][BTM * BSTRIDE];
     __shared__ __align__(16) int8_t Bs[2][BTN * BSTRIDE];
-    int tile = blockIdx.x;
-    if ((ntiles & 7) == 0) tile = (tile & 7) * (ntiles >> 3) + (tile >> 3);
+    const int tile = xcd_tile(blockIdx.x, tiles_n, ntiles);
     const int m0 = (tile / tiles_n) * BTM, n0 = (tile % tiles_n) * BTN;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int wm = wave >> 1, wn = wave & 1;
