@@ -153,6 +153,7 @@ struct Side {
     hipStream_t gemm_stream = nullptr;   // early integer GEMM
     hipEvent_t fork = nullptr, join = nullptr;
     hipEvent_t gate = nullptr, gate_b = nullptr, gdone = nullptr;
+    int cus = 0;                         // compute units of the device
     bool ok = false;
 } g_side;
 
@@ -164,6 +165,9 @@ bool side_ready() {
         if (hipEventCreateWithFlags(e, hipEventDisableTiming) != hipSuccess) return false;
     if (hipEventCreateWithFlags(&g_side.fork, hipEventDisableTiming) != hipSuccess) return false;
     if (hipEventCreateWithFlags(&g_side.join, hipEventDisableTiming) != hipSuccess) return false;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
+    if (hipDeviceGetAttribute(&g_side.cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return false;
     g_side.ok = true;
     return true;
 }
@@ -504,13 +508,17 @@ int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int
         after_svd_b = [=] {     // issued by the host after both SVD launches
             for (hipEvent_t e : {g_side.gate, g_side.gate_b})    // recorded after both quantizations
                 if (hipStreamWaitEvent(gst, e, 0) != hipSuccess) return LRQMM_ERR_HIP;
-            for (int t = 0; t < 3; ++t) {
+            // the two small-SVD workgroups hold a CU each while the product runs
+            const int resident = g_side.cus - 2;
+            const int zeroed = launch_int8_gemm_sums_prepare(M, N, K, w.Aq, w.BqT, reinterpret_cast<int32_t*>(C),
+                                                             resident, gst);
+            if (zeroed < 0) return zeroed;
+            for (int t = zeroed; t < 3; ++t) {      // the zeroing kernel delays as much as a tick
                 const int r = launch_tick(w.tick, gst);
                 if (r != LRQMM_OK) return r;
             }
             prof_mark(slot, 9, gst);
-            const int r = launch_int8_gemm(M, N, K, w.Aq, w.BqT, nullptr, nullptr, nullptr, nullptr, 0, GemmOut{nullptr, N, 1.0f, 0.0f},
-                                           reinterpret_cast<int32_t*>(C), gst);
+            const int r = launch_int8_gemm_sums(M, N, K, w.Aq, w.BqT, reinterpret_cast<int32_t*>(C), resident, gst);
             prof_mark(slot, 10, gst);
             if (r != LRQMM_OK) return r;
             return hipEventRecord(g_side.gdone, gst) == hipSuccess ? LRQMM_OK : LRQMM_ERR_HIP;

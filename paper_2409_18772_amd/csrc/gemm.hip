@@ -210,7 +210,11 @@ __global__ __launch_bounds__(256) void int8_gemm_kernel(int M, int N, int K,
 #define BLOADS (256 / BROWS)    // staged 16-byte chunks per thread and operand
 // FULL: M, N multiples of 256 and K a multiple of the tile depth -- operand loads carry no guard at all, so
 // nothing consumes a loaded register before it is written to LDS two iterations later.
-template <bool VEC, bool COMP, bool WCINT, bool FULL>
+// SPLITK (raw sums only, FULL shapes): workgroups [0, full_tiles) compute one tile each as usual;
+// the remaining ntiles - full_tiles tiles are cut into `slices` ranges of K, one workgroup per
+// (tile, range), which add their int32 partial sums to C with atomics (integer addition: exact
+// and independent of the order).  Those tiles of C must be zero when the kernel starts.
+template <bool VEC, bool COMP, bool WCINT, bool FULL, bool SPLITK = false>
 __global__ __launch_bounds__(512, 1) void int8_gemm256_kernel(int M, int N, int K,
                                                               const int8_t* __restrict__ Aq,
                                                               const int8_t* __restrict__ BqT,
@@ -220,11 +224,22 @@ __global__ __launch_bounds__(512, 1) void int8_gemm256_kernel(int M, int N, int 
                                                               const float* __restrict__ Rp, int R2P,
                                                               GemmOut out,
                                                               int32_t* __restrict__ Cint, int tiles_n,
-                                                              int ntiles) {
+                                                              int ntiles, int full_tiles, int slices) {
     float* __restrict__ C = out.C;
     __shared__ __align__(16) int8_t As[2][BTM * BSTRIDE];
     __shared__ __align__(16) int8_t Bs[2][BTN * BSTRIDE];
-    const int tile = xcd_tile(blockIdx.x, tiles_n, ntiles);
+    int wg = blockIdx.x, kt0 = 0, nk = (K + BBK - 1) / BBK;
+    bool partial = false;
+    if constexpr (SPLITK) {
+        if (wg >= full_tiles) {
+            const int e = wg - full_tiles, lt = e / slices, sl = e - lt * slices;
+            wg = full_tiles + lt;
+            kt0 = (int)((long long)sl * nk / slices);
+            nk = (int)((long long)(sl + 1) * nk / slices) - kt0;
+            partial = true;
+        }
+    }
+    const int tile = xcd_tile(wg, tiles_n, ntiles);
     const int m0 = (tile / tiles_n) * BTM, n0 = (tile % tiles_n) * BTN;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int wm = wave >> 1, wn = wave & 1;
@@ -290,17 +305,16 @@ __global__ __launch_bounds__(512, 1) void int8_gemm256_kernel(int M, int N, int 
                     acc[mt][nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[mt], bf[nt], acc[mt][nt], 0, 0, 0);
         }
     };
-    const int nk = (K + BBK - 1) / BBK;
-    LRQ_GLOAD(r0, 0);
-    LRQ_GLOAD(r1, BBK);
-    LRQ_GLOAD(r2, 2 * BBK);
+    LRQ_GLOAD(r0, kt0 * BBK);
+    LRQ_GLOAD(r1, (kt0 + 1) * BBK);
+    LRQ_GLOAD(r2, (kt0 + 2) * BBK);
     LRQ_SSTORE(r0, 0);
     __syncthreads();
     // iteration i: set i%3 is free -> load tile i+3; compute tile i; publish tile i+1
 #define LRQ_GEMM_STEP(J, SCUR, SNEXT)                  \
     if (kt + J < nk) {                                 \
         const int i = kt + J;                          \
-        LRQ_GLOAD(SCUR, (i + 3) * BBK);             \
+        LRQ_GLOAD(SCUR, (kt0 + i + 3) * BBK);       \
         compute(i & 1);                                \
         if (i + 1 < nk) { LRQ_SSTORE(SNEXT, (i + 1) & 1); } \
         __syncthreads();                               \
@@ -340,7 +354,10 @@ __global__ __launch_bounds__(512, 1) void int8_gemm256_kernel(int M, int N, int 
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = rbase + 8 * (v >> 2) + 4 * lh + (v & 3);
-                if (WCINT && row < M && col_ok) Cint[(size_t)row * N + col] = acc[mt][nt][v];
+                if (WCINT && row < M && col_ok) {
+                    if (SPLITK && partial) atomicAdd(&Cint[(size_t)row * N + col], acc[mt][nt][v]);
+                    else Cint[(size_t)row * N + col] = acc[mt][nt][v];
+                }
                 f[v] = ((float)acc[mt][nt][v] * sa[v]) * sb;
             }
             if (COMP) {
@@ -772,10 +789,10 @@ static void dispatch_gemm256(bool comp, bool wcint, dim3 grid, hipStream_t st, i
     do {                                                                                                     \
         if (full)                                                                                            \
             hipLaunchKernelGGL((int8_gemm256_kernel<VEC, COMP, WC, VEC>), grid, dim3(512), 0, st, M, N, K, Aq, \
-                               BqT, sA, sB, Lp, Rp, R2P, C, Cint, tiles_n, ntiles);                           \
+                               BqT, sA, sB, Lp, Rp, R2P, C, Cint, tiles_n, ntiles, ntiles, 1);                \
         else                                                                                                 \
             hipLaunchKernelGGL((int8_gemm256_kernel<VEC, COMP, WC, false>), grid, dim3(512), 0, st, M, N, K,  \
-                               Aq, BqT, sA, sB, Lp, Rp, R2P, C, Cint, tiles_n, ntiles);                       \
+                               Aq, BqT, sA, sB, Lp, Rp, R2P, C, Cint, tiles_n, ntiles, ntiles, 1);            \
     } while (0)
     if (comp) {
         if (wcint) LRQ_GEMM(true, true); else LRQ_GEMM(true, false);
@@ -798,6 +815,58 @@ static void dispatch_gemm(bool comp, bool wcint, dim3 grid, hipStream_t st, int 
         if (wcint) LRQ_GEMM(false, true); else LRQ_GEMM(false, false);
     }
 #undef LRQ_GEMM
+}
+
+// Zeroes the tiles [first, ntiles) (in xcd_tile order) of an int32 matrix with row stride N.
+__global__ __launch_bounds__(256) void zero_tiles_kernel(int32_t* __restrict__ Cint, int N, int tiles_n, int ntiles,
+                                                         int first) {
+    const int tile = xcd_tile(first + blockIdx.y, tiles_n, ntiles);
+    const int m0 = (tile / tiles_n) * BTM, n0 = (tile % tiles_n) * BTN;
+    const int e = blockIdx.x * 256 + threadIdx.x;            // 16-byte group of the tile
+    const int row = e / (BTN / 4), c4 = e % (BTN / 4);
+    *reinterpret_cast<int4*>(Cint + (size_t)(m0 + row) * N + n0 + 4 * c4) = make_int4(0, 0, 0, 0);
+}
+
+namespace {
+struct SumsPlan { int tiles_n, ntiles, left, slices; };
+// Which tiles of the raw-sum product are cut along K when only `resident` CUs are free.
+SumsPlan plan_sums(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, int resident) {
+    const bool vec = (K % 16 == 0) && (((uintptr_t)Aq | (uintptr_t)BqT) & 15) == 0;
+    const bool full = vec && int8_gemm_large_tiles(M, N) && M % BTM == 0 && N % BTN == 0 && K % BBK == 0 && K >= BBK;
+    SumsPlan p = {N / BTN, (M / BTM) * (N / BTN), 0, 1};
+    // (with many rounds the last one matters little, and the free CUs change along the way)
+    if (full && resident > 0 && p.ntiles > resident && p.ntiles < 4 * resident) {
+        p.left = p.ntiles % resident;
+        // as many ranges as fill the chip once, each at least four K-tiles deep
+        if (p.left > 0) p.slices = max(1, min(K / BBK / 4, resident / p.left));
+    }
+    if (p.slices < 2) p.left = 0;
+    return p;
+}
+}  // namespace
+
+int launch_int8_gemm_sums_prepare(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, int32_t* Cint,
+                                  int resident, hipStream_t st) {
+    const SumsPlan p = plan_sums(M, N, K, Aq, BqT, resident);
+    if (p.left == 0) return 0;
+    hipLaunchKernelGGL(zero_tiles_kernel, dim3(BTM * BTN / 4 / 256, p.left), dim3(256), 0, st, Cint, N, p.tiles_n,
+                       p.ntiles, p.ntiles - p.left);
+    LRQ_CHECK_LAUNCH();
+    return 1;
+}
+
+int launch_int8_gemm_sums(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, int32_t* Cint, int resident,
+                          hipStream_t st) {
+    const SumsPlan p = plan_sums(M, N, K, Aq, BqT, resident);
+    if (p.left == 0)
+        return launch_int8_gemm(M, N, K, Aq, BqT, nullptr, nullptr, nullptr, nullptr, 0, GemmOut{nullptr, N, 1.0f, 0.0f},
+                                Cint, st);
+    const int full_tiles = p.ntiles - p.left;
+    hipLaunchKernelGGL((int8_gemm256_kernel<true, false, true, true, true>), dim3(full_tiles + p.left * p.slices),
+                       dim3(512), 0, st, M, N, K, Aq, BqT, nullptr, nullptr, nullptr, nullptr, 0,
+                       GemmOut{nullptr, N, 1.0f, 0.0f}, Cint, p.tiles_n, p.ntiles, full_tiles, p.slices);
+    LRQ_CHECK_LAUNCH();
+    return LRQMM_OK;
 }
 
 bool int8_gemm_large_tiles(int M, int N) {

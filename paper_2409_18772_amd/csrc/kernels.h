@@ -108,6 +108,17 @@ struct GemmOut {
 int launch_int8_gemm(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, const float* sA,
                      const float* sB, const float* Lp, const float* Rp, int R2P, GemmOut C,
                      int32_t* Cint, hipStream_t st);
+// The raw int32 sums alone (C_int, row stride N), for a chip on which only `resident` CUs are
+// free (0: unknown): with one 256x256 tile per workgroup, the tiles beyond a whole number of
+// rounds over those CUs would cost a full extra round; they are cut along K instead and summed
+// with integer atomics (bit-identical result).  Falls back to launch_int8_gemm otherwise.
+// launch_int8_gemm_sums_prepare, with the same arguments and earlier on the same stream, zeroes
+// the tiles that will be summed; it returns 1 if it launched a kernel, 0 if there was nothing to
+// do, a negative status on error.
+int launch_int8_gemm_sums_prepare(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, int32_t* Cint,
+                                  int resident, hipStream_t st);
+int launch_int8_gemm_sums(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, int32_t* Cint, int resident,
+                          hipStream_t st);
 // True when launch_int8_gemm uses the large-tile kernel, which accepts C == null together with
 // Cint != null (raw int32 sums only; sA, sB are then not read).
 bool int8_gemm_large_tiles(int M, int N);

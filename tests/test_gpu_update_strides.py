@@ -180,3 +180,25 @@ def test_bad_strides_are_rejected():
     assert lib.lrqmm_matmul_ex(*args(8, 8, 8, 2)) == -1
     assert lib.lrqmm_matmul_ex(*args(8, 8, 8, 0)) == 0
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("K", [512, 2112])
+def test_early_product_equals_fused_store_phase_bitwise(K):
+    """256 tiles on a chip whose two SVD workgroups leave 254 CUs: the early integer product cuts its last
+    tiles along K (evenly at K = 512, unevenly at 33 K-tiles) and sums them with integer atomics.  The dense
+    call takes that schedule, the call into a window of a wider array the fused kernel: same bits."""
+    import torch
+    import paper_2409_18772_amd as L
+    M = N = 4096
+    A = wl.random_matrix("normal", M, K, seed=31)
+    B = wl.random_matrix("normal", K, N, seed=32)
+    dA, dB = to_dev(A), to_dev(B)
+    say("early vs fused", K)
+    D1 = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    L.lrqmm_matmul_ex(dA, dB, D1, 4, 8, 4, 1, seed=5)
+    big, D2 = window(np.zeros((M, N), dtype=np.float32), 4)
+    L.lrqmm_matmul_ex(dA, dB, D2, 4, 8, 4, 1, seed=5)
+    assert torch.equal(D1, D2)
+    # twice in a row on the same output: the zeroing of the summed tiles is part of every call
+    L.lrqmm_matmul_ex(dA, dB, D1, 4, 8, 4, 1, seed=5)
+    assert torch.equal(D1, D2)
