@@ -84,6 +84,7 @@ struct MatmulWs {
     int8_t *Aq, *BqT;
     float *amaxA, *amaxB, *U, *Sig, *Vt, *W, *Gam, *Zt;
     uint32_t* tick;
+    int32_t* parts;                   // partial sums of the early integer product's K ranges
     void *sub, *subA, *subB;          // gemm scratch aliases the two rsvd regions
     size_t sub_bytes, subA_bytes, subB_bytes;
 };
@@ -95,6 +96,9 @@ size_t carve_matmul(Arena& a, int M, int N, int K, int rank, int oversample, Mat
     t.amaxA = a.take<float>(M);
     t.amaxB = a.take<float>(N);
     t.tick = a.take<uint32_t>(64);
+    t.parts = nullptr;
+    if (rank > 0 && int8_gemm_sums_scratch_bytes(M, N, K) > 0)
+        t.parts = a.take<int32_t>(int8_gemm_sums_scratch_bytes(M, N, K) / sizeof(int32_t));
     if (rank > 0) {
         t.U = a.take<float>((size_t)M * rank);
         t.Sig = a.take<float>(rank);
@@ -510,16 +514,15 @@ int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int
                 if (hipStreamWaitEvent(gst, e, 0) != hipSuccess) return LRQMM_ERR_HIP;
             // the two small-SVD workgroups hold a CU each while the product runs
             const int resident = g_side.cus - 2;
-            const int zeroed = launch_int8_gemm_sums_prepare(M, N, K, w.Aq, w.BqT, reinterpret_cast<int32_t*>(C),
-                                                             resident, gst);
-            if (zeroed < 0) return zeroed;
-            for (int t = zeroed; t < 3; ++t) {      // the zeroing kernel delays as much as a tick
+            for (int t = 0; t < 3; ++t) {
                 const int r = launch_tick(w.tick, gst);
                 if (r != LRQMM_OK) return r;
             }
             prof_mark(slot, 9, gst);
-            const int r = launch_int8_gemm_sums(M, N, K, w.Aq, w.BqT, reinterpret_cast<int32_t*>(C), resident, gst);
+            int r = launch_int8_gemm_sums(M, N, K, w.Aq, w.BqT, reinterpret_cast<int32_t*>(C), resident, w.parts, gst);
             prof_mark(slot, 10, gst);
+            if (r != LRQMM_OK) return r;
+            r = launch_int8_gemm_sums_finish(M, N, K, w.Aq, w.BqT, reinterpret_cast<int32_t*>(C), resident, w.parts, gst);
             if (r != LRQMM_OK) return r;
             return hipEventRecord(g_side.gdone, gst) == hipSuccess ? LRQMM_OK : LRQMM_ERR_HIP;
         };

@@ -212,8 +212,8 @@ __global__ __launch_bounds__(256) void int8_gemm_kernel(int M, int N, int K,
 // nothing consumes a loaded register before it is written to LDS two iterations later.
 // SPLITK (raw sums only, FULL shapes): workgroups [0, full_tiles) compute one tile each as usual;
 // the remaining ntiles - full_tiles tiles are cut into `slices` ranges of K, one workgroup per
-// (tile, range), which add their int32 partial sums to C with atomics (integer addition: exact
-// and independent of the order).  Those tiles of C must be zero when the kernel starts.
+// (tile, range), which leave their int32 partial sums in `part` ([tile][range][256][256]) for
+// sum_tile_slices_kernel (integer addition: exact whatever the cut).
 template <bool VEC, bool COMP, bool WCINT, bool FULL, bool SPLITK = false>
 __global__ __launch_bounds__(512, 1) void int8_gemm256_kernel(int M, int N, int K,
                                                               const int8_t* __restrict__ Aq,
@@ -224,7 +224,8 @@ __global__ __launch_bounds__(512, 1) void int8_gemm256_kernel(int M, int N, int 
                                                               const float* __restrict__ Rp, int R2P,
                                                               GemmOut out,
                                                               int32_t* __restrict__ Cint, int tiles_n,
-                                                              int ntiles, int full_tiles, int slices) {
+                                                              int ntiles, int full_tiles, int slices,
+                                                              int32_t* __restrict__ part) {
     float* __restrict__ C = out.C;
     __shared__ __align__(16) int8_t As[2][BTM * BSTRIDE];
     __shared__ __align__(16) int8_t Bs[2][BTN * BSTRIDE];
@@ -234,6 +235,7 @@ __global__ __launch_bounds__(512, 1) void int8_gemm256_kernel(int M, int N, int 
         if (wg >= full_tiles) {
             const int e = wg - full_tiles, lt = e / slices, sl = e - lt * slices;
             wg = full_tiles + lt;
+            part += (size_t)e * (BTM * BTN);
             kt0 = (int)((long long)sl * nk / slices);
             nk = (int)((long long)(sl + 1) * nk / slices) - kt0;
             partial = true;
@@ -355,7 +357,7 @@ __global__ __launch_bounds__(512, 1) void int8_gemm256_kernel(int M, int N, int 
             for (int v = 0; v < 16; ++v) {
                 const int row = rbase + 8 * (v >> 2) + 4 * lh + (v & 3);
                 if (WCINT && row < M && col_ok) {
-                    if (SPLITK && partial) atomicAdd(&Cint[(size_t)row * N + col], acc[mt][nt][v]);
+                    if (SPLITK && partial) part[(row - m0) * BTN + (col - n0)] = acc[mt][nt][v];
                     else Cint[(size_t)row * N + col] = acc[mt][nt][v];
                 }
                 f[v] = ((float)acc[mt][nt][v] * sa[v]) * sb;
@@ -789,10 +791,10 @@ static void dispatch_gemm256(bool comp, bool wcint, dim3 grid, hipStream_t st, i
     do {                                                                                                     \
         if (full)                                                                                            \
             hipLaunchKernelGGL((int8_gemm256_kernel<VEC, COMP, WC, VEC>), grid, dim3(512), 0, st, M, N, K, Aq, \
-                               BqT, sA, sB, Lp, Rp, R2P, C, Cint, tiles_n, ntiles, ntiles, 1);                \
+                               BqT, sA, sB, Lp, Rp, R2P, C, Cint, tiles_n, ntiles, ntiles, 1, nullptr);       \
         else                                                                                                 \
             hipLaunchKernelGGL((int8_gemm256_kernel<VEC, COMP, WC, false>), grid, dim3(512), 0, st, M, N, K,  \
-                               Aq, BqT, sA, sB, Lp, Rp, R2P, C, Cint, tiles_n, ntiles, ntiles, 1);            \
+                               Aq, BqT, sA, sB, Lp, Rp, R2P, C, Cint, tiles_n, ntiles, ntiles, 1, nullptr);   \
     } while (0)
     if (comp) {
         if (wcint) LRQ_GEMM(true, true); else LRQ_GEMM(true, false);
@@ -817,14 +819,24 @@ static void dispatch_gemm(bool comp, bool wcint, dim3 grid, hipStream_t st, int 
 #undef LRQ_GEMM
 }
 
-// Zeroes the tiles [first, ntiles) (in xcd_tile order) of an int32 matrix with row stride N.
-__global__ __launch_bounds__(256) void zero_tiles_kernel(int32_t* __restrict__ Cint, int N, int tiles_n, int ntiles,
-                                                         int first) {
+// Tiles [first, ntiles) (in xcd_tile order) of C_int <- sum over the K ranges of their partial sums.
+__global__ __launch_bounds__(256) void sum_tile_slices_kernel(int32_t* __restrict__ Cint, int N, int tiles_n, int ntiles,
+                                                              int first, const int32_t* __restrict__ part, int slices) {
     const int tile = xcd_tile(first + blockIdx.y, tiles_n, ntiles);
     const int m0 = (tile / tiles_n) * BTM, n0 = (tile % tiles_n) * BTN;
     const int e = blockIdx.x * 256 + threadIdx.x;            // 16-byte group of the tile
     const int row = e / (BTN / 4), c4 = e % (BTN / 4);
-    *reinterpret_cast<int4*>(Cint + (size_t)(m0 + row) * N + n0 + 4 * c4) = make_int4(0, 0, 0, 0);
+    const int4* src = reinterpret_cast<const int4*>(part + (size_t)blockIdx.y * slices * (BTM * BTN)) + e;
+    int4 acc = make_int4(0, 0, 0, 0);
+    for (int s0 = 0; s0 < slices; s0 += 8) {                 // eight loads in flight
+        int4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = src[(size_t)min(s0 + u, slices - 1) * (BTM * BTN / 4)];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (s0 + u < slices) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
+    }
+    *reinterpret_cast<int4*>(Cint + (size_t)(m0 + row) * N + n0 + 4 * c4) = acc;
 }
 
 namespace {
@@ -838,33 +850,38 @@ SumsPlan plan_sums(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, int
     if (full && resident > 0 && p.ntiles > resident && p.ntiles < 4 * resident) {
         p.left = p.ntiles % resident;
         // as many ranges as fill the chip once, each at least four K-tiles deep
-        if (p.left > 0) p.slices = max(1, min(K / BBK / 4, resident / p.left));
+        if (p.left > 0) p.slices = max(1, min(min(K / BBK / 4, resident / p.left), LRQ_SUMS_MAX_PARTS / p.left));
     }
     if (p.slices < 2) p.left = 0;
     return p;
 }
 }  // namespace
 
-int launch_int8_gemm_sums_prepare(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, int32_t* Cint,
-                                  int resident, hipStream_t st) {
-    const SumsPlan p = plan_sums(M, N, K, Aq, BqT, resident);
-    if (p.left == 0) return 0;
-    hipLaunchKernelGGL(zero_tiles_kernel, dim3(BTM * BTN / 4 / 256, p.left), dim3(256), 0, st, Cint, N, p.tiles_n,
-                       p.ntiles, p.ntiles - p.left);
-    LRQ_CHECK_LAUNCH();
-    return 1;
+size_t int8_gemm_sums_scratch_bytes(int M, int N, int K) {
+    const bool shape = int8_gemm_large_tiles(M, N) && M % BTM == 0 && N % BTN == 0 && K % BBK == 0 && K >= 8 * BBK;
+    return shape ? (size_t)LRQ_SUMS_MAX_PARTS * BTM * BTN * sizeof(int32_t) : 0;
 }
 
 int launch_int8_gemm_sums(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, int32_t* Cint, int resident,
-                          hipStream_t st) {
-    const SumsPlan p = plan_sums(M, N, K, Aq, BqT, resident);
+                          int32_t* part, hipStream_t st) {
+    const SumsPlan p = part ? plan_sums(M, N, K, Aq, BqT, resident) : SumsPlan{0, 0, 0, 1};
     if (p.left == 0)
         return launch_int8_gemm(M, N, K, Aq, BqT, nullptr, nullptr, nullptr, nullptr, 0, GemmOut{nullptr, N, 1.0f, 0.0f},
                                 Cint, st);
     const int full_tiles = p.ntiles - p.left;
     hipLaunchKernelGGL((int8_gemm256_kernel<true, false, true, true, true>), dim3(full_tiles + p.left * p.slices),
                        dim3(512), 0, st, M, N, K, Aq, BqT, nullptr, nullptr, nullptr, nullptr, 0,
-                       GemmOut{nullptr, N, 1.0f, 0.0f}, Cint, p.tiles_n, p.ntiles, full_tiles, p.slices);
+                       GemmOut{nullptr, N, 1.0f, 0.0f}, Cint, p.tiles_n, p.ntiles, full_tiles, p.slices, part);
+    LRQ_CHECK_LAUNCH();
+    return LRQMM_OK;
+}
+
+int launch_int8_gemm_sums_finish(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, int32_t* Cint, int resident,
+                                 const int32_t* part, hipStream_t st) {
+    const SumsPlan p = part ? plan_sums(M, N, K, Aq, BqT, resident) : SumsPlan{0, 0, 0, 1};
+    if (p.left == 0) return LRQMM_OK;
+    hipLaunchKernelGGL(sum_tile_slices_kernel, dim3(BTM * BTN / 4 / 256, p.left), dim3(256), 0, st, Cint, N, p.tiles_n,
+                       p.ntiles, p.ntiles - p.left, part, p.slices);
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }

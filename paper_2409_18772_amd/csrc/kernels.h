@@ -110,15 +110,16 @@ int launch_int8_gemm(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, c
                      int32_t* Cint, hipStream_t st);
 // The raw int32 sums alone (C_int, row stride N), for a chip on which only `resident` CUs are
 // free (0: unknown): with one 256x256 tile per workgroup, the tiles beyond a whole number of
-// rounds over those CUs would cost a full extra round; they are cut along K instead and summed
-// with integer atomics (bit-identical result).  Falls back to launch_int8_gemm otherwise.
-// launch_int8_gemm_sums_prepare, with the same arguments and earlier on the same stream, zeroes
-// the tiles that will be summed; it returns 1 if it launched a kernel, 0 if there was nothing to
-// do, a negative status on error.
-int launch_int8_gemm_sums_prepare(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, int32_t* Cint,
-                                  int resident, hipStream_t st);
+// rounds over those CUs would cost a full extra round; they are cut along K instead, one
+// workgroup per range, which leave partial sums in `part` (int8_gemm_sums_scratch_bytes; null:
+// no cut), and launch_int8_gemm_sums_finish (same arguments, later on the same stream) adds
+// them up into C_int.  Integer sums: the result is bit-identical to the plain kernel's.
+#define LRQ_SUMS_MAX_PARTS 64       // (tile, range) pairs at most
+size_t int8_gemm_sums_scratch_bytes(int M, int N, int K);
 int launch_int8_gemm_sums(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, int32_t* Cint, int resident,
-                          hipStream_t st);
+                          int32_t* part, hipStream_t st);
+int launch_int8_gemm_sums_finish(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, int32_t* Cint, int resident,
+                                 const int32_t* part, hipStream_t st);
 // True when launch_int8_gemm uses the large-tile kernel, which accepts C == null together with
 // Cint != null (raw int32 sums only; sA, sB are then not read).
 bool int8_gemm_large_tiles(int M, int N);
