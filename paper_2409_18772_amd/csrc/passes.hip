@@ -161,18 +161,33 @@ typedef __bf16 v8bf16 __attribute__((ext_vector_type(8)));
 struct Planes3 {
     v8bf16 p1, p2, p3;
 };
+typedef __bf16 v2bf16 __attribute__((ext_vector_type(2)));
+typedef float v2f32 __attribute__((ext_vector_type(2)));
+// Two values per conversion instruction; a bfloat16 is the upper half of its float32, so the
+// converted pair is widened again with a shift and a mask.
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector((v2f32){a, b}, v2bf16));
+}
 __device__ __forceinline__ Planes3 split_planes(const float (&r)[8]) {
-    Planes3 o;
+    uint32_t w1[4], w2[4], w3[4];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const __bf16 h = (__bf16)r[e];
-        const float rem = r[e] - (float)h;          // exact
-        const __bf16 m = (__bf16)rem;
-        const float rem2 = rem - (float)m;          // exact
-        o.p1[e] = h;
-        o.p2[e] = m;
-        o.p3[e] = (__bf16)rem2;
+    for (int e = 0; e < 4; ++e) {
+        const float a = r[2 * e], b = r[2 * e + 1];
+        const uint32_t h = pack_bf16x2(a, b);
+        const float ra = a - __uint_as_float(h << 16);              // exact
+        const float rb = b - __uint_as_float(h & 0xffff0000u);
+        const uint32_t m = pack_bf16x2(ra, rb);
+        const float ra2 = ra - __uint_as_float(m << 16);            // exact
+        const float rb2 = rb - __uint_as_float(m & 0xffff0000u);
+        w1[e] = h;
+        w2[e] = m;
+        w3[e] = pack_bf16x2(ra2, rb2);
     }
+    typedef uint32_t v4u32 __attribute__((ext_vector_type(4)));
+    Planes3 o;
+    o.p1 = __builtin_bit_cast(v8bf16, (v4u32){w1[0], w1[1], w1[2], w1[3]});
+    o.p2 = __builtin_bit_cast(v8bf16, (v4u32){w2[0], w2[1], w2[2], w2[3]});
+    o.p3 = __builtin_bit_cast(v8bf16, (v4u32){w3[0], w3[1], w3[2], w3[3]});
     return o;
 }
 // acc[m][n] += a[m] . b[n] for NA x NB independent accumulators: the six plane products are
@@ -201,6 +216,23 @@ struct WStageBf16 {
     static constexpr int UNITS = LP * (KC / 8);
     static constexpr int NU = (UNITS + 255) / 256;
     float v[NU][8];
+    int off[NU];        // this thread's units: offset of their first element inside a chunk of W
+    __device__ __forceinline__ void init() {
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+            const int unit = min((int)threadIdx.x + 256 * u, UNITS - 1);
+            const int n = unit % LP, grp = unit / LP;
+            off[u] = (32 * (grp >> 2) + 4 * (grp & 3)) * LP + n;
+        }
+    }
+    // whole chunk inside the reduction range: no clamps, constant offsets from one base
+    __device__ __forceinline__ void load_full(const float* __restrict__ W, int k0) {
+        const float* p = W + (size_t)k0 * LP;
+#pragma unroll
+        for (int u = 0; u < NU; ++u)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[u][e] = p[off[u] + ((e & 3) + 16 * (e >> 2)) * LP];
+    }
     __device__ __forceinline__ void load(const float* __restrict__ W, int k0, int kend) {
 #pragma unroll
         for (int u = 0; u < NU; ++u) {
@@ -231,7 +263,9 @@ struct WStageBf16 {
     }
 };
 
-template <int NT, int AXIS, bool VEC>
+// FULLK: the vector path with cols and the split length multiples of the chunk depth, so no
+// load in the loop needs a guard along the reduction (rows past the end read row 0 and are not stored).
+template <int NT, int AXIS, bool VEC, bool FULLK = false>
 __global__ __launch_bounds__(256) void resid_mul_n_bf16_kernel(
     const float* __restrict__ X, int ldx, int rows, int cols, const float* __restrict__ lam,
     const float* __restrict__ sc, QuantParams q, const float* __restrict__ W, int chunk,
@@ -262,7 +296,16 @@ __global__ __launch_bounds__(256) void resid_mul_n_bf16_kernel(
     float4 xr[KS];
     float scale_reg = 0.f;     // this thread's element of the chunk's lambda (t < KC) or step vector
     WS ws;
+    if (FULLK) ws.init();
+    const float* xq = xp + 4 * g;
+    const float* scq = ((threadIdx.x & KC) == 0 ? lam : sc) + (threadIdx.x & (KC - 1));
     auto load_x = [&](int k0) {
+        if (FULLK) {
+#pragma unroll
+            for (int j = 0; j < KS; ++j) xr[j] = *reinterpret_cast<const float4*>(xq + k0 + 16 * j);
+            if (AXIS == 1) scale_reg = scq[k0];
+            return;
+        }
 #pragma unroll
         for (int j = 0; j < KS; ++j) xr[j] = load4f<VEC>(xp, k0 + 16 * j + 4 * g, ke, row_ok);
         if (AXIS == 1) {
@@ -272,9 +315,13 @@ __global__ __launch_bounds__(256) void resid_mul_n_bf16_kernel(
             scale_reg = (k0 + t < ke) ? v : 0.f;
         }
     };
+    auto load_w = [&](int k0) {
+        if (FULLK) ws.load_full(W, k0);
+        else ws.load(W, k0, ke);
+    };
     if (kb < ke) {
         load_x(kb);
-        ws.load(W, kb, ke);
+        load_w(kb);
     }
     int buf = 0;
     for (int k0 = kb; k0 < ke; k0 += KC, buf ^= 1) {
@@ -305,7 +352,7 @@ __global__ __launch_bounds__(256) void resid_mul_n_bf16_kernel(
         }
         if (k0 + KC < ke) {      // next chunk's loads fly during this chunk's MFMAs
             load_x(k0 + KC);
-            ws.load(W, k0 + KC, ke);
+            load_w(k0 + KC);
         }
         const uint16_t* wb = wl[buf];
 #pragma unroll
@@ -815,6 +862,14 @@ template <int NT>
 static void dispatch_n(int axis, bool vec, dim3 grid, hipStream_t st, const float* X, int ldx, int rows, int cols,
                        const float* lam, const float* s, QuantParams q, const float* W, int chunk,
                        float* partial) {
+    if constexpr (NT > 1) {
+        // every chunk of every split is whole: the guard-free instantiation
+        if (vec && cols % 64 == 0 && chunk % 64 == 0) {
+            if (axis == 0) hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 0, true, true>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+            else           hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 1, true, true>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+            return;
+        }
+    }
     if (axis == 0) {
         if (vec) hipLaunchKernelGGL((PassKernels<NT, 0, true>::n), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
         else     hipLaunchKernelGGL((PassKernels<NT, 0, false>::n), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
