@@ -51,6 +51,15 @@ __device__ __forceinline__ float quant_code(float x, float lam, const QuantParam
     return fminf(fmaxf(c, q.lo), q.hi);
 }
 
+// The same residual with the rounding mode fixed at compile time (callers branch once on
+// q.round_mode around a block of these instead of selecting per element).
+template <int ROUND_MODE>
+__device__ __forceinline__ float quant_residual_m(float x, float lam, float s, const QuantParams& q) {
+    const float t = x * lam;
+    const float c = ROUND_MODE == 0 ? floorf(t) : rintf(t);
+    return fmaf(-fminf(fmaxf(c, q.lo), q.hi), s, x);
+}
+
 // residual x - code * s with a single rounding.
 __device__ __forceinline__ float quant_residual(float x, float lam, float s, const QuantParams& q) {
     float c = quant_code(x, lam, q);

@@ -11,6 +11,7 @@
 //
 // MFMA 16x16x4 f32 operand layout (lane l): A[i = l%16][k = l/16],
 // B[k = l/16][j = l%16], D[i = 4*(l/16)+v][j = l%16] for v = 0..3.
+#include <type_traits>
 #include "kernels.h"
 
 #define KCHUNK 128   // reduction elements staged per LDS step in the N-type kernels
@@ -329,27 +330,32 @@ __global__ __launch_bounds__(256) void resid_mul_n_bf16_kernel(
         if (AXIS == 1 && threadIdx.x < 2 * KC) sl[buf][threadIdx.x] = scale_reg;
         __syncthreads();             // wl[buf], sl[buf] complete; the other buffers no longer read
         Planes3 ap[KC / 32][1];
+        auto residuals = [&](auto mode) {       // one uniform branch on the rounding mode per chunk
+            constexpr int RM = decltype(mode)::value;
 #pragma unroll
-        for (int jj = 0; jj < KC / 32; ++jj) {
-            float res[8];
+            for (int jj = 0; jj < KC / 32; ++jj) {
+                float res[8];
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int j = 2 * jj + h;
-                float4 l4, s4;
-                if (AXIS == 0) {
-                    l4 = make_float4(lam_r, lam_r, lam_r, lam_r);
-                    s4 = make_float4(s_r, s_r, s_r, s_r);
-                } else {
-                    l4 = *reinterpret_cast<const float4*>(&sl[buf][16 * j + 4 * g]);
-                    s4 = *reinterpret_cast<const float4*>(&sl[buf][KC + 16 * j + 4 * g]);
+                for (int h = 0; h < 2; ++h) {
+                    const int j = 2 * jj + h;
+                    float4 l4, s4;
+                    if (AXIS == 0) {
+                        l4 = make_float4(lam_r, lam_r, lam_r, lam_r);
+                        s4 = make_float4(s_r, s_r, s_r, s_r);
+                    } else {
+                        l4 = *reinterpret_cast<const float4*>(&sl[buf][16 * j + 4 * g]);
+                        s4 = *reinterpret_cast<const float4*>(&sl[buf][KC + 16 * j + 4 * g]);
+                    }
+                    res[4 * h + 0] = quant_residual_m<RM>(xr[j].x, l4.x, s4.x, q);
+                    res[4 * h + 1] = quant_residual_m<RM>(xr[j].y, l4.y, s4.y, q);
+                    res[4 * h + 2] = quant_residual_m<RM>(xr[j].z, l4.z, s4.z, q);
+                    res[4 * h + 3] = quant_residual_m<RM>(xr[j].w, l4.w, s4.w, q);
                 }
-                res[4 * h + 0] = quant_residual(xr[j].x, l4.x, s4.x, q);
-                res[4 * h + 1] = quant_residual(xr[j].y, l4.y, s4.y, q);
-                res[4 * h + 2] = quant_residual(xr[j].z, l4.z, s4.z, q);
-                res[4 * h + 3] = quant_residual(xr[j].w, l4.w, s4.w, q);
+                ap[jj][0] = split_planes(res);
             }
-            ap[jj][0] = split_planes(res);
-        }
+        };
+        if (q.round_mode == 0) residuals(std::integral_constant<int, 0>{});
+        else residuals(std::integral_constant<int, 1>{});
         if (k0 + KC < ke) {      // next chunk's loads fly during this chunk's MFMAs
             load_x(k0 + KC);
             load_w(k0 + KC);
@@ -712,8 +718,11 @@ __global__ __launch_bounds__(256) void resid_mul_t_kernel(
 // which are its 8 k-slots; both operands come straight from global memory in that order (a
 // float4 of X and NT floats of W per row), so no LDS is needed before the final merge.
 // (two workgroups per CU up to l = 64: the register cap costs no spills there and hides the loads better)
-template <int NT, int AXIS, bool VEC>
-__global__ __launch_bounds__(256, NT <= 4 ? 2 : 1) void resid_mul_t_bf16_kernel(
+// FULLT: the vector path with whole column strips and a split length that is a multiple of the
+// 128 rows a workgroup takes per step: no load needs a guard, and the row part of every address
+// is wave-uniform (scalar registers), the lane part a constant 32-bit offset.
+template <int NT, int AXIS, bool VEC, bool FULLT = false>
+__global__ __launch_bounds__(256, (NT <= 4 || FULLT) ? 2 : 1) void resid_mul_t_bf16_kernel(
     const float* __restrict__ X, int ldx, int rows, int cols, const float* __restrict__ lam,
     const float* __restrict__ sc, QuantParams q, const float* __restrict__ W, int chunk,
     float* __restrict__ partial) {
@@ -764,11 +773,29 @@ __global__ __launch_bounds__(256, NT <= 4 ? 2 : 1) void resid_mul_t_bf16_kernel(
             }
         }
     };
+    const int xoff = g * ldx + kc, woff = g * LP + NT * c;      // lane part of the addresses (FULLT)
+    auto load_group_full = [&](int i0, Group& f) {              // i0 wave-uniform
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float* xrow = X + (size_t)(i0 + 4 * e) * ldx;
+            const float4 xv = *reinterpret_cast<const float4*>(xrow + xoff);
+            f.x[e][0] = xv.x; f.x[e][1] = xv.y; f.x[e][2] = xv.z; f.x[e][3] = xv.w;
+            if (AXIS == 0) {
+                f.lr[e] = (lam + i0 + 4 * e)[g];
+                f.sr[e] = (sc + i0 + 4 * e)[g];
+            }
+            const float* wrow = W + (size_t)(i0 + 4 * e) * LP;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) f.w[e][nt] = wrow[woff + nt];
+        }
+    };
     Group cur, nxt;
-    const int istart = ib + 32 * wave;
-    load_group(istart, cur);
+    const int istart = ib + 32 * (FULLT ? __builtin_amdgcn_readfirstlane(wave) : wave);
+    if (FULLT) load_group_full(istart, cur);
+    else load_group(istart, cur);
     for (int i0 = istart; i0 < ie; i0 += 128) {
-        load_group(i0 + 128, nxt);      // past the end: every row masked
+        if (FULLT) load_group_full(i0 + 128 < ie ? i0 + 128 : i0, nxt);     // last step: re-reads its own rows
+        else load_group(i0 + 128, nxt);      // past the end: every row masked
         Planes3 bp[NT];
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
@@ -843,7 +870,9 @@ PassPlan plan_pass_n(int rows, int cols) {
 PassPlan plan_pass_t(int rows, int cols) {
     PassPlan p;
     int s = pick_splits(ceil_div(cols, 64), rows, 16, MAX_SPLITS_T);     // few column strips: many row chunks
-    p.chunk = ceil_div(ceil_div(rows, s), 16) * 16;
+    // (a multiple of the 128 rows a workgroup takes per step when there are enough rows: guard-free kernel)
+    const int unit = rows >= 512 * s ? 128 : 16;
+    p.chunk = ceil_div(ceil_div(rows, s), unit) * unit;
     p.splits = ceil_div(rows, p.chunk);
     return p;
 }
@@ -883,6 +912,14 @@ template <int NT>
 static void dispatch_t(int axis, bool vec, dim3 grid, hipStream_t st, const float* X, int ldx, int rows, int cols,
                        const float* lam, const float* s, QuantParams q, const float* W, int chunk,
                        float* partial) {
+    if constexpr (NT > 1) {
+        // whole column strips, whole 128-row steps in every split: the guard-free instantiation
+        if (vec && cols % 64 == 0 && chunk % 128 == 0 && rows % 128 == 0) {
+            if (axis == 0) hipLaunchKernelGGL((resid_mul_t_bf16_kernel<NT, 0, true, true>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+            else           hipLaunchKernelGGL((resid_mul_t_bf16_kernel<NT, 1, true, true>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+            return;
+        }
+    }
     if (axis == 0) {
         if (vec) hipLaunchKernelGGL((PassKernels<NT, 0, true>::t), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
         else     hipLaunchKernelGGL((PassKernels<NT, 0, false>::t), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
