@@ -219,7 +219,7 @@ static int rsvd_plan(LaunchList& ops, const float* X, int ldx, const float* amax
                      int round_mode, int rank, int oversample, int power_iters, uint64_t seed,
                      const float* omega_or_null, float* U, float* Sigma, float* Vt, void* workspace,
                      size_t workspace_bytes, hipStream_t st, const std::function<int()>& before_svd = nullptr,
-                     const std::function<int()>& after_svd = nullptr) {
+                     const std::function<int()>& after_svd = nullptr, bool prepared = false) {
     if (rows < 0 || cols < 0 || rank < 1 || oversample < 0 || power_iters < 0 || ldx < cols) return LRQMM_ERR_INVALID_ARG;
     if (axis != LRQMM_AXIS_ROW && axis != LRQMM_AXIS_COL) return LRQMM_ERR_INVALID_ARG;
     if (round_mode != LRQMM_ROUND_FLOOR && round_mode != LRQMM_ROUND_NEAREST) return LRQMM_ERR_INVALID_ARG;
@@ -236,7 +236,9 @@ static int rsvd_plan(LaunchList& ops, const float* X, int ldx, const float* amax
     if (carve_rsvd(a, rows, cols, axis, LP, rank, &w) > workspace_bytes) return LRQMM_ERR_WORKSPACE;
     const QuantParams q = make_quant_params(bits, round_mode);
     const int nscale = axis == LRQMM_AXIS_ROW ? rows : cols;
-    if (omega_or_null) {
+    if (prepared) {
+        // the caller has already filled the sketch (w.Wc) and the step vectors (w.lam, w.s) on this stream
+    } else if (omega_or_null) {
         ops.push_back([=] { return launch_scales(amax, nscale, pad_to(nscale, 4), q.qmaxf, w.lam, w.s, st); });
         ops.push_back([=] { return launch_pad_copy(omega_or_null, cols, ell, LP, w.Wc, st); });
     } else {
@@ -532,13 +534,31 @@ int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int
                           seed, nullptr, w.U, w.Sig, w.Vt, w.subA, w.subA_bytes, ast, before_svd));
     opsA.push_back([=] { prof_mark(slot, 2, ast); return LRQMM_OK; });
     opsB.push_back([=] { prof_mark(slot, 3, bst); return LRQMM_OK; });
-    if (K > 0) opsB.push_back([=] { return lrqmm_quantize_ex(B, ldb, K, N, LRQMM_AXIS_COL, bits, round_mode, scale_mode, w.BqT, w.amaxB, bst); });
+    // B's chain is the critical one.  With a factorization to follow, its first kernel fills the sketch
+    // (which depends on nothing) and clears the column maxima in one launch, and the quantizing kernel
+    // leaves the step vectors: the factorization then starts with its first pass at once.
+    const bool fuse_b = rank > 0 && K > 0;
+    RsvdWs wb = {};
+    if (fuse_b) {
+        Arena rb(w.subB);
+        if (carve_rsvd(rb, K, N, LRQMM_AXIS_COL, pad_to(rank + oversample, 16), rank, &wb) > w.subB_bytes)
+            return LRQMM_ERR_WORKSPACE;
+        const QuantParams qb = make_quant_params(bits, round_mode);
+        opsB.push_back([=] {
+            return launch_sketch_and_zero(seed, LRQMM_AXIS_COL, N, rank + oversample, pad_to(rank + oversample, 16),
+                                          wb.Wc, reinterpret_cast<uint32_t*>(w.amaxB), N, bst);
+        });
+        opsB.push_back([=] {
+            return launch_quantize_cols(B, ldb, K, N, qb, scale_mode == LRQMM_SCALE_TENSOR, nullptr, w.BqT, w.amaxB, bst,
+                                        true, wb.lam, wb.s);
+        });
+    } else if (K > 0) opsB.push_back([=] { return lrqmm_quantize_ex(B, ldb, K, N, LRQMM_AXIS_COL, bits, round_mode, scale_mode, w.BqT, w.amaxB, bst); });
     else opsB.push_back([=] { return launch_pad_copy(nullptr, N, 0, 1, w.amaxB, bst); });
     opsB.push_back([=] { prof_mark(slot, 4, bst); return LRQMM_OK; });
     if (rank > 0)
         LRQ_TRY(rsvd_plan(opsB, B, ldb, w.amaxB, K, N, LRQMM_AXIS_COL, bits, round_mode, rank, oversample, power_iters,
                           seed, nullptr, w.W, w.Gam, w.Zt, w.subB, w.subB_bytes, bst, before_svd_b,
-                          after_svd_b));
+                          after_svd_b, fuse_b));
     opsB.push_back([=] { prof_mark(slot, 5, bst); return LRQMM_OK; });
     LRQ_TRY(run_interleaved(opsB, opsA));
     if (overlap) {

@@ -11,8 +11,12 @@
 // first quantization whose group maxima are amax0 (second level of Eq. (gemm_r_split)).
 int launch_quantize_rows(const float* X, int ldx, int rows, int cols, QuantParams q, bool per_tensor,
                          const float* amax0, int8_t* codes, float* amax, hipStream_t st);
+// amax_zeroed: the caller has already cleared amax[0 .. cols) on this stream (the column maxima are merged
+// with atomics and must start at zero).  lam_out, s_out (both or neither): also write the step vectors
+// lam = qmax/amax, s = amax/qmax of the columns, zero padded to a multiple of 4 entries.
 int launch_quantize_cols(const float* X, int ldx, int rows, int cols, QuantParams q, bool per_tensor,
-                         const float* amax0, int8_t* codesT, float* amax, hipStream_t st);
+                         const float* amax0, int8_t* codesT, float* amax, hipStream_t st, bool amax_zeroed = false,
+                         float* lam_out = nullptr, float* s_out = nullptr);
 // lam[n], s[n] from amax[n]; entries n..npad-1 are zero-filled.
 // A minimal kernel (writes one zero word): used as a few microseconds of delay on a stream.
 int launch_tick(uint32_t* word, hipStream_t st);
@@ -28,6 +32,10 @@ int launch_fill_sketch(uint64_t seed, int stream_id, int rows, int cols, int ld,
 int launch_sketch_and_scales(uint64_t seed, int stream_id, int rows, int cols, int ld, float* omega,
                              const float* amax, int n, int npad, float qmaxf, float* lam, float* s,
                              hipStream_t st);
+// The sketch plus, in the same launch, zero_n words cleared at zero_words: the first kernel of a
+// column-wise quantization followed by a factorization (the sketch depends on neither).
+int launch_sketch_and_zero(uint64_t seed, int stream_id, int rows, int cols, int ld, float* omega,
+                           uint32_t* zero_words, int zero_n, hipStream_t st);
 // dst[i*ld + j] = (j < cols) ? src[i*cols + j] : 0
 int launch_pad_copy(const float* src, int rows, int cols, int ld, float* dst, hipStream_t st);
 

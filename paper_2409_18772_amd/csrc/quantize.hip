@@ -169,17 +169,27 @@ __global__ __launch_bounds__(256) void quant_cols_kernel(const float* __restrict
                                                          int cols, const float* __restrict__ amax,
                                                          QuantParams q,
                                                          int8_t* __restrict__ codesT,
-                                                         const float* __restrict__ amax0) {
+                                                         const float* __restrict__ amax0,
+                                                         float* __restrict__ lam_out,
+                                                         float* __restrict__ s_out, int npad) {
     __shared__ __align__(16) int8_t tile[64][80];
     const int n0 = blockIdx.x * 64, k0 = blockIdx.y * 64;
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
     const int n = n0 + tx * 4;
-    float lam[4];
+    float lam[4], stp[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         float a = (n + t < cols) ? amax[n + t] : 0.0f;
-        float s_unused;
-        make_scales(a, q.qmaxf, lam[t], s_unused);
+        make_scales(a, q.qmaxf, lam[t], stp[t]);
+    }
+    // the step vectors of this operand, zero padded to npad entries, for the kernels that follow
+    if (lam_out && blockIdx.y == 0 && ty == 0) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            if (n + t < npad) {
+                lam_out[n + t] = lam[t];     // zero beyond cols (amax read as 0 there)
+                s_out[n + t] = stp[t];
+            }
     }
     float lam0[4] = {0.f, 0.f, 0.f, 0.f}, s0[4] = {0.f, 0.f, 0.f, 0.f};
     if (amax0) {
@@ -281,12 +291,16 @@ static int rows_launch(const float* X, int ldx, int rows, int cols, QuantParams 
 }
 
 int launch_quantize_cols(const float* X, int ldx, int rows, int cols, QuantParams q, bool per_tensor,
-                         const float* amax0, int8_t* codesT, float* amax, hipStream_t st) {
+                         const float* amax0, int8_t* codesT, float* amax, hipStream_t st, bool amax_zeroed,
+                         float* lam_out, float* s_out) {
     const bool vec = (cols % 4 == 0) && (ldx % 4 == 0) && aligned16(X);
     const bool vecout = (rows % 16 == 0) && aligned16(codesT);
-    hipLaunchKernelGGL(fill_u32_kernel, dim3(ceil_div(cols, 256)), dim3(256), 0, st,
-                       reinterpret_cast<uint32_t*>(amax), cols, 0u);
-    LRQ_CHECK_LAUNCH();
+    const int npad = (cols + 3) / 4 * 4;
+    if (!amax_zeroed) {
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(ceil_div(cols, 256)), dim3(256), 0, st,
+                           reinterpret_cast<uint32_t*>(amax), cols, 0u);
+        LRQ_CHECK_LAUNCH();
+    }
     // enough row slabs to fill the chip, at least 32 rows each
     const int col_blocks = ceil_div(cols, 1024);
     int slabs = max(1, min(ceil_div(rows, 32), ceil_div(2048, col_blocks)));
@@ -306,13 +320,13 @@ int launch_quantize_cols(const float* X, int ldx, int rows, int cols, QuantParam
     }
     dim3 g2(ceil_div(cols, 64), ceil_div(rows, 64));
     if (vec && vecout)
-        hipLaunchKernelGGL((quant_cols_kernel<true, true>), g2, dim3(256), 0, st, X, ldx, rows, cols, amax, q, codesT, amax0);
+        hipLaunchKernelGGL((quant_cols_kernel<true, true>), g2, dim3(256), 0, st, X, ldx, rows, cols, amax, q, codesT, amax0, lam_out, s_out, npad);
     else if (vec)
-        hipLaunchKernelGGL((quant_cols_kernel<true, false>), g2, dim3(256), 0, st, X, ldx, rows, cols, amax, q, codesT, amax0);
+        hipLaunchKernelGGL((quant_cols_kernel<true, false>), g2, dim3(256), 0, st, X, ldx, rows, cols, amax, q, codesT, amax0, lam_out, s_out, npad);
     else if (vecout)
-        hipLaunchKernelGGL((quant_cols_kernel<false, true>), g2, dim3(256), 0, st, X, ldx, rows, cols, amax, q, codesT, amax0);
+        hipLaunchKernelGGL((quant_cols_kernel<false, true>), g2, dim3(256), 0, st, X, ldx, rows, cols, amax, q, codesT, amax0, lam_out, s_out, npad);
     else
-        hipLaunchKernelGGL((quant_cols_kernel<false, false>), g2, dim3(256), 0, st, X, ldx, rows, cols, amax, q, codesT, amax0);
+        hipLaunchKernelGGL((quant_cols_kernel<false, false>), g2, dim3(256), 0, st, X, ldx, rows, cols, amax, q, codesT, amax0, lam_out, s_out, npad);
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }

@@ -100,9 +100,14 @@ __device__ static float gaussian_at(uint64_t key, uint32_t i, uint32_t j) {
 // preparation of a factorization is one launch.
 __global__ void fill_sketch_kernel(uint64_t key, int rows, int cols, int ld, float* __restrict__ omega,
                                    int nb_sketch, const float* __restrict__ amax, int n, int npad, float qmaxf,
-                                   float* __restrict__ lam, float* __restrict__ s) {
+                                   float* __restrict__ lam, float* __restrict__ s,
+                                   uint32_t* __restrict__ zero_words, int zero_n) {
     if ((int)blockIdx.x >= nb_sketch) {
         const int i = ((int)blockIdx.x - nb_sketch) * blockDim.x + threadIdx.x;
+        if (zero_words) {       // the trailing workgroups clear words instead (column maxima before their merge)
+            if (i < zero_n) zero_words[i] = 0u;
+            return;
+        }
         if (i >= npad) return;
         float l = 0.0f, st = 0.0f;
         if (i < n) make_scales(amax[i], qmaxf, l, st);
@@ -147,7 +152,19 @@ int launch_sketch_and_scales(uint64_t seed, int stream_id, int rows, int cols, i
     const int nb_sketch = (int)((total + 255) / 256), nb_scale = amax ? (npad + 255) / 256 : 0;
     if (nb_sketch + nb_scale == 0) return LRQMM_OK;
     hipLaunchKernelGGL(fill_sketch_kernel, dim3(nb_sketch + nb_scale), dim3(256), 0, st, key, rows, cols, ld,
-                       omega, nb_sketch, amax, n, npad, qmaxf, lam, s);
+                       omega, nb_sketch, amax, n, npad, qmaxf, lam, s, nullptr, 0);
+    LRQ_CHECK_LAUNCH();
+    return LRQMM_OK;
+}
+
+int launch_sketch_and_zero(uint64_t seed, int stream_id, int rows, int cols, int ld, float* omega,
+                           uint32_t* zero_words, int zero_n, hipStream_t st) {
+    const uint64_t key = host_mix64(seed + 0x9E3779B97F4A7C15ull * (uint64_t)(stream_id + 1));
+    const size_t total = (size_t)rows * ld;
+    const int nb_sketch = (int)((total + 255) / 256), nb_zero = (zero_n + 255) / 256;
+    if (nb_sketch + nb_zero == 0) return LRQMM_OK;
+    hipLaunchKernelGGL(fill_sketch_kernel, dim3(nb_sketch + nb_zero), dim3(256), 0, st, key, rows, cols, ld, omega,
+                       nb_sketch, nullptr, 0, 0, 0.f, nullptr, nullptr, zero_words, zero_n);
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }
