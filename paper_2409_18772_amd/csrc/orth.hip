@@ -132,10 +132,9 @@ __global__ __launch_bounds__(64) void gram_sum_kernel(const double* __restrict__
 // The matrix lives in registers as KR x KC tiles with strided ownership: worker (ti, tg)
 // owns rows ti + NTI*ir (ir < KR) and columns tg + NTI*kc (kc < KC = 2 KR; NTI = LP / KR
 // workers each way), so pivot j = tj + NTI*jr sits in register row jr and register column
-// jr: compile-time constants inside the unrolled jr loop.  A thread reads KR + KC + 2 LDS
-// words per step for KR*KC updates, and at most four wavefronts (one per SIMD) do the work
-// for l <= 64.  A step publishes the pivot row and pivot column in LDS (two generations, so
-// one workgroup barrier per step is enough).  The serial chain per step is LDS write ->
+// jr: compile-time constants inside the unrolled jr loop.  At most four wavefronts (one per SIMD)
+// do the work for l <= 64.  A step publishes pivot rows and pivot columns in LDS (two generations,
+// so one workgroup barrier per step is enough).  The serial chain per step is LDS write ->
 // barrier -> LDS read -> reciprocal -> FMA; the square roots are taken once at the end.
 // A pivot below 1e-10 of its original diagonal (rank-deficient sketch) is dead: it
 // eliminates nothing and its row and column of T are zero.  The workgroup holds only the
@@ -152,108 +151,18 @@ struct CholShape {
     static constexpr int THREADS = (WORKERS + 63) / 64 * 64;
 };
 
-template <int NT>
-__global__ __launch_bounds__(CholShape<NT>::THREADS) void chol_inverse_kernel(const double* __restrict__ gram, int ell,
-                                                                    double* __restrict__ T) {
-    using S = CholShape<NT>;
-    constexpr int LP = S::LP, KR = S::KR, KC = S::KC, NTI = S::NTI;
-    __shared__ double rowb[2][2 * LP];
-    __shared__ double colb[2][LP];
-    __shared__ __align__(16) double2 pivb[2];
-    const int tid = threadIdx.x;
-    const bool worker = tid < S::WORKERS;
-    const int ti = worker ? tid / NTI : 0, tg = worker ? tid - ti * NTI : 0;
-    double mreg[KR][KC];
-    double thr[KR];             // 1e-10 * original diagonal of the thread's rows
-#pragma unroll
-    for (int ir = 0; ir < KR; ++ir) {
-        const int i = ti + NTI * ir;        // < LP; rows and columns >= ell enter as zeros
-        const double gd = gram[i * LP + i];
-        thr[ir] = i < ell ? 1e-10 * gd : 0.0;
-#pragma unroll
-        for (int kc = 0; kc < KC; ++kc) {
-            const int c = tg + NTI * kc;        // < 2 LP
-            const double g = gram[i * LP + (c < LP ? c : c - LP)];     // always inside the LP x LP array
-            mreg[ir][kc] = (c < LP) ? ((i < ell && c < ell) ? g : 0.0) : ((c - LP == i && i < ell) ? 1.0 : 0.0);
-        }
-    }
-    double pivot[KR];           // pivots of the thread's rows, 0 when dead
-#pragma unroll
-    for (int ir = 0; ir < KR; ++ir) pivot[ir] = 0.0;
-    int par = 0;
-#pragma unroll
-    for (int jr = 0; jr < KR; ++jr) {
-        for (int tj = 0; tj < NTI; ++tj) {
-            const int j = tj + NTI * jr;
-            if (j >= ell) break;
-            if (worker) {
-                if (tg == tj) {
-#pragma unroll
-                    for (int ir = 0; ir < KR; ++ir) colb[par][ti + NTI * ir] = mreg[ir][jr];
-                }
-                if (ti == tj) {
-#pragma unroll
-                    for (int kc = 0; kc < KC; ++kc) rowb[par][tg + NTI * kc] = mreg[jr][kc];
-                    if (tg == tj) pivb[par] = make_double2(mreg[jr][jr], thr[jr]);
-                }
-            }
-            __syncthreads();
-            const double2 pv = pivb[par];
-            double l[KR], r[KC];
-#pragma unroll
-            for (int ir = 0; ir < KR; ++ir) l[ir] = colb[par][ti + NTI * ir];
-#pragma unroll
-            for (int kc = 0; kc < KC; ++kc) r[kc] = rowb[par][tg + NTI * kc];
-            const double d = pv.x;
-            const bool live = d > pv.y && d > 0.0;
-            double q = 0.0;
-            if (live) {         // 1/d: hardware estimate and two Newton steps
-                q = __builtin_amdgcn_rcp(d);
-                q = fma(fma(-d, q, 1.0), q, q);
-                q = fma(fma(-d, q, 1.0), q, q);
-            }
-            if (ti == tj) pivot[jr] = live ? d : 0.0;
-#pragma unroll
-            for (int ir = 0; ir < KR; ++ir) {
-                const double lq = (ti + NTI * ir > j) ? -(l[ir] * q) : 0.0;
-#pragma unroll
-                for (int kc = 0; kc < KC; ++kc) mreg[ir][kc] = fma(lq, r[kc], mreg[ir][kc]);
-            }
-            par ^= 1;
-        }
-    }
-    if (!worker) return;
-#pragma unroll
-    for (int ir = 0; ir < KR; ++ir) {
-        const double pv = pivot[ir];
-        double inv = 0.0;
-        if (pv > 0.0) {      // 1/sqrt by the hardware estimate and three Newton steps
-            inv = __builtin_amdgcn_rsq(pv);
-            inv = inv * fma(-0.5 * pv, inv * inv, 1.5);
-            inv = inv * fma(-0.5 * pv, inv * inv, 1.5);
-            inv = inv * fma(-0.5 * pv, inv * inv, 1.5);
-        }
-        const int i = ti + NTI * ir;
-#pragma unroll
-        for (int kc = 0; kc < KC; ++kc) {
-            const int c = tg + NTI * kc;
-            if (c >= LP) T[(c - LP) * LP + i] = mreg[ir][kc] * inv;
-        }
-    }
-}
-
-// The same elimination, two pivots per step: pivots j and j+1 share one publication (rows j, j+1
+// Two pivots per step: pivots j and j+1 share one publication (rows j, j+1
 // and columns j, j+1 as they stand before pivot j), one barrier and one LDS round trip, and every
 // worker derives the effect of pivot j on row j+1 and on column j+1 itself (redundantly) before it
-// applies both rank-1 updates.  Every matrix element receives exactly the operations of the
-// one-pivot-per-step kernel in the same order, so T is bit-identical; the serial chain per pivot
+// applies both rank-1 updates.  Every matrix element receives exactly the operations of plain
+// one-pivot-at-a-time elimination in the same order; the serial chain per pivot
 // (LDS write -> barrier -> LDS read -> reciprocal -> FMA) is paid once per pair.  NTI is even, so
 // a pair never straddles two register rows; an odd l ends with a dead second pivot (zero row).
 // Updates that cannot change a value that is read later are skipped at compile time (rows above the
 // pivots; eliminated columns of G; columns of the identity half that are still exactly zero):
 // 12.5 instead of 32 FMAs per worker and pivot on average, with the same live values.
 template <int NT>
-__global__ __launch_bounds__(CholShape<NT>::THREADS) void chol_inverse2_kernel(const double* __restrict__ gram, int ell,
+__global__ __launch_bounds__(CholShape<NT>::THREADS) void chol_inverse_kernel(const double* __restrict__ gram, int ell,
                                                                      double* __restrict__ T) {
     using S = CholShape<NT>;
     constexpr int LP = S::LP, KR = S::KR, KC = S::KC, NTI = S::NTI;
@@ -728,7 +637,7 @@ int launch_gram_sum(const double* gpart, int nb, int LP, double* gram, hipStream
 }
 
 int launch_chol_inverse(const double* gram, int ell, int LP, double* T, hipStream_t st) {
-    NT_SWITCH(LP / 16, hipLaunchKernelGGL((chol_inverse2_kernel<NT_>), dim3(1), dim3(CholShape<NT_>::THREADS), 0, st, gram, ell,
+    NT_SWITCH(LP / 16, hipLaunchKernelGGL((chol_inverse_kernel<NT_>), dim3(1), dim3(CholShape<NT_>::THREADS), 0, st, gram, ell,
                                           T));
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
