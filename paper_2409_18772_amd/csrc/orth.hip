@@ -49,6 +49,43 @@ __global__ __launch_bounds__(256) void reduce_gram_kernel(const float* __restric
     const size_t plane = (size_t)n * LP;
     for (int r0 = rb; r0 < re; r0 += GB_TILE) {
         __syncthreads();
+        if (splits <= MAX_SPLITS) {
+            // One batch of splits: every load of the tile is issued before the first add (branch free:
+            // clamped row and split indices, masked afterwards), so the tile costs one memory latency
+            // instead of one per group of 256 float4.
+            constexpr int ITER = (GB_TILE * Q4 + 255) / 256;
+            float4 p[ITER][MAX_SPLITS];
+#pragma unroll
+            for (int it = 0; it < ITER; ++it) {
+                const int idx = min((int)threadIdx.x + 256 * it, GB_TILE * Q4 - 1);
+                const int rr = idx / Q4, c = (idx % Q4) * 4;
+                const size_t off = (size_t)min(r0 + rr, re - 1) * LP + c;
+#pragma unroll
+                for (int sp = 0; sp < MAX_SPLITS; ++sp)
+                    p[it][sp] = *reinterpret_cast<const float4*>(partial + (size_t)min(sp, splits - 1) * plane + off);
+            }
+#pragma unroll
+            for (int it = 0; it < ITER; ++it) {
+                const int idx = (int)threadIdx.x + 256 * it;
+                if (idx < GB_TILE * Q4) {
+                    const int rr = idx / Q4, c = (idx % Q4) * 4;
+                    const int row = r0 + rr;
+                    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (row < re) {
+#pragma unroll
+                        for (int sp = 0; sp < MAX_SPLITS; ++sp)
+                            if (sp < splits) { v.x += p[it][sp].x; v.y += p[it][sp].y; v.z += p[it][sp].z; v.w += p[it][sp].w; }
+                        if (rowscale) {
+                            const float rs = rowscale[row];
+                            v.x *= rs; v.y *= rs; v.z *= rs; v.w *= rs;
+                        }
+                        *reinterpret_cast<float4*>(Y + (size_t)row * LP + c) = v;
+                    }
+                    float* t = tile + rr * ld + c;
+                    t[0] = v.x; t[1] = v.y; t[2] = v.z; t[3] = v.w;
+                }
+            }
+        } else
         for (int idx = threadIdx.x; idx < GB_TILE * Q4; idx += 256) {
             const int rr = idx / Q4, c = (idx % Q4) * 4;
             const int row = r0 + rr;

@@ -542,9 +542,9 @@ __global__ __launch_bounds__(256, 1) void codes_mul_bf16_kernel(CodesJobBf16 j0,
         // codes past K meet zero planes, so clamped addresses need no mask
         uint4 ca[4][NC];
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-            for (int c = 0; c < NC; ++c)
+        for (int c = 0; c < NC; ++c)            // issued in the order of use: the first chunk's products can start
+#pragma unroll                                  // while the later chunks are still on their way
+            for (int mt = 0; mt < 4; ++mt)
                 ca[mt][c] = *reinterpret_cast<const uint4*>(ap[mt] + min(ks + 64 * c + 16 * kq, K - 16));
         if (ks > kb) __syncthreads();       // previous slab no longer read
         for (int p0 = threadIdx.x; p0 < S::PIECES; p0 += 256 * S::BATCH) {
