@@ -490,9 +490,18 @@ __global__ __launch_bounds__(SVD_THREADS) void small_svd_kernel(const double* __
     for (int idx = tid; idx < m * m; idx += SVD_THREADS) Vt[idx] = (idx / m == idx % m) ? 1.0 : 0.0;
     if (tid == 0) finished = 0;
     __syncthreads();
-    for (int idx = tid; idx < ell * ell; idx += SVD_THREADS) {      // stored by slot
-        const int a = idx / ell, b = idx % ell;
-        G0[home(a) * ldg + home(b)] = gram[a * LP + b];
+    for (int base = 0; base < ell * ell; base += 4 * SVD_THREADS) {     // stored by slot; four loads in flight
+        double v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = min(base + u * SVD_THREADS + tid, ell * ell - 1);
+            v[u] = gram[(idx / ell) * LP + idx % ell];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = base + u * SVD_THREADS + tid;
+            if (idx < ell * ell) G0[home(idx / ell) * ldg + home(idx % ell)] = v[u];
+        }
     }
     __syncthreads();
 
@@ -624,6 +633,7 @@ __global__ __launch_bounds__(SVD_THREADS) void small_svd_kernel(const double* __
     if (tid < ell) {
         const double mine = G[home(tid) * ldg + home(tid)];
         int pos = 0;
+#pragma unroll 8
         for (int o = 0; o < ell; ++o) {
             const double other = G[home(o) * ldg + home(o)];
             if (other > mine || (other == mine && o < tid)) ++pos;
