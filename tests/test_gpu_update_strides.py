@@ -202,3 +202,26 @@ def test_early_product_equals_fused_store_phase_bitwise(K):
     # twice in a row on the same output: the zeroing of the summed tiles is part of every call
     L.lrqmm_matmul_ex(dA, dB, D1, 4, 8, 4, 1, seed=5)
     assert torch.equal(D1, D2)
+
+
+@pytest.mark.parametrize("axis", [0, 1])
+@pytest.mark.parametrize("ell,round_mode,rows,cols", [(24, 0, 640, 512), (40, 0, 640, 512), (72, 0, 640, 512),
+                                                       (40, 1, 640, 512), (40, 0, 4096, 4096)])
+def test_guard_free_pass_kernels_equal_the_guarded_ones_bitwise(axis, ell, round_mode, rows, cols):
+    """A dense operand whose sizes are multiples of 128 takes the guard-free instantiations of the two
+    residual products; the same values inside an array with an odd row stride take the guarded scalar-load
+    kernels.  Same arithmetic in the same order: the factors must agree bit for bit.  (At 640 x 512 only R.W
+    has whole chunks; at 4096 x 4096 the row chunks of Rt.W are multiples of 128 as well.)"""
+    import torch
+    import paper_2409_18772_amd as L
+    X = wl.random_matrix("normal", rows, cols, seed=41 + ell)
+    oax = o.ROWWISE if axis == 0 else o.COLWISE
+    amax = to_dev(np.asarray(o.absmax(X, oax), dtype=np.float32).reshape(-1))
+    dense = to_dev(X)
+    _, view = window(X, 1)
+    rank, p = ell - 8, 8
+    say("guard-free vs guarded", axis, ell, round_mode)
+    a = L.lrqmm_rsvd_ex(dense, amax, axis, 4, rank, p, 1, seed=13, round_mode=round_mode)
+    b = L.lrqmm_rsvd_ex(view, amax, axis, 4, rank, p, 1, seed=13, round_mode=round_mode)
+    for x, y, name in zip(a, b, ("U", "Sigma", "Vt")):
+        assert torch.equal(x, y), name
