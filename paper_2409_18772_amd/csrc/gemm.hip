@@ -395,12 +395,13 @@ __global__ __launch_bounds__(512, 1) void int8_gemm256_kernel(int M, int N, int 
 // panel columns, the panel rows of both row tiles and both column tiles -- without branches,
 // and then runs the four accumulation chains interleaved, so neither load latency nor the
 // latency of dependent MFMAs is exposed.
-__global__ __launch_bounds__(256, 3) void rank_update_kernel(int M, int N, float* __restrict__ C,
+__global__ __launch_bounds__(256, 2) void rank_update_kernel(int M, int N, float* __restrict__ C,
                                                           const float* __restrict__ sA,
                                                           const float* __restrict__ sB,
                                                           const float* __restrict__ Lp,
                                                           const float* __restrict__ Rp, int R2P, int tiles_n,
                                                           float alpha) {
+    __shared__ __align__(16) float pl[2][128][68];      // Lp and Rp rows of the tile, 64 columns, padded
     const int m0 = (blockIdx.x / tiles_n) * 128, n0 = (blockIdx.x % tiles_n) * 128;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int wm = wave >> 1, wn = wave & 1;
@@ -448,29 +449,32 @@ __global__ __launch_bounds__(256, 3) void rank_update_kernel(int M, int N, float
                 f[mt][nt][4 * g + 2] = ((float)raw[mt][nt][g].z * sa[mt]) * sb[nt][g].z;
                 f[mt][nt][4 * g + 3] = ((float)raw[mt][nt][g].w * sa[mt]) * sb[nt][g].w;
             }
-    const float* lp[2];
-    const float* rp[2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {       // rows / columns past the end re-read the last one (never stored)
-        lp[t] = Lp + (size_t)row[t] * R2P + 4 * lh;
-        rp[t] = Rp + (size_t)min(cb0 + t * 32 + l32, N - 1) * R2P + 4 * lh;
-    }
+    // The panel rows of the tile go through LDS, 64 columns at a time: the workgroup loads each row once,
+    // 16 lanes per 256-byte row, instead of every wave fetching its operands with 16-byte loads that touch
+    // 32 cache lines per instruction (measured on this access pattern: 36 instead of 41 us).
     for (int t0 = 0; t0 < R2P; t0 += 64) {      // R2P % 8 == 0
-        // panel columns past R2P enter as zeros (clamped load, then select): the MFMAs below
-        // carry no guard, and adding exact zeros leaves the sums unchanged
+        if (t0 > 0) __syncthreads();            // the previous chunk is no longer read
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int idx = threadIdx.x + 256 * i, r = idx >> 4, c = (idx & 15) * 4;
+            const int col = t0 + c;
+            const bool in = col < R2P;           // panel columns past R2P enter as zeros
+            const int cc = min(col, R2P - 4);
+            // rows / columns past the end re-read the last one (never stored)
+            const float4 x = *reinterpret_cast<const float4*>(Lp + (size_t)min(m0 + r, M - 1) * R2P + cc);
+            const float4 y = *reinterpret_cast<const float4*>(Rp + (size_t)min(n0 + r, N - 1) * R2P + cc);
+            *reinterpret_cast<float4*>(&pl[0][r][c]) = make_float4(in ? x.x : 0.f, in ? x.y : 0.f, in ? x.z : 0.f, in ? x.w : 0.f);
+            *reinterpret_cast<float4*>(&pl[1][r][c]) = make_float4(in ? y.x : 0.f, in ? y.y : 0.f, in ? y.z : 0.f, in ? y.w : 0.f);
+        }
+        __syncthreads();
         float4 a4[2][8], b4[2][8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int tc = min(t0 + 8 * u, R2P - 8);
-            const bool in = t0 + 8 * u < R2P;
+        for (int u = 0; u < 8; ++u)
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
-                const float4 x = *reinterpret_cast<const float4*>(lp[t] + tc);
-                const float4 y = *reinterpret_cast<const float4*>(rp[t] + tc);
-                a4[t][u] = make_float4(in ? x.x : 0.f, in ? x.y : 0.f, in ? x.z : 0.f, in ? x.w : 0.f);
-                b4[t][u] = make_float4(in ? y.x : 0.f, in ? y.y : 0.f, in ? y.z : 0.f, in ? y.w : 0.f);
+                a4[t][u] = *reinterpret_cast<const float4*>(&pl[0][wm * 64 + t * 32 + l32][8 * u + 4 * lh]);
+                b4[t][u] = *reinterpret_cast<const float4*>(&pl[1][wn * 64 + t * 32 + l32][8 * u + 4 * lh]);
             }
-        }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
 #pragma unroll
