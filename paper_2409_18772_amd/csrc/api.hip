@@ -151,29 +151,36 @@ struct Prof {
     bool created = false;
 } g_prof;
 
-// Second stream (default priority) on which the factorization of R_B runs next to R_A's.
+// Streams and events that lrqmm_matmul needs beyond the caller's stream, one set per device (created on
+// the first call on that device, never destroyed: they live as long as the process).  `stream` carries
+// A's quantization and factorization next to B's on the caller's stream; `gemm_stream` the early integer
+// product.  All at default priority.
 struct Side {
-    hipStream_t stream = nullptr;        // factorization of R_B
+    hipStream_t stream = nullptr;        // A's chain
     hipStream_t gemm_stream = nullptr;   // early integer GEMM
     hipEvent_t fork = nullptr, join = nullptr;
     hipEvent_t gate = nullptr, gate_b = nullptr, gdone = nullptr;
     int cus = 0;                         // compute units of the device
     bool ok = false;
-} g_side;
+};
+constexpr int kMaxDevices = 16;
+Side g_side_dev[kMaxDevices];
 
-bool side_ready() {
-    if (g_side.ok) return true;
-    if (hipStreamCreateWithFlags(&g_side.stream, hipStreamNonBlocking) != hipSuccess) return false;
-    if (hipStreamCreateWithFlags(&g_side.gemm_stream, hipStreamNonBlocking) != hipSuccess) return false;
-    for (hipEvent_t* e : {&g_side.gate, &g_side.gate_b, &g_side.gdone})
-        if (hipEventCreateWithFlags(e, hipEventDisableTiming) != hipSuccess) return false;
-    if (hipEventCreateWithFlags(&g_side.fork, hipEventDisableTiming) != hipSuccess) return false;
-    if (hipEventCreateWithFlags(&g_side.join, hipEventDisableTiming) != hipSuccess) return false;
+// The current device's set, or null when it does not exist yet and `create` is false (a call under
+// stream capture must not create streams) or when creating it failed.
+Side* side_state(bool create) {
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return false;
-    if (hipDeviceGetAttribute(&g_side.cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return false;
-    g_side.ok = true;
-    return true;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    Side& s = g_side_dev[dev];
+    if (s.ok) return &s;
+    if (!create) return nullptr;
+    if (hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
+    if (hipStreamCreateWithFlags(&s.gemm_stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
+    for (hipEvent_t* e : {&s.gate, &s.gate_b, &s.gdone, &s.fork, &s.join})
+        if (hipEventCreateWithFlags(e, hipEventDisableTiming) != hipSuccess) return nullptr;
+    if (hipDeviceGetAttribute(&s.cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return nullptr;
+    s.ok = true;
+    return &s;
 }
 
 inline void prof_mark(int slot, int i, hipStream_t st) {
@@ -199,27 +206,29 @@ bool k_fits_int32(int K, int bits) {
 // microseconds per launch, and each list holds ~30).
 using LaunchList = std::vector<std::function<int()>>;
 
-static int run_interleaved(const LaunchList& a, const LaunchList& b) {
-    const size_t n = a.size() > b.size() ? a.size() : b.size();
-    for (size_t i = 0; i < n; ++i) {
-        if (i < a.size()) {
-            const int rc = a[i]();
+// Issues a[a0 .. a1) and b[b0 .. b1) alternately.
+static int run_interleaved(const LaunchList& a, size_t a0, size_t a1, const LaunchList& b, size_t b0, size_t b1) {
+    while (a0 < a1 || b0 < b1) {
+        if (a0 < a1) {
+            const int rc = a[a0++]();
             if (rc != LRQMM_OK) return rc;
         }
-        if (i < b.size()) {
-            const int rc = b[i]();
+        if (b0 < b1) {
+            const int rc = b[b0++]();
             if (rc != LRQMM_OK) return rc;
         }
     }
     return LRQMM_OK;
+}
+static int run_interleaved(const LaunchList& a, const LaunchList& b) {
+    return run_interleaved(a, 0, a.size(), b, 0, b.size());
 }
 
 // Validates the arguments of lrqmm_rsvd and appends its launches to `ops`.
 static int rsvd_plan(LaunchList& ops, const float* X, int ldx, const float* amax, int rows, int cols, int axis, int bits,
                      int round_mode, int rank, int oversample, int power_iters, uint64_t seed,
                      const float* omega_or_null, float* U, float* Sigma, float* Vt, void* workspace,
-                     size_t workspace_bytes, hipStream_t st, const std::function<int()>& before_svd = nullptr,
-                     const std::function<int()>& after_svd = nullptr, bool prepared = false) {
+                     size_t workspace_bytes, hipStream_t st, size_t* svd_index = nullptr, bool prepared = false) {
     if (rows < 0 || cols < 0 || rank < 1 || oversample < 0 || power_iters < 0 || ldx < cols) return LRQMM_ERR_INVALID_ARG;
     if (axis != LRQMM_AXIS_ROW && axis != LRQMM_AXIS_COL) return LRQMM_ERR_INVALID_ARG;
     if (round_mode != LRQMM_ROUND_FLOOR && round_mode != LRQMM_ROUND_NEAREST) return LRQMM_ERR_INVALID_ARG;
@@ -275,9 +284,8 @@ static int rsvd_plan(LaunchList& ops, const float* X, int ldx, const float* amax
     pass_t();
     ops.push_back([=] { return launch_reduce_gram(w.partial, pt.splits, cols, LP, nullptr, w.Wc, w.gpart, st); });
     ops.push_back([=] { return launch_gram_sum(w.gpart, gram_blocks(cols), LP, w.gram, st); });
-    if (before_svd) ops.push_back(before_svd);      // the GPU is nearly idle from here to the end of the SVD
+    if (svd_index) *svd_index = ops.size();         // the GPU is nearly idle from this launch to its end
     ops.push_back([=] { return launch_small_svd(w.gram, ell, LP, rank, Sigma, w.Ur, w.Mv, st); });
-    if (after_svd) ops.push_back(after_svd);
     ops.push_back([=] {
         return launch_apply2(w.Yr, rows, w.Ur, rank, rank, U, rank, 0, w.Wc, cols, w.Mv, rank, rank, Vt, cols, 1, LP,
                              st);
@@ -393,6 +401,14 @@ static int gemm_impl(int M, int N, int K, int bits, int rank, const int8_t* Aq, 
     Arena a(workspace);
     if (carve_gemm(a, M, N, K, rank, &w) > workspace_bytes) return LRQMM_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (K == 0) {
+        // An empty reduction: C_F = 0 (rank <= K leaves no compensation either), so only the update
+        // D <- alpha * 0 + beta * D remains.  No operand is read and no GEMM kernel is launched.
+        prof_mark(prof_slot, 7, st);
+        const int r0 = launch_empty_product(M, N, out, Cint_or_null, st);
+        for (int e = 8; e <= 10; ++e) prof_mark(prof_slot, e, st);
+        return r0;
+    }
     const QuantParams q = make_quant_params(bits, 0);
     int rc;
     int R2P = 0;
@@ -470,26 +486,23 @@ int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int
     MatmulWs w;
     Arena a(workspace);
     if (carve_matmul(a, M, N, K, rank, oversample, &w) > workspace_bytes) return LRQMM_ERR_WORKSPACE;
-    int rc;
     hipStream_t pst = static_cast<hipStream_t>(stream);
-    const int slot = (g_prof.on && g_prof.ncalls < kProfMaxCalls) ? g_prof.ncalls++ : -1;
+    // Under stream capture the call may only enqueue kernels, event records and event waits: it cannot
+    // create its streams and events, and timing events do not belong in a graph.
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(pst, &capture) != hipSuccess) return LRQMM_ERR_HIP;
+    const bool capturing = capture != hipStreamCaptureStatusNone;
+    if (capturing && g_prof.on) return LRQMM_ERR_UNSUPPORTED;
     // the two operands' quantization and factorization run on two streams; rank 0 stays on one stream
-    const bool overlap = rank > 0 && K > 0 && side_ready();
+    Side* const side = (rank > 0 && K > 0) ? side_state(!capturing) : nullptr;
+    if (rank > 0 && K > 0 && !side) return capturing ? LRQMM_ERR_UNSUPPORTED : LRQMM_ERR_HIP;
+    const bool overlap = side != nullptr;
+    const int slot = (g_prof.on && g_prof.ncalls < kProfMaxCalls) ? g_prof.ncalls++ : -1;
     // B's chain is the longer one (its quantization needs two passes over B), so it stays on the
     // caller's stream and starts at once; A's chain takes the side stream and absorbs the latency of
     // the fork event, and has normally finished when the caller's stream reaches the join.
     hipStream_t bst = pst;
-    hipStream_t ast = overlap ? g_side.stream : pst;
-    if (overlap) {
-        if (hipEventRecord(g_side.fork, pst) != hipSuccess) return LRQMM_ERR_HIP;
-        if (hipStreamWaitEvent(ast, g_side.fork, 0) != hipSuccess) return LRQMM_ERR_HIP;
-    }
-    // the two sides are planned first and then issued alternately (see LaunchList)
-    LaunchList opsA, opsB;
-    opsA.push_back([=] { prof_mark(slot, 0, ast); return LRQMM_OK; });
-    if (K > 0) opsA.push_back([=] { return lrqmm_quantize_ex(A, lda, M, K, LRQMM_AXIS_ROW, bits, round_mode, scale_mode, w.Aq, w.amaxA, ast); });
-    else opsA.push_back([=] { return launch_pad_copy(nullptr, M, 0, 1, w.amaxA, ast); });
-    opsA.push_back([=] { prof_mark(slot, 1, ast); return LRQMM_OK; });
+    hipStream_t ast = overlap ? side->stream : pst;
     // Early integer GEMM: with both factorizations in their single-workgroup SVD the GPU is
     // nearly idle, so the int8 product (which needs only the codes) runs there on a third
     // stream, leaves raw int32 sums in C, and the epilogue follows the panels as a kernel of
@@ -497,41 +510,18 @@ int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int
     // (the raw sums need D's memory: only when its old contents are not an input and it is dense)
     const bool early = overlap && rank_update_usable(M, N, C) && beta == 0.0f && ldd == N;
     if (slot >= 0) g_prof.early[slot] = early;
-    hipStream_t gst = early ? g_side.gemm_stream : pst;
-    std::function<int()> before_svd = nullptr, before_svd_b = nullptr, after_svd_b = nullptr;
-    if (early) {
-        // The GEMM must not take the CUs before the two SVD workgroups have theirs: it waits
-        // for the kernels that precede both SVDs and then for a few minimal kernels, which
-        // gives the SVD launches (one dependent launch behind their events) a head start.
-        before_svd = [=] {
-            if (hipEventRecord(g_side.gate, ast) != hipSuccess) return LRQMM_ERR_HIP;
-            return LRQMM_OK;
-        };
-        before_svd_b = [=] {
-            if (hipEventRecord(g_side.gate_b, bst) != hipSuccess) return LRQMM_ERR_HIP;
-            return LRQMM_OK;
-        };
-        after_svd_b = [=] {     // issued by the host after both SVD launches
-            for (hipEvent_t e : {g_side.gate, g_side.gate_b})    // recorded after both quantizations
-                if (hipStreamWaitEvent(gst, e, 0) != hipSuccess) return LRQMM_ERR_HIP;
-            // the two small-SVD workgroups hold a CU each while the product runs
-            const int resident = g_side.cus - 2;
-            for (int t = 0; t < 3; ++t) {
-                const int r = launch_tick(w.tick, gst);
-                if (r != LRQMM_OK) return r;
-            }
-            prof_mark(slot, 9, gst);
-            int r = launch_int8_gemm_sums(M, N, K, w.Aq, w.BqT, reinterpret_cast<int32_t*>(C), resident, w.parts, gst);
-            prof_mark(slot, 10, gst);
-            if (r != LRQMM_OK) return r;
-            r = launch_int8_gemm_sums_finish(M, N, K, w.Aq, w.BqT, reinterpret_cast<int32_t*>(C), resident, w.parts, gst);
-            if (r != LRQMM_OK) return r;
-            return hipEventRecord(g_side.gdone, gst) == hipSuccess ? LRQMM_OK : LRQMM_ERR_HIP;
-        };
-    }
+    hipStream_t gst = early ? side->gemm_stream : pst;
+    // the two sides are planned first and then issued alternately (see LaunchList)
+    LaunchList opsA, opsB;
+    size_t svdA = 0, svdB = 0;      // positions of the small-SVD launches in the two lists
+    int rc;
+    opsA.push_back([=] { prof_mark(slot, 0, ast); return LRQMM_OK; });
+    if (K > 0) opsA.push_back([=] { return lrqmm_quantize_ex(A, lda, M, K, LRQMM_AXIS_ROW, bits, round_mode, scale_mode, w.Aq, w.amaxA, ast); });
+    else opsA.push_back([=] { return launch_pad_copy(nullptr, M, 0, 1, w.amaxA, ast); });
+    opsA.push_back([=] { prof_mark(slot, 1, ast); return LRQMM_OK; });
     if (rank > 0)
         LRQ_TRY(rsvd_plan(opsA, A, lda, w.amaxA, M, K, LRQMM_AXIS_ROW, bits, round_mode, rank, oversample, power_iters,
-                          seed, nullptr, w.U, w.Sig, w.Vt, w.subA, w.subA_bytes, ast, before_svd));
+                          seed, nullptr, w.U, w.Sig, w.Vt, w.subA, w.subA_bytes, ast, &svdA));
     opsA.push_back([=] { prof_mark(slot, 2, ast); return LRQMM_OK; });
     opsB.push_back([=] { prof_mark(slot, 3, bst); return LRQMM_OK; });
     // B's chain is the critical one.  With a factorization to follow, its first kernel fills the sketch
@@ -557,17 +547,64 @@ int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int
     opsB.push_back([=] { prof_mark(slot, 4, bst); return LRQMM_OK; });
     if (rank > 0)
         LRQ_TRY(rsvd_plan(opsB, B, ldb, w.amaxB, K, N, LRQMM_AXIS_COL, bits, round_mode, rank, oversample, power_iters,
-                          seed, nullptr, w.W, w.Gam, w.Zt, w.subB, w.subB_bytes, bst, before_svd_b,
-                          after_svd_b, fuse_b));
+                          seed, nullptr, w.W, w.Gam, w.Zt, w.subB, w.subB_bytes, bst, &svdB, fuse_b));
     opsB.push_back([=] { prof_mark(slot, 5, bst); return LRQMM_OK; });
-    LRQ_TRY(run_interleaved(opsB, opsA));
-    if (overlap) {
-        if (hipEventRecord(g_side.join, ast) != hipSuccess) return LRQMM_ERR_HIP;
-        if (hipStreamWaitEvent(pst, g_side.join, 0) != hipSuccess) return LRQMM_ERR_HIP;
+
+    // Nothing has been enqueued so far.  From the fork on, every path -- errors included -- joins the
+    // library's streams back into the caller's, so that a capture is never left with an open branch
+    // and a later call never meets work of a failed one.
+    bool forked = false, gemm_forked = false;
+    auto issue = [&]() -> int {
+        int rc;
+        if (overlap) {
+            if (hipEventRecord(side->fork, pst) != hipSuccess) return LRQMM_ERR_HIP;
+            forked = true;
+            if (hipStreamWaitEvent(ast, side->fork, 0) != hipSuccess) return LRQMM_ERR_HIP;
+        }
+        if (!early) return run_interleaved(opsB, opsA);
+        // everything that precedes the two small SVDs
+        LRQ_TRY(run_interleaved(opsB, 0, svdB, opsA, 0, svdA));
+        // Both gates are recorded here, in this call, before anything waits on them: the integer
+        // product needs both operands' codes, and starting it behind the kernels that precede both
+        // SVDs keeps it out of the passes' way.
+        if (hipEventRecord(side->gate_b, bst) != hipSuccess) return LRQMM_ERR_HIP;
+        if (hipEventRecord(side->gate, ast) != hipSuccess) return LRQMM_ERR_HIP;
+        LRQ_TRY(opsB[svdB]());
+        LRQ_TRY(opsA[svdA]());
+        gemm_forked = true;
+        for (hipEvent_t e : {side->gate, side->gate_b})
+            if (hipStreamWaitEvent(gst, e, 0) != hipSuccess) return LRQMM_ERR_HIP;
+        // The product must not take the CUs before the two SVD workgroups have theirs: a few minimal
+        // kernels give the SVD launches (one dependent launch behind their events) a head start.  The
+        // two SVD workgroups hold a CU each while the product runs.
+        const int resident = side->cus - 2;
+        for (int t = 0; t < 3; ++t) LRQ_TRY(launch_tick(w.tick, gst));
+        prof_mark(slot, 9, gst);
+        rc = launch_int8_gemm_sums(M, N, K, w.Aq, w.BqT, reinterpret_cast<int32_t*>(C), resident, w.parts, gst);
+        prof_mark(slot, 10, gst);
+        if (rc != LRQMM_OK) return rc;
+        LRQ_TRY(launch_int8_gemm_sums_finish(M, N, K, w.Aq, w.BqT, reinterpret_cast<int32_t*>(C), resident, w.parts, gst));
+        if (hipEventRecord(side->gdone, gst) != hipSuccess) return LRQMM_ERR_HIP;
+        return run_interleaved(opsB, svdB + 1, opsB.size(), opsA, svdA + 1, opsA.size());
+    };
+    rc = issue();
+    if (forked) {
+        if (hipEventRecord(side->join, ast) != hipSuccess || hipStreamWaitEvent(pst, side->join, 0) != hipSuccess)
+            rc = rc != LRQMM_OK ? rc : LRQMM_ERR_HIP;
     }
-    prof_mark(slot, 6, pst);
-    return gemm_impl(M, N, K, bits, rank, w.Aq, w.amaxA, w.BqT, w.amaxB, w.U, w.Sig, w.Vt, w.W, w.Gam, w.Zt,
-                     GemmOut{D, ldd, alpha, beta}, nullptr, w.sub, w.sub_bytes, stream, slot, early ? g_side.gdone : nullptr);
+    if (rc == LRQMM_OK) {
+        prof_mark(slot, 6, pst);
+        rc = gemm_impl(M, N, K, bits, rank, w.Aq, w.amaxA, w.BqT, w.amaxB, w.U, w.Sig, w.Vt, w.W, w.Gam, w.Zt,
+                       GemmOut{D, ldd, alpha, beta}, nullptr, w.sub, w.sub_bytes, stream, slot,
+                       early ? side->gdone : nullptr);
+    }
+    if (rc != LRQMM_OK && gemm_forked) {
+        // failed somewhere behind the fork of the third stream: join it too (a second record of the
+        // event after a successful first one is harmless)
+        (void)hipEventRecord(side->gdone, gst);
+        (void)hipStreamWaitEvent(pst, side->gdone, 0);
+    }
+    return rc;
 }
 
 namespace {

@@ -847,7 +847,7 @@ namespace {
 struct SumsPlan { int tiles_n, ntiles, left, slices; };
 // Which tiles of the raw-sum product are cut along K when only `resident` CUs are free.
 SumsPlan plan_sums(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, int resident) {
-    const bool vec = (K % 16 == 0) && (((uintptr_t)Aq | (uintptr_t)BqT) & 15) == 0;
+    const bool vec = (K % 16 == 0) && K >= 16 && (((uintptr_t)Aq | (uintptr_t)BqT) & 15) == 0;
     const bool full = vec && int8_gemm_large_tiles(M, N) && M % BTM == 0 && N % BTN == 0 && K % BBK == 0 && K >= BBK;
     SumsPlan p = {N / BTN, (M / BTM) * (N / BTN), 0, 1};
     // (with many rounds the last one matters little, and the free CUs change along the way)
@@ -908,10 +908,30 @@ int launch_rank_update(int M, int N, float* C, const float* sA, const float* sB,
     return LRQMM_OK;
 }
 
+// K == 0: every sum is empty.  One thread per output element.
+__global__ __launch_bounds__(256) void empty_product_kernel(int M, int N, GemmOut out, int32_t* __restrict__ Cint) {
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (size_t)M * N) return;
+    const int row = (int)(idx / N), col = (int)(idx % N);
+    if (Cint) Cint[idx] = 0;
+    if (out.C) store_out(out, row, col, 0.0f);
+}
+
+int launch_empty_product(int M, int N, GemmOut C, int32_t* Cint, hipStream_t st) {
+    const size_t total = (size_t)M * N;
+    if (total == 0) return LRQMM_OK;
+    hipLaunchKernelGGL(empty_product_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, M, N, C, Cint);
+    LRQ_CHECK_LAUNCH();
+    return LRQMM_OK;
+}
+
 int launch_int8_gemm(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, const float* sA,
                      const float* sB, const float* Lp, const float* Rp, int R2P, GemmOut C, int32_t* Cint,
                      hipStream_t st) {
-    const bool vec = (K % 16 == 0) && (((uintptr_t)Aq | (uintptr_t)BqT) & 15) == 0;
+    // the GEMM kernels issue their first operand loads unconditionally: an empty reduction never reaches them
+    if (K <= 0) return launch_empty_product(M, N, C, Cint, st);
+    // (the 16-byte load path clamps its address to K - 16, so it needs at least one whole group)
+    const bool vec = (K % 16 == 0) && K >= 16 && (((uintptr_t)Aq | (uintptr_t)BqT) & 15) == 0;
     const bool comp = Lp != nullptr;
     // big problems: 256x256 tiles, one workgroup per CU
     const int btiles = ceil_div(M, BTM) * ceil_div(N, BTN);

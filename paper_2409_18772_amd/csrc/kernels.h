@@ -116,6 +116,9 @@ struct GemmOut {
 int launch_int8_gemm(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, const float* sA,
                      const float* sB, const float* Lp, const float* Rp, int R2P, GemmOut C,
                      int32_t* Cint, hipStream_t st);
+// The product with an empty reduction (K == 0): D <- alpha * 0 + beta * D (D not read when beta == 0) and,
+// when Cint is given, zeros in Cint.  Reads no operand.
+int launch_empty_product(int M, int N, GemmOut C, int32_t* Cint, hipStream_t st);
 // The raw int32 sums alone (C_int, row stride N), for a chip on which only `resident` CUs are
 // free (0: unknown): with one 256x256 tile per workgroup, the tiles beyond a whole number of
 // rounds over those CUs would cost a full extra round; they are cut along K instead, one

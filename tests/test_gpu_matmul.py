@@ -17,7 +17,7 @@ import pytest
 
 from oracle import lrqmm_oracle as o
 import lrqmm_workloads as wl
-from gpu_util import say, to_dev, to_np, rel_fro
+from gpu_util import say, to_dev, to_np, rel_fro, check_elementwise
 
 pytestmark = pytest.mark.gpu
 
@@ -43,6 +43,7 @@ def test_config_one_full():
     C = _run_gpu(w, A, B)
     ref = o.lrqmm(A, B, w.bits, w.rank, w.oversample, w.power_iters, seed=w.sketch_seed)
     assert rel_fro(ref["C"], C) < TOL
+    check_elementwise(C, ref, w.rank, what=w.name)
     exact = o.exact_product(A, B)
     assert o.rel_err(exact, C) <= o.rel_err(exact, ref["C0"])
     # bit-identical on a second run (no atomics on floats, fixed reduction orders)
@@ -69,6 +70,7 @@ def test_scaled_configs_full_output(name, M, N, K):
     d = rel_fro(ref["C"], C)
     say(w.name, "gpu vs oracle", d, "tol", tol_for(ref))
     assert d < tol_for(ref)
+    check_elementwise(C, ref, w.rank, what=w.name)
 
 
 def test_rank_zero_is_direct_quant_and_modes():
@@ -79,6 +81,7 @@ def test_rank_zero_is_direct_quant_and_modes():
         C = to_np(L.lrqmm_matmul(to_dev(A), to_dev(B), 8, 0, round_mode=mode))
         ref = o.lrqmm(A, B, 8, 0, round_mode=mode)
         assert rel_fro(ref["C"], C) < 1e-6
+        check_elementwise(C, ref, 0, what=f"rank 0, round mode {mode}")
     C = to_np(L.lrqmm_matmul(to_dev(A), to_dev(B), 4, 6, 2, 1, seed=3, round_mode=o.NEAREST))
     ref = o.lrqmm(A, B, 4, 6, 2, 1, seed=3, round_mode=o.NEAREST)
     assert rel_fro(ref["C"], C) < TOL
@@ -123,6 +126,7 @@ def test_full_size_sampled_rows(name):
     d = rel_fro(ref["C"], C[rows])
     say(name, "gpu vs oracle", d, "tol", tol_for(ref))
     assert d < tol_for(ref)
+    check_elementwise(C[rows], ref, w.rank, rows, what=name)
     exact = o.exact_product(A[rows], B)
     e_lr, e_dq = o.rel_err(exact, C[rows]), o.rel_err(exact, ref["C0"])
     say(name, "err lrqmm", e_lr, "err direct quant", e_dq)
@@ -140,12 +144,136 @@ def test_resnet_conv_shape_sampled_rows():
     ref = o.lrqmm(A, B, w.bits, w.rank, w.oversample, w.power_iters, seed=w.sketch_seed, row_sample=rows,
                   want_cint=False)
     assert rel_fro(ref["C"], C[rows]) < TOL
+    check_elementwise(C[rows], ref, w.rank, rows, what=w.name)
+
+
+# Rows of C checked against the oracle at 16384^3.  With one 256 x 256 tile per workgroup and two compute
+# units held by the small SVDs, the early integer product cuts the tiles beyond a whole number of rounds
+# along K; in the launch order of a 64 x 64 tile grid dealt to 8 XCDs those are whole tile rows 31 and 63
+# (rows 7936-8191 and 16128-16383), so the sample takes three rows from each and eight drawn at random.
+C4_ROWS = np.concatenate([[7936, 8050, 8191, 16128, 16250, 16383],
+                          np.random.default_rng(7).choice(16384, size=8, replace=False)])
+
+
+def test_largest_config_oracle_rows():
+    """c4 (16384^3, int4, r = 64, l = 80, two power iterations) at full size, in the benchmark's launch
+    configuration, against the oracle: both residual factorizations in full, C on sampled rows (rows of C
+    are independent given the factors)."""
+    import torch
+    import paper_2409_18772_amd as L
+    w = wl.CONFIGS["c4_16384_int4_r64"]
+    say("inputs", w.name)
+    A, B = wl.make_inputs(w)
+    dA, dB = to_dev(A), to_dev(B)
+    ws = L.Workspace.for_problem(w.M, w.N, w.K, w.rank, w.oversample)
+    say("matmul full", w.name)
+    C = L.lrqmm_matmul(dA, dB, w.bits, w.rank, w.oversample, w.power_iters, seed=w.sketch_seed, workspace=ws)
+    rows = np.sort(C4_ROWS)
+    Cr = C[torch.from_numpy(rows).cuda()].cpu().numpy()
+    del C, dA, dB, ws
+    torch.cuda.empty_cache()
+    say("oracle: factorizations in full, C on", len(rows), "rows")
+    ref = o.lrqmm(A, B, w.bits, w.rank, w.oversample, w.power_iters, seed=w.sketch_seed, row_sample=rows,
+                  want_cint=False)
+    d = rel_fro(ref["C"], Cr)
+    say(w.name, "gpu vs oracle", d, "tol", tol_for(ref))
+    assert d < tol_for(ref)
+    check_elementwise(Cr, ref, w.rank, rows, what=w.name)
+    exact = o.exact_product(A[rows], B)
+    e_lr, e_dq = o.rel_err(exact, Cr), o.rel_err(exact, ref["C0"])
+    say(w.name, "err lrqmm", e_lr, "err direct quant", e_dq)
+    assert e_lr * 10.0 < e_dq
+
+
+RAGGED_LARGE = [
+    # shapes on the 256 x 256 tile kernel that are no multiples of its tile: guarded loads, guarded
+    # epilogue, clamped rows and columns of the rank update
+    (4100, 2052, 528),      # K % 16 == 0: 16-byte operand loads with guards
+    (4100, 2052, 500),      # byte-wise operand loads
+]
+
+
+@pytest.mark.parametrize("M,N,K", RAGGED_LARGE)
+@pytest.mark.parametrize("fused", [False, True])
+def test_ragged_large_tile_shapes(M, N, K, fused):
+    """fused = False: beta = 0 and a dense D, the schedule with the early integer product and the rank
+    update as a kernel of its own; fused = True: a strided D with beta != 0, the GEMM with the fused
+    epilogue.  Oracle on sampled rows, including the last (partial) tile row."""
+    import torch
+    import paper_2409_18772_amd as L
+    bits, r, p, q = 4, 12, 4, 1
+    A = wl.random_matrix("normal", M, K, seed=41)
+    B = wl.random_matrix("uniform01", K, N, seed=42)
+    rows = np.sort(np.concatenate([[0, 255, 256, 4095, 4096, M - 1],
+                                   np.random.default_rng(8).choice(M, size=10, replace=False)]))
+    say("ragged large tiles", M, N, K, "fused" if fused else "early product")
+    ref = o.lrqmm(A, B, bits, r, p, q, seed=11, row_sample=rows, want_cint=False)
+    if not fused:
+        C = to_np(L.lrqmm_matmul(to_dev(A), to_dev(B), bits, r, p, q, seed=11))
+        d = rel_fro(ref["C"], C[rows])
+        say("gpu vs oracle", d, "tol", tol_for(ref))
+        assert d < tol_for(ref)
+        check_elementwise(C[rows], ref, r, rows, what="ragged early")
+        return
+    alpha, beta = 1.5, -0.5
+    D0 = wl.random_matrix("normal", M, N, seed=43)
+    big = torch.full((M, N + 3), -7.0, dtype=torch.float32, device="cuda")
+    dD = big[:, :N]
+    dD.copy_(torch.from_numpy(D0))
+    L.lrqmm_matmul_ex(to_dev(A), to_dev(B), dD, bits, r, p, q, seed=11, alpha=alpha, beta=beta)
+    got = to_np(dD)[rows].astype(np.float64)
+    want = o.scaled_update(ref["C"], alpha, beta, D0[rows])
+    # the update of the plain product: |alpha| times its error plus three roundings (see test_gpu_update_strides.py)
+    nc, nd = np.linalg.norm(ref["C"]), np.linalg.norm(D0[rows])
+    bound = abs(alpha) * tol_for(ref) * nc + 3 * 2.0 ** -24 * (abs(alpha) * nc + abs(beta) * nd)
+    err = np.linalg.norm(got - want)
+    say("gpu vs oracle", err, "bound", bound)
+    assert err < bound
+    # element-wise: the product's budget scaled by |alpha| plus the three roundings of the update
+    from gpu_util import elementwise_budget
+    budget, _ = elementwise_budget(ref, r, rows)
+    lim = abs(alpha) * budget + 3 * 2.0 ** -24 * (abs(alpha) * np.abs(ref["C"]) + abs(beta) * np.abs(D0[rows]))
+    assert np.all(np.abs(got - want) <= lim)
+    assert np.all(to_np(big)[:, N:] == -7.0)
+
+
+def test_empty_reduction_reads_no_operand():
+    """K = 0 with M, N > 0: C_F = 0, so D <- beta D (zeros when beta = 0); the GEMM kernels are not
+    launched at all (they load their first operand tile unconditionally)."""
+    import torch
+    import paper_2409_18772_amd as L
+    M, N = 300, 260
+    A = torch.empty((M, 0), dtype=torch.float32, device="cuda")
+    B = torch.empty((0, N), dtype=torch.float32, device="cuda")
+    say("K = 0: matmul")
+    C = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    L.lrqmm_matmul(A, B, 8, 0, C=C)
+    assert torch.all(C == 0)
+    D0 = wl.random_matrix("normal", M, N, seed=3)
+    D = to_dev(D0)
+    L.lrqmm_matmul_ex(A, B, D, 4, 0, alpha=2.0, beta=-1.5)
+    assert np.array_equal(to_np(D), np.float32(-1.5) * D0)
+    say("K = 0: gemm")
+    Aq = torch.empty((M, 0), dtype=torch.int8, device="cuda")
+    BqT = torch.empty((N, 0), dtype=torch.int8, device="cuda")
+    am, an = torch.ones(M, device="cuda"), torch.ones(N, device="cuda")
+    C2, Cint = L.lrqmm_gemm(Aq, am, BqT, an, 8, want_cint=True)
+    assert torch.all(C2 == 0) and torch.all(Cint == 0)
+    say("K = 0: residual_matmul")
+    D = to_dev(D0)
+    L.lrqmm_residual_matmul(A, B, D, 4, 4, alpha=1.0, beta=1.0)
+    assert np.array_equal(to_np(D), D0)
+    # large enough for the 256 x 256 tile kernel's dispatch
+    M, N = 4096, 2048
+    C = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    L.lrqmm_matmul(torch.empty((M, 0), dtype=torch.float32, device="cuda"),
+                   torch.empty((0, N), dtype=torch.float32, device="cuda"), 4, 0, C=C)
+    assert torch.all(C == 0)
 
 
 def test_largest_config_properties():
-    """c4 (16384^3, l = 80, two power iterations) at full size: the oracle's factorization of two
-    16384^2 residuals does not fit a test's time budget, so this checks what must hold at any size:
-    finite output, bit-identical repeat, and on sampled rows an error against the exact float64
+    """c4 (16384^3, l = 80, two power iterations) at full size, properties beside the oracle comparison
+    above: finite output, bit-identical repeat, and on sampled rows an error against the exact float64
     product far below that of direct (floor) quantization computed by the same library."""
     import torch
     import paper_2409_18772_amd as L
@@ -210,6 +338,41 @@ def test_call_can_be_captured_in_a_graph(shape):
         step()                       # eager work between replays
         torch.cuda.synchronize()
         assert torch.equal(C, ref), i
+
+
+def test_capture_with_profiling_on_is_refused():
+    """Timing events do not belong in a graph: a call under stream capture with stage timing enabled
+    returns LRQMM_ERR_UNSUPPORTED before it enqueues anything, and the capture stays valid (empty)."""
+    import torch
+    import paper_2409_18772_amd as L
+    M, N, K = 300, 200, 260
+    A = to_dev(wl.random_matrix("normal", M, K, seed=31))
+    B = to_dev(wl.random_matrix("normal", K, N, seed=32))
+    ws = L.Workspace.for_problem(M, N, K, 8, 4)
+    C = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    L.lrqmm_matmul(A, B, 4, 8, 4, 1, seed=7, workspace=ws, C=C)      # library streams exist from here on
+    torch.cuda.synchronize()
+    ref = C.clone()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    tmp = torch.ones(16, device="cuda")
+    L.lrqmm_profile_enable(True)
+    status = None
+    try:
+        with torch.cuda.graph(g, stream=s):
+            tmp.zero_()                  # (the graph is not empty)
+            try:
+                L.lrqmm_matmul(A, B, 4, 8, 4, 1, seed=7, workspace=ws, C=C)
+            except L.LrqmmError as e:
+                status = e.status
+    finally:
+        L.lrqmm_profile_enable(False)
+    torch.cuda.synchronize()
+    assert status == -2
+    L.lrqmm_matmul(A, B, 4, 8, 4, 1, seed=7, workspace=ws, C=C)      # the library still works
+    torch.cuda.synchronize()
+    assert torch.equal(C, ref)
 
 
 def test_gemm_only_profiling_mode():
