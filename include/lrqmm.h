@@ -40,6 +40,7 @@ extern "C" {
 #define LRQMM_ERR_UNSUPPORTED   -2   /* bits outside [2,8], K too large for int32, l > LRQMM_MAX_SKETCH */
 #define LRQMM_ERR_WORKSPACE     -3   /* workspace missing, misaligned or too small */
 #define LRQMM_ERR_HIP           -4   /* a HIP launch failed */
+#define LRQMM_ERR_STATIC_LIMIT  -5   /* lrqmm_gemm_static: the problem needs more than LRQMM_STATIC_SCRATCH_BYTES */
 
 #define LRQMM_AXIS_ROW  0
 #define LRQMM_AXIS_COL  1
@@ -160,6 +161,28 @@ LRQMM_API int lrqmm_gemm_ex(int M, int N, int K, int bits, int rank,
                   const float* W, const float* Gam, const float* Zt,
                   float alpha, float beta, float* D, int ldd, int32_t* Cint_or_null,
                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * lrqmm_gemm_ex for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and bit-identical results; the scratch memory (step vectors, padded factor copies, partial
+ * code products and the two panels of the rank-2r update) is a fixed array of
+ * LRQMM_STATIC_SCRATCH_BYTES bytes inside the library's device image, one copy per GPU, held until
+ * the process ends.  The call allocates and frees nothing.  (Its first call on a device looks the
+ * array's address up; make that call outside a capture.)
+ * Problems that need more than LRQMM_STATIC_SCRATCH_BYTES return LRQMM_ERR_STATIC_LIMIT and enqueue
+ * nothing (the need is what lrqmm_workspace_bytes reports for lrqmm_gemm alone, about
+ * 4 (M + N) (3 rank + 4 rank * splits) + 20 K rank bytes; 16 MiB covers M = N = K = 4096 at rank 32).
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams,
+ * two threads) race on it and must be serialised by the caller; a call does not depend on what an
+ * earlier call left there (every word a kernel reads is written earlier in the same call).
+ */
+#define LRQMM_STATIC_SCRATCH_BYTES (16u << 20)
+LRQMM_API int lrqmm_gemm_static(int M, int N, int K, int bits, int rank,
+                      const int8_t* Aq, const float* amaxA, const int8_t* BqT, const float* amaxB,
+                      const float* U, const float* Sig, const float* Vt,
+                      const float* W, const float* Gam, const float* Zt,
+                      float alpha, float beta, float* D, int ldd, int32_t* Cint_or_null, void* stream);
 
 /*
  * The whole hot path, all of Algorithm 2 except its final alpha/beta update, from float32 A (M x K) and

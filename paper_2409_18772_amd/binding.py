@@ -18,7 +18,8 @@ _LIB = None
 EXPORTS = ("lrqmm_status_string", "lrqmm_workspace_bytes", "lrqmm_quantize", "lrqmm_fill_sketch",
            "lrqmm_rsvd", "lrqmm_gemm", "lrqmm_matmul", "lrqmm_profile_enable", "lrqmm_profile_read",
            "lrqmm_quantize_ex", "lrqmm_rsvd_ex", "lrqmm_gemm_ex", "lrqmm_matmul_ex",
-           "lrqmm_quantize_residual", "lrqmm_residual_workspace_bytes", "lrqmm_residual_matmul")
+           "lrqmm_quantize_residual", "lrqmm_residual_workspace_bytes", "lrqmm_residual_matmul",
+           "lrqmm_gemm_static")
 PROF_STAGES = ("quantize_a", "rsvd_a", "quantize_b", "rsvd_b", "panels", "gemm", "int_gemm")
 
 
@@ -65,6 +66,8 @@ def load_library() -> ctypes.CDLL:
     lib.lrqmm_rsvd_ex.argtypes = [c_vp, c_int, c_vp] + [c_int] * 8 + [c_u64, c_vp, c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
     lib.lrqmm_gemm_ex.restype = c_int
     lib.lrqmm_gemm_ex.argtypes = [c_int] * 5 + [c_vp] * 10 + [c_f, c_f, c_vp, c_int, c_vp, c_vp, c_sz, c_vp]
+    lib.lrqmm_gemm_static.restype = c_int
+    lib.lrqmm_gemm_static.argtypes = [c_int] * 5 + [c_vp] * 10 + [c_f, c_f, c_vp, c_int, c_vp, c_vp]
     lib.lrqmm_matmul_ex.restype = c_int
     lib.lrqmm_matmul_ex.argtypes = [c_int] * 7 + [c_u64, c_int, c_int, c_vp, c_int, c_vp, c_int, c_f, c_f, c_vp,
                                     c_int, c_vp, c_sz, c_vp]
@@ -310,6 +313,45 @@ def lrqmm_gemm_ex(Aq, amaxA, BqT, amaxB, bits: int, D, alpha: float = 1.0, beta:
                                       float(beta), _ptr(D), ldd, _ptr(Cint), ctypes.c_void_p(workspace.ptr),
                                       workspace.nbytes, _stream())
     _check(st, "lrqmm_gemm_ex")
+    return (D, Cint) if want_cint else D
+
+
+STATIC_SCRATCH_BYTES = 16 << 20
+ERR_STATIC_LIMIT = -5
+
+
+def lrqmm_gemm_static(Aq, amaxA, BqT, amaxB, bits: int, D, alpha: float = 1.0, beta: float = 0.0, factors_a=None,
+                      factors_b=None, want_cint: bool = False):
+    """lrqmm_gemm_ex on the library's static scratch buffer: no workspace, nothing allocated by the call
+    itself (the optional int32 output is the caller's choice)."""
+    import torch
+    _dev(Aq, torch.int8, "Aq")
+    _dev(BqT, torch.int8, "BqT")
+    _dev(amaxA, torch.float32, "amaxA")
+    _dev(amaxB, torch.float32, "amaxB")
+    M, K = Aq.shape
+    N, K2 = BqT.shape
+    if K != K2:
+        raise ValueError("Aq is M x K and BqT is N x K")
+    ldd = _dev2d(D, torch.float32, "D")
+    if tuple(D.shape) != (M, N):
+        raise ValueError("D must be M x N")
+    rank = 0
+    U = Sig = Vt = W = Gam = Zt = None
+    if factors_a is not None:
+        U, Sig, Vt = factors_a
+        W, Gam, Zt = factors_b
+        for n, t in (("U", U), ("Sig", Sig), ("Vt", Vt), ("W", W), ("Gam", Gam), ("Zt", Zt)):
+            _dev(t, torch.float32, n)
+        rank = Sig.numel()
+        if tuple(U.shape) != (M, rank) or tuple(Vt.shape) != (rank, K) or tuple(W.shape) != (K, rank) \
+                or tuple(Zt.shape) != (rank, N) or Gam.numel() != rank:
+            raise ValueError("factor shapes")
+    Cint = torch.empty((M, N), dtype=torch.int32, device=Aq.device) if want_cint else None
+    st = load_library().lrqmm_gemm_static(M, N, K, bits, rank, _ptr(Aq), _ptr(amaxA), _ptr(BqT), _ptr(amaxB),
+                                          _ptr(U), _ptr(Sig), _ptr(Vt), _ptr(W), _ptr(Gam), _ptr(Zt), float(alpha),
+                                          float(beta), _ptr(D), ldd, _ptr(Cint), _stream())
+    _check(st, "lrqmm_gemm_static")
     return (D, Cint) if want_cint else D
 
 

@@ -183,6 +183,26 @@ Side* side_state(bool create) {
     return &s;
 }
 
+// Scratch memory of lrqmm_gemm_static: a fixed array in the library's device image (every GPU that loads
+// the library holds its own copy, at its own address, until the process ends).  In host code the array's
+// name is only a handle for hipGetSymbolAddress; the device address is looked up once per device, with
+// that device current, and kept.
+static __device__ __align__(256) unsigned char scratch[LRQMM_STATIC_SCRATCH_BYTES];
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void** out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LRQMM_ERR_HIP;
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return LRQMM_ERR_HIP;
+        if ((uintptr_t)ptr & 255) return LRQMM_ERR_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return LRQMM_OK;
+}
+
 inline void prof_mark(int slot, int i, hipStream_t st) {
     if (slot < 0) return;
     if (g_prof.gemm_only) {     // events 9, 10 bracket the early product, 7, 8 the fused kernel
@@ -310,6 +330,7 @@ const char* lrqmm_status_string(int status) {
         case LRQMM_ERR_UNSUPPORTED: return "unsupported configuration";
         case LRQMM_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case LRQMM_ERR_HIP: return "HIP launch failed";
+        case LRQMM_ERR_STATIC_LIMIT: return "problem needs more scratch memory than the library's static buffer holds";
         default: return "unknown status";
     }
 }
@@ -456,6 +477,23 @@ int lrqmm_gemm_ex(int M, int N, int K, int bits, int rank, const int8_t* Aq, con
     const GemmOut out = {D, ldd, alpha, beta};
     return gemm_impl(M, N, K, bits, rank, Aq, amaxA, BqT, amaxB, U, Sig, Vt, W, Gam, Zt, out, Cint_or_null,
                      workspace, workspace_bytes, stream, -1);
+}
+
+int lrqmm_gemm_static(int M, int N, int K, int bits, int rank, const int8_t* Aq, const float* amaxA,
+                      const int8_t* BqT, const float* amaxB, const float* U, const float* Sig, const float* Vt,
+                      const float* W, const float* Gam, const float* Zt, float alpha, float beta, float* D, int ldd,
+                      int32_t* Cint_or_null, void* stream) {
+    if (M < 0 || N < 0 || K < 0 || rank < 0 || ldd < N) return LRQMM_ERR_INVALID_ARG;
+    if (rank > LRQMM_MAX_SKETCH) return LRQMM_ERR_UNSUPPORTED;
+    if (M == 0 || N == 0) return LRQMM_OK;
+    Arena a(nullptr);
+    if (carve_gemm(a, M, N, K, rank, nullptr) > (size_t)LRQMM_STATIC_SCRATCH_BYTES) return LRQMM_ERR_STATIC_LIMIT;
+    void* ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc != LRQMM_OK) return rc;
+    const GemmOut out = {D, ldd, alpha, beta};
+    return gemm_impl(M, N, K, bits, rank, Aq, amaxA, BqT, amaxB, U, Sig, Vt, W, Gam, Zt, out, Cint_or_null, ws,
+                     LRQMM_STATIC_SCRATCH_BYTES, stream, -1);
 }
 
 int lrqmm_matmul(int M, int N, int K, int bits, int rank, int oversample, int power_iters, uint64_t seed,
