@@ -37,6 +37,21 @@ def read_traffic(name: str, key: str = "traffic_bytes_per_launch"):
     return None
 
 
+INPUT_TEXT = {
+    "uniform_pm1": "U[-1,1]",
+    "normal": "N(0,1)",
+    "normal_outliers": "N(0,1) with 0.1% entries from N(0,20^2)",
+    "relu_normal": "A = max(0, N(0,1)), B ~ N(0, 2/K)",
+}
+SHORT = {"c1_256_int8_r8": "c1", "c2_4096_int8_r16": "c2", "c3_4096_int4_r32_outliers": "c3",
+         "c4_16384_int4_r64": "c4", "c5_resnet50_conv_int4_r8": "c5"}
+
+
+def metric_text(w):
+    shape = f"{w.M}^3" if w.M == w.N == w.K else f"{w.M}x{w.N}x{w.K}"
+    return f"LRQMM effective TOPS (2MNK/t) at {shape} int{w.bits} r={w.rank}; rel. error vs direct quant"
+
+
 def cpu_baseline(w, A, B, budget_rows: int):
     """Time the oracle (as it stands) on a bounded sample: all O(N^2) stages in full, the
     O(N^3) integer product / compensation / exact product on `budget_rows` rows of C."""
@@ -67,7 +82,10 @@ def cpu_baseline(w, A, B, budget_rows: int):
         "sample": (f"oracle.lrqmm on the same inputs: quantization and both residual factorizations in full, "
                    f"integer GEMM/compensation on {len(rows)} of {w.M} rows of C ({t_sample:.1f} s measured); "
                    f"row-proportional time {per_row * 1e3:.1f} ms/row extrapolated to all rows "
-                   f"({t_full:.0f} s)"),
+                   f"({t_full:.0f} s).  Threads: the float64 stages (residual products, QR, SVD, compensation) "
+                   f"run on the BLAS pool of {int(threads)} threads; the quantizer is single-threaded numpy and "
+                   f"the int64 integer product, which is the row-proportional part, runs on 1 thread (numpy has "
+                   f"no BLAS for integers)"),
     }
 
 
@@ -79,6 +97,10 @@ def main():
     ap.add_argument("--workload", default="c3_4096_int4_r32_outliers")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=48)
+    ap.add_argument("--precision-modes", action="store_true",
+                    help="also time the reduced-precision compensation modes and report their errors")
+    ap.add_argument("--no-baselines", action="store_true",
+                    help="skip the complete-residual-compensation baselines (several extra full-size GEMMs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 64 MiB device copy (reference for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -190,28 +212,44 @@ def main():
 
     # complete residual compensation (Eq. (gemm_r_split) with three / four full-size integer GEMMs): the
     # alternative that the low-rank terms replace, on the same inputs and by the same library
-    rws = L.Workspace(L.lrqmm_residual_workspace_bytes(w.M, w.N, w.K))
     full_residual = {}
-    for terms, name in ((3, "three_terms_QT110"), (4, "four_terms_QT111")):
+    rws = None if args.no_baselines else L.Workspace(L.lrqmm_residual_workspace_bytes(w.M, w.N, w.K))
+    for terms, name in (() if args.no_baselines else ((3, "three_terms_QT110"), (4, "four_terms_QT111"))):
         fn = lambda: L.lrqmm_residual_matmul(dA, dB, C, w.bits, terms, workspace=rws)
         t_r = timed(fn, max(5, args.steps // 2), 2)
         full_residual[name] = {"ms": round(t_r * 1e3, 4), "rel_error": o.rel_err(exact, C.cpu().numpy()[rows])}
     del rws
 
+    # reduced-precision compensation modes (lrqmm.h, LRQMM_PREC_*): step time, error against the exact product
+    # and distance from the default mode's output, on the same sampled rows
+    precision_modes = {}
+    if args.precision_modes and w.rank > 0:
+        for pname, mode in (("bf16x2_subspace_only", L.PREC_SUBSPACE_BF16X2), ("bf16x2", L.PREC_BF16X2),
+                            ("bf16", L.PREC_BF16)):
+            fn = lambda: L.lrqmm_matmul_ex(dA, dB, C, w.bits, w.rank, w.oversample, w.power_iters,
+                                           seed=w.sketch_seed, workspace=ws, precision=mode)
+            t_m = timed(fn, args.steps, 3)
+            Cm = C.cpu().numpy()[rows]
+            precision_modes[pname] = {
+                "ms_per_step": round(t_m * 1e3, 4), "rel_error": o.rel_err(exact, Cm),
+                "distance_from_default": float(np.linalg.norm(Cm.astype(np.float64) - Cn[rows])
+                                               / np.linalg.norm(Cn[rows].astype(np.float64)))}
+
     out = {
-        "metric": "LRQMM effective TOPS (2MNK/t) at 4096^3 int4 r=32; rel. error vs direct quant",
+        "metric": metric_text(w),
         "value": round(tops, 3), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(t_step * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": w.name, "M": w.M, "N": w.N, "K": w.K, "bits": w.bits, "rank": w.rank,
                    "oversample": w.oversample, "power_iters": w.power_iters, "sketch_seed": w.sketch_seed,
-                   "inputs": "N(0,1) with 0.1% entries from N(0,20^2), seeds 0/1"},
+                   "inputs": f"{INPUT_TEXT.get(w.kind, w.kind)}, seeds {w.seed_a}/{w.seed_b}"},
         "roofline": {"kernel": ("int8_gemm256_kernel (int8 MFMA GEMM, raw int32 sums; on the library's third "
                                 "stream beside the single-workgroup SVD kernels)") if early else
                                "int8_gemm256_kernel (int8 MFMA GEMM + fused dequant and rank-2r epilogue)",
                      "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                      "frac": round(achieved / PEAK_INT8_TOPS, 4),
-                     "traffic": read_traffic("int8_gemm_c3_pmc.txt") if early else None,
+                     # counter bytes of this kernel on this workload, or null when no summary is tracked for it
+                     "traffic": read_traffic(f"int8_gemm_{SHORT.get(w.name, w.name)}_pmc.txt") if early else None,
                      "launch_ms": round(stages[gemm_key], 4), "ops_per_launch": ops},
         "stages": stage_info,
         "stages_note": "GEMM launch time from HIP events inside the timed region; the other stages from a "
@@ -222,6 +260,8 @@ def main():
                       "gain_vs_floor": err_dq / err_lr, "rows_sampled": int(len(rows))},
         "full_residual_baselines": full_residual,
     }
+    if precision_modes:
+        out["precision_modes"] = precision_modes
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, A, B, args.cpu_rows)
     print(json.dumps(out), flush=True)

@@ -51,6 +51,21 @@ extern "C" {
 #define LRQMM_SCALE_VECTOR   0   /* one scale per row of A / per column of B (Background 2.2) */
 #define LRQMM_SCALE_TENSOR   1   /* one scale per matrix, as in the paper's own equations (Eq. (quantA)) */
 
+/* Arithmetic of the compensation path (Methodology, text after Eq. (gemm_r_split): the compensation terms
+ * may be computed in the original precision or in half precision).  It selects how the float32 operands of
+ * the residual products R.Omega, R^T Q, R Z, Q^T R and the factors in A~ W, V^T B~ enter the bfloat16 matrix
+ * cores: as three bfloat16 planes each with the six plane products of weight >= 2^-16 (float32 accuracy),
+ * as two planes with three products (relative error of a product 2^-16), or as plain bfloat16 values (2^-8).
+ * Quantization, the integer product, the Gram/Cholesky/eigen steps (float64) and the rank-2r update of C
+ * (float32) are the same in every mode.  Shapes that take the float32 matrix-core kernels (sketches of up to
+ * 16 columns in LRQMM_PREC_FP32 only; reduction lengths that are no multiple of 16 in the code products) are
+ * computed at full precision.  Measured error budgets of the three modes: the design doc. */
+#define LRQMM_PREC_FP32    0     /* default: float32-equivalent, results match the float64 oracle to 1e-5 */
+#define LRQMM_PREC_BF16X2  1     /* two bfloat16 planes per operand */
+#define LRQMM_PREC_BF16    2     /* one bfloat16 plane per operand: "half precision" */
+#define LRQMM_PREC_SUBSPACE_BF16X2  3   /* two planes in the sketch and power-iteration products, which only shape
+                                           the subspace; three planes where values enter C (Q^T R, code products) */
+
 #define LRQMM_MAX_SKETCH  80     /* largest supported sketch width l = rank + oversample */
 
 /* Human-readable text for a status code (static storage). */
@@ -117,10 +132,11 @@ LRQMM_API int lrqmm_rsvd(const float* X, const float* amax, int rows, int cols, 
                const float* omega_or_null, float* U, float* Sigma, float* Vt,
                void* workspace, size_t workspace_bytes, void* stream);
 
-/* lrqmm_rsvd for an X with row stride ldx >= cols (elements). */
+/* lrqmm_rsvd for an X with row stride ldx >= cols (elements) and a choice of arithmetic for the four
+ * residual products (precision: LRQMM_PREC_*; anything else is LRQMM_ERR_INVALID_ARG). */
 LRQMM_API int lrqmm_rsvd_ex(const float* X, int ldx, const float* amax, int rows, int cols, int axis, int bits,
                   int round_mode, int rank, int oversample, int power_iters, uint64_t seed,
-                  const float* omega_or_null, float* U, float* Sigma, float* Vt,
+                  const float* omega_or_null, int precision, float* U, float* Sigma, float* Vt,
                   void* workspace, size_t workspace_bytes, void* stream);
 
 /*
@@ -214,17 +230,19 @@ LRQMM_API int lrqmm_matmul(int M, int N, int K, int bits, int rank, int oversamp
  *   A  M x K, row stride lda >= K;   B  K x N, row stride ldb >= N;
  *   D  M x N, row stride ldd >= N, input (unless beta == 0) and output
  *   scale_mode  LRQMM_SCALE_VECTOR or LRQMM_SCALE_TENSOR (see lrqmm_quantize_ex)
- * lrqmm_matmul is this call with dense operands, alpha = 1, beta = 0 and vector
- * scales.  Schedule and stream rules are those of lrqmm_matmul; the early integer
+ *   precision   LRQMM_PREC_*: arithmetic of the residual products of both factorizations and of the
+ *               code products A~ W, V^T B~ in the panels
+ * lrqmm_matmul is this call with dense operands, alpha = 1, beta = 0, vector
+ * scales and LRQMM_PREC_FP32.  Schedule and stream rules are those of lrqmm_matmul; the early integer
  * product is used only when beta == 0 and ldd == N (it needs D's memory for the raw
  * sums), otherwise the update is fused into the GEMM's store phase.  Strides that are
  * not multiples of 4 elements (or bases that are not 16-byte aligned) select the
  * scalar-load variants of the streaming kernels.
  * Errors: LRQMM_ERR_INVALID_ARG for a stride below the row length or an unknown
- * scale_mode, otherwise as lrqmm_matmul.
+ * scale_mode or precision, otherwise as lrqmm_matmul.
  */
 LRQMM_API int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int power_iters,
-                    uint64_t seed, int round_mode, int scale_mode,
+                    uint64_t seed, int round_mode, int scale_mode, int precision,
                     const float* A, int lda, const float* B, int ldb,
                     float alpha, float beta, float* D, int ldd,
                     void* workspace, size_t workspace_bytes, void* stream);

@@ -11,4 +11,5 @@ from .binding import (  # noqa: F401
     lrqmm_profile_read, PROF_STAGES, SCALE_VECTOR, SCALE_TENSOR, lrqmm_quantize_ex, lrqmm_rsvd_ex,
     lrqmm_gemm_ex, lrqmm_matmul_ex, lrqmm_quantize_residual, lrqmm_residual_workspace_bytes,
     lrqmm_residual_matmul, PROF_GEMM_ONLY, lrqmm_gemm_static, STATIC_SCRATCH_BYTES, ERR_STATIC_LIMIT,
+    PREC_FP32, PREC_BF16X2, PREC_BF16, PREC_SUBSPACE_BF16X2,
 )

@@ -9,9 +9,9 @@
   size    error against the matrix size at rank 10 (same figure)
 
 Every product runs through lrqmm_matmul_ex (rank 0 = direct quantization, the first term of
-Eq. (gemm_r_split)).  torch is used for device memory, for the float64 reference product
-C_ref = A.B and for the two norms of the error metric |C_ref - X|_F / |C_ref|_F; nothing of the
-method itself is computed outside the library.  One JSON line per measurement.
+Eq. (gemm_r_split)).  torch only holds the device memory; the float64 reference product
+C_ref = A.B and the two norms of the error metric |C_ref - X|_F / |C_ref|_F are numpy on the host;
+nothing of the method itself is computed outside the library.  One JSON line per measurement.
 """
 from __future__ import annotations
 
@@ -32,11 +32,12 @@ def _workloads():
 
 
 def measure(A, B, bits: int, rank: int, oversample: int = 0, power_iters: int = 1, seed: int = 1,
-            per_tensor: bool = True, round_mode: int = 0, rows=None) -> dict:
+            per_tensor: bool = True, round_mode: int = 0, rows=None, precision: int = 0) -> dict:
     """Errors of direct quantization and of LRQMM for host arrays A (M x K), B (K x N).
 
     rows: optional row indices of C on which the errors are evaluated (all rows if None).
     """
+    import numpy as np
     import torch
     from . import binding as L
     dA = torch.from_numpy(A).cuda()
@@ -45,16 +46,16 @@ def measure(A, B, bits: int, rank: int, oversample: int = 0, power_iters: int = 
     N = B.shape[1]
     mode = L.SCALE_TENSOR if per_tensor else L.SCALE_VECTOR
     ws = L.Workspace.for_problem(M, N, K, rank, oversample)
-    ref = dA.double() @ dB.double()
-    sel = slice(None) if rows is None else torch.as_tensor(rows, device="cuda", dtype=torch.long)
-    ref = ref[sel]
-    den = torch.linalg.norm(ref)
+    sel = slice(None) if rows is None else np.asarray(rows, dtype=np.int64)
+    ref = A[sel].astype(np.float64) @ B.astype(np.float64)
+    den = np.linalg.norm(ref)
 
     def err(rk):
         D = torch.empty((M, N), dtype=torch.float32, device="cuda")
         L.lrqmm_matmul_ex(dA, dB, D, bits, rk, oversample if rk else 0, power_iters if rk else 0, seed=seed,
-                          round_mode=round_mode, scale_mode=mode, workspace=ws)
-        return float(torch.linalg.norm(ref - D[sel].double()) / den)
+                          round_mode=round_mode, scale_mode=mode, workspace=ws, precision=precision)
+        torch.cuda.synchronize()
+        return float(np.linalg.norm(ref - D.cpu().numpy()[sel].astype(np.float64)) / den)
 
     e_dq = err(0)
     e_lr = err(rank) if rank > 0 else e_dq

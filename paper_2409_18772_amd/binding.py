@@ -10,6 +10,7 @@ import os
 AXIS_ROW, AXIS_COL = 0, 1
 ROUND_FLOOR, ROUND_NEAREST = 0, 1
 SCALE_VECTOR, SCALE_TENSOR = 0, 1
+PREC_FP32, PREC_BF16X2, PREC_BF16, PREC_SUBSPACE_BF16X2 = 0, 1, 2, 3
 MAX_SKETCH = 80
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -63,13 +64,13 @@ def load_library() -> ctypes.CDLL:
     lib.lrqmm_quantize_ex.restype = c_int
     lib.lrqmm_quantize_ex.argtypes = [c_vp] + [c_int] * 7 + [c_vp, c_vp, c_vp]
     lib.lrqmm_rsvd_ex.restype = c_int
-    lib.lrqmm_rsvd_ex.argtypes = [c_vp, c_int, c_vp] + [c_int] * 8 + [c_u64, c_vp, c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
+    lib.lrqmm_rsvd_ex.argtypes = [c_vp, c_int, c_vp] + [c_int] * 8 + [c_u64, c_vp, c_int, c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
     lib.lrqmm_gemm_ex.restype = c_int
     lib.lrqmm_gemm_ex.argtypes = [c_int] * 5 + [c_vp] * 10 + [c_f, c_f, c_vp, c_int, c_vp, c_vp, c_sz, c_vp]
     lib.lrqmm_gemm_static.restype = c_int
     lib.lrqmm_gemm_static.argtypes = [c_int] * 5 + [c_vp] * 10 + [c_f, c_f, c_vp, c_int, c_vp, c_vp]
     lib.lrqmm_matmul_ex.restype = c_int
-    lib.lrqmm_matmul_ex.argtypes = [c_int] * 7 + [c_u64, c_int, c_int, c_vp, c_int, c_vp, c_int, c_f, c_f, c_vp,
+    lib.lrqmm_matmul_ex.argtypes = [c_int] * 7 + [c_u64, c_int, c_int, c_int, c_vp, c_int, c_vp, c_int, c_f, c_f, c_vp,
                                     c_int, c_vp, c_sz, c_vp]
     lib.lrqmm_quantize_residual.restype = c_int
     lib.lrqmm_quantize_residual.argtypes = [c_vp, c_int, c_vp] + [c_int] * 6 + [c_vp, c_vp, c_vp]
@@ -257,8 +258,9 @@ def lrqmm_rsvd(X, amax, axis: int, bits: int, rank: int, oversample: int = 0, po
 
 
 def lrqmm_rsvd_ex(X, amax, axis: int, bits: int, rank: int, oversample: int = 0, power_iters: int = 0,
-                  seed: int = 0, round_mode: int = ROUND_FLOOR, omega=None, workspace: Workspace | None = None):
-    """lrqmm_rsvd for a row-strided X."""
+                  seed: int = 0, round_mode: int = ROUND_FLOOR, omega=None, workspace: Workspace | None = None,
+                  precision: int = PREC_FP32):
+    """lrqmm_rsvd for a row-strided X, with a choice of arithmetic for the residual products."""
     import torch
     ldx = _dev2d(X, torch.float32, "X")
     _dev(amax, torch.float32, "amax")
@@ -272,9 +274,9 @@ def lrqmm_rsvd_ex(X, amax, axis: int, bits: int, rank: int, oversample: int = 0,
     if workspace is None:
         workspace = Workspace.for_problem(max(rows, cols), max(rows, cols), max(rows, cols), rank, oversample)
     st = load_library().lrqmm_rsvd_ex(_ptr(X), ldx, _ptr(amax), rows, cols, axis, bits, round_mode, rank,
-                                      oversample, power_iters, seed & 0xFFFFFFFFFFFFFFFF, _ptr(omega), _ptr(U),
-                                      _ptr(Sigma), _ptr(Vt), ctypes.c_void_p(workspace.ptr), workspace.nbytes,
-                                      _stream())
+                                      oversample, power_iters, seed & 0xFFFFFFFFFFFFFFFF, _ptr(omega),
+                                      int(precision), _ptr(U), _ptr(Sigma), _ptr(Vt),
+                                      ctypes.c_void_p(workspace.ptr), workspace.nbytes, _stream())
     _check(st, "lrqmm_rsvd_ex")
     return U, Sigma, Vt
 
@@ -413,7 +415,7 @@ def lrqmm_matmul(A, B, bits: int, rank: int, oversample: int = 0, power_iters: i
 
 def lrqmm_matmul_ex(A, B, D, bits: int, rank: int, oversample: int = 0, power_iters: int = 0, seed: int = 0,
                     round_mode: int = ROUND_FLOOR, scale_mode: int = SCALE_VECTOR, alpha: float = 1.0,
-                    beta: float = 0.0, workspace: Workspace | None = None):
+                    beta: float = 0.0, workspace: Workspace | None = None, precision: int = PREC_FP32):
     """All of Algorithm 2: D <- alpha C_F + beta D in place; A, B, D may be row-strided windows."""
     import torch
     lda = _dev2d(A, torch.float32, "A")
@@ -426,7 +428,7 @@ def lrqmm_matmul_ex(A, B, D, bits: int, rank: int, oversample: int = 0, power_it
     if workspace is None:
         workspace = Workspace.for_problem(M, N, K, rank, oversample)
     st = load_library().lrqmm_matmul_ex(M, N, K, bits, rank, oversample, power_iters, seed & 0xFFFFFFFFFFFFFFFF,
-                                        round_mode, scale_mode, _ptr(A), lda, _ptr(B), ldb, float(alpha),
+                                        round_mode, scale_mode, int(precision), _ptr(A), lda, _ptr(B), ldb, float(alpha),
                                         float(beta), _ptr(D), ldd, ctypes.c_void_p(workspace.ptr),
                                         workspace.nbytes, _stream())
     _check(st, "lrqmm_matmul_ex")

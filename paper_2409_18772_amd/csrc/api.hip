@@ -212,7 +212,18 @@ inline void prof_mark(int slot, int i, hipStream_t st) {
     (void)hipEventRecord(g_prof.ev[slot][i], st);
 }
 
+// arithmetic of the entry points that take no precision argument (lrqmm_rsvd, lrqmm_matmul)
+#ifndef LRQMM_DEFAULT_PREC
+#define LRQMM_DEFAULT_PREC LRQMM_PREC_FP32
+#endif
 bool bits_ok(int bits) { return bits >= 2 && bits <= 8; }
+bool precision_ok(int p) {
+    return p == LRQMM_PREC_FP32 || p == LRQMM_PREC_BF16X2 || p == LRQMM_PREC_BF16 || p == LRQMM_PREC_SUBSPACE_BF16X2;
+}
+// bfloat16 planes per operand: in the products that only shape the subspace (sketch and power iterations) and in
+// the products whose values enter C directly (the projection Q^T R and the code products of the panels)
+int planes_subspace(int p) { return p == LRQMM_PREC_BF16 ? 1 : (p == LRQMM_PREC_FP32 ? 3 : 2); }
+int planes_values(int p) { return p == LRQMM_PREC_BF16 ? 1 : (p == LRQMM_PREC_BF16X2 ? 2 : 3); }
 
 // int32 accumulation is safe when K * (qmax+1)^2 < 2^31.
 bool k_fits_int32(int K, int bits) {
@@ -248,8 +259,11 @@ static int run_interleaved(const LaunchList& a, const LaunchList& b) {
 static int rsvd_plan(LaunchList& ops, const float* X, int ldx, const float* amax, int rows, int cols, int axis, int bits,
                      int round_mode, int rank, int oversample, int power_iters, uint64_t seed,
                      const float* omega_or_null, float* U, float* Sigma, float* Vt, void* workspace,
-                     size_t workspace_bytes, hipStream_t st, size_t* svd_index = nullptr, bool prepared = false) {
+                     size_t workspace_bytes, hipStream_t st, int precision, size_t* svd_index = nullptr,
+                     bool prepared = false) {
     if (rows < 0 || cols < 0 || rank < 1 || oversample < 0 || power_iters < 0 || ldx < cols) return LRQMM_ERR_INVALID_ARG;
+    if (!precision_ok(precision)) return LRQMM_ERR_INVALID_ARG;
+    const int planes = planes_subspace(precision), planes_last = planes_values(precision);
     if (axis != LRQMM_AXIS_ROW && axis != LRQMM_AXIS_COL) return LRQMM_ERR_INVALID_ARG;
     if (round_mode != LRQMM_ROUND_FLOOR && round_mode != LRQMM_ROUND_NEAREST) return LRQMM_ERR_INVALID_ARG;
     if (!bits_ok(bits)) return LRQMM_ERR_UNSUPPORTED;
@@ -285,23 +299,23 @@ static int rsvd_plan(LaunchList& ops, const float* X, int ldx, const float* amax
         ops.push_back([=] { return launch_apply(buf, n, LP, w.T, LP, LP, buf, LP, 0, st); });
     };
     auto pass_n = [&] {
-        ops.push_back([=] { return launch_resid_mul_n(X, ldx, rows, cols, axis, w.lam, w.s, q, w.Wc, LP, pn, w.partial, st); });
+        ops.push_back([=] { return launch_resid_mul_n(X, ldx, rows, cols, axis, w.lam, w.s, q, w.Wc, LP, pn, w.partial, st, planes); });
     };
-    auto pass_t = [&] {
-        ops.push_back([=] { return launch_resid_mul_t(X, ldx, rows, cols, axis, w.lam, w.s, q, w.Yr, LP, pt, w.partial, st); });
+    auto pass_t = [&](int pl) {
+        ops.push_back([=] { return launch_resid_mul_t(X, ldx, rows, cols, axis, w.lam, w.s, q, w.Yr, LP, pt, w.partial, st, pl); });
     };
     // Y = R Omega
     pass_n();
     orth(pn.splits, rows, w.Yr);
     for (int it = 0; it < power_iters; ++it) {
         // Z = orth(R^T Q); Q = orth(R Z)
-        pass_t();
+        pass_t(planes);
         orth(pt.splits, cols, w.Wc);
         pass_n();
         orth(pn.splits, rows, w.Yr);
     }
     // B^T = R^T Q (cols x l), its Gram B B^T, small SVD, U = Q U', V = B^T U' / sigma
-    pass_t();
+    pass_t(planes_last);
     ops.push_back([=] { return launch_reduce_gram(w.partial, pt.splits, cols, LP, nullptr, w.Wc, w.gpart, st); });
     ops.push_back([=] { return launch_gram_sum(w.gpart, gram_blocks(cols), LP, w.gram, st); });
     if (svd_index) *svd_index = ops.size();         // the GPU is nearly idle from this launch to its end
@@ -390,15 +404,16 @@ int lrqmm_rsvd(const float* X, const float* amax, int rows, int cols, int axis, 
                int rank, int oversample, int power_iters, uint64_t seed, const float* omega_or_null, float* U,
                float* Sigma, float* Vt, void* workspace, size_t workspace_bytes, void* stream) {
     return lrqmm_rsvd_ex(X, cols, amax, rows, cols, axis, bits, round_mode, rank, oversample, power_iters, seed,
-                         omega_or_null, U, Sigma, Vt, workspace, workspace_bytes, stream);
+                         omega_or_null, LRQMM_DEFAULT_PREC, U, Sigma, Vt, workspace, workspace_bytes, stream);
 }
 
 int lrqmm_rsvd_ex(const float* X, int ldx, const float* amax, int rows, int cols, int axis, int bits, int round_mode,
-                  int rank, int oversample, int power_iters, uint64_t seed, const float* omega_or_null, float* U,
-                  float* Sigma, float* Vt, void* workspace, size_t workspace_bytes, void* stream) {
+                  int rank, int oversample, int power_iters, uint64_t seed, const float* omega_or_null, int precision,
+                  float* U, float* Sigma, float* Vt, void* workspace, size_t workspace_bytes, void* stream) {
     LaunchList ops;
     int rc = rsvd_plan(ops, X, ldx, amax, rows, cols, axis, bits, round_mode, rank, oversample, power_iters, seed,
-                       omega_or_null, U, Sigma, Vt, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+                       omega_or_null, U, Sigma, Vt, workspace, workspace_bytes, static_cast<hipStream_t>(stream),
+                       precision);
     if (rc != LRQMM_OK) return rc;
     return run_interleaved(ops, LaunchList());
 }
@@ -407,7 +422,7 @@ static int gemm_impl(int M, int N, int K, int bits, int rank, const int8_t* Aq, 
                      const int8_t* BqT, const float* amaxB, const float* U, const float* Sig, const float* Vt,
                      const float* W, const float* Gam, const float* Zt, GemmOut out, int32_t* Cint_or_null,
                      void* workspace, size_t workspace_bytes, void* stream, int prof_slot,
-                     hipEvent_t raw_sums_ready = nullptr) {
+                     hipEvent_t raw_sums_ready = nullptr, int planes = 3) {
     float* const C = out.C;
     if (M < 0 || N < 0 || K < 0 || rank < 0 || out.ldc < N) return LRQMM_ERR_INVALID_ARG;
     if (!bits_ok(bits)) return LRQMM_ERR_UNSUPPORTED;
@@ -441,7 +456,7 @@ static int gemm_impl(int M, int N, int K, int bits, int rank, const int8_t* Aq, 
         // A~ W and (V^T B~)^T without their step vectors, split along K; one launch for both
         const PassPlan pa = plan_pass_n(M, K), pb = plan_pass_n(N, K);
         LRQ_TRY(launch_codes_mul_n2(Aq, M, w.Wp, w.Wp3, pa, w.partialA, BqT, N, w.Vp, w.Vp3, pb, w.partialB, K,
-                                    pad_to(K, 64), RP, st));
+                                    pad_to(K, 64), RP, st, planes));
         LRQ_TRY(launch_build_panels(M, N, K, rank, RP, R2P, U, Sig, w.sA, w.partialA, pa.splits, w.sB,
                                     w.partialB, pb.splits, w.X, Gam, Zt, w.Lp, w.Rp, st));
     }
@@ -499,15 +514,16 @@ int lrqmm_gemm_static(int M, int N, int K, int bits, int rank, const int8_t* Aq,
 int lrqmm_matmul(int M, int N, int K, int bits, int rank, int oversample, int power_iters, uint64_t seed,
                  int round_mode, const float* A, const float* B, float* C, void* workspace,
                  size_t workspace_bytes, void* stream) {
-    return lrqmm_matmul_ex(M, N, K, bits, rank, oversample, power_iters, seed, round_mode, LRQMM_SCALE_VECTOR, A, K,
-                           B, N, 1.0f, 0.0f, C, N, workspace, workspace_bytes, stream);
+    return lrqmm_matmul_ex(M, N, K, bits, rank, oversample, power_iters, seed, round_mode, LRQMM_SCALE_VECTOR,
+                           LRQMM_DEFAULT_PREC, A, K, B, N, 1.0f, 0.0f, C, N, workspace, workspace_bytes, stream);
 }
 
 int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int power_iters, uint64_t seed,
-                    int round_mode, int scale_mode, const float* A, int lda, const float* B, int ldb, float alpha,
-                    float beta, float* D, int ldd, void* workspace, size_t workspace_bytes, void* stream) {
+                    int round_mode, int scale_mode, int precision, const float* A, int lda, const float* B, int ldb,
+                    float alpha, float beta, float* D, int ldd, void* workspace, size_t workspace_bytes, void* stream) {
     float* const C = D;
     if (M < 0 || N < 0 || K < 0 || rank < 0 || oversample < 0 || power_iters < 0) return LRQMM_ERR_INVALID_ARG;
+    if (!precision_ok(precision)) return LRQMM_ERR_INVALID_ARG;
     if (lda < K || ldb < N || ldd < N) return LRQMM_ERR_INVALID_ARG;
     if (scale_mode != LRQMM_SCALE_VECTOR && scale_mode != LRQMM_SCALE_TENSOR) return LRQMM_ERR_INVALID_ARG;
     if (round_mode != LRQMM_ROUND_FLOOR && round_mode != LRQMM_ROUND_NEAREST) return LRQMM_ERR_INVALID_ARG;
@@ -559,7 +575,7 @@ int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int
     opsA.push_back([=] { prof_mark(slot, 1, ast); return LRQMM_OK; });
     if (rank > 0)
         LRQ_TRY(rsvd_plan(opsA, A, lda, w.amaxA, M, K, LRQMM_AXIS_ROW, bits, round_mode, rank, oversample, power_iters,
-                          seed, nullptr, w.U, w.Sig, w.Vt, w.subA, w.subA_bytes, ast, &svdA));
+                          seed, nullptr, w.U, w.Sig, w.Vt, w.subA, w.subA_bytes, ast, precision, &svdA));
     opsA.push_back([=] { prof_mark(slot, 2, ast); return LRQMM_OK; });
     opsB.push_back([=] { prof_mark(slot, 3, bst); return LRQMM_OK; });
     // B's chain is the critical one.  With a factorization to follow, its first kernel fills the sketch
@@ -585,7 +601,7 @@ int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int
     opsB.push_back([=] { prof_mark(slot, 4, bst); return LRQMM_OK; });
     if (rank > 0)
         LRQ_TRY(rsvd_plan(opsB, B, ldb, w.amaxB, K, N, LRQMM_AXIS_COL, bits, round_mode, rank, oversample, power_iters,
-                          seed, nullptr, w.W, w.Gam, w.Zt, w.subB, w.subB_bytes, bst, &svdB, fuse_b));
+                          seed, nullptr, w.W, w.Gam, w.Zt, w.subB, w.subB_bytes, bst, precision, &svdB, fuse_b));
     opsB.push_back([=] { prof_mark(slot, 5, bst); return LRQMM_OK; });
 
     // Nothing has been enqueued so far.  From the fork on, every path -- errors included -- joins the
@@ -634,7 +650,7 @@ int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int
         prof_mark(slot, 6, pst);
         rc = gemm_impl(M, N, K, bits, rank, w.Aq, w.amaxA, w.BqT, w.amaxB, w.U, w.Sig, w.Vt, w.W, w.Gam, w.Zt,
                        GemmOut{D, ldd, alpha, beta}, nullptr, w.sub, w.sub_bytes, stream, slot,
-                       early ? side->gdone : nullptr);
+                       early ? side->gdone : nullptr, planes_values(precision));
     }
     if (rc != LRQMM_OK && gemm_forked) {
         // failed somewhere behind the fork of the third stream: join it too (a second record of the

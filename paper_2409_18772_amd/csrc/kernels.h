@@ -49,21 +49,25 @@ struct PassPlan {
 PassPlan plan_pass_n(int rows, int cols);
 PassPlan plan_pass_t(int rows, int cols);
 // X is rows x cols with row stride ldx (>= cols) in both passes.
+// planes: bfloat16 planes per float32 operand in the matrix-core products (3: float32 accuracy, the default;
+// 2: relative error 2^-16 per product; 1: plain bfloat16 operands) -- the reduced-precision compensation of the
+// Methodology (text after Eq. (gemm_r_split)).  With planes == 3 sketches of up to 16 columns use the float32
+// matrix-core kernels.
 // partial[s][rows][LP] = R[:, chunk s] . W[chunk s, :]      (W is cols x LP)
 int launch_resid_mul_n(const float* X, int ldx, int rows, int cols, int axis, const float* lam,
                        const float* s, QuantParams q, const float* W, int LP, PassPlan plan,
-                       float* partial, hipStream_t st);
+                       float* partial, hipStream_t st, int planes = 3);
 // partial[s][cols][LP] = R[chunk s, :]^T . W[chunk s, :]    (W is rows x LP)
 int launch_resid_mul_t(const float* X, int ldx, int rows, int cols, int axis, const float* lam,
                        const float* s, QuantParams q, const float* W, int LP, PassPlan plan,
-                       float* partial, hipStream_t st);
+                       float* partial, hipStream_t st, int planes = 3);
 // Two independent products in one launch:
 // partialX[s][rowsX][LP] = scale-free codesX[:, chunk s] . WX[chunk s, :]  (codesX rowsX x K int8)
 // WX: K x LP float32; WX3: the same factor as three bfloat16 planes [3][LP][Kp] (k fastest,
 // Kp = K rounded up to 64, zero padded), used when K % 16 == 0.
 int launch_codes_mul_n2(const int8_t* codesA, int rowsA, const float* WA, const uint16_t* WA3, PassPlan planA,
                         float* partialA, const int8_t* codesB, int rowsB, const float* WB, const uint16_t* WB3,
-                        PassPlan planB, float* partialB, int K, int Kp, int LP, hipStream_t st);
+                        PassPlan planB, float* partialB, int K, int Kp, int LP, hipStream_t st, int planes = 3);
 
 // ---- orth.hip -----------------------------------------------------------
 int gram_blocks(int n);

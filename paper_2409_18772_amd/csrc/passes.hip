@@ -169,48 +169,61 @@ typedef float v2f32 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector((v2f32){a, b}, v2bf16));
 }
+// PL planes are formed (1, 2 or 3); the members beyond PL stay unset and must not be used.
+template <int PL = 3>
 __device__ __forceinline__ Planes3 split_planes(const float (&r)[8]) {
     uint32_t w1[4], w2[4], w3[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
         const float a = r[2 * e], b = r[2 * e + 1];
         const uint32_t h = pack_bf16x2(a, b);
-        const float ra = a - __uint_as_float(h << 16);              // exact
-        const float rb = b - __uint_as_float(h & 0xffff0000u);
-        const uint32_t m = pack_bf16x2(ra, rb);
-        const float ra2 = ra - __uint_as_float(m << 16);            // exact
-        const float rb2 = rb - __uint_as_float(m & 0xffff0000u);
         w1[e] = h;
-        w2[e] = m;
-        w3[e] = pack_bf16x2(ra2, rb2);
+        if (PL >= 2) {
+            const float ra = a - __uint_as_float(h << 16);              // exact
+            const float rb = b - __uint_as_float(h & 0xffff0000u);
+            const uint32_t m = pack_bf16x2(ra, rb);
+            w2[e] = m;
+            if (PL >= 3) {
+                const float ra2 = ra - __uint_as_float(m << 16);            // exact
+                const float rb2 = rb - __uint_as_float(m & 0xffff0000u);
+                w3[e] = pack_bf16x2(ra2, rb2);
+            }
+        }
     }
     typedef uint32_t v4u32 __attribute__((ext_vector_type(4)));
     Planes3 o;
     o.p1 = __builtin_bit_cast(v8bf16, (v4u32){w1[0], w1[1], w1[2], w1[3]});
-    o.p2 = __builtin_bit_cast(v8bf16, (v4u32){w2[0], w2[1], w2[2], w2[3]});
-    o.p3 = __builtin_bit_cast(v8bf16, (v4u32){w3[0], w3[1], w3[2], w3[3]});
+    if (PL >= 2) o.p2 = __builtin_bit_cast(v8bf16, (v4u32){w2[0], w2[1], w2[2], w2[3]});
+    if (PL >= 3) o.p3 = __builtin_bit_cast(v8bf16, (v4u32){w3[0], w3[1], w3[2], w3[3]});
     return o;
 }
 // acc[m][n] += a[m] . b[n] for NA x NB independent accumulators: the six plane products are
 // the outer loop (smallest terms first), so consecutive matrix instructions never depend on
 // each other.
-template <int NA, int NB>
+// Reduced precision (the compensation terms "in half precision", Methodology, after Eq. (gemm_r_split)):
+// with PL = 2 planes per operand the three products of weight >= 2^-8 are formed (relative error of a
+// product 2^-16), with PL = 1 the leading product alone (2^-8, plain bfloat16 operands).
+template <int NA, int NB, int PL = 3>
 __device__ __forceinline__ void mfma_planes(const Planes3 (&a)[NA], const Planes3 (&b)[NB], v4f (&acc)[NA][NB]) {
 #define LRQ_PP(PA, PB)                                                                               \
     _Pragma("unroll") for (int m = 0; m < NA; ++m) _Pragma("unroll") for (int n = 0; n < NB; ++n)     \
         acc[m][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m].PA, b[n].PB, acc[m][n], 0, 0, 0);
-    LRQ_PP(p3, p1)
-    LRQ_PP(p2, p2)
-    LRQ_PP(p1, p3)
-    LRQ_PP(p2, p1)
-    LRQ_PP(p1, p2)
+    if constexpr (PL >= 3) {
+        LRQ_PP(p3, p1)
+        LRQ_PP(p2, p2)
+        LRQ_PP(p1, p3)
+    }
+    if constexpr (PL >= 2) {
+        LRQ_PP(p2, p1)
+        LRQ_PP(p1, p2)
+    }
     LRQ_PP(p1, p1)
 #undef LRQ_PP
 }
 
 // One thread's share of the chunk W[k0 .. k0+KC)[0..LP): units (n, group), a unit being the 8
 // rows of W that form one lane group's k-slots of one 32-deep step, for one column n.
-template <int NT, int KC>
+template <int NT, int KC, int PL = 3>
 struct WStageBf16 {
     static constexpr int LP = NT * 16;
     static constexpr int LDK = KC + 8;                      // plane row stride in bfloat16
@@ -254,11 +267,11 @@ struct WStageBf16 {
             const int unit = (int)threadIdx.x + 256 * u;
             if (unit < UNITS) {
                 const int n = unit % LP, grp = unit / LP;
-                const Planes3 pl = split_planes(v[u]);
+                const Planes3 pl = split_planes<PL>(v[u]);
                 uint16_t* dst = wl + n * LDK + 8 * grp;
                 *reinterpret_cast<v8bf16*>(dst) = pl.p1;
-                *reinterpret_cast<v8bf16*>(dst + LP * LDK) = pl.p2;
-                *reinterpret_cast<v8bf16*>(dst + 2 * LP * LDK) = pl.p3;
+                if (PL >= 2) *reinterpret_cast<v8bf16*>(dst + LP * LDK) = pl.p2;
+                if (PL >= 3) *reinterpret_cast<v8bf16*>(dst + 2 * LP * LDK) = pl.p3;
             }
         }
     }
@@ -266,7 +279,7 @@ struct WStageBf16 {
 
 // FULLK: the vector path with cols and the split length multiples of the chunk depth, so no
 // load in the loop needs a guard along the reduction (rows past the end read row 0 and are not stored).
-template <int NT, int AXIS, bool VEC, bool FULLK = false>
+template <int NT, int AXIS, bool VEC, bool FULLK = false, int PL = 3>
 __global__ __launch_bounds__(256) void resid_mul_n_bf16_kernel(
     const float* __restrict__ X, int ldx, int rows, int cols, const float* __restrict__ lam,
     const float* __restrict__ sc, QuantParams q, const float* __restrict__ W, int chunk,
@@ -274,9 +287,9 @@ __global__ __launch_bounds__(256) void resid_mul_n_bf16_kernel(
     constexpr int LP = NT * 16;
     constexpr int KC = 64;      // two 32-deep steps per chunk; 41 KB of LDS at l <= 48 (three workgroups per CU)
     constexpr int KS = KC / 16;                             // float4 loads per lane per chunk
-    using WS = WStageBf16<NT, KC>;
+    using WS = WStageBf16<NT, KC, PL>;
     constexpr int LDK = WS::LDK;
-    __shared__ __align__(16) uint16_t wl[2][3 * LP * LDK];
+    __shared__ __align__(16) uint16_t wl[2][PL * LP * LDK];
     __shared__ __align__(16) float sl[2][2 * KC];   // per-column lambda | step of the chunk (AXIS 1)
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r = lane & 15, g = lane >> 4;
@@ -351,7 +364,7 @@ __global__ __launch_bounds__(256) void resid_mul_n_bf16_kernel(
                     res[4 * h + 2] = quant_residual_m<RM>(xr[j].z, l4.z, s4.z, q);
                     res[4 * h + 3] = quant_residual_m<RM>(xr[j].w, l4.w, s4.w, q);
                 }
-                ap[jj][0] = split_planes(res);
+                ap[jj][0] = split_planes<PL>(res);
             }
         };
         if (q.round_mode == 0) residuals(std::integral_constant<int, 0>{});
@@ -368,10 +381,10 @@ __global__ __launch_bounds__(256) void resid_mul_n_bf16_kernel(
             for (int nt = 0; nt < NT; ++nt) {
                 const uint16_t* src = wb + (16 * nt + r) * LDK + 32 * jj + 8 * g;
                 bp[nt].p1 = *reinterpret_cast<const v8bf16*>(src);
-                bp[nt].p2 = *reinterpret_cast<const v8bf16*>(src + LP * LDK);
-                bp[nt].p3 = *reinterpret_cast<const v8bf16*>(src + 2 * LP * LDK);
+                if (PL >= 2) bp[nt].p2 = *reinterpret_cast<const v8bf16*>(src + LP * LDK);
+                if (PL >= 3) bp[nt].p3 = *reinterpret_cast<const v8bf16*>(src + 2 * LP * LDK);
             }
-            mfma_planes<1, NT>(ap[jj], bp, acc);
+            mfma_planes<1, NT, PL>(ap[jj], bp, acc);
         }
     }
     float* out = partial + (size_t)blockIdx.y * rows * LP;
@@ -508,21 +521,22 @@ __device__ __forceinline__ v8bf codes_to_bf16(uint32_t lo, uint32_t hi) {
 // row, up to 128 registers), the four waves copy the slab of Bp into LDS meanwhile, and after
 // one barrier the matrix cores run through the slab without further waits: the HBM latency
 // is paid once per slab with the whole operand in flight.
-template <int NT>
+template <int NT, int PL = 3>
 struct CodesShape {
     static constexpr int RP = NT * 16;
     static constexpr int KB = NT <= 3 ? 512 : 256;      // slab depth: 3 RP (KB + 8) bf16 must fit LDS
     static constexpr int LDK = KB + 8;
     static constexpr int NC = KB / 64;                  // 64-deep chunks per slab
-    static constexpr int PIECES = 3 * RP * (KB / 8);    // 16-byte pieces of a slab of Bp
+    static constexpr int PIECES = PL * RP * (KB / 8);   // 16-byte pieces of a slab of the first PL planes of Bp
     static constexpr int BATCH = 8;
 };
 
-template <int NT>
+// PL: planes of the factor that enter (3: float32 accuracy; 2: relative error 2^-16; 1: plain bfloat16 factor).
+template <int NT, int PL = 3>
 __global__ __launch_bounds__(256, 1) void codes_mul_bf16_kernel(CodesJobBf16 j0, CodesJobBf16 j1, int K, int Kp) {
-    using S = CodesShape<NT>;
+    using S = CodesShape<NT, PL>;
     constexpr int RP = S::RP, KB = S::KB, LDK = S::LDK, NC = S::NC;
-    __shared__ __align__(16) uint16_t bs[3 * RP * LDK];
+    __shared__ __align__(16) uint16_t bs[PL * RP * LDK];
     const CodesJobBf16 job = blockIdx.z == 0 ? j0 : j1;
     if ((int)blockIdx.x * 256 >= job.rows || (int)blockIdx.y >= job.splits) return;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -580,7 +594,7 @@ __global__ __launch_bounds__(256, 1) void codes_mul_bf16_kernel(CodesJobBf16 j0,
 #pragma unroll
                     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-                        for (int pl = 0; pl < 3; ++pl) {
+                        for (int pl = 0; pl < PL; ++pl) {
                             union { uint4 u; v8bf v; } b;
                             b.u = *reinterpret_cast<const uint4*>(
                                 &bs[(pl * RP + 16 * nt + li) * LDK + 64 * c + 16 * kq + 8 * sidx]);
@@ -721,7 +735,7 @@ __global__ __launch_bounds__(256) void resid_mul_t_kernel(
 // FULLT: the vector path with whole column strips and a split length that is a multiple of the
 // 128 rows a workgroup takes per step: no load needs a guard, and the row part of every address
 // is wave-uniform (scalar registers), the lane part a constant 32-bit offset.
-template <int NT, int AXIS, bool VEC, bool FULLT = false>
+template <int NT, int AXIS, bool VEC, bool FULLT = false, int PL = 3>
 __global__ __launch_bounds__(256, (NT <= 4 || FULLT) ? 2 : 1) void resid_mul_t_bf16_kernel(
     const float* __restrict__ X, int ldx, int rows, int cols, const float* __restrict__ lam,
     const float* __restrict__ sc, QuantParams q, const float* __restrict__ W, int chunk,
@@ -802,7 +816,7 @@ __global__ __launch_bounds__(256, (NT <= 4 || FULLT) ? 2 : 1) void resid_mul_t_b
             float wv[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) wv[e] = cur.w[e][nt];
-            bp[nt] = split_planes(wv);
+            bp[nt] = split_planes<PL>(wv);
         }
 #pragma unroll
         for (int th = 0; th < 2; ++th) {        // two column components at a time: 2 NT independent chains
@@ -815,10 +829,10 @@ __global__ __launch_bounds__(256, (NT <= 4 || FULLT) ? 2 : 1) void resid_mul_t_b
                 for (int e = 0; e < 8; ++e)
                     res[e] = quant_residual(cur.x[e][t], AXIS == 0 ? cur.lr[e] : lcol[t],
                                             AXIS == 0 ? cur.sr[e] : scol[t], q);
-                ap[tt] = split_planes(res);
+                ap[tt] = split_planes<PL>(res);
             }
             v4f (&a2)[2][NT] = *reinterpret_cast<v4f (*)[2][NT]>(&acc[2 * th]);
-            mfma_planes<2, NT>(ap, bp, a2);
+            mfma_planes<2, NT, PL>(ap, bp, a2);
         }
         cur = nxt;
     }
@@ -887,45 +901,84 @@ struct PassKernels {
     static constexpr auto n = NT == 1 ? resid_mul_n_kernel<NT, AXIS, VEC> : resid_mul_n_bf16_kernel<NT, AXIS, VEC>;
     static constexpr auto t = NT == 1 ? resid_mul_t_kernel<NT, AXIS, VEC> : resid_mul_t_bf16_kernel<NT, AXIS, VEC>;
 };
+#define LRQ_PASS_ARGS grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial
+#define LRQ_PASS_ARGS_TAIL grid, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial
+// Reduced precision (planes 2 or 1): the bf16 kernels for every sketch width.
+template <int NT, int PL>
+static void dispatch_n_reduced(int axis, bool vec, bool fullk, dim3 grid, hipStream_t st, const float* X, int ldx,
+                               int rows, int cols, const float* lam, const float* s, QuantParams q, const float* W,
+                               int chunk, float* partial) {
+    if (fullk) {
+        if (axis == 0) hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 0, true, true, PL>), LRQ_PASS_ARGS);
+        else           hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 1, true, true, PL>), LRQ_PASS_ARGS);
+    } else if (axis == 0) {
+        if (vec) hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 0, true, false, PL>), LRQ_PASS_ARGS);
+        else     hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 0, false, false, PL>), LRQ_PASS_ARGS);
+    } else {
+        if (vec) hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 1, true, false, PL>), LRQ_PASS_ARGS);
+        else     hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 1, false, false, PL>), LRQ_PASS_ARGS);
+    }
+}
+template <int NT, int PL>
+static void dispatch_t_reduced(int axis, bool vec, bool fullt, dim3 grid, hipStream_t st, const float* X, int ldx,
+                               int rows, int cols, const float* lam, const float* s, QuantParams q, const float* W,
+                               int chunk, float* partial) {
+    if (fullt) {
+        if (axis == 0) hipLaunchKernelGGL((resid_mul_t_bf16_kernel<NT, 0, true, true, PL>), LRQ_PASS_ARGS);
+        else           hipLaunchKernelGGL((resid_mul_t_bf16_kernel<NT, 1, true, true, PL>), LRQ_PASS_ARGS);
+    } else if (axis == 0) {
+        if (vec) hipLaunchKernelGGL((resid_mul_t_bf16_kernel<NT, 0, true, false, PL>), LRQ_PASS_ARGS);
+        else     hipLaunchKernelGGL((resid_mul_t_bf16_kernel<NT, 0, false, false, PL>), LRQ_PASS_ARGS);
+    } else {
+        if (vec) hipLaunchKernelGGL((resid_mul_t_bf16_kernel<NT, 1, true, false, PL>), LRQ_PASS_ARGS);
+        else     hipLaunchKernelGGL((resid_mul_t_bf16_kernel<NT, 1, false, false, PL>), LRQ_PASS_ARGS);
+    }
+}
 template <int NT>
-static void dispatch_n(int axis, bool vec, dim3 grid, hipStream_t st, const float* X, int ldx, int rows, int cols,
-                       const float* lam, const float* s, QuantParams q, const float* W, int chunk,
+static void dispatch_n(int axis, bool vec, int planes, dim3 grid, hipStream_t st, const float* X, int ldx, int rows,
+                       int cols, const float* lam, const float* s, QuantParams q, const float* W, int chunk,
                        float* partial) {
+    // every chunk of every split is whole: the guard-free instantiation
+    const bool fullk = vec && cols % 64 == 0 && chunk % 64 == 0;
+    if (planes == 2) return dispatch_n_reduced<NT, 2>(axis, vec, fullk, LRQ_PASS_ARGS_TAIL);
+    if (planes == 1) return dispatch_n_reduced<NT, 1>(axis, vec, fullk, LRQ_PASS_ARGS_TAIL);
     if constexpr (NT > 1) {
-        // every chunk of every split is whole: the guard-free instantiation
-        if (vec && cols % 64 == 0 && chunk % 64 == 0) {
-            if (axis == 0) hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 0, true, true>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
-            else           hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 1, true, true>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+        if (fullk) {
+            if (axis == 0) hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 0, true, true>), LRQ_PASS_ARGS);
+            else           hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 1, true, true>), LRQ_PASS_ARGS);
             return;
         }
     }
     if (axis == 0) {
-        if (vec) hipLaunchKernelGGL((PassKernels<NT, 0, true>::n), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
-        else     hipLaunchKernelGGL((PassKernels<NT, 0, false>::n), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+        if (vec) hipLaunchKernelGGL((PassKernels<NT, 0, true>::n), LRQ_PASS_ARGS);
+        else     hipLaunchKernelGGL((PassKernels<NT, 0, false>::n), LRQ_PASS_ARGS);
     } else {
-        if (vec) hipLaunchKernelGGL((PassKernels<NT, 1, true>::n), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
-        else     hipLaunchKernelGGL((PassKernels<NT, 1, false>::n), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+        if (vec) hipLaunchKernelGGL((PassKernels<NT, 1, true>::n), LRQ_PASS_ARGS);
+        else     hipLaunchKernelGGL((PassKernels<NT, 1, false>::n), LRQ_PASS_ARGS);
     }
 }
 
 template <int NT>
-static void dispatch_t(int axis, bool vec, dim3 grid, hipStream_t st, const float* X, int ldx, int rows, int cols,
-                       const float* lam, const float* s, QuantParams q, const float* W, int chunk,
+static void dispatch_t(int axis, bool vec, int planes, dim3 grid, hipStream_t st, const float* X, int ldx, int rows,
+                       int cols, const float* lam, const float* s, QuantParams q, const float* W, int chunk,
                        float* partial) {
+    // whole column strips, whole 128-row steps in every split: the guard-free instantiation
+    const bool fullt = vec && cols % 64 == 0 && chunk % 128 == 0 && rows % 128 == 0;
+    if (planes == 2) return dispatch_t_reduced<NT, 2>(axis, vec, fullt, LRQ_PASS_ARGS_TAIL);
+    if (planes == 1) return dispatch_t_reduced<NT, 1>(axis, vec, fullt, LRQ_PASS_ARGS_TAIL);
     if constexpr (NT > 1) {
-        // whole column strips, whole 128-row steps in every split: the guard-free instantiation
-        if (vec && cols % 64 == 0 && chunk % 128 == 0 && rows % 128 == 0) {
-            if (axis == 0) hipLaunchKernelGGL((resid_mul_t_bf16_kernel<NT, 0, true, true>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
-            else           hipLaunchKernelGGL((resid_mul_t_bf16_kernel<NT, 1, true, true>), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+        if (fullt) {
+            if (axis == 0) hipLaunchKernelGGL((resid_mul_t_bf16_kernel<NT, 0, true, true>), LRQ_PASS_ARGS);
+            else           hipLaunchKernelGGL((resid_mul_t_bf16_kernel<NT, 1, true, true>), LRQ_PASS_ARGS);
             return;
         }
     }
     if (axis == 0) {
-        if (vec) hipLaunchKernelGGL((PassKernels<NT, 0, true>::t), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
-        else     hipLaunchKernelGGL((PassKernels<NT, 0, false>::t), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+        if (vec) hipLaunchKernelGGL((PassKernels<NT, 0, true>::t), LRQ_PASS_ARGS);
+        else     hipLaunchKernelGGL((PassKernels<NT, 0, false>::t), LRQ_PASS_ARGS);
     } else {
-        if (vec) hipLaunchKernelGGL((PassKernels<NT, 1, true>::t), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
-        else     hipLaunchKernelGGL((PassKernels<NT, 1, false>::t), grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial);
+        if (vec) hipLaunchKernelGGL((PassKernels<NT, 1, true>::t), LRQ_PASS_ARGS);
+        else     hipLaunchKernelGGL((PassKernels<NT, 1, false>::t), LRQ_PASS_ARGS);
     }
 }
 
@@ -947,33 +1000,35 @@ static void dispatch_c(bool vec, dim3 grid, hipStream_t st, CodesJob j0, CodesJo
 
 int launch_resid_mul_n(const float* X, int ldx, int rows, int cols, int axis, const float* lam, const float* s,
                        QuantParams q, const float* W, int LP, PassPlan plan, float* partial,
-                       hipStream_t st) {
+                       hipStream_t st, int planes) {
     const bool vec = (cols % 4 == 0) && (ldx % 4 == 0) && aligned16(X);
     dim3 grid(ceil_div(rows, 64), plan.splits);
-    NT_SWITCH(LP / 16, (dispatch_n<NT_>(axis, vec, grid, st, X, ldx, rows, cols, lam, s, q, W, plan.chunk, partial)));
+    NT_SWITCH(LP / 16, (dispatch_n<NT_>(axis, vec, planes, grid, st, X, ldx, rows, cols, lam, s, q, W, plan.chunk, partial)));
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }
 
 int launch_resid_mul_t(const float* X, int ldx, int rows, int cols, int axis, const float* lam, const float* s,
                        QuantParams q, const float* W, int LP, PassPlan plan, float* partial,
-                       hipStream_t st) {
+                       hipStream_t st, int planes) {
     const bool vec = (cols % 4 == 0) && (ldx % 4 == 0) && aligned16(X);
     dim3 grid(ceil_div(cols, 64), plan.splits);
-    NT_SWITCH(LP / 16, (dispatch_t<NT_>(axis, vec, grid, st, X, ldx, rows, cols, lam, s, q, W, plan.chunk, partial)));
+    NT_SWITCH(LP / 16, (dispatch_t<NT_>(axis, vec, planes, grid, st, X, ldx, rows, cols, lam, s, q, W, plan.chunk, partial)));
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }
 
 int launch_codes_mul_n2(const int8_t* codesA, int rowsA, const float* WA, const uint16_t* WA3, PassPlan planA,
                         float* partialA, const int8_t* codesB, int rowsB, const float* WB, const uint16_t* WB3,
-                        PassPlan planB, float* partialB, int K, int Kp, int LP, hipStream_t st) {
+                        PassPlan planB, float* partialB, int K, int Kp, int LP, hipStream_t st, int planes) {
     const bool fast = (K % 16 == 0) && K >= 16 && ((uintptr_t)codesA % 16 == 0) && ((uintptr_t)codesB % 16 == 0);
     if (fast) {
         CodesJobBf16 j0 = {codesA, WA3, partialA, rowsA, planA.chunk, planA.splits};
         CodesJobBf16 j1 = {codesB, WB3, partialB, rowsB, planB.chunk, planB.splits};
         dim3 grid(ceil_div(max(rowsA, rowsB), 256), max(planA.splits, planB.splits), 2);
-        NT_SWITCH(LP / 16, hipLaunchKernelGGL((codes_mul_bf16_kernel<NT_>), grid, dim3(256), 0, st, j0, j1, K, Kp));
+        if (planes == 2) { NT_SWITCH(LP / 16, hipLaunchKernelGGL((codes_mul_bf16_kernel<NT_, 2>), grid, dim3(256), 0, st, j0, j1, K, Kp)); }
+        else if (planes == 1) { NT_SWITCH(LP / 16, hipLaunchKernelGGL((codes_mul_bf16_kernel<NT_, 1>), grid, dim3(256), 0, st, j0, j1, K, Kp)); }
+        else { NT_SWITCH(LP / 16, hipLaunchKernelGGL((codes_mul_bf16_kernel<NT_>), grid, dim3(256), 0, st, j0, j1, K, Kp)); }
         LRQ_CHECK_LAUNCH();
         return LRQMM_OK;
     }

@@ -172,7 +172,7 @@ def test_bad_strides_are_rejected():
     A = torch.zeros((8, 8), dtype=torch.float32, device="cuda")
     ws = L.Workspace.for_problem(8, 8, 8, 0, 0)
     import ctypes
-    args = lambda lda, ldb, ldd, mode: (8, 8, 8, 8, 0, 0, 0, 0, 0, mode, A.data_ptr(), lda, A.data_ptr(), ldb, 1.0, 0.0,
+    args = lambda lda, ldb, ldd, mode: (8, 8, 8, 8, 0, 0, 0, 0, 0, mode, 0, A.data_ptr(), lda, A.data_ptr(), ldb, 1.0, 0.0,
                                         A.data_ptr(), ldd, ctypes.c_void_p(ws.ptr), ws.nbytes, None)
     assert lib.lrqmm_matmul_ex(*args(7, 8, 8, 0)) == -1
     assert lib.lrqmm_matmul_ex(*args(8, 7, 8, 0)) == -1

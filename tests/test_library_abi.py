@@ -56,10 +56,12 @@ def test_host_side_validation_without_a_gpu():
     # strides below the row length, unknown scale granularity
     assert lib.lrqmm_quantize_ex(None, 3, 4, 4, 0, 8, 0, 0, None, None, None) == -1
     assert lib.lrqmm_quantize_ex(None, 4, 4, 4, 0, 8, 0, 7, None, None, None) == -1
-    assert lib.lrqmm_rsvd_ex(None, 7, None, 8, 8, 0, 8, 0, 2, 0, 0, 0, None, None, None, None, None, 0, None) == -1
+    assert lib.lrqmm_rsvd_ex(None, 7, None, 8, 8, 0, 8, 0, 2, 0, 0, 0, None, 0, None, None, None, None, 0, None) == -1
+    assert lib.lrqmm_rsvd_ex(None, 8, None, 8, 8, 0, 8, 0, 2, 0, 0, 0, None, 3, None, None, None, None, 0, None) == -1     # unknown precision
     assert lib.lrqmm_gemm_ex(4, 4, 4, 8, 0, *([None] * 10), 1.0, 0.0, None, 3, None, None, 0, None) == -1
-    assert lib.lrqmm_matmul_ex(4, 4, 4, 8, 0, 0, 0, 0, 0, 0, None, 3, None, 4, 1.0, 0.0, None, 4, None, 0, None) == -1
-    assert lib.lrqmm_matmul_ex(4, 4, 4, 8, 0, 0, 0, 0, 0, 3, None, 4, None, 4, 1.0, 0.0, None, 4, None, 0, None) == -1
+    assert lib.lrqmm_matmul_ex(4, 4, 4, 8, 0, 0, 0, 0, 0, 0, 0, None, 3, None, 4, 1.0, 0.0, None, 4, None, 0, None) == -1
+    assert lib.lrqmm_matmul_ex(4, 4, 4, 8, 0, 0, 0, 0, 0, 3, 0, None, 4, None, 4, 1.0, 0.0, None, 4, None, 0, None) == -1
+    assert lib.lrqmm_matmul_ex(4, 4, 4, 8, 0, 0, 0, 0, 0, 0, 5, None, 4, None, 4, 1.0, 0.0, None, 4, None, 0, None) == -1     # unknown precision
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
