@@ -260,7 +260,7 @@ static int rsvd_plan(LaunchList& ops, const float* X, int ldx, const float* amax
                      int round_mode, int rank, int oversample, int power_iters, uint64_t seed,
                      const float* omega_or_null, float* U, float* Sigma, float* Vt, void* workspace,
                      size_t workspace_bytes, hipStream_t st, int precision, size_t* svd_index = nullptr,
-                     bool prepared = false) {
+                     bool prepared = false, int8_t* fused_codes = nullptr) {
     if (rows < 0 || cols < 0 || rank < 1 || oversample < 0 || power_iters < 0 || ldx < cols) return LRQMM_ERR_INVALID_ARG;
     if (!precision_ok(precision)) return LRQMM_ERR_INVALID_ARG;
     const int planes = planes_subspace(precision), planes_last = planes_values(precision);
@@ -280,7 +280,8 @@ static int rsvd_plan(LaunchList& ops, const float* X, int ldx, const float* amax
     const QuantParams q = make_quant_params(bits, round_mode);
     const int nscale = axis == LRQMM_AXIS_ROW ? rows : cols;
     if (prepared) {
-        // the caller has already filled the sketch (w.Wc) and the step vectors (w.lam, w.s) on this stream
+        // the caller has already filled the sketch (w.Wc) on this stream, and either the step vectors (w.lam, w.s)
+        // too or -- with fused_codes -- only the group maxima: the first pass then quantizes as well
     } else if (omega_or_null) {
         ops.push_back([=] { return launch_scales(amax, nscale, pad_to(nscale, 4), q.qmaxf, w.lam, w.s, st); });
         ops.push_back([=] { return launch_pad_copy(omega_or_null, cols, ell, LP, w.Wc, st); });
@@ -304,8 +305,14 @@ static int rsvd_plan(LaunchList& ops, const float* X, int ldx, const float* amax
     auto pass_t = [&](int pl) {
         ops.push_back([=] { return launch_resid_mul_t(X, ldx, rows, cols, axis, w.lam, w.s, q, w.Yr, LP, pt, w.partial, st, pl); });
     };
-    // Y = R Omega
-    pass_n();
+    // Y = R Omega (with fused_codes: the same launch also writes the codes and the step vectors)
+    if (fused_codes)
+        ops.push_back([=] {
+            return launch_quant_sketch(X, ldx, rows, cols, axis, amax, q, w.Wc, LP, pn, w.partial, w.lam, w.s, fused_codes,
+                                       st, planes);
+        });
+    else
+        pass_n();
     orth(pn.splits, rows, w.Yr);
     for (int it = 0; it < power_iters; ++it) {
         // Z = orth(R^T Q); Q = orth(R Z)
@@ -569,39 +576,56 @@ int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int
     LaunchList opsA, opsB;
     size_t svdA = 0, svdB = 0;      // positions of the small-SVD launches in the two lists
     int rc;
+    // With a factorization to follow, and for shapes that take the guard-free pass kernels, quantization is
+    // split differently: the group maxima come first (one read of the operand), and the operand's second read
+    // yields codes, step vectors and the sketch product Y = R.Omega in one launch (one full-size read fewer
+    // per operand than quantizing and sketching separately).  The sketch is filled by the chain's first launch
+    // (it depends on nothing).  Otherwise: quantize, then factor.
+    const QuantParams qp = make_quant_params(bits, round_mode);
+    const bool per_tensor = scale_mode == LRQMM_SCALE_TENSOR;
+    const int LPm = pad_to(rank + oversample, 16);
+    RsvdWs wa = {}, wb = {};
+    if (rank > 0 && K > 0) {
+        Arena ra(w.subA), rb(w.subB);
+        if (carve_rsvd(ra, M, K, LRQMM_AXIS_ROW, LPm, rank, &wa) > w.subA_bytes) return LRQMM_ERR_WORKSPACE;
+        if (carve_rsvd(rb, K, N, LRQMM_AXIS_COL, LPm, rank, &wb) > w.subB_bytes) return LRQMM_ERR_WORKSPACE;
+    }
+    const bool fuse_a = rank > 0 && K > 0 && quant_sketch_fusable(A, lda, M, K, LPm, plan_pass_n(M, K), w.Aq);
+    const bool fuse_b = rank > 0 && K > 0 && quant_sketch_fusable(B, ldb, K, N, LPm, plan_pass_n(K, N), w.BqT);
     opsA.push_back([=] { prof_mark(slot, 0, ast); return LRQMM_OK; });
-    if (K > 0) opsA.push_back([=] { return lrqmm_quantize_ex(A, lda, M, K, LRQMM_AXIS_ROW, bits, round_mode, scale_mode, w.Aq, w.amaxA, ast); });
+    if (fuse_a) {
+        opsA.push_back([=] { return launch_fill_sketch(seed, LRQMM_AXIS_ROW, K, rank + oversample, LPm, wa.Wc, ast); });
+        opsA.push_back([=] { return launch_absmax_rows(A, lda, M, K, qp, per_tensor, w.amaxA, ast); });
+    } else if (K > 0) opsA.push_back([=] { return lrqmm_quantize_ex(A, lda, M, K, LRQMM_AXIS_ROW, bits, round_mode, scale_mode, w.Aq, w.amaxA, ast); });
     else opsA.push_back([=] { return launch_pad_copy(nullptr, M, 0, 1, w.amaxA, ast); });
     opsA.push_back([=] { prof_mark(slot, 1, ast); return LRQMM_OK; });
     if (rank > 0)
         LRQ_TRY(rsvd_plan(opsA, A, lda, w.amaxA, M, K, LRQMM_AXIS_ROW, bits, round_mode, rank, oversample, power_iters,
-                          seed, nullptr, w.U, w.Sig, w.Vt, w.subA, w.subA_bytes, ast, precision, &svdA));
+                          seed, nullptr, w.U, w.Sig, w.Vt, w.subA, w.subA_bytes, ast, precision, &svdA, fuse_a,
+                          fuse_a ? w.Aq : nullptr));
     opsA.push_back([=] { prof_mark(slot, 2, ast); return LRQMM_OK; });
     opsB.push_back([=] { prof_mark(slot, 3, bst); return LRQMM_OK; });
-    // B's chain is the critical one.  With a factorization to follow, its first kernel fills the sketch
-    // (which depends on nothing) and clears the column maxima in one launch, and the quantizing kernel
-    // leaves the step vectors: the factorization then starts with its first pass at once.
-    const bool fuse_b = rank > 0 && K > 0;
-    RsvdWs wb = {};
-    if (fuse_b) {
-        Arena rb(w.subB);
-        if (carve_rsvd(rb, K, N, LRQMM_AXIS_COL, pad_to(rank + oversample, 16), rank, &wb) > w.subB_bytes)
-            return LRQMM_ERR_WORKSPACE;
-        const QuantParams qb = make_quant_params(bits, round_mode);
+    // B's chain is the critical one (its maxima need a pass of their own).  Its first kernel fills the sketch
+    // and clears the column maxima in one launch.
+    const bool prep_b = rank > 0 && K > 0;
+    if (prep_b) {
         opsB.push_back([=] {
-            return launch_sketch_and_zero(seed, LRQMM_AXIS_COL, N, rank + oversample, pad_to(rank + oversample, 16),
-                                          wb.Wc, reinterpret_cast<uint32_t*>(w.amaxB), N, bst);
+            return launch_sketch_and_zero(seed, LRQMM_AXIS_COL, N, rank + oversample, LPm, wb.Wc,
+                                          reinterpret_cast<uint32_t*>(w.amaxB), N, bst);
         });
-        opsB.push_back([=] {
-            return launch_quantize_cols(B, ldb, K, N, qb, scale_mode == LRQMM_SCALE_TENSOR, nullptr, w.BqT, w.amaxB, bst,
-                                        true, wb.lam, wb.s);
-        });
+        if (fuse_b)
+            opsB.push_back([=] { return launch_absmax_cols(B, ldb, K, N, qp, per_tensor, w.amaxB, bst, true); });
+        else    // the quantizing kernel leaves the step vectors: the factorization starts with its first pass at once
+            opsB.push_back([=] {
+                return launch_quantize_cols(B, ldb, K, N, qp, per_tensor, nullptr, w.BqT, w.amaxB, bst, true, wb.lam, wb.s);
+            });
     } else if (K > 0) opsB.push_back([=] { return lrqmm_quantize_ex(B, ldb, K, N, LRQMM_AXIS_COL, bits, round_mode, scale_mode, w.BqT, w.amaxB, bst); });
     else opsB.push_back([=] { return launch_pad_copy(nullptr, N, 0, 1, w.amaxB, bst); });
     opsB.push_back([=] { prof_mark(slot, 4, bst); return LRQMM_OK; });
     if (rank > 0)
         LRQ_TRY(rsvd_plan(opsB, B, ldb, w.amaxB, K, N, LRQMM_AXIS_COL, bits, round_mode, rank, oversample, power_iters,
-                          seed, nullptr, w.W, w.Gam, w.Zt, w.subB, w.subB_bytes, bst, precision, &svdB, fuse_b));
+                          seed, nullptr, w.W, w.Gam, w.Zt, w.subB, w.subB_bytes, bst, precision, &svdB, prep_b,
+                          fuse_b ? w.BqT : nullptr));
     opsB.push_back([=] { prof_mark(slot, 5, bst); return LRQMM_OK; });
 
     // Nothing has been enqueued so far.  From the fork on, every path -- errors included -- joins the

@@ -17,6 +17,12 @@ int launch_quantize_rows(const float* X, int ldx, int rows, int cols, QuantParam
 int launch_quantize_cols(const float* X, int ldx, int rows, int cols, QuantParams q, bool per_tensor,
                          const float* amax0, int8_t* codesT, float* amax, hipStream_t st, bool amax_zeroed = false,
                          float* lam_out = nullptr, float* s_out = nullptr);
+// The group maxima alone (first half of the two launchers above; for columns amax must be zero at launch when
+// amax_zeroed is set, and is cleared by a fill kernel otherwise).
+int launch_absmax_rows(const float* X, int ldx, int rows, int cols, QuantParams q, bool per_tensor, float* amax,
+                       hipStream_t st);
+int launch_absmax_cols(const float* X, int ldx, int rows, int cols, QuantParams q, bool per_tensor, float* amax,
+                       hipStream_t st, bool amax_zeroed);
 // lam[n], s[n] from amax[n]; entries n..npad-1 are zero-filled.
 // A minimal kernel (writes one zero word): used as a few microseconds of delay on a stream.
 int launch_tick(uint32_t* word, hipStream_t st);
@@ -57,6 +63,15 @@ PassPlan plan_pass_t(int rows, int cols);
 int launch_resid_mul_n(const float* X, int ldx, int rows, int cols, int axis, const float* lam,
                        const float* s, QuantParams q, const float* W, int LP, PassPlan plan,
                        float* partial, hipStream_t st, int planes = 3);
+// The quantization of X fused into its first residual product: with the group maxima amax known (rows for
+// axis 0, columns for axis 1), one read of X writes the codes (row-major for axis 0, transposed for axis 1), the
+// step vectors lam_out / s_out, and the partials of R.W as launch_resid_mul_n does (same arithmetic, same bits).
+// Only for the shapes quant_sketch_fusable accepts (guard-free: rows, cols and the split length multiples of 64,
+// sketch width above 16, aligned pointers); otherwise LRQMM_ERR_UNSUPPORTED and nothing is launched.
+bool quant_sketch_fusable(const float* X, int ldx, int rows, int cols, int LP, PassPlan plan, const int8_t* codes);
+int launch_quant_sketch(const float* X, int ldx, int rows, int cols, int axis, const float* amax, QuantParams q,
+                        const float* W, int LP, PassPlan plan, float* partial, float* lam_out, float* s_out,
+                        int8_t* codes, hipStream_t st, int planes = 3);
 // partial[s][cols][LP] = R[chunk s, :]^T . W[chunk s, :]    (W is rows x LP)
 int launch_resid_mul_t(const float* X, int ldx, int rows, int cols, int axis, const float* lam,
                        const float* s, QuantParams q, const float* W, int LP, PassPlan plan,

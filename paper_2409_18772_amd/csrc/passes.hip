@@ -48,6 +48,18 @@ struct WStage {
     }
 };
 
+// Quantization fused into the first residual product (the sketch pass): with the group maxima known, one
+// read of the operand yields both its codes and Y = R.Omega.  amax: the group maxima (rows of X for AXIS 0,
+// columns for AXIS 1); lam_out / s_out: the step vectors lambda = qmax/amax, s = amax/qmax that the later
+// passes read; codes: rows x cols row-major (AXIS 0) or transposed, cols x rows (AXIS 1).  Guard-free shapes
+// only: rows a multiple of 64 besides the FULLK conditions, 16-byte aligned codes.
+struct QOut {
+    const float* amax;
+    float* lam_out;
+    float* s_out;
+    int8_t* codes;
+};
+
 // ---------------------------------------------------------------------------
 // N-type: partial[split][rows][LP] = R[:, k-range] . W[k-range, :]
 // grid (ceil(rows/64), splits); 4 waves x 16 rows.  Per KCHUNK columns: the W chunk goes
@@ -58,7 +70,7 @@ template <int NT, int AXIS, bool VEC>
 __global__ __launch_bounds__(256) void resid_mul_n_kernel(
     const float* __restrict__ X, int ldx, int rows, int cols, const float* __restrict__ lam,
     const float* __restrict__ sc, QuantParams q, const float* __restrict__ W, int chunk,
-    float* __restrict__ partial) {
+    float* __restrict__ partial, QOut) {
     constexpr int LP = NT * 16;
     // wide sketches stage 64-deep chunks: 128 x (LP + 4) floats twice would leave one workgroup per CU
     constexpr int KC = NT <= 3 ? KCHUNK : KCHUNK / 2;
@@ -277,15 +289,27 @@ struct WStageBf16 {
     }
 };
 
+// residual x - code s and the code itself (the arithmetic of quant_code / quant_residual_m)
+template <int ROUND_MODE>
+__device__ __forceinline__ float quant_code_residual(float x, float lam, float s, const QuantParams& q, float& code) {
+    const float t = x * lam;
+    const float c = ROUND_MODE == 0 ? floorf(t) : rintf(t);
+    code = fminf(fmaxf(c, q.lo), q.hi);
+    return fmaf(-code, s, x);
+}
+
 // FULLK: the vector path with cols and the split length multiples of the chunk depth, so no
 // load in the loop needs a guard along the reduction (rows past the end read row 0 and are not stored).
-template <int NT, int AXIS, bool VEC, bool FULLK = false, int PL = 3>
+template <int NT, int AXIS, bool VEC, bool FULLK = false, int PL = 3, bool QOUT = false>
 __global__ __launch_bounds__(256) void resid_mul_n_bf16_kernel(
     const float* __restrict__ X, int ldx, int rows, int cols, const float* __restrict__ lam,
     const float* __restrict__ sc, QuantParams q, const float* __restrict__ W, int chunk,
-    float* __restrict__ partial) {
+    float* __restrict__ partial, QOut qo) {
+    static_assert(!QOUT || FULLK, "the fused quantization exists for the guard-free shapes only");
     constexpr int LP = NT * 16;
     constexpr int KC = 64;      // two 32-deep steps per chunk; 41 KB of LDS at l <= 48 (three workgroups per CU)
+    constexpr int CTS = 80;     // row stride of the staged code tile (64 codes + padding), bytes
+    __shared__ __align__(16) int8_t ct[QOUT ? 2 : 1][QOUT ? 64 * CTS : 16];
     constexpr int KS = KC / 16;                             // float4 loads per lane per chunk
     using WS = WStageBf16<NT, KC, PL>;
     constexpr int LDK = WS::LDK;
@@ -300,8 +324,16 @@ __global__ __launch_bounds__(256) void resid_mul_n_bf16_kernel(
     const int ke = min(cols, kb + chunk);
     float lam_r = 0.f, s_r = 0.f;
     if (AXIS == 0 && row_ok) {
-        lam_r = lam[row];
-        s_r = sc[row];
+        if (QOUT) {
+            make_scales(qo.amax[row], q.qmaxf, lam_r, s_r);
+            if (blockIdx.y == 0 && g == 0) {
+                qo.lam_out[row] = lam_r;
+                qo.s_out[row] = s_r;
+            }
+        } else {
+            lam_r = lam[row];
+            s_r = sc[row];
+        }
     }
     v4f acc[1][NT];
 #pragma unroll
@@ -312,12 +344,12 @@ __global__ __launch_bounds__(256) void resid_mul_n_bf16_kernel(
     WS ws;
     if (FULLK) ws.init();
     const float* xq = xp + 4 * g;
-    const float* scq = ((threadIdx.x & KC) == 0 ? lam : sc) + (threadIdx.x & (KC - 1));
+    const float* scq = (QOUT ? qo.amax : ((threadIdx.x & KC) == 0 ? lam : sc)) + (threadIdx.x & (KC - 1));
     auto load_x = [&](int k0) {
         if (FULLK) {
 #pragma unroll
             for (int j = 0; j < KS; ++j) xr[j] = *reinterpret_cast<const float4*>(xq + k0 + 16 * j);
-            if (AXIS == 1) scale_reg = scq[k0];
+            if (AXIS == 1) scale_reg = scq[k0];     // (QOUT: the column's maximum, turned into lambda or s below)
             return;
         }
 #pragma unroll
@@ -337,11 +369,30 @@ __global__ __launch_bounds__(256) void resid_mul_n_bf16_kernel(
         load_x(kb);
         load_w(kb);
     }
+    // QOUT: the 64 x 64 code tile of a chunk is staged in LDS (two tiles, so the chunk loop keeps its single
+    // barrier) and leaves for global memory one chunk later, 16 bytes per thread: rows of 64 contiguous bytes.
+    // Tile rows are X rows (AXIS 0, codes row-major) or X columns (AXIS 1, codes transposed).
+    auto flush_codes = [&](int tb, int kprev) {
+        const int tr = threadIdx.x >> 2, seg = (threadIdx.x & 3) * 16;
+        const uint4 v = *reinterpret_cast<const uint4*>(&ct[tb][tr * CTS + seg]);
+        int8_t* dst = AXIS == 0 ? qo.codes + (size_t)(blockIdx.x * 64 + tr) * cols + kprev + seg
+                                : qo.codes + (size_t)(kprev + tr) * rows + blockIdx.x * 64 + seg;
+        *reinterpret_cast<uint4*>(dst) = v;
+    };
     int buf = 0;
     for (int k0 = kb; k0 < ke; k0 += KC, buf ^= 1) {
         ws.store(wl[buf]);
-        if (AXIS == 1 && threadIdx.x < 2 * KC) sl[buf][threadIdx.x] = scale_reg;
+        if (AXIS == 1 && threadIdx.x < 2 * KC) {
+            if (QOUT) {     // scale_reg holds the column maximum: lambda for the first KC threads, the step for the next
+                float l, st;
+                make_scales(scale_reg, q.qmaxf, l, st);
+                scale_reg = (threadIdx.x & KC) == 0 ? l : st;
+                if (blockIdx.x == 0) ((threadIdx.x & KC) == 0 ? qo.lam_out : qo.s_out)[k0 + (threadIdx.x & (KC - 1))] = scale_reg;
+            }
+            sl[buf][threadIdx.x] = scale_reg;
+        }
         __syncthreads();             // wl[buf], sl[buf] complete; the other buffers no longer read
+        if (QOUT && k0 > kb) flush_codes(buf ^ 1, k0 - KC);
         Planes3 ap[KC / 32][1];
         auto residuals = [&](auto mode) {       // one uniform branch on the rounding mode per chunk
             constexpr int RM = decltype(mode)::value;
@@ -359,10 +410,30 @@ __global__ __launch_bounds__(256) void resid_mul_n_bf16_kernel(
                         l4 = *reinterpret_cast<const float4*>(&sl[buf][16 * j + 4 * g]);
                         s4 = *reinterpret_cast<const float4*>(&sl[buf][KC + 16 * j + 4 * g]);
                     }
-                    res[4 * h + 0] = quant_residual_m<RM>(xr[j].x, l4.x, s4.x, q);
-                    res[4 * h + 1] = quant_residual_m<RM>(xr[j].y, l4.y, s4.y, q);
-                    res[4 * h + 2] = quant_residual_m<RM>(xr[j].z, l4.z, s4.z, q);
-                    res[4 * h + 3] = quant_residual_m<RM>(xr[j].w, l4.w, s4.w, q);
+                    if (QOUT) {
+                        float c0, c1, c2, c3;
+                        res[4 * h + 0] = quant_code_residual<RM>(xr[j].x, l4.x, s4.x, q, c0);
+                        res[4 * h + 1] = quant_code_residual<RM>(xr[j].y, l4.y, s4.y, q, c1);
+                        res[4 * h + 2] = quant_code_residual<RM>(xr[j].z, l4.z, s4.z, q, c2);
+                        res[4 * h + 3] = quant_code_residual<RM>(xr[j].w, l4.w, s4.w, q, c3);
+                        const int i0 = (int)c0, i1 = (int)c1, i2 = (int)c2, i3 = (int)c3;
+                        if (AXIS == 0) {    // four codes along the row: one packed word
+                            const uint32_t pk = (uint32_t)(i0 & 0xff) | ((uint32_t)(i1 & 0xff) << 8) |
+                                                ((uint32_t)(i2 & 0xff) << 16) | ((uint32_t)(i3 & 0xff) << 24);
+                            *reinterpret_cast<uint32_t*>(&ct[buf][(wave * 16 + r) * CTS + 16 * j + 4 * g]) = pk;
+                        } else {            // four columns of the transposed tile
+                            int8_t* cp = &ct[buf][(16 * j + 4 * g) * CTS + wave * 16 + r];
+                            cp[0] = (int8_t)i0;
+                            cp[CTS] = (int8_t)i1;
+                            cp[2 * CTS] = (int8_t)i2;
+                            cp[3 * CTS] = (int8_t)i3;
+                        }
+                    } else {
+                        res[4 * h + 0] = quant_residual_m<RM>(xr[j].x, l4.x, s4.x, q);
+                        res[4 * h + 1] = quant_residual_m<RM>(xr[j].y, l4.y, s4.y, q);
+                        res[4 * h + 2] = quant_residual_m<RM>(xr[j].z, l4.z, s4.z, q);
+                        res[4 * h + 3] = quant_residual_m<RM>(xr[j].w, l4.w, s4.w, q);
+                    }
                 }
                 ap[jj][0] = split_planes<PL>(res);
             }
@@ -386,6 +457,10 @@ __global__ __launch_bounds__(256) void resid_mul_n_bf16_kernel(
             }
             mfma_planes<1, NT, PL>(ap[jj], bp, acc);
         }
+    }
+    if (QOUT && kb < ke) {
+        __syncthreads();
+        flush_codes(buf ^ 1, ke - KC);
     }
     float* out = partial + (size_t)blockIdx.y * rows * LP;
     const int orow0 = blockIdx.x * 64 + wave * 16 + 4 * g;
@@ -902,6 +977,7 @@ struct PassKernels {
     static constexpr auto t = NT == 1 ? resid_mul_t_kernel<NT, AXIS, VEC> : resid_mul_t_bf16_kernel<NT, AXIS, VEC>;
 };
 #define LRQ_PASS_ARGS grid, dim3(256), 0, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial
+#define LRQ_PASS_ARGS_N LRQ_PASS_ARGS, QOut{}
 #define LRQ_PASS_ARGS_TAIL grid, st, X, ldx, rows, cols, lam, s, q, W, chunk, partial
 // Reduced precision (planes 2 or 1): the bf16 kernels for every sketch width.
 template <int NT, int PL>
@@ -909,14 +985,14 @@ static void dispatch_n_reduced(int axis, bool vec, bool fullk, dim3 grid, hipStr
                                int rows, int cols, const float* lam, const float* s, QuantParams q, const float* W,
                                int chunk, float* partial) {
     if (fullk) {
-        if (axis == 0) hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 0, true, true, PL>), LRQ_PASS_ARGS);
-        else           hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 1, true, true, PL>), LRQ_PASS_ARGS);
+        if (axis == 0) hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 0, true, true, PL>), LRQ_PASS_ARGS_N);
+        else           hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 1, true, true, PL>), LRQ_PASS_ARGS_N);
     } else if (axis == 0) {
-        if (vec) hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 0, true, false, PL>), LRQ_PASS_ARGS);
-        else     hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 0, false, false, PL>), LRQ_PASS_ARGS);
+        if (vec) hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 0, true, false, PL>), LRQ_PASS_ARGS_N);
+        else     hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 0, false, false, PL>), LRQ_PASS_ARGS_N);
     } else {
-        if (vec) hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 1, true, false, PL>), LRQ_PASS_ARGS);
-        else     hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 1, false, false, PL>), LRQ_PASS_ARGS);
+        if (vec) hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 1, true, false, PL>), LRQ_PASS_ARGS_N);
+        else     hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 1, false, false, PL>), LRQ_PASS_ARGS_N);
     }
 }
 template <int NT, int PL>
@@ -944,17 +1020,17 @@ static void dispatch_n(int axis, bool vec, int planes, dim3 grid, hipStream_t st
     if (planes == 1) return dispatch_n_reduced<NT, 1>(axis, vec, fullk, LRQ_PASS_ARGS_TAIL);
     if constexpr (NT > 1) {
         if (fullk) {
-            if (axis == 0) hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 0, true, true>), LRQ_PASS_ARGS);
-            else           hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 1, true, true>), LRQ_PASS_ARGS);
+            if (axis == 0) hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 0, true, true>), LRQ_PASS_ARGS_N);
+            else           hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NT, 1, true, true>), LRQ_PASS_ARGS_N);
             return;
         }
     }
     if (axis == 0) {
-        if (vec) hipLaunchKernelGGL((PassKernels<NT, 0, true>::n), LRQ_PASS_ARGS);
-        else     hipLaunchKernelGGL((PassKernels<NT, 0, false>::n), LRQ_PASS_ARGS);
+        if (vec) hipLaunchKernelGGL((PassKernels<NT, 0, true>::n), LRQ_PASS_ARGS_N);
+        else     hipLaunchKernelGGL((PassKernels<NT, 0, false>::n), LRQ_PASS_ARGS_N);
     } else {
-        if (vec) hipLaunchKernelGGL((PassKernels<NT, 1, true>::n), LRQ_PASS_ARGS);
-        else     hipLaunchKernelGGL((PassKernels<NT, 1, false>::n), LRQ_PASS_ARGS);
+        if (vec) hipLaunchKernelGGL((PassKernels<NT, 1, true>::n), LRQ_PASS_ARGS_N);
+        else     hipLaunchKernelGGL((PassKernels<NT, 1, false>::n), LRQ_PASS_ARGS_N);
     }
 }
 
@@ -1004,6 +1080,39 @@ int launch_resid_mul_n(const float* X, int ldx, int rows, int cols, int axis, co
     const bool vec = (cols % 4 == 0) && (ldx % 4 == 0) && aligned16(X);
     dim3 grid(ceil_div(rows, 64), plan.splits);
     NT_SWITCH(LP / 16, (dispatch_n<NT_>(axis, vec, planes, grid, st, X, ldx, rows, cols, lam, s, q, W, plan.chunk, partial)));
+    LRQ_CHECK_LAUNCH();
+    return LRQMM_OK;
+}
+
+bool quant_sketch_fusable(const float* X, int ldx, int rows, int cols, int LP, PassPlan plan, const int8_t* codes) {
+    return LP >= 32 && rows % 64 == 0 && cols % 64 == 0 && plan.chunk % 64 == 0 && ldx % 4 == 0 && aligned16(X) &&
+           aligned16(codes);
+}
+
+int launch_quant_sketch(const float* X, int ldx, int rows, int cols, int axis, const float* amax, QuantParams q,
+                        const float* W, int LP, PassPlan plan, float* partial, float* lam_out, float* s_out,
+                        int8_t* codes, hipStream_t st, int planes) {
+    if (!quant_sketch_fusable(X, ldx, rows, cols, LP, plan, codes)) return LRQMM_ERR_UNSUPPORTED;
+    dim3 grid(rows / 64, plan.splits);
+    const QOut qo = {amax, lam_out, s_out, codes};
+    const float* lam = nullptr;
+    const float* s = nullptr;
+    const int chunk = plan.chunk;
+#define LRQ_QS(NTV, PLV)                                                                                           \
+    do {                                                                                                            \
+        if (axis == 0) hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NTV, 0, true, true, PLV, true>), LRQ_PASS_ARGS, qo); \
+        else           hipLaunchKernelGGL((resid_mul_n_bf16_kernel<NTV, 1, true, true, PLV, true>), LRQ_PASS_ARGS, qo); \
+    } while (0)
+#define LRQ_QS_PL(NTV) do { if (planes == 2) LRQ_QS(NTV, 2); else if (planes == 1) LRQ_QS(NTV, 1); else LRQ_QS(NTV, 3); } while (0)
+    switch (LP / 16) {
+        case 2: LRQ_QS_PL(2); break;
+        case 3: LRQ_QS_PL(3); break;
+        case 4: LRQ_QS_PL(4); break;
+        case 5: LRQ_QS_PL(5); break;
+        default: return LRQMM_ERR_UNSUPPORTED;
+    }
+#undef LRQ_QS_PL
+#undef LRQ_QS
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }

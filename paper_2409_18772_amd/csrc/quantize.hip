@@ -123,16 +123,21 @@ __global__ void fill_u32_kernel(uint32_t* p, int n, uint32_t v) {
     if (i < n) p[i] = v;
 }
 
-// Column absmax of a row-major matrix: each thread owns 4 adjacent columns and walks a
-// slab of rows (coalesced 4 KB per row per block); slabs are merged with an unsigned
-// atomic max on the bit pattern of |x| (exact and order independent for x >= 0).
+// Column absmax of a row-major matrix.  A workgroup takes 256 columns and a slab of rows: a wave reads 1 KB
+// of one row per instruction (each lane 4 adjacent columns), the four waves take every fourth row of the slab,
+// 16 row loads in flight per lane; the waves' maxima are merged through LDS and the slabs with one unsigned
+// atomic max per column on the bit pattern of |x| (exact and order independent for x >= 0).
+#ifndef LRQ_ABSMAX_WGS
+#define LRQ_ABSMAX_WGS 1024     // workgroups aimed at (more slabs: more atomics per column)
+#endif
 template <bool VEC>
 __global__ __launch_bounds__(256) void absmax_cols_kernel(const float* __restrict__ X, int ldx, int rows,
                                                           int cols, int rows_per_block,
                                                           uint32_t* __restrict__ amax_bits, QuantParams q,
                                                           const float* __restrict__ amax0) {
-    const int c = (blockIdx.x * 256 + threadIdx.x) * 4;
-    if (c >= cols) return;
+    __shared__ float4 red[4][64];
+    const int quad = threadIdx.x & 63, rg = threadIdx.x >> 6;
+    const int c = (blockIdx.x * 64 + quad) * 4;
     float lam0[4] = {0.f, 0.f, 0.f, 0.f}, s0[4] = {0.f, 0.f, 0.f, 0.f};
     if (amax0) {
 #pragma unroll
@@ -141,10 +146,10 @@ __global__ __launch_bounds__(256) void absmax_cols_kernel(const float* __restric
     const int r0 = blockIdx.y * rows_per_block;
     const int r1 = min(rows, r0 + rows_per_block);
     float4 m = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int rb = r0; rb < r1; rb += 16) {      // 16 row loads in flight per thread (rows clamped, max is idempotent)
+    for (int rb = r0 + rg; rb < r1; rb += 64) {     // rows clamped into the slab: max is idempotent
         float4 v[16];
 #pragma unroll
-        for (int u = 0; u < 16; ++u) v[u] = load4f<VEC>(X + (size_t)min(rb + u, r1 - 1) * ldx, c, cols, true);
+        for (int u = 0; u < 16; ++u) v[u] = load4f<VEC>(X + (size_t)min(rb + 4 * u, r1 - 1) * ldx, c, cols, true);
 #pragma unroll
         for (int u = 0; u < 16; ++u) {
             if (amax0)
@@ -155,6 +160,14 @@ __global__ __launch_bounds__(256) void absmax_cols_kernel(const float* __restric
             m.z = fmaxf(m.z, fabsf(v[u].z));
             m.w = fmaxf(m.w, fabsf(v[u].w));
         }
+    }
+    red[rg][quad] = m;
+    __syncthreads();
+    if (rg != 0 || c >= cols) return;
+#pragma unroll
+    for (int g = 1; g < 4; ++g) {
+        const float4 o = red[g][quad];
+        m.x = fmaxf(m.x, o.x); m.y = fmaxf(m.y, o.y); m.z = fmaxf(m.z, o.z); m.w = fmaxf(m.w, o.w);
     }
     if (c + 0 < cols) atomicMax(amax_bits + c + 0, __float_as_uint(m.x));
     if (c + 1 < cols) atomicMax(amax_bits + c + 1, __float_as_uint(m.y));
@@ -290,20 +303,17 @@ static int rows_launch(const float* X, int ldx, int rows, int cols, QuantParams 
     return LRQMM_OK;
 }
 
-int launch_quantize_cols(const float* X, int ldx, int rows, int cols, QuantParams q, bool per_tensor,
-                         const float* amax0, int8_t* codesT, float* amax, hipStream_t st, bool amax_zeroed,
-                         float* lam_out, float* s_out) {
+static int absmax_cols_launch(const float* X, int ldx, int rows, int cols, QuantParams q, bool per_tensor,
+                              const float* amax0, float* amax, hipStream_t st, bool amax_zeroed) {
     const bool vec = (cols % 4 == 0) && (ldx % 4 == 0) && aligned16(X);
-    const bool vecout = (rows % 16 == 0) && aligned16(codesT);
-    const int npad = (cols + 3) / 4 * 4;
     if (!amax_zeroed) {
         hipLaunchKernelGGL(fill_u32_kernel, dim3(ceil_div(cols, 256)), dim3(256), 0, st,
                            reinterpret_cast<uint32_t*>(amax), cols, 0u);
         LRQ_CHECK_LAUNCH();
     }
-    // enough row slabs to fill the chip, at least 32 rows each
-    const int col_blocks = ceil_div(cols, 1024);
-    int slabs = max(1, min(ceil_div(rows, 32), ceil_div(2048, col_blocks)));
+    // enough row slabs to fill the chip, at least 64 rows each (one batch of loads per lane)
+    const int col_blocks = ceil_div(cols, 256);
+    int slabs = max(1, min(ceil_div(rows, 64), ceil_div(LRQ_ABSMAX_WGS, col_blocks)));
     const int rows_per_block = ceil_div(rows, slabs);
     slabs = ceil_div(rows, rows_per_block);
     dim3 g1(col_blocks, slabs);
@@ -318,6 +328,31 @@ int launch_quantize_cols(const float* X, int ldx, int rows, int cols, QuantParam
         hipLaunchKernelGGL(tensor_max_kernel, dim3(1), dim3(1024), 0, st, amax, cols);
         LRQ_CHECK_LAUNCH();
     }
+    return LRQMM_OK;
+}
+
+int launch_absmax_cols(const float* X, int ldx, int rows, int cols, QuantParams q, bool per_tensor, float* amax,
+                       hipStream_t st, bool amax_zeroed) {
+    return absmax_cols_launch(X, ldx, rows, cols, q, per_tensor, nullptr, amax, st, amax_zeroed);
+}
+
+int launch_absmax_rows(const float* X, int ldx, int rows, int cols, QuantParams q, bool per_tensor, float* amax,
+                       hipStream_t st) {
+    int rc = rows_launch(X, ldx, rows, cols, q, nullptr, amax, ROWS_AMAX_ONLY, nullptr, st);
+    if (rc != LRQMM_OK || !per_tensor) return rc;
+    hipLaunchKernelGGL(tensor_max_kernel, dim3(1), dim3(1024), 0, st, amax, rows);
+    LRQ_CHECK_LAUNCH();
+    return LRQMM_OK;
+}
+
+int launch_quantize_cols(const float* X, int ldx, int rows, int cols, QuantParams q, bool per_tensor,
+                         const float* amax0, int8_t* codesT, float* amax, hipStream_t st, bool amax_zeroed,
+                         float* lam_out, float* s_out) {
+    const bool vec = (cols % 4 == 0) && (ldx % 4 == 0) && aligned16(X);
+    const bool vecout = (rows % 16 == 0) && aligned16(codesT);
+    const int npad = (cols + 3) / 4 * 4;
+    const int rc = absmax_cols_launch(X, ldx, rows, cols, q, per_tensor, amax0, amax, st, amax_zeroed);
+    if (rc != LRQMM_OK) return rc;
     dim3 g2(ceil_div(cols, 64), ceil_div(rows, 64));
     if (vec && vecout)
         hipLaunchKernelGGL((quant_cols_kernel<true, true>), g2, dim3(256), 0, st, X, ldx, rows, cols, amax, q, codesT, amax0, lam_out, s_out, npad);

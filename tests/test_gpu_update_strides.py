@@ -225,3 +225,32 @@ def test_guard_free_pass_kernels_equal_the_guarded_ones_bitwise(axis, ell, round
     b = L.lrqmm_rsvd_ex(view, amax, axis, 4, rank, p, 1, seed=13, round_mode=round_mode)
     for x, y, name in zip(a, b, ("U", "Sigma", "Vt")):
         assert torch.equal(x, y), name
+
+
+@pytest.mark.parametrize("M,N,K,r,p,mode,tensor", [(640, 512, 768, 24, 8, 0, False), (512, 640, 1024, 16, 8, 1, False),
+                                                   (640, 512, 768, 60, 12, 0, True)])
+def test_fused_quantize_and_sketch_equals_the_separate_calls_bitwise(M, N, K, r, p, mode, tensor):
+    """For shapes on the guard-free pass kernels, lrqmm_matmul takes the group maxima first and lets the first
+    residual product write the codes and the step vectors as well (one read of each operand fewer).  The same
+    arithmetic in the same order as quantizing and factoring separately: the chain of lrqmm_quantize_ex,
+    lrqmm_rsvd and lrqmm_gemm must give the same C bit for bit (both rounding modes, both scale granularities)."""
+    import torch
+    import paper_2409_18772_amd as L
+    A = wl.random_matrix("normal", M, K, seed=51)
+    B = wl.random_matrix("uniform01", K, N, seed=52)
+    dA, dB = to_dev(A), to_dev(B)
+    say("fused quantize + sketch", M, N, K, r, p, mode, tensor)
+    sm = L.SCALE_TENSOR if tensor else L.SCALE_VECTOR
+    D = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    L.lrqmm_matmul_ex(dA, dB, D, 4, r, p, 1, seed=17, round_mode=mode, scale_mode=sm)
+    Aq, amA = L.lrqmm_quantize_ex(dA, 0, 4, mode, sm)
+    BqT, amB = L.lrqmm_quantize_ex(dB, 1, 4, mode, sm)
+    fa = L.lrqmm_rsvd(dA, amA, 0, 4, r, p, 1, seed=17, round_mode=mode)
+    fb = L.lrqmm_rsvd(dB, amB, 1, 4, r, p, 1, seed=17, round_mode=mode)
+    C = L.lrqmm_gemm(Aq, amA, BqT, amB, 4, fa, fb)
+    assert torch.equal(C, D)
+    # and against the oracle, like every other path
+    ref = o.lrqmm(A, B, 4, r, p, 1, seed=17, round_mode=mode, per_tensor=tensor)
+    from gpu_util import rel_fro, check_elementwise
+    assert rel_fro(ref["C"], to_np(D)) < tol_for(ref)
+    check_elementwise(to_np(D), ref, r, what="fused quantize + sketch")
