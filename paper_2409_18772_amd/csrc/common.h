@@ -107,6 +107,50 @@ __device__ __forceinline__ float4 load4_padded(const float* __restrict__ p, int 
     return make_float4(ok ? t.x : 0.f, ok ? t.y : 0.f, ok ? t.z : 0.f, ok ? t.w : 0.f);
 }
 
+// ---- float32 values as sums of bfloat16 planes (for the bf16 matrix cores) ----
+// A float32 value is the exact sum of three bfloat16 planes (8 + 8 + 8 significant bits: round to nearest,
+// subtract, repeat); products of such sums are evaluated plane by plane, each product exact, accumulated in
+// float32 by the matrix core.
+typedef __bf16 v8bf16 __attribute__((ext_vector_type(8)));
+struct Planes3 {
+    v8bf16 p1, p2, p3;
+};
+typedef __bf16 v2bf16 __attribute__((ext_vector_type(2)));
+typedef float v2f32 __attribute__((ext_vector_type(2)));
+// Two values per conversion instruction; a bfloat16 is the upper half of its float32, so the
+// converted pair is widened again with a shift and a mask.
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector((v2f32){a, b}, v2bf16));
+}
+// PL planes are formed (1, 2 or 3); the members beyond PL stay unset and must not be used.
+template <int PL = 3>
+__device__ __forceinline__ Planes3 split_planes(const float (&r)[8]) {
+    uint32_t w1[4], w2[4], w3[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float a = r[2 * e], b = r[2 * e + 1];
+        const uint32_t h = pack_bf16x2(a, b);
+        w1[e] = h;
+        if (PL >= 2) {
+            const float ra = a - __uint_as_float(h << 16);              // exact
+            const float rb = b - __uint_as_float(h & 0xffff0000u);
+            const uint32_t m = pack_bf16x2(ra, rb);
+            w2[e] = m;
+            if (PL >= 3) {
+                const float ra2 = ra - __uint_as_float(m << 16);            // exact
+                const float rb2 = rb - __uint_as_float(m & 0xffff0000u);
+                w3[e] = pack_bf16x2(ra2, rb2);
+            }
+        }
+    }
+    typedef uint32_t v4u32 __attribute__((ext_vector_type(4)));
+    Planes3 o;
+    o.p1 = __builtin_bit_cast(v8bf16, (v4u32){w1[0], w1[1], w1[2], w1[3]});
+    if (PL >= 2) o.p2 = __builtin_bit_cast(v8bf16, (v4u32){w2[0], w2[1], w2[2], w2[3]});
+    if (PL >= 3) o.p3 = __builtin_bit_cast(v8bf16, (v4u32){w3[0], w3[1], w3[2], w3[3]});
+    return o;
+}
+
 #define LRQ_CHECK_LAUNCH()                                   \
     do {                                                     \
         if (hipGetLastError() != hipSuccess) return LRQMM_ERR_HIP; \

@@ -500,6 +500,132 @@ __global__ __launch_bounds__(256, 2) void rank_update_kernel(int M, int N, float
                                     alpha * f[mt][nt][4 * g + 2], alpha * f[mt][nt][4 * g + 3]);
 }
 
+// The same update for wide panels (2r > 64), where the float32 matrix cores are the limit (4 R2P flops per output:
+// 0.87 ms of matrix-core time at 16384^2 and r = 64).  The panel rows are split into three bfloat16 planes while
+// they are staged in LDS (exact: a float32 is the sum of its three planes) and the six plane products of weight
+// >= 2^-16 run on v_mfma_f32_32x32x16_bf16 with float32 accumulation: 192 instead of 512 matrix-core cycles per
+// 16 panel columns.  Float32-equivalent, but a different rounding order than the float32 instructions: results
+// are not bit-identical to the fused epilogue.  Operand layout (lane l): A[i = l%32][k = 8(l/32) .. +8],
+// B[k = 8(l/32) .. +8][j = l%32]; D as for the 32x32 float32 instruction.
+#define RU_KC 32        // panel columns per LDS chunk
+#define RU_LD 40        // plane row stride in bfloat16 (80 bytes: conflict-free 16-byte reads)
+__global__ __launch_bounds__(256, 2) void rank_update_bf16_kernel(int M, int N, float* __restrict__ C,
+                                                                  const float* __restrict__ sA,
+                                                                  const float* __restrict__ sB,
+                                                                  const float* __restrict__ Lp,
+                                                                  const float* __restrict__ Rp, int R2P, int tiles_n,
+                                                                  float alpha) {
+    __shared__ __align__(16) uint16_t pp[2][3][128 * RU_LD];     // [Lp | Rp][plane][row][column of the chunk]
+    const int m0 = (blockIdx.x / tiles_n) * 128, n0 = (blockIdx.x % tiles_n) * 128;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int rb0 = m0 + wm * 64, cb0 = n0 + wn * 64;
+    int row[2], colb[2][4];
+    bool row_ok[2], col_ok[2][4];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        row_ok[t] = rb0 + t * 32 + l32 < M;
+        row[t] = min(rb0 + t * 32 + l32, M - 1);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int c = cb0 + t * 32 + 8 * g + 4 * lh;
+            col_ok[t][g] = c < N;
+            colb[t][g] = min(c, N - 4);
+        }
+    }
+    v16f f[2][2];
+    {
+        int4 raw[2][2][4];
+        float4 sb[2][4];
+        float sa[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            sa[t] = sA[row[t]];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) sb[t][g] = *reinterpret_cast<const float4*>(sB + colb[t][g]);
+        }
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    raw[mt][nt][g] = *reinterpret_cast<const int4*>(C + (size_t)row[mt] * N + colb[nt][g]);
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    f[mt][nt][4 * g + 0] = ((float)raw[mt][nt][g].x * sa[mt]) * sb[nt][g].x;
+                    f[mt][nt][4 * g + 1] = ((float)raw[mt][nt][g].y * sa[mt]) * sb[nt][g].y;
+                    f[mt][nt][4 * g + 2] = ((float)raw[mt][nt][g].z * sa[mt]) * sb[nt][g].z;
+                    f[mt][nt][4 * g + 3] = ((float)raw[mt][nt][g].w * sa[mt]) * sb[nt][g].w;
+                }
+    }
+    for (int t0 = 0; t0 < R2P; t0 += RU_KC) {       // R2P % 8 == 0
+        if (t0 > 0) __syncthreads();                // the previous chunk is no longer read
+        // 2 panels x 128 rows x 4 groups of 8 columns = 1024 units, four per thread: load, split, store the planes
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int unit = threadIdx.x + 256 * i;
+            const int pnl = unit >> 9, r = (unit >> 2) & 127, c8 = (unit & 3) * 8;
+            const float* src = pnl == 0 ? Lp + (size_t)min(m0 + r, M - 1) * R2P : Rp + (size_t)min(n0 + r, N - 1) * R2P;
+            float v[8];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {           // rows / columns past the end re-read the last one (never stored)
+                const int col = t0 + c8 + 4 * h;
+                const bool in = col < R2P;          // panel columns past R2P enter as zeros
+                const float4 x = *reinterpret_cast<const float4*>(src + min(col, R2P - 4));
+                v[4 * h + 0] = in ? x.x : 0.f; v[4 * h + 1] = in ? x.y : 0.f;
+                v[4 * h + 2] = in ? x.z : 0.f; v[4 * h + 3] = in ? x.w : 0.f;
+            }
+            const Planes3 pl = split_planes<3>(v);
+            *reinterpret_cast<v8bf16*>(&pp[pnl][0][r * RU_LD + c8]) = pl.p1;
+            *reinterpret_cast<v8bf16*>(&pp[pnl][1][r * RU_LD + c8]) = pl.p2;
+            *reinterpret_cast<v8bf16*>(&pp[pnl][2][r * RU_LD + c8]) = pl.p3;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < RU_KC / 16; ++u) {
+            Planes3 a[2], b[2];     // a: Lp rows of the two row tiles (B operand), b: Rp rows of the two column tiles (A operand)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int oa = (wm * 64 + t * 32 + l32) * RU_LD + 16 * u + 8 * lh;
+                const int ob = (wn * 64 + t * 32 + l32) * RU_LD + 16 * u + 8 * lh;
+                a[t].p1 = *reinterpret_cast<const v8bf16*>(&pp[0][0][oa]);
+                a[t].p2 = *reinterpret_cast<const v8bf16*>(&pp[0][1][oa]);
+                a[t].p3 = *reinterpret_cast<const v8bf16*>(&pp[0][2][oa]);
+                b[t].p1 = *reinterpret_cast<const v8bf16*>(&pp[1][0][ob]);
+                b[t].p2 = *reinterpret_cast<const v8bf16*>(&pp[1][1][ob]);
+                b[t].p3 = *reinterpret_cast<const v8bf16*>(&pp[1][2][ob]);
+            }
+            // the six plane products, smallest first; the four tiles are independent chains
+#define LRQ_RU_PP(PB, PA)                                                                                   \
+    _Pragma("unroll") for (int mt = 0; mt < 2; ++mt) _Pragma("unroll") for (int nt = 0; nt < 2; ++nt)        \
+        f[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[nt].PB, a[mt].PA, f[mt][nt], 0, 0, 0);
+            LRQ_RU_PP(p3, p1)
+            LRQ_RU_PP(p2, p2)
+            LRQ_RU_PP(p1, p3)
+            LRQ_RU_PP(p2, p1)
+            LRQ_RU_PP(p1, p2)
+            LRQ_RU_PP(p1, p1)
+#undef LRQ_RU_PP
+        }
+    }
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                if (row_ok[mt] && col_ok[nt][g])
+                    *reinterpret_cast<float4*>(C + (size_t)row[mt] * N + colb[nt][g]) =
+                        make_float4(alpha * f[mt][nt][4 * g + 0], alpha * f[mt][nt][4 * g + 1],
+                                    alpha * f[mt][nt][4 * g + 2], alpha * f[mt][nt][4 * g + 3]);
+}
+
 // ---------------------------------------------------------------------------
 // Panels of the rank-2r update (compensation terms of Algorithm 2 regrouped):
 //   C = C0 + [U Sigma | A~ W] . [V^T B~ + (V^T W) Gamma Z^T ; Gamma Z^T]
@@ -902,8 +1028,12 @@ bool rank_update_usable(int M, int N, const float* C) {
 int launch_rank_update(int M, int N, float* C, const float* sA, const float* sB, const float* Lp, const float* Rp,
                        int R2P, float alpha, hipStream_t st) {
     const int tiles_n = ceil_div(N, 128);
-    hipLaunchKernelGGL(rank_update_kernel, dim3(ceil_div(M, 128) * tiles_n), dim3(256), 0, st, M, N, C, sA, sB, Lp,
-                       Rp, R2P, tiles_n, alpha);
+    if (R2P > 64)       // wide panels: bound by the float32 matrix cores, so the plane products on the bf16 ones
+        hipLaunchKernelGGL(rank_update_bf16_kernel, dim3(ceil_div(M, 128) * tiles_n), dim3(256), 0, st, M, N, C, sA, sB,
+                           Lp, Rp, R2P, tiles_n, alpha);
+    else
+        hipLaunchKernelGGL(rank_update_kernel, dim3(ceil_div(M, 128) * tiles_n), dim3(256), 0, st, M, N, C, sA, sB, Lp,
+                           Rp, R2P, tiles_n, alpha);
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }

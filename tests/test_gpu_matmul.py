@@ -237,6 +237,24 @@ def test_ragged_large_tile_shapes(M, N, K, fused):
     assert np.all(to_np(big)[:, N:] == -7.0)
 
 
+def test_wide_panels_large_tiles_sampled_rows():
+    """Rank 64 on the large-tile schedule (early integer product, rank update as its own kernel): panels of
+    2r = 128 columns take the update kernel that forms the panel products from bfloat16 planes.  Oracle on
+    sampled rows, Frobenius and element-wise."""
+    import paper_2409_18772_amd as L
+    M, N, K, bits, r, p, q = 4096, 2048, 512, 4, 64, 16, 1
+    A = wl.random_matrix("normal", M, K, seed=61)
+    B = wl.random_matrix("normal", K, N, seed=62)
+    rows = np.sort(np.random.default_rng(9).choice(M, size=16, replace=False))
+    say("wide panels", M, N, K, r)
+    C = to_np(L.lrqmm_matmul(to_dev(A), to_dev(B), bits, r, p, q, seed=13))
+    ref = o.lrqmm(A, B, bits, r, p, q, seed=13, row_sample=rows, want_cint=False)
+    d = rel_fro(ref["C"], C[rows])
+    say("gpu vs oracle", d, "tol", tol_for(ref))
+    assert d < tol_for(ref)
+    check_elementwise(C[rows], ref, r, rows, what="wide panels")
+
+
 def test_empty_reduction_reads_no_operand():
     """K = 0 with M, N > 0: C_F = 0, so D <- beta D (zeros when beta = 0); the GEMM kernels are not
     launched at all (they load their first operand tile unconditionally)."""
