@@ -209,11 +209,13 @@ LRQMM_API int lrqmm_gemm_static(int M, int N, int K, int bits, int rank,
  * a second stream owned by the library (created on first use, default priority),
  * forked from and joined back into `stream` with events, so the call is still
  * ordered like a single-stream call from the caller's point of view.  For large
- * problems the integer product is enqueued on a third library stream while both
+ * problems with a sketch of at least 32 columns (a small SVD long enough to hide it)
+ * the integer product is enqueued on a third library stream while both
  * factorizations are in their small SVD (the GPU is nearly idle then); it leaves
  * raw int32 sums in C's memory, and the dequantizing rank-2r update runs after the
  * panels as a kernel of its own with the arithmetic of the fused epilogue (same
- * bits).  C must therefore not be read between the call and its completion on
+ * bits for panels of up to 64 columns, 2 rank <= 64; wider panels are accumulated from
+ * bfloat16 planes, float32-equivalent but in another rounding order).  C must therefore not be read between the call and its completion on
  * `stream`.  Calls must not be issued concurrently from several host threads.
  * The call enqueues only kernels and event waits (memory is cleared by fill kernels), so it may be
  * recorded into a HIP graph by stream capture on `stream`; the library's own streams join the

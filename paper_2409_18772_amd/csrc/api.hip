@@ -569,7 +569,11 @@ int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int
     // stream, leaves raw int32 sums in C, and the epilogue follows the panels as a kernel of
     // its own.  Used for problems on the large-tile kernel.
     // (the raw sums need D's memory: only when its old contents are not an input and it is dense)
-    const bool early = overlap && rank_update_usable(M, N, C) && beta == 0.0f && ldd == N;
+    // Measured on both sides of the rule (4096^3): at l = 24 the SVD takes ~60 us, the product ~85 us -- it outlasts
+    // the window, holds the CUs the panel kernels need, and the fused kernel after the panels is 3-5 % faster; at
+    // l = 40 (SVD ~115 us) the early product wins by 3-5 %; at 16384^3, l = 80 by 10 % (the SVD and the panel
+    // kernels run beside the product, and the update of wide panels has a faster kernel of its own).
+    const bool early = overlap && rank_update_usable(M, N, C) && beta == 0.0f && ldd == N && rank + oversample >= 32;
     if (slot >= 0) g_prof.early[slot] = early;
     hipStream_t gst = early ? side->gemm_stream : pst;
     // the two sides are planned first and then issued alternately (see LaunchList)

@@ -201,7 +201,7 @@ def test_ragged_large_tile_shapes(M, N, K, fused):
     epilogue.  Oracle on sampled rows, including the last (partial) tile row."""
     import torch
     import paper_2409_18772_amd as L
-    bits, r, p, q = 4, 12, 4, 1
+    bits, r, p, q = 4, 28, 4, 1      # a sketch of 32 columns: the width from which the early-product schedule is used
     A = wl.random_matrix("normal", M, K, seed=41)
     B = wl.random_matrix("uniform01", K, N, seed=42)
     rows = np.sort(np.concatenate([[0, 255, 256, 4095, 4096, M - 1],
@@ -322,17 +322,18 @@ def test_largest_config_properties():
 def test_call_can_be_captured_in_a_graph(shape):
     """The call only enqueues kernels and event waits (its clears are fill kernels), so it may be recorded
     into a HIP graph, side streams included; every replay must reproduce the eager result, with eager work
-    and synchronizations between the replays.  The first shape takes the three-stream schedule."""
+    and synchronizations between the replays.  The first shape takes the three-stream schedule (sketch of 32
+    columns on the large-tile kernel)."""
     import torch
     import paper_2409_18772_amd as L
     M, N, K = shape
     A = to_dev(wl.random_matrix("normal", M, K, seed=31))
     B = to_dev(wl.random_matrix("normal", K, N, seed=32))
-    ws = L.Workspace.for_problem(M, N, K, 8, 4)
+    ws = L.Workspace.for_problem(M, N, K, 28, 4)
     C = torch.empty((M, N), dtype=torch.float32, device="cuda")
 
     def step():
-        L.lrqmm_matmul(A, B, 4, 8, 4, 1, seed=7, workspace=ws, C=C)
+        L.lrqmm_matmul(A, B, 4, 28, 4, 1, seed=7, workspace=ws, C=C)
 
     step()
     torch.cuda.synchronize()
@@ -366,9 +367,9 @@ def test_capture_with_profiling_on_is_refused():
     M, N, K = 300, 200, 260
     A = to_dev(wl.random_matrix("normal", M, K, seed=31))
     B = to_dev(wl.random_matrix("normal", K, N, seed=32))
-    ws = L.Workspace.for_problem(M, N, K, 8, 4)
+    ws = L.Workspace.for_problem(M, N, K, 28, 4)
     C = torch.empty((M, N), dtype=torch.float32, device="cuda")
-    L.lrqmm_matmul(A, B, 4, 8, 4, 1, seed=7, workspace=ws, C=C)      # library streams exist from here on
+    L.lrqmm_matmul(A, B, 4, 28, 4, 1, seed=7, workspace=ws, C=C)      # library streams exist from here on
     torch.cuda.synchronize()
     ref = C.clone()
     s = torch.cuda.Stream()
@@ -381,14 +382,14 @@ def test_capture_with_profiling_on_is_refused():
         with torch.cuda.graph(g, stream=s):
             tmp.zero_()                  # (the graph is not empty)
             try:
-                L.lrqmm_matmul(A, B, 4, 8, 4, 1, seed=7, workspace=ws, C=C)
+                L.lrqmm_matmul(A, B, 4, 28, 4, 1, seed=7, workspace=ws, C=C)
             except L.LrqmmError as e:
                 status = e.status
     finally:
         L.lrqmm_profile_enable(False)
     torch.cuda.synchronize()
     assert status == -2
-    L.lrqmm_matmul(A, B, 4, 8, 4, 1, seed=7, workspace=ws, C=C)      # the library still works
+    L.lrqmm_matmul(A, B, 4, 28, 4, 1, seed=7, workspace=ws, C=C)      # the library still works
     torch.cuda.synchronize()
     assert torch.equal(C, ref)
 
@@ -399,11 +400,11 @@ def test_gemm_only_profiling_mode():
     M, N, K = 4096, 2048, 512
     A = to_dev(wl.random_matrix("normal", M, K, seed=33))
     B = to_dev(wl.random_matrix("normal", K, N, seed=34))
-    ws = L.Workspace.for_problem(M, N, K, 8, 4)
+    ws = L.Workspace.for_problem(M, N, K, 28, 4)
     L.lrqmm_profile_enable(L.PROF_GEMM_ONLY)
     try:
         for _ in range(3):
-            L.lrqmm_matmul(A, B, 4, 8, 4, 1, workspace=ws)          # early product: stage int_gemm
+            L.lrqmm_matmul(A, B, 4, 28, 4, 1, workspace=ws)         # early product: stage int_gemm
         torch.cuda.synchronize()
         st, n = L.lrqmm_profile_read()
         assert n == 3 and st["int_gemm"] > 0 and st["gemm"] == 0 and st["rsvd_a"] == 0

@@ -149,7 +149,7 @@ def test_large_tile_paths_sampled_rows(alpha, beta, pad_d):
     """Sizes on the large-tile kernel: beta = 0 on a dense D takes the early-product schedule (alpha is
     applied by the update kernel), any other case the fused store phase."""
     import paper_2409_18772_amd as L
-    M, N, K, bits, r, p, q = 4096, 2048, 512, 4, 8, 4, 1
+    M, N, K, bits, r, p, q = 4096, 2048, 512, 4, 28, 4, 1
     A = wl.random_matrix("normal", M, K, seed=12)
     B = wl.random_matrix("normal", K, N, seed=13)
     D0 = wl.random_matrix("normal", M, N, seed=14)
@@ -195,12 +195,12 @@ def test_early_product_equals_fused_store_phase_bitwise(K):
     dA, dB = to_dev(A), to_dev(B)
     say("early vs fused", K)
     D1 = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
-    L.lrqmm_matmul_ex(dA, dB, D1, 4, 8, 4, 1, seed=5)
+    L.lrqmm_matmul_ex(dA, dB, D1, 4, 28, 4, 1, seed=5)
     big, D2 = window(np.zeros((M, N), dtype=np.float32), 4)
-    L.lrqmm_matmul_ex(dA, dB, D2, 4, 8, 4, 1, seed=5)
+    L.lrqmm_matmul_ex(dA, dB, D2, 4, 28, 4, 1, seed=5)
     assert torch.equal(D1, D2)
     # twice in a row on the same output: the zeroing of the summed tiles is part of every call
-    L.lrqmm_matmul_ex(dA, dB, D1, 4, 8, 4, 1, seed=5)
+    L.lrqmm_matmul_ex(dA, dB, D1, 4, 28, 4, 1, seed=5)
     assert torch.equal(D1, D2)
 
 
