@@ -184,15 +184,18 @@ def main():
     stage_info = {
         k: {"ms": round(v, 4)} for k, v in stages.items()
     }
-    # quantize: A read twice (second touch from cache) -> algorithmic 4 B read + 1 B written per element;
-    # B additionally one absmax pass
-    for key, q_bytes in (("quantize_a", 5.0 * w.M * w.K), ("quantize_b", 9.0 * w.K * w.N)):
-        gbs = q_bytes / (stages[key] * 1e-3) / 1e9
-        stage_info[key].update(algorithmic_GBs=round(gbs, 1), frac_hbm=round(gbs / PEAK_HBM_GBS, 4))
-    for key, elems in (("rsvd_a", w.M * w.K), ("rsvd_b", w.K * w.N)):
-        if stages[key] > 0:
-            gbs = passes * 4.0 * elems / (stages[key] * 1e-3) / 1e9
-            stage_info[key].update(passes=passes, algorithmic_GBs=round(gbs, 1), frac_hbm=round(gbs / PEAK_HBM_GBS, 4))
+    # Quantization + factorization of one operand as one streaming job.  Algorithmic bytes: one read for the
+    # group maxima, one per residual product (the first of them also writes the codes), 4 B per element each,
+    # plus 1 B per element of codes.  (Shapes off the guard-free kernels read B once more: maxima, codes,
+    # products.)  With rank 0 only the maxima and the codes remain.
+    for op, elems in (("a", w.M * w.K), ("b", w.K * w.N)):
+        n_reads = (1 + passes) if w.rank > 0 else (1 if op == "a" else 2)
+        job_ms = stages["quantize_" + op] + stages["rsvd_" + op]
+        gbs = (4.0 * n_reads + 1.0) * elems / (job_ms * 1e-3) / 1e9
+        stage_info["rsvd_" + op].update(passes=passes)
+        stage_info["quantize_and_factor_" + op] = {
+            "ms": round(job_ms, 4), "operand_reads": n_reads, "algorithmic_GBs": round(gbs, 1),
+            "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
     stage_info[gemm_key].update(TOPs=round(achieved, 1), frac_int8_mfma=round(achieved / PEAK_INT8_TOPS, 4))
     if early:   # the dequantizing rank-2r update alone: reads and rewrites C
         gbs = 8.0 * w.M * w.N / (stages["gemm"] * 1e-3) / 1e9

@@ -35,7 +35,9 @@ size_t carve_rsvd(Arena& a, int rows, int cols, int axis, int LP, int rank, Rsvd
     const size_t part = (size_t)LP * (size_t)((size_t)pn.splits * rows > (size_t)pt.splits * cols
                                                   ? (size_t)pn.splits * rows
                                                   : (size_t)pt.splits * cols);
-    const int nb = gram_blocks(rows > cols ? rows : cols);
+    // (the block count is not monotone in the row count -- 4096 rows make 64 blocks of 64, 4100 rows 33 of 128 --
+    // so take the larger of the two uses, Gram of a rows x LP and of a cols x LP factor)
+    const int nb = gram_blocks(rows, LP) > gram_blocks(cols, LP) ? gram_blocks(rows, LP) : gram_blocks(cols, LP);
     RsvdWs t;
     t.lam = a.take<float>(npad);
     t.s = a.take<float>(npad);
@@ -295,7 +297,7 @@ static int rsvd_plan(LaunchList& ops, const float* X, int ldx, const float* amax
     // Q = orth(partial sums) in place: Gram (float64) -> Cholesky -> Q = Y T
     auto orth = [&](int splits, int n, float* buf) {
         ops.push_back([=] { return launch_reduce_gram(w.partial, splits, n, LP, nullptr, buf, w.gpart, st); });
-        ops.push_back([=] { return launch_gram_sum(w.gpart, gram_blocks(n), LP, w.gram, st); });
+        ops.push_back([=] { return launch_gram_sum(w.gpart, gram_blocks(n, LP), LP, w.gram, st); });
         ops.push_back([=] { return launch_chol_inverse(w.gram, ell, LP, w.T, st); });
         ops.push_back([=] { return launch_apply(buf, n, LP, w.T, LP, LP, buf, LP, 0, st); });
     };
@@ -324,7 +326,7 @@ static int rsvd_plan(LaunchList& ops, const float* X, int ldx, const float* amax
     // B^T = R^T Q (cols x l), its Gram B B^T, small SVD, U = Q U', V = B^T U' / sigma
     pass_t(planes_last);
     ops.push_back([=] { return launch_reduce_gram(w.partial, pt.splits, cols, LP, nullptr, w.Wc, w.gpart, st); });
-    ops.push_back([=] { return launch_gram_sum(w.gpart, gram_blocks(cols), LP, w.gram, st); });
+    ops.push_back([=] { return launch_gram_sum(w.gpart, gram_blocks(cols, LP), LP, w.gram, st); });
     if (svd_index) *svd_index = ops.size();         // the GPU is nearly idle from this launch to its end
     ops.push_back([=] { return launch_small_svd(w.gram, ell, LP, rank, Sigma, w.Ur, w.Mv, st); });
     ops.push_back([=] {

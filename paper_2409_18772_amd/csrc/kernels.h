@@ -85,7 +85,7 @@ int launch_codes_mul_n2(const int8_t* codesA, int rowsA, const float* WA, const 
                         PassPlan planB, float* partialB, int K, int Kp, int LP, hipStream_t st, int planes = 3);
 
 // ---- orth.hip -----------------------------------------------------------
-int gram_blocks(int n);
+int gram_blocks(int n, int LP);
 // Y[n][LP] = sum_s partial[s][n][LP] (optionally times rowscale[i]);
 // gpart[b][LP*LP] = Gram of rows 64b..64b+63 of Y in float64.
 int launch_reduce_gram(const float* partial, int splits, int n, int LP, const float* rowscale,

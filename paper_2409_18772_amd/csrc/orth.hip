@@ -13,16 +13,21 @@
 #include "kernels.h"
 
 #define GB_TILE 64        // rows of Y staged per LDS tile in the Gram kernel
-#define GRAM_MAX_BLOCKS 64
+#define GRAM_BATCH 64         // Gram partials that gram_sum_kernel adds per batch of loads
 #define GRAM_MIN_ROWS 64
 #define MAXL LRQMM_MAX_SKETCH
 
-static int gram_rows_per_block(int n) {
-    int nblk = min(GRAM_MAX_BLOCKS, max(1, ceil_div(n, GRAM_MIN_ROWS)));
+// Workgroups of the Gram kernel: 64 for wide sketches (each leaves an LP x LP float64 partial that a later
+// kernel has to add up: ~1 MB in all at LP = 48), more for narrow sketches, whose partials are small -- a tall
+// operand (10^5 rows at LP = 16) would otherwise keep 64 compute units busy for 25 tiles each.
+static int gram_max_blocks(int LP) { return LP <= 16 ? 512 : (LP <= 32 ? 128 : 64); }
+
+static int gram_rows_per_block(int n, int LP) {
+    int nblk = min(gram_max_blocks(LP), max(1, ceil_div(n, GRAM_MIN_ROWS)));
     return ceil_div(ceil_div(n, nblk), GB_TILE) * GB_TILE;
 }
 
-int gram_blocks(int n) { return max(1, ceil_div(n, gram_rows_per_block(n))); }
+int gram_blocks(int n, int LP) { return max(1, ceil_div(n, gram_rows_per_block(n, LP))); }
 
 // Y = sum of the pass partials (fixed order, optional row scale); gpart[block] = float64
 // Gram matrix of the block's rows.  Threads form a 16 x 16 grid; thread (ta, tb) keeps the
@@ -141,9 +146,9 @@ __global__ __launch_bounds__(256) void reduce_gram_kernel(const float* __restric
     }
 }
 
-// Gram matrix = the nb <= GRAM_MAX_BLOCKS block partials summed in fixed order, one thread per
-// entry.  The partials were written by other workgroups (other XCDs), so every load is a
-// long-latency miss: a thread issues all its loads before the first add, without branches (a
+// Gram matrix = the nb block partials summed in fixed order, one thread per entry, GRAM_BATCH partials per
+// batch of loads.  The partials were written by other workgroups (other XCDs), so every load is a
+// long-latency miss: a thread issues all loads of a batch before the first add, without branches (a
 // clamped index re-reads the last partial, whose value is then masked), and the entries are
 // spread over many small workgroups because one compute unit alone is load-bandwidth bound.
 __global__ __launch_bounds__(64) void gram_sum_kernel(const double* __restrict__ gpart, int nb, int entries,
@@ -151,12 +156,14 @@ __global__ __launch_bounds__(64) void gram_sum_kernel(const double* __restrict__
     const int idx = blockIdx.x * 64 + threadIdx.x;
     if (idx >= entries) return;
     const double* src = gpart + idx;
-    double v[GRAM_MAX_BLOCKS];
-#pragma unroll
-    for (int blk = 0; blk < GRAM_MAX_BLOCKS; ++blk) v[blk] = src[(size_t)min(blk, nb - 1) * entries];
     double acc = 0.0;
+    for (int b0 = 0; b0 < nb; b0 += GRAM_BATCH) {
+        double v[GRAM_BATCH];
 #pragma unroll
-    for (int blk = 0; blk < GRAM_MAX_BLOCKS; ++blk) acc += (blk < nb) ? v[blk] : 0.0;
+        for (int blk = 0; blk < GRAM_BATCH; ++blk) v[blk] = src[(size_t)min(b0 + blk, nb - 1) * entries];
+#pragma unroll
+        for (int blk = 0; blk < GRAM_BATCH; ++blk) acc += (b0 + blk < nb) ? v[blk] : 0.0;
+    }
     gram[idx] = acc;
 }
 
@@ -669,8 +676,8 @@ __global__ __launch_bounds__(SVD_THREADS) void small_svd_kernel(const double* __
 
 int launch_reduce_gram(const float* partial, int splits, int n, int LP, const float* rowscale, float* Y,
                        double* gpart, hipStream_t st) {
-    const int rpb = gram_rows_per_block(n);
-    dim3 grid(gram_blocks(n));
+    const int rpb = gram_rows_per_block(n, LP);
+    dim3 grid(gram_blocks(n, LP));
     NT_SWITCH(LP / 16, hipLaunchKernelGGL((reduce_gram_kernel<NT_>), grid, dim3(256), 0, st, partial, splits, n,
                                           rpb, rowscale, Y, gpart));
     LRQ_CHECK_LAUNCH();

@@ -37,6 +37,12 @@ RSVD_CASES = [
     (1024, 768, o.ROWWISE, 4, 32, 8, 1, "normal_outliers"),
     (768, 1024, o.COLWISE, 4, 64, 16, 2, "normal"),
     (96, 80, o.ROWWISE, 8, 80, 0, 0, "normal"),
+    # 4100 rows make fewer Gram workgroups (33 of 128 rows) than 4096 columns (64 of 64): the scratch for the
+    # Gram partials has to cover the larger of the two
+    (4100, 4096, o.ROWWISE, 4, 24, 8, 1, "normal"),
+    # a tall operand with a narrow sketch: more than 64 Gram workgroups, summed in several batches
+    (20000, 64, o.ROWWISE, 4, 8, 0, 1, "relu_normal"),
+    (64, 20000, o.COLWISE, 4, 8, 0, 1, "normal"),
 ]
 
 
