@@ -96,7 +96,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c3_4096_int4_r32_outliers")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rows", type=int, default=48)
+    ap.add_argument("--cpu-rows", type=int, default=192)
     ap.add_argument("--precision-modes", action="store_true",
                     help="also time the reduced-precision compensation modes and report their errors")
     ap.add_argument("--no-baselines", action="store_true",
@@ -252,7 +252,7 @@ def main():
                      "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                      "frac": round(achieved / PEAK_INT8_TOPS, 4),
                      # counter bytes of this kernel on this workload, or null when no summary is tracked for it
-                     "traffic": read_traffic(f"int8_gemm_{SHORT.get(w.name, w.name)}_pmc.txt") if early else None,
+                     "traffic": read_traffic(f"int8_gemm_{SHORT.get(w.name, w.name)}_pmc.txt"),
                      "launch_ms": round(stages[gemm_key], 4), "ops_per_launch": ops},
         "stages": stage_info,
         "stages_note": "GEMM launch time from HIP events inside the timed region; the other stages from a "

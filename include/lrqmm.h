@@ -59,7 +59,7 @@ extern "C" {
  * Quantization, the integer product, the Gram/Cholesky/eigen steps (float64) and the rank-2r update of C
  * (float32) are the same in every mode.  Shapes that take the float32 matrix-core kernels (sketches of up to
  * 16 columns in LRQMM_PREC_FP32 only; reduction lengths that are no multiple of 16 in the code products) are
- * computed at full precision.  Measured error budgets of the three modes: the design doc. */
+ * computed at full precision.  `bench.py --precision-modes` measures time and error of every mode. */
 #define LRQMM_PREC_FP32    0     /* default: float32-equivalent, results match the float64 oracle to 1e-5 */
 #define LRQMM_PREC_BF16X2  1     /* two bfloat16 planes per operand */
 #define LRQMM_PREC_BF16    2     /* one bfloat16 plane per operand: "half precision" */
@@ -219,8 +219,10 @@ LRQMM_API int lrqmm_gemm_static(int M, int N, int K, int bits, int rank,
  * `stream`.  Calls must not be issued concurrently from several host threads.
  * The call enqueues only kernels and event waits (memory is cleared by fill kernels), so it may be
  * recorded into a HIP graph by stream capture on `stream`; the library's own streams join the
- * capture through their fork event.  Call it once outside a capture first (its streams and
- * events are created on first use), and keep profiling off while capturing.
+ * capture through their fork event.  The call asks hipStreamIsCapturing itself: under capture it creates
+ * nothing and returns LRQMM_ERR_UNSUPPORTED (nothing enqueued) if profiling is enabled (timing events do not
+ * belong in a graph) or if this device's streams and events do not exist yet -- they are created by the first
+ * call with rank > 0 outside a capture, so make one such call first.
  */
 LRQMM_API int lrqmm_matmul(int M, int N, int K, int bits, int rank, int oversample, int power_iters,
                  uint64_t seed, int round_mode, const float* A, const float* B, float* C,

@@ -80,7 +80,19 @@ __device__ __forceinline__ int xcd_tile(int id, int tiles_n, int ntiles) {
     // ntiles % 8 == 0 guarantees that one of the four cuts divides both tile counts
     const int gn = 8 / gm, bn = tiles_n / gn, bm = tiles_m / gm;
     const int x = id & 7, j = id >> 3;
-    return ((x / gn) * bm + j / bn) * tiles_n + (x % gn) * bn + j % bn;
+    // Inside its rectangle an XCD works through sub-blocks of 32 tiles (one per CU, the tiles that run at the
+    // same time), 4 x 8 or 8 x 4 where the rectangle allows: the panels that one round of tiles streams through
+    // the L2 are then 12 instead of bn + 32 / bn.
+    int r = j / bn, c = j % bn;
+    if (bm * bn > 32) {
+        const int sm = (bm % 4 == 0 && bn % 8 == 0) ? 4 : ((bm % 8 == 0 && bn % 4 == 0) ? 8 : 0);
+        if (sm) {
+            const int sn = 32 / sm, sub = j >> 5, in = j & 31, per_row = bn / sn;
+            r = (sub / per_row) * sm + in / sn;
+            c = (sub % per_row) * sn + in % sn;
+        }
+    }
+    return ((x / gn) * bm + r) * tiles_n + (x % gn) * bn + c;
 }
 
 template <bool VEC, bool COMP, bool WCINT>

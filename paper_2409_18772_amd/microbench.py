@@ -19,7 +19,8 @@ OUT = os.path.join(HERE, "_build", "peaks")
 def build() -> str:
     os.makedirs(os.path.dirname(OUT), exist_ok=True)
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    subprocess.run([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", SRC, "-o", OUT], check=True)
+    subprocess.run([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+                    "-packed-fp32-ops", SRC, "-o", OUT], check=True)
     return OUT
 
 
