@@ -147,10 +147,11 @@ def test_resnet_conv_shape_sampled_rows():
     check_elementwise(C[rows], ref, w.rank, rows, what=w.name)
 
 
-# Rows of C checked against the oracle at 16384^3.  With one 256 x 256 tile per workgroup and two compute
-# units held by the small SVDs, the early integer product cuts the tiles beyond a whole number of rounds
-# along K; in the launch order of a 64 x 64 tile grid dealt to 8 XCDs those are whole tile rows 31 and 63
-# (rows 7936-8191 and 16128-16383), so the sample takes three rows from each and eight drawn at random.
+# Rows of C checked against the oracle at 16384^3.  The 64 x 64 grid of 256 x 256 tiles is dealt to the 8 XCDs as
+# rectangles of 32 x 16 tiles, each worked through in 16 rounds of 32 tiles; tile rows 31 and 63 (rows 7936-8191
+# and 16128-16383) are the last rows of the two bands of rectangles, i.e. tiles of the last round, next to the
+# band boundary.  The sample takes three rows from each and eight drawn at random.  (At this size the early
+# product is not cut along K: that happens only below four rounds, and is covered at 4096^3.)
 C4_ROWS = np.concatenate([[7936, 8050, 8191, 16128, 16250, 16383],
                           np.random.default_rng(7).choice(16384, size=8, replace=False)])
 
@@ -182,6 +183,8 @@ def test_largest_config_oracle_rows():
     exact = o.exact_product(A[rows], B)
     e_lr, e_dq = o.rel_err(exact, Cr), o.rel_err(exact, ref["C0"])
     say(w.name, "err lrqmm", e_lr, "err direct quant", e_dq)
+    # against floor rounding, the quantizer of the method (Eq. (get_ra2)); against round-to-nearest direct
+    # quantization of zero-mean data the two errors are about equal
     assert e_lr * 10.0 < e_dq
 
 
