@@ -48,6 +48,11 @@ extern "C" {
 #define LRQMM_ROUND_FLOOR    0   /* round down: residual entries in [0, s)  (Eq. (get_ra2)) */
 #define LRQMM_ROUND_NEAREST  1   /* round to nearest, ties to even          (Eq. (quantAB)) */
 
+/* Largest supported extent of any matrix dimension (M, N, K, rows, cols); an M x N output may further have
+ * at most 2^31 - 1 tiles of 128 x 128.  Beyond that the entry points return LRQMM_ERR_UNSUPPORTED (the size
+ * functions return 0): host-side block, grid and padding arithmetic is in int. */
+#define LRQMM_MAX_DIM (1 << 24)
+
 #define LRQMM_SCALE_VECTOR   0   /* one scale per row of A / per column of B (Background 2.2) */
 #define LRQMM_SCALE_TENSOR   1   /* one scale per matrix, as in the paper's own equations (Eq. (quantA)) */
 

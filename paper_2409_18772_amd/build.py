@@ -57,6 +57,34 @@ def build(verbose: bool = True, incremental: bool = False, extra_flags=()) -> st
     return LIB
 
 
+def build_host_check(verbose: bool = False) -> str:
+    """Checked host build: every source with -DLRQMM_CHECK and the host pass under AddressSanitizer and
+    UndefinedBehaviorSanitizer (device code as usual), linked with csrc/host_check/host_check.cpp into the
+    executable _build/host_check.  Running it needs no GPU: it exercises argument validation and workspace
+    carving only (see the driver's header)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    obj_dir = os.path.join(OBJ, "checked")
+    os.makedirs(obj_dir, exist_ok=True)
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined", "-DLRQMM_CHECK", "-g"]
+    flags = [f for f in FLAGS if f != "-O3"] + ["-O1"] + san
+    jobs, objs = [], []
+    for s in SOURCES:
+        obj = os.path.join(obj_dir, s.replace(".hip", ".o"))
+        objs.append(obj)
+        jobs.append([hipcc] + flags + ["-c", os.path.join(CSRC, s), "-o", obj])
+    drv = os.path.join(obj_dir, "host_check.o")
+    jobs.append([hipcc, "-x", "c++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined",
+                 "-fno-sanitize-recover=undefined", "-I", os.path.join(HERE, "..", "include"), "-c",
+                 os.path.join(CSRC, "host_check", "host_check.cpp"), "-o", drv])
+    with ThreadPoolExecutor(max_workers=min(7, len(jobs))) as pool:
+        list(pool.map(lambda c: _run(c, verbose), jobs))
+    exe = os.path.join(OBJ, "host_check")
+    _run([hipcc, "--offload-arch=gfx950", "-fsanitize=address,undefined", "-fno-gpu-sanitize"] + objs + [drv, "-o", exe],
+         verbose)
+    return exe
+
+
 if __name__ == "__main__":
     build(incremental="--incremental" in sys.argv)
     print("built", LIB)

@@ -3,6 +3,8 @@
 // for lrqmm_rsvd).  No device memory is allocated here; everything lives in the
 // caller's buffers and workspace.
 #include "kernels.h"
+#include <cstdio>
+#include <cstdlib>
 #include <functional>
 #include <vector>
 
@@ -16,6 +18,15 @@ struct Arena {
     T* take(size_t count) {
         off = align_up(off, 256);
         T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+#ifdef LRQMM_CHECK      // checked host build: sizes must not wrap, regions must stay aligned and ordered
+        size_t bytes = 0, end = 0;
+        if (__builtin_mul_overflow(count, sizeof(T), &bytes) || __builtin_add_overflow(off, bytes, &end) ||
+            (base && ((uintptr_t)p & 255) != 0) || end < off) {
+            std::fprintf(stderr, "LRQMM_CHECK: workspace region overflows (count %zu x %zu bytes at offset %zu)\n", count,
+                         sizeof(T), off);
+            std::abort();
+        }
+#endif
         off += count * sizeof(T);
         return p;
     }
@@ -219,6 +230,10 @@ inline void prof_mark(int slot, int i, hipStream_t st) {
 #define LRQMM_DEFAULT_PREC LRQMM_PREC_FP32
 #endif
 bool bits_ok(int bits) { return bits >= 2 && bits <= 8; }
+// Host-side size arithmetic (padding, block counts) is done in int: dimensions stay well below 2^31.
+bool dims_ok(int a, int b, int c = 0) { return a <= LRQMM_MAX_DIM && b <= LRQMM_MAX_DIM && c <= LRQMM_MAX_DIM; }
+// ... and an M x N output must leave the number of 128 x 128 tiles (a grid size) below 2^31
+bool output_ok(int M, int N) { return (long long)((M + 127) / 128) * ((N + 127) / 128) < (1ll << 31); }
 bool precision_ok(int p) {
     return p == LRQMM_PREC_FP32 || p == LRQMM_PREC_BF16X2 || p == LRQMM_PREC_BF16 || p == LRQMM_PREC_SUBSPACE_BF16X2;
 }
@@ -264,6 +279,7 @@ static int rsvd_plan(LaunchList& ops, const float* X, int ldx, const float* amax
                      size_t workspace_bytes, hipStream_t st, int precision, size_t* svd_index = nullptr,
                      bool prepared = false, int8_t* fused_codes = nullptr) {
     if (rows < 0 || cols < 0 || rank < 1 || oversample < 0 || power_iters < 0 || ldx < cols) return LRQMM_ERR_INVALID_ARG;
+    if (!dims_ok(rows, cols)) return LRQMM_ERR_UNSUPPORTED;
     if (!precision_ok(precision)) return LRQMM_ERR_INVALID_ARG;
     const int planes = planes_subspace(precision), planes_last = planes_values(precision);
     if (axis != LRQMM_AXIS_ROW && axis != LRQMM_AXIS_COL) return LRQMM_ERR_INVALID_ARG;
@@ -359,7 +375,7 @@ const char* lrqmm_status_string(int status) {
 }
 
 size_t lrqmm_workspace_bytes(int M, int N, int K, int rank, int oversample) {
-    if (M < 0 || N < 0 || K < 0 || rank < 0 || oversample < 0) return 0;
+    if (M < 0 || N < 0 || K < 0 || rank < 0 || oversample < 0 || !dims_ok(M, N, K) || !output_ok(M, N)) return 0;
     if (rank + oversample > LRQMM_MAX_SKETCH) return 0;
     Arena a(nullptr);
     return carve_matmul(a, M, N, K, rank, oversample, nullptr) + 256;
@@ -373,6 +389,7 @@ int lrqmm_quantize(const float* X, int rows, int cols, int axis, int bits, int r
 int lrqmm_quantize_ex(const float* X, int ldx, int rows, int cols, int axis, int bits, int round_mode,
                       int scale_mode, int8_t* codes, float* amax, void* stream) {
     if (rows < 0 || cols < 0 || ldx < cols) return LRQMM_ERR_INVALID_ARG;
+    if (!dims_ok(rows, cols)) return LRQMM_ERR_UNSUPPORTED;
     if (scale_mode != LRQMM_SCALE_VECTOR && scale_mode != LRQMM_SCALE_TENSOR) return LRQMM_ERR_INVALID_ARG;
     if (axis != LRQMM_AXIS_ROW && axis != LRQMM_AXIS_COL) return LRQMM_ERR_INVALID_ARG;
     if (round_mode != LRQMM_ROUND_FLOOR && round_mode != LRQMM_ROUND_NEAREST) return LRQMM_ERR_INVALID_ARG;
@@ -389,6 +406,7 @@ int lrqmm_quantize_ex(const float* X, int ldx, int rows, int cols, int axis, int
 int lrqmm_quantize_residual(const float* X, int ldx, const float* amax0, int rows, int cols, int axis, int bits,
                             int round_mode, int scale_mode, int8_t* codesR, float* amaxR, void* stream) {
     if (rows < 0 || cols < 0 || ldx < cols) return LRQMM_ERR_INVALID_ARG;
+    if (!dims_ok(rows, cols)) return LRQMM_ERR_UNSUPPORTED;
     if (scale_mode != LRQMM_SCALE_VECTOR && scale_mode != LRQMM_SCALE_TENSOR) return LRQMM_ERR_INVALID_ARG;
     if (axis != LRQMM_AXIS_ROW && axis != LRQMM_AXIS_COL) return LRQMM_ERR_INVALID_ARG;
     if (round_mode != LRQMM_ROUND_FLOOR && round_mode != LRQMM_ROUND_NEAREST) return LRQMM_ERR_INVALID_ARG;
@@ -404,6 +422,7 @@ int lrqmm_quantize_residual(const float* X, int ldx, const float* amax0, int row
 
 int lrqmm_fill_sketch(uint64_t seed, int stream_id, int rows, int cols, float* omega, void* stream) {
     if (rows < 0 || cols < 0 || stream_id < 0) return LRQMM_ERR_INVALID_ARG;
+    if (!dims_ok(rows, cols)) return LRQMM_ERR_UNSUPPORTED;
     if (rows == 0 || cols == 0) return LRQMM_OK;
     if (!omega) return LRQMM_ERR_INVALID_ARG;
     return launch_fill_sketch(seed, stream_id, rows, cols, cols, omega, static_cast<hipStream_t>(stream));
@@ -434,6 +453,7 @@ static int gemm_impl(int M, int N, int K, int bits, int rank, const int8_t* Aq, 
                      hipEvent_t raw_sums_ready = nullptr, int planes = 3) {
     float* const C = out.C;
     if (M < 0 || N < 0 || K < 0 || rank < 0 || out.ldc < N) return LRQMM_ERR_INVALID_ARG;
+    if (!dims_ok(M, N, K) || !output_ok(M, N)) return LRQMM_ERR_UNSUPPORTED;
     if (!bits_ok(bits)) return LRQMM_ERR_UNSUPPORTED;
     if (!k_fits_int32(K, bits)) return LRQMM_ERR_UNSUPPORTED;
     if (M == 0 || N == 0) return LRQMM_OK;
@@ -508,6 +528,7 @@ int lrqmm_gemm_static(int M, int N, int K, int bits, int rank, const int8_t* Aq,
                       const float* W, const float* Gam, const float* Zt, float alpha, float beta, float* D, int ldd,
                       int32_t* Cint_or_null, void* stream) {
     if (M < 0 || N < 0 || K < 0 || rank < 0 || ldd < N) return LRQMM_ERR_INVALID_ARG;
+    if (!dims_ok(M, N, K) || !output_ok(M, N)) return LRQMM_ERR_UNSUPPORTED;
     if (rank > LRQMM_MAX_SKETCH) return LRQMM_ERR_UNSUPPORTED;
     if (M == 0 || N == 0) return LRQMM_OK;
     Arena a(nullptr);
@@ -532,6 +553,7 @@ int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int
                     float alpha, float beta, float* D, int ldd, void* workspace, size_t workspace_bytes, void* stream) {
     float* const C = D;
     if (M < 0 || N < 0 || K < 0 || rank < 0 || oversample < 0 || power_iters < 0) return LRQMM_ERR_INVALID_ARG;
+    if (!dims_ok(M, N, K) || !output_ok(M, N)) return LRQMM_ERR_UNSUPPORTED;
     if (!precision_ok(precision)) return LRQMM_ERR_INVALID_ARG;
     if (lda < K || ldb < N || ldd < N) return LRQMM_ERR_INVALID_ARG;
     if (scale_mode != LRQMM_SCALE_VECTOR && scale_mode != LRQMM_SCALE_TENSOR) return LRQMM_ERR_INVALID_ARG;
@@ -719,7 +741,7 @@ size_t carve_residual(Arena& a, int M, int N, int K, ResidualWs* w) {
 }  // namespace
 
 size_t lrqmm_residual_workspace_bytes(int M, int N, int K) {
-    if (M < 0 || N < 0 || K < 0) return 0;
+    if (M < 0 || N < 0 || K < 0 || !dims_ok(M, N, K) || !output_ok(M, N)) return 0;
     Arena a(nullptr);
     return carve_residual(a, M, N, K, nullptr) + 256;
 }
@@ -728,6 +750,7 @@ int lrqmm_residual_matmul(int M, int N, int K, int bits, int terms, int round_mo
                           int lda, const float* B, int ldb, float alpha, float beta, float* D, int ldd,
                           void* workspace, size_t workspace_bytes, void* stream) {
     if (M < 0 || N < 0 || K < 0 || lda < K || ldb < N || ldd < N) return LRQMM_ERR_INVALID_ARG;
+    if (!dims_ok(M, N, K) || !output_ok(M, N)) return LRQMM_ERR_UNSUPPORTED;
     if (terms != 1 && terms != 3 && terms != 4) return LRQMM_ERR_INVALID_ARG;
     if (round_mode != LRQMM_ROUND_FLOOR && round_mode != LRQMM_ROUND_NEAREST) return LRQMM_ERR_INVALID_ARG;
     if (scale_mode != LRQMM_SCALE_VECTOR && scale_mode != LRQMM_SCALE_TENSOR) return LRQMM_ERR_INVALID_ARG;

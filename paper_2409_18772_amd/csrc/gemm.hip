@@ -1029,7 +1029,7 @@ int launch_int8_gemm_sums_finish(int M, int N, int K, const int8_t* Aq, const in
 }
 
 bool int8_gemm_large_tiles(int M, int N) {
-    return M >= BTM && N >= BTN && ceil_div(M, BTM) * ceil_div(N, BTN) >= 128;
+    return M >= BTM && N >= BTN && (long long)ceil_div(M, BTM) * ceil_div(N, BTN) >= 128;
 }
 
 // The early-GEMM schedule needs the large-tile kernel and 16-byte accesses to the rows of C.
