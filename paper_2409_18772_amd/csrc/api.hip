@@ -583,9 +583,9 @@ int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int
     if (rank > 0 && K > 0 && !side) return capturing ? LRQMM_ERR_UNSUPPORTED : LRQMM_ERR_HIP;
     const bool overlap = side != nullptr;
     const int slot = (g_prof.on && g_prof.ncalls < kProfMaxCalls) ? g_prof.ncalls++ : -1;
-    // B's chain is the longer one (its quantization needs two passes over B), so it stays on the
-    // caller's stream and starts at once; A's chain takes the side stream and absorbs the latency of
-    // the fork event, and has normally finished when the caller's stream reaches the join.
+    // B's chain stays on the caller's stream and starts at once (it is the longer one whenever B is quantized by
+    // the separate kernels, which read B twice); A's chain takes the side stream and absorbs the latency of
+    // the fork event.
     hipStream_t bst = pst;
     hipStream_t ast = overlap ? side->stream : pst;
     // Early integer GEMM: with both factorizations in their single-workgroup SVD the GPU is
@@ -633,8 +633,8 @@ int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int
                           fuse_a ? w.Aq : nullptr));
     opsA.push_back([=] { prof_mark(slot, 2, ast); return LRQMM_OK; });
     opsB.push_back([=] { prof_mark(slot, 3, bst); return LRQMM_OK; });
-    // B's chain is the critical one (its maxima need a pass of their own).  Its first kernel fills the sketch
-    // and clears the column maxima in one launch.
+    // B's first kernel fills the sketch and clears the column maxima (they are formed with atomic maxima) in one
+    // launch.
     const bool prep_b = rank > 0 && K > 0;
     if (prep_b) {
         opsB.push_back([=] {
