@@ -167,6 +167,12 @@ def main():
 
     # direct-quantization pipeline alone (rank 0) for the overhead figure
     t_dq = timed(lambda: step(0), max(5, args.steps // 2), 2)
+    # the integer product alone on the idle chip (codes resident, fused dequantizing store, no compensation):
+    # context for the in-schedule figure of the roofline object
+    cA, mA = L.lrqmm_quantize(dA, L.AXIS_ROW, w.bits)
+    cB, mB = L.lrqmm_quantize(dB, L.AXIS_COL, w.bits)
+    t_gemm_alone = timed(lambda: L.lrqmm_gemm(cA, mA, cB, mB, w.bits, workspace=ws, C=C), max(5, args.steps // 2), 2)
+    del cA, cB
     step()
     torch.cuda.synchronize()
     Cn = C.cpu().numpy()
@@ -253,7 +259,11 @@ def main():
                      "frac": round(achieved / PEAK_INT8_TOPS, 4),
                      # counter bytes of this kernel on this workload, or null when no summary is tracked for it
                      "traffic": read_traffic(f"int8_gemm_{SHORT.get(w.name, w.name)}_pmc.txt"),
-                     "launch_ms": round(stages[gemm_key], 4), "ops_per_launch": ops},
+                     "launch_ms": round(stages[gemm_key], 4), "ops_per_launch": ops,
+                     "alone": {"ms": round(t_gemm_alone * 1e3, 4), "achieved": round(ops / t_gemm_alone / 1e12, 2),
+                               "frac": round(ops / t_gemm_alone / 1e12 / PEAK_INT8_TOPS, 4),
+                               "note": "lrqmm_gemm at rank 0 on the idle chip: the same product with its "
+                                       "dequantizing float32 store, wall time per call"}},
         "stages": stage_info,
         "stages_note": "GEMM launch time from HIP events inside the timed region; the other stages from a "
                        "separate fully instrumented pass of the same step",
