@@ -258,6 +258,32 @@ def test_wide_panels_large_tiles_sampled_rows():
     check_elementwise(C[rows], ref, r, rows, what="wide panels")
 
 
+def test_three_stream_schedule_is_repeatable():
+    """The two factorization chains, the early integer product on the third stream and the K-cut tiles involve
+    no atomics on floating-point data and no order that depends on timing: 300 calls at the headline shape,
+    with other calls through the same workspace in between, all give the first call's bits.  (A missing event
+    wait between the three streams would show up here as an occasional difference.)"""
+    import torch
+    import paper_2409_18772_amd as L
+    w = wl.CONFIGS["c3_4096_int4_r32_outliers"]
+    A, B = wl.make_inputs(w)
+    dA, dB = to_dev(A), to_dev(B)
+    ws = L.Workspace.for_problem(w.M, w.N, w.K, w.rank, w.oversample)
+    C = torch.empty((w.M, w.N), dtype=torch.float32, device="cuda")
+    first, differing = None, 0
+    for it in range(300):
+        L.lrqmm_matmul(dA, dB, w.bits, w.rank, w.oversample, w.power_iters, seed=w.sketch_seed, workspace=ws, C=C)
+        if first is None:
+            first = C.clone()
+        elif not torch.equal(first, C):
+            differing += 1
+        if it % 7 == 3:     # a direct-quantization call and another sketch seed through the same workspace
+            L.lrqmm_matmul(dA, dB, w.bits, 0, workspace=ws, C=C)
+            L.lrqmm_matmul(dA, dB, w.bits, w.rank, w.oversample, w.power_iters, seed=it, workspace=ws, C=C)
+    say("calls differing from the first:", differing)
+    assert differing == 0
+
+
 def test_empty_reduction_reads_no_operand():
     """K = 0 with M, N > 0: C_F = 0, so D <- beta D (zeros when beta = 0); the GEMM kernels are not
     launched at all (they load their first operand tile unconditionally)."""
