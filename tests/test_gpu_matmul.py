@@ -284,6 +284,35 @@ def test_three_stream_schedule_is_repeatable():
     assert differing == 0
 
 
+def test_call_is_ordered_like_one_stream_on_a_caller_stream():
+    """On a caller's stream the call must wait for earlier work of that stream (its operands may still be in
+    the making) and later work of that stream must see its result, although two library streams do part of it:
+    the operands are produced by kernels enqueued on the stream right before the call, the result is copied on
+    the stream right after it, nothing is synchronized in between, and the copy must equal the result of the
+    same call on settled inputs, bit for bit."""
+    import torch
+    import paper_2409_18772_amd as L
+    w = wl.CONFIGS["c3_4096_int4_r32_outliers"]
+    A, B = wl.make_inputs(w)
+    dA, dB = to_dev(A), to_dev(B)
+    ws = L.Workspace.for_problem(w.M, w.N, w.K, w.rank, w.oversample)
+    want = L.lrqmm_matmul(dA, dB, w.bits, w.rank, w.oversample, w.power_iters, seed=w.sketch_seed, workspace=ws).clone()
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    A2, B2 = torch.empty_like(dA), torch.empty_like(dB)
+    C = torch.empty((w.M, w.N), dtype=torch.float32, device="cuda")
+    with torch.cuda.stream(s):
+        for _ in range(3):
+            # operands rebuilt on the stream just before the call (x * 0.5 + x * 0.5 is exact in binary)
+            torch.add(dA * 0.5, dA * 0.5, out=A2)
+            torch.add(dB * 0.5, dB * 0.5, out=B2)
+            L.lrqmm_matmul(A2, B2, w.bits, w.rank, w.oversample, w.power_iters, seed=w.sketch_seed, workspace=ws, C=C)
+            got = C.clone()             # consumer on the same stream
+            A2.zero_(); B2.zero_()      # and the operands are destroyed right behind the call
+        s.synchronize()
+    assert torch.equal(got, want)
+
+
 def test_empty_reduction_reads_no_operand():
     """K = 0 with M, N > 0: C_F = 0, so D <- beta D (zeros when beta = 0); the GEMM kernels are not
     launched at all (they load their first operand tile unconditionally)."""
