@@ -363,12 +363,35 @@ __global__ __launch_bounds__(512, 1) void int8_gemm256_kernel(int M, int N, int 
     // C == nullptr: only the raw int32 sums are wanted (the dequantization and the update then
     // run later, in rank_update_kernel), and the step vectors are not read.
     const bool want_c = C != nullptr;
+    // Panels of up to 64 columns: the tile's 256 rows of Lp and of Rp are staged in the LDS that the operand
+    // tiles have left (whole-row loads; rows past the end as zeros; row stride R2P + 4 floats: conflict-free
+    // 16-byte reads), instead of 32 cache lines per load instruction from global memory.  Same values, same
+    // order of the products.
+    const bool staged = COMP && R2P <= 64;
+    const int LDP = R2P + 4;
+    float* const Ls = reinterpret_cast<float*>(&As[0][0]);
+    float* const Rs = reinterpret_cast<float*>(&Bs[0][0]);
+    static_assert(2 * BTM * BSTRIDE >= 256 * 68 * 4, "a 64-column panel tile fits an operand's LDS");
+    if (staged) {
+        __syncthreads();        // every wave has read its last operand fragments
+        const int q4 = R2P / 4;
+        for (int idx = tid; idx < 256 * q4; idx += 512) {
+            const int rr = idx / q4, c4 = idx - rr * q4;
+            const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+            const float4 lv = m0 + rr < M ? *reinterpret_cast<const float4*>(Lp + (size_t)(m0 + rr) * R2P + 4 * c4) : z;
+            const float4 rv = n0 + rr < N ? *reinterpret_cast<const float4*>(Rp + (size_t)(n0 + rr) * R2P + 4 * c4) : z;
+            *reinterpret_cast<float4*>(Ls + rr * LDP + 4 * c4) = lv;
+            *reinterpret_cast<float4*>(Rs + rr * LDP + 4 * c4) = rv;
+        }
+        __syncthreads();
+    }
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
         const int rbase = m0 + wm * 64 + mt * 32;
         const int lrow = rbase + l32;
         const bool lok = lrow < M;
         const float* lp = COMP ? Lp + (size_t)(lok ? lrow : 0) * R2P + 4 * lh : nullptr;
+        const float* lps = Ls + (wm * 64 + mt * 32 + l32) * LDP + 4 * lh;
         float sa[16];
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
@@ -390,7 +413,17 @@ __global__ __launch_bounds__(512, 1) void int8_gemm256_kernel(int M, int N, int 
                 }
                 f[v] = ((float)acc[mt][nt][v] * sa[v]) * sb;
             }
-            if (COMP) {
+            if (COMP && staged) {
+                const float* rps = Rs + (wn * 128 + nt * 32 + l32) * LDP + 4 * lh;
+                for (int t0 = 0; t0 < R2P; t0 += 8) {
+                    const float4 a4 = *reinterpret_cast<const float4*>(lps + t0);
+                    const float4 b4 = *reinterpret_cast<const float4*>(rps + t0);
+                    f = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.x, b4.x, f, 0, 0, 0);
+                    f = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.y, b4.y, f, 0, 0, 0);
+                    f = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.z, b4.z, f, 0, 0, 0);
+                    f = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.w, b4.w, f, 0, 0, 0);
+                }
+            } else if (COMP) {
                 const float* rp = Rp + (size_t)(col_ok ? col : 0) * R2P + 4 * lh;
                 for (int t0 = 0; t0 < R2P; t0 += 8) {
                     float4 a4 = lok ? *reinterpret_cast<const float4*>(lp + t0) : make_float4(0.f, 0.f, 0.f, 0.f);
