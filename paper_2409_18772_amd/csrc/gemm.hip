@@ -1,6 +1,6 @@
 // Integer GEMM on the int8 matrix cores with a fused dequantize + low-rank
-// compensation epilogue (paper: Eq. (INTGEMM), Eq. (QUANTGEMM); Algorithm 2 lines
-// 2-3 and 8-12).
+// compensation epilogue (paper: Eq. (INTGEMM), Eq. (QUANTGEMM); Algorithm 2, integer product,
+// dequantization and compensation steps).
 //
 // The three compensation terms of Algorithm 2 are never formed as M x N matrices:
 //   RC1 + RC2 + RC3 = (U Sig)(Vt B~) + (A~ W)(Gam Zt) + (U Sig)(Vt W)(Gam Zt)
@@ -1077,6 +1077,8 @@ int launch_int8_gemm_sums_finish(int M, int N, int K, const int8_t* Aq, const in
     return LRQMM_OK;
 }
 
+// (Measured on both sides of the limit: at 121 tiles of 256 x 256 the 128-tile kernel is as fast, 59 us at
+// 2816^3; at 144 tiles it needs 103 us against 63 us at 3072^3.)
 bool int8_gemm_large_tiles(int M, int N) {
     return M >= BTM && N >= BTN && (long long)ceil_div(M, BTM) * ceil_div(N, BTN) >= 128;
 }
