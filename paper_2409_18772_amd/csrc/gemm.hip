@@ -122,30 +122,26 @@ __global__ __launch_bounds__(256) void int8_gemm_kernel(int M, int N, int K,
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0;
 
-    // staging: 512 16-byte chunks per operand tile, two per thread
+    // staging: 512 16-byte chunks per operand tile, two per thread.  Global loads run three K-tiles ahead of the
+    // matrix cores in a ring of three sets of named registers (as arrays they would go to scratch memory): with
+    // one tile of lookahead every iteration waited for a global load, which short reductions (K = 576 for the
+    // conv-shaped workload: nine tiles) never amortize.  Tiles past the end load zeros and are never stored.
     const int srow0 = tid >> 2, skc = (tid & 3) * 16;
-    uint4 ra[2], rb[2];
-    auto gload = [&](int k0) {
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            ra[u] = load16b<VEC>(Aq, m0 + srow0 + 64 * u, M, K, k0 + skc);
-            rb[u] = load16b<VEC>(BqT, n0 + srow0 + 64 * u, N, K, k0 + skc);
-        }
-    };
-    auto sstore = [&](int buf) {
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            *reinterpret_cast<uint4*>(&As[buf][(srow0 + 64 * u) * LDS_STRIDE + skc]) = ra[u];
-            *reinterpret_cast<uint4*>(&Bs[buf][(srow0 + 64 * u) * LDS_STRIDE + skc]) = rb[u];
-        }
-    };
-    const int nk = (K + BK - 1) / BK;
-    gload(0);
-    sstore(0);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nk) gload((kt + 1) * BK);
+#define LRQ_DECL(S) uint4 S##a0, S##a1, S##b0, S##b1
+#define LRQ_GLOAD(S, k0)                                                   \
+    S##a0 = load16b<VEC>(Aq, m0 + srow0, M, K, (k0) + skc);                \
+    S##b0 = load16b<VEC>(BqT, n0 + srow0, N, K, (k0) + skc);               \
+    S##a1 = load16b<VEC>(Aq, m0 + srow0 + 64, M, K, (k0) + skc);           \
+    S##b1 = load16b<VEC>(BqT, n0 + srow0 + 64, N, K, (k0) + skc);
+#define LRQ_SSTORE(S, buf)                                                                  \
+    *reinterpret_cast<uint4*>(&As[buf][srow0 * LDS_STRIDE + skc]) = S##a0;                  \
+    *reinterpret_cast<uint4*>(&Bs[buf][srow0 * LDS_STRIDE + skc]) = S##b0;                  \
+    *reinterpret_cast<uint4*>(&As[buf][(srow0 + 64) * LDS_STRIDE + skc]) = S##a1;           \
+    *reinterpret_cast<uint4*>(&Bs[buf][(srow0 + 64) * LDS_STRIDE + skc]) = S##b1;
+    LRQ_DECL(r0);
+    LRQ_DECL(r1);
+    LRQ_DECL(r2);
+    auto compute = [&](int buf) {
 #pragma unroll
         for (int kk = 0; kk < BK / 32; ++kk) {
             v4i af[2], bf[2];
@@ -163,9 +159,31 @@ __global__ __launch_bounds__(256) void int8_gemm_kernel(int M, int N, int K,
                 for (int nt = 0; nt < 2; ++nt)
                     acc[mt][nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[mt], bf[nt], acc[mt][nt], 0, 0, 0);
         }
-        if (kt + 1 < nk) sstore(buf ^ 1);
-        __syncthreads();
+    };
+    const int nk = (K + BK - 1) / BK;
+    LRQ_GLOAD(r0, 0);
+    LRQ_GLOAD(r1, BK);
+    LRQ_GLOAD(r2, 2 * BK);
+    LRQ_SSTORE(r0, 0);
+    __syncthreads();
+    // iteration i: the set that held tile i is free -> load tile i + 3; compute tile i; publish tile i + 1
+#define LRQ_GEMM_STEP(J, SCUR, SNEXT)                       \
+    if (kt + J < nk) {                                      \
+        const int i = kt + J;                               \
+        LRQ_GLOAD(SCUR, (i + 3) * BK);                      \
+        compute(i & 1);                                     \
+        if (i + 1 < nk) { LRQ_SSTORE(SNEXT, (i + 1) & 1); } \
+        __syncthreads();                                    \
     }
+    for (int kt = 0; kt < nk; kt += 3) {
+        LRQ_GEMM_STEP(0, r0, r1)
+        LRQ_GEMM_STEP(1, r1, r2)
+        LRQ_GEMM_STEP(2, r2, r0)
+    }
+#undef LRQ_GEMM_STEP
+#undef LRQ_DECL
+#undef LRQ_GLOAD
+#undef LRQ_SSTORE
 
     // ---- epilogue: dequantize, rank-2r update, store ----
 #pragma unroll
