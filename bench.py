@@ -203,6 +203,17 @@ def main():
             "ms": round(job_ms, 4), "operand_reads": n_reads, "algorithmic_GBs": round(gbs, 1),
             "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
     stage_info[gemm_key].update(TOPs=round(achieved, 1), frac_int8_mfma=round(achieved / PEAK_INT8_TOPS, 4))
+    # which roof bounds the product: its algorithmic bytes (codes read once, 4-byte results written once, panels)
+    # against its operations; below peak_ops / peak_bytes operations per byte the kernel is bound by memory
+    gemm_bytes = float(w.M * w.K + w.K * w.N + 4 * w.M * w.N + (0 if early else 8 * w.rank * (w.M + w.N)))
+    large_tiles = w.M >= 256 and w.N >= 256 and -(-w.M // 256) * -(-w.N // 256) >= 128
+    if ops / gemm_bytes >= PEAK_INT8_TOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
+        roof = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+                "frac": round(achieved / PEAK_INT8_TOPS, 4)}
+    else:
+        gbs_gemm = gemm_bytes / gemm_s / 1e9 if gemm_s > 0 else 0.0
+        roof = {"bound": "hbm", "achieved": round(gbs_gemm, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": round(gbs_gemm / PEAK_HBM_GBS, 4), "algorithmic_bytes_per_launch": gemm_bytes}
     if early:   # the dequantizing rank-2r update alone: reads and rewrites C
         gbs = 8.0 * w.M * w.N / (stages["gemm"] * 1e-3) / 1e9
         stage_info["gemm"].update(kernel="rank_update_kernel", algorithmic_GBs=round(gbs, 1),
@@ -254,9 +265,9 @@ def main():
                    "inputs": f"{INPUT_TEXT.get(w.kind, w.kind)}, seeds {w.seed_a}/{w.seed_b}"},
         "roofline": {"kernel": ("int8_gemm256_kernel (int8 MFMA GEMM, raw int32 sums; on the library's third "
                                 "stream beside the single-workgroup SVD kernels)") if early else
-                               "int8_gemm256_kernel (int8 MFMA GEMM + fused dequant and rank-2r epilogue)",
-                     "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
-                     "frac": round(achieved / PEAK_INT8_TOPS, 4),
+                               (("int8_gemm256_kernel" if large_tiles else "int8_gemm_kernel (128 x 128 tiles)")
+                                + " (int8 MFMA GEMM + fused dequant and rank-2r epilogue)"),
+                     **roof,
                      # counter bytes of this kernel on this workload, or null when no summary is tracked for it
                      "traffic": read_traffic(f"int8_gemm_{SHORT.get(w.name, w.name)}_pmc.txt"),
                      "launch_ms": round(stages[gemm_key], 4), "ops_per_launch": ops,
