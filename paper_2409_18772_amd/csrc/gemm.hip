@@ -95,7 +95,10 @@ __device__ __forceinline__ int xcd_tile(int id, int tiles_n, int ntiles) {
     return ((x / gn) * bm + r) * tiles_n + (x % gn) * bn + c;
 }
 
-template <bool VEC, bool COMP, bool WCINT>
+// NTW: 32-column MFMA tiles per wave along N.  2: the 128 x 128 tile (waves 2 x 2, each 64 x 64); 1: a 128 x 64 tile
+// (each wave 64 x 32) for outputs of at most 64 columns, e.g. a convolution with 64 output channels as a product --
+// on a 128-wide tile half the matrix-core work and half of B's LDS tile would be zeros.
+template <bool VEC, bool COMP, bool WCINT, int NTW = 2>
 __global__ __launch_bounds__(256) void int8_gemm_kernel(int M, int N, int K,
                                                         const int8_t* __restrict__ Aq,
                                                         const int8_t* __restrict__ BqT,
@@ -107,18 +110,19 @@ __global__ __launch_bounds__(256) void int8_gemm_kernel(int M, int N, int K,
                                                         int32_t* __restrict__ Cint, int tiles_n,
                                                         int ntiles) {
     __shared__ __align__(16) int8_t As[2][TM * LDS_STRIDE];
-    __shared__ __align__(16) int8_t Bs[2][TN * LDS_STRIDE];
+    constexpr int TNW = 64 * NTW;       // tile width
+    __shared__ __align__(16) int8_t Bs[2][TNW * LDS_STRIDE];
     const int tile = xcd_tile(blockIdx.x, tiles_n, ntiles);
-    const int m0 = (tile / tiles_n) * TM, n0 = (tile % tiles_n) * TN;
+    const int m0 = (tile / tiles_n) * TM, n0 = (tile % tiles_n) * TNW;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, lh = lane >> 5;
 
-    v16i acc[2][2];
+    v16i acc[2][NTW];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < NTW; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0;
 
@@ -132,31 +136,31 @@ __global__ __launch_bounds__(256) void int8_gemm_kernel(int M, int N, int K,
     S##a0 = load16b<VEC>(Aq, m0 + srow0, M, K, (k0) + skc);                \
     S##b0 = load16b<VEC>(BqT, n0 + srow0, N, K, (k0) + skc);               \
     S##a1 = load16b<VEC>(Aq, m0 + srow0 + 64, M, K, (k0) + skc);           \
-    S##b1 = load16b<VEC>(BqT, n0 + srow0 + 64, N, K, (k0) + skc);
+    if (NTW == 2) S##b1 = load16b<VEC>(BqT, n0 + srow0 + 64, N, K, (k0) + skc);
 #define LRQ_SSTORE(S, buf)                                                                  \
     *reinterpret_cast<uint4*>(&As[buf][srow0 * LDS_STRIDE + skc]) = S##a0;                  \
     *reinterpret_cast<uint4*>(&Bs[buf][srow0 * LDS_STRIDE + skc]) = S##b0;                  \
     *reinterpret_cast<uint4*>(&As[buf][(srow0 + 64) * LDS_STRIDE + skc]) = S##a1;           \
-    *reinterpret_cast<uint4*>(&Bs[buf][(srow0 + 64) * LDS_STRIDE + skc]) = S##b1;
+    if (NTW == 2) *reinterpret_cast<uint4*>(&Bs[buf][(srow0 + 64) * LDS_STRIDE + skc]) = S##b1;
     LRQ_DECL(r0);
     LRQ_DECL(r1);
     LRQ_DECL(r2);
     auto compute = [&](int buf) {
 #pragma unroll
         for (int kk = 0; kk < BK / 32; ++kk) {
-            v4i af[2], bf[2];
+            v4i af[2], bf[NTW];
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
                 af[mt] = *reinterpret_cast<const v4i*>(
                     &As[buf][(wm * 64 + mt * 32 + l32) * LDS_STRIDE + kk * 32 + lh * 16]);
 #pragma unroll
-            for (int nt = 0; nt < 2; ++nt)
+            for (int nt = 0; nt < NTW; ++nt)
                 bf[nt] = *reinterpret_cast<const v4i*>(
-                    &Bs[buf][(wn * 64 + nt * 32 + l32) * LDS_STRIDE + kk * 32 + lh * 16]);
+                    &Bs[buf][(wn * 32 * NTW + nt * 32 + l32) * LDS_STRIDE + kk * 32 + lh * 16]);
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
+                for (int nt = 0; nt < NTW; ++nt)
                     acc[mt][nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[mt], bf[nt], acc[mt][nt], 0, 0, 0);
         }
     };
@@ -190,8 +194,8 @@ __global__ __launch_bounds__(256) void int8_gemm_kernel(int M, int N, int K,
     for (int mt = 0; mt < 2; ++mt) {
         const int rbase = m0 + wm * 64 + mt * 32;
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
-            const int col = n0 + wn * 64 + nt * 32 + l32;
+        for (int nt = 0; nt < NTW; ++nt) {
+            const int col = n0 + wn * 32 * NTW + nt * 32 + l32;
             const bool col_ok = col < N;
             const float sb = col_ok ? sB[col] : 0.f;
             v16f f;
@@ -1018,8 +1022,15 @@ static void dispatch_gemm(bool comp, bool wcint, dim3 grid, hipStream_t st, int 
                           const int8_t* Aq, const int8_t* BqT, const float* sA, const float* sB,
                           const float* Lp, const float* Rp, int R2P, GemmOut C, int32_t* Cint, int tiles_n,
                           int ntiles) {
-#define LRQ_GEMM(COMP, WC) \
-    hipLaunchKernelGGL((int8_gemm_kernel<VEC, COMP, WC>), grid, dim3(256), 0, st, M, N, K, Aq, BqT, sA, sB, Lp, Rp, R2P, C, Cint, tiles_n, ntiles)
+#define LRQ_GEMM(COMP, WC)                                                                                        \
+    do {                                                                                                           \
+        if (N <= 64)                                                                                               \
+            hipLaunchKernelGGL((int8_gemm_kernel<VEC, COMP, WC, 1>), grid, dim3(256), 0, st, M, N, K, Aq, BqT, sA, sB, \
+                               Lp, Rp, R2P, C, Cint, tiles_n, ntiles);                                             \
+        else                                                                                                       \
+            hipLaunchKernelGGL((int8_gemm_kernel<VEC, COMP, WC, 2>), grid, dim3(256), 0, st, M, N, K, Aq, BqT, sA, sB, \
+                               Lp, Rp, R2P, C, Cint, tiles_n, ntiles);                                             \
+    } while (0)
     if (comp) {
         if (wcint) LRQ_GEMM(true, true); else LRQ_GEMM(true, false);
     } else {
@@ -1154,7 +1165,7 @@ int launch_int8_gemm(int M, int N, int K, const int8_t* Aq, const int8_t* BqT, c
         LRQ_CHECK_LAUNCH();
         return LRQMM_OK;
     }
-    const int tiles_m = ceil_div(M, TM), tiles_n = ceil_div(N, TN);
+    const int tiles_m = ceil_div(M, TM), tiles_n = N <= 64 ? 1 : ceil_div(N, TN);     // (one 64-wide tile column)
     const int ntiles = tiles_m * tiles_n;
     dim3 grid(ntiles);
     if (vec) dispatch_gemm<true>(comp, Cint != nullptr, grid, st, M, N, K, Aq, BqT, sA, sB, Lp, Rp, R2P, C, Cint, tiles_n, ntiles);

@@ -103,6 +103,9 @@ GEMM_CASES = [
     (64, 640, 576, 4, 8),
     (500, 300, 77, 8, 3),       # K not a multiple of 16: byte-wise operand path
     (384, 512, 2048, 4, 32),
+    (1000, 64, 576, 4, 8),      # at most 64 columns: the 128 x 64 tile
+    (300, 40, 100, 8, 4),       # ... ragged, byte-wise operand path
+    (257, 65, 128, 4, 0),       # one column more: back to the 128-wide tile
 ]
 
 
