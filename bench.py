@@ -265,7 +265,7 @@ def main():
                    "inputs": f"{INPUT_TEXT.get(w.kind, w.kind)}, seeds {w.seed_a}/{w.seed_b}"},
         "roofline": {"kernel": ("int8_gemm256_kernel (int8 MFMA GEMM, raw int32 sums; on the library's third "
                                 "stream beside the single-workgroup SVD kernels)") if early else
-                               (("int8_gemm256_kernel" if large_tiles else "int8_gemm_kernel (128 x 128 tiles)")
+                               (("int8_gemm256_kernel" if large_tiles else ("int8_gemm_kernel (128 x 64 tiles)" if w.N <= 64 else "int8_gemm_kernel (128 x 128 tiles)"))
                                 + " (int8 MFMA GEMM + fused dequant and rank-2r epilogue)"),
                      **roof,
                      # counter bytes of this kernel on this workload, or null when no summary is tracked for it
