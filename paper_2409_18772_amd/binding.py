@@ -235,11 +235,12 @@ def lrqmm_fill_sketch(seed: int, stream_id: int, rows: int, cols: int, device="c
     return omega
 
 
-def lrqmm_rsvd(X, amax, axis: int, bits: int, rank: int, oversample: int = 0, power_iters: int = 0,
-               seed: int = 0, round_mode: int = ROUND_FLOOR, omega=None, workspace: Workspace | None = None):
-    """U (rows x rank), Sigma (rank), Vt (rank x cols) of the residual of X."""
+def _rsvd_args(X, amax, omega, rank: int, oversample: int, workspace, strided: bool):
+    """Checks shared by the two factorization entry points; allocates the outputs and, if none is given, a workspace."""
     import torch
-    _dev(X, torch.float32, "X")
+    ldx = _dev2d(X, torch.float32, "X") if strided else None
+    if not strided:
+        _dev(X, torch.float32, "X")
     _dev(amax, torch.float32, "amax")
     _dev(omega, torch.float32, "omega")
     rows, cols = X.shape
@@ -250,6 +251,13 @@ def lrqmm_rsvd(X, amax, axis: int, bits: int, rank: int, oversample: int = 0, po
     Vt = torch.empty((rank, cols), dtype=torch.float32, device=X.device)
     if workspace is None:
         workspace = Workspace.for_problem(max(rows, cols), max(rows, cols), max(rows, cols), rank, oversample)
+    return ldx, rows, cols, U, Sigma, Vt, workspace
+
+
+def lrqmm_rsvd(X, amax, axis: int, bits: int, rank: int, oversample: int = 0, power_iters: int = 0,
+               seed: int = 0, round_mode: int = ROUND_FLOOR, omega=None, workspace: Workspace | None = None):
+    """U (rows x rank), Sigma (rank), Vt (rank x cols) of the residual of X."""
+    _, rows, cols, U, Sigma, Vt, workspace = _rsvd_args(X, amax, omega, rank, oversample, workspace, False)
     st = load_library().lrqmm_rsvd(_ptr(X), _ptr(amax), rows, cols, axis, bits, round_mode, rank, oversample,
                                    power_iters, seed & 0xFFFFFFFFFFFFFFFF, _ptr(omega), _ptr(U), _ptr(Sigma),
                                    _ptr(Vt), ctypes.c_void_p(workspace.ptr), workspace.nbytes, _stream())
@@ -261,18 +269,7 @@ def lrqmm_rsvd_ex(X, amax, axis: int, bits: int, rank: int, oversample: int = 0,
                   seed: int = 0, round_mode: int = ROUND_FLOOR, omega=None, workspace: Workspace | None = None,
                   precision: int = PREC_FP32):
     """lrqmm_rsvd for a row-strided X, with a choice of arithmetic for the residual products."""
-    import torch
-    ldx = _dev2d(X, torch.float32, "X")
-    _dev(amax, torch.float32, "amax")
-    _dev(omega, torch.float32, "omega")
-    rows, cols = X.shape
-    if omega is not None and tuple(omega.shape) != (cols, rank + oversample):
-        raise ValueError("omega must be cols x (rank + oversample)")
-    U = torch.empty((rows, rank), dtype=torch.float32, device=X.device)
-    Sigma = torch.empty((rank,), dtype=torch.float32, device=X.device)
-    Vt = torch.empty((rank, cols), dtype=torch.float32, device=X.device)
-    if workspace is None:
-        workspace = Workspace.for_problem(max(rows, cols), max(rows, cols), max(rows, cols), rank, oversample)
+    ldx, rows, cols, U, Sigma, Vt, workspace = _rsvd_args(X, amax, omega, rank, oversample, workspace, True)
     st = load_library().lrqmm_rsvd_ex(_ptr(X), ldx, _ptr(amax), rows, cols, axis, bits, round_mode, rank,
                                       oversample, power_iters, seed & 0xFFFFFFFFFFFFFFFF, _ptr(omega),
                                       int(precision), _ptr(U), _ptr(Sigma), _ptr(Vt),
@@ -281,9 +278,9 @@ def lrqmm_rsvd_ex(X, amax, axis: int, bits: int, rank: int, oversample: int = 0,
     return U, Sigma, Vt
 
 
-def lrqmm_gemm_ex(Aq, amaxA, BqT, amaxB, bits: int, D, alpha: float = 1.0, beta: float = 0.0, factors_a=None,
-                  factors_b=None, want_cint: bool = False, workspace: Workspace | None = None):
-    """D <- alpha (deq(Aq . Bq) + compensation) + beta D, in place in the (row-strided) tensor D."""
+def _gemm_args(Aq, amaxA, BqT, amaxB, factors_a, factors_b, want_cint: bool):
+    """Checks shared by the three product entry points: shapes, the six factor tensors (or none), the optional
+    int32 output.  Returns (M, N, K, rank, [U, Sig, Vt, W, Gam, Zt], Cint)."""
     import torch
     _dev(Aq, torch.int8, "Aq")
     _dev(BqT, torch.int8, "BqT")
@@ -293,27 +290,40 @@ def lrqmm_gemm_ex(Aq, amaxA, BqT, amaxB, bits: int, D, alpha: float = 1.0, beta:
     N, K2 = BqT.shape
     if K != K2:
         raise ValueError("Aq is M x K and BqT is N x K")
-    ldd = _dev2d(D, torch.float32, "D")
-    if tuple(D.shape) != (M, N):
-        raise ValueError("D must be M x N")
     rank = 0
-    U = Sig = Vt = W = Gam = Zt = None
+    factors = [None] * 6
     if factors_a is not None:
         U, Sig, Vt = factors_a
         W, Gam, Zt = factors_b
-        for n, t in (("U", U), ("Sig", Sig), ("Vt", Vt), ("W", W), ("Gam", Gam), ("Zt", Zt)):
+        factors = [U, Sig, Vt, W, Gam, Zt]
+        for n, t in zip(("U", "Sig", "Vt", "W", "Gam", "Zt"), factors):
             _dev(t, torch.float32, n)
         rank = Sig.numel()
         if tuple(U.shape) != (M, rank) or tuple(Vt.shape) != (rank, K) or tuple(W.shape) != (K, rank) \
                 or tuple(Zt.shape) != (rank, N) or Gam.numel() != rank:
             raise ValueError("factor shapes")
     Cint = torch.empty((M, N), dtype=torch.int32, device=Aq.device) if want_cint else None
+    return M, N, K, rank, factors, Cint
+
+
+def _strided_output(D, M: int, N: int) -> int:
+    import torch
+    ldd = _dev2d(D, torch.float32, "D")
+    if tuple(D.shape) != (M, N):
+        raise ValueError("D must be M x N")
+    return ldd
+
+
+def lrqmm_gemm_ex(Aq, amaxA, BqT, amaxB, bits: int, D, alpha: float = 1.0, beta: float = 0.0, factors_a=None,
+                  factors_b=None, want_cint: bool = False, workspace: Workspace | None = None):
+    """D <- alpha (deq(Aq . Bq) + compensation) + beta D, in place in the (row-strided) tensor D."""
+    M, N, K, rank, f, Cint = _gemm_args(Aq, amaxA, BqT, amaxB, factors_a, factors_b, want_cint)
+    ldd = _strided_output(D, M, N)
     if workspace is None:
         workspace = Workspace.for_problem(M, N, K, rank, 0)
     st = load_library().lrqmm_gemm_ex(M, N, K, bits, rank, _ptr(Aq), _ptr(amaxA), _ptr(BqT), _ptr(amaxB),
-                                      _ptr(U), _ptr(Sig), _ptr(Vt), _ptr(W), _ptr(Gam), _ptr(Zt), float(alpha),
-                                      float(beta), _ptr(D), ldd, _ptr(Cint), ctypes.c_void_p(workspace.ptr),
-                                      workspace.nbytes, _stream())
+                                      *map(_ptr, f), float(alpha), float(beta), _ptr(D), ldd, _ptr(Cint),
+                                      ctypes.c_void_p(workspace.ptr), workspace.nbytes, _stream())
     _check(st, "lrqmm_gemm_ex")
     return (D, Cint) if want_cint else D
 
@@ -326,33 +336,11 @@ def lrqmm_gemm_static(Aq, amaxA, BqT, amaxB, bits: int, D, alpha: float = 1.0, b
                       factors_b=None, want_cint: bool = False):
     """lrqmm_gemm_ex on the library's static scratch buffer: no workspace, nothing allocated by the call
     itself (the optional int32 output is the caller's choice)."""
-    import torch
-    _dev(Aq, torch.int8, "Aq")
-    _dev(BqT, torch.int8, "BqT")
-    _dev(amaxA, torch.float32, "amaxA")
-    _dev(amaxB, torch.float32, "amaxB")
-    M, K = Aq.shape
-    N, K2 = BqT.shape
-    if K != K2:
-        raise ValueError("Aq is M x K and BqT is N x K")
-    ldd = _dev2d(D, torch.float32, "D")
-    if tuple(D.shape) != (M, N):
-        raise ValueError("D must be M x N")
-    rank = 0
-    U = Sig = Vt = W = Gam = Zt = None
-    if factors_a is not None:
-        U, Sig, Vt = factors_a
-        W, Gam, Zt = factors_b
-        for n, t in (("U", U), ("Sig", Sig), ("Vt", Vt), ("W", W), ("Gam", Gam), ("Zt", Zt)):
-            _dev(t, torch.float32, n)
-        rank = Sig.numel()
-        if tuple(U.shape) != (M, rank) or tuple(Vt.shape) != (rank, K) or tuple(W.shape) != (K, rank) \
-                or tuple(Zt.shape) != (rank, N) or Gam.numel() != rank:
-            raise ValueError("factor shapes")
-    Cint = torch.empty((M, N), dtype=torch.int32, device=Aq.device) if want_cint else None
+    M, N, K, rank, f, Cint = _gemm_args(Aq, amaxA, BqT, amaxB, factors_a, factors_b, want_cint)
+    ldd = _strided_output(D, M, N)
     st = load_library().lrqmm_gemm_static(M, N, K, bits, rank, _ptr(Aq), _ptr(amaxA), _ptr(BqT), _ptr(amaxB),
-                                          _ptr(U), _ptr(Sig), _ptr(Vt), _ptr(W), _ptr(Gam), _ptr(Zt), float(alpha),
-                                          float(beta), _ptr(D), ldd, _ptr(Cint), _stream())
+                                          *map(_ptr, f), float(alpha), float(beta), _ptr(D), ldd, _ptr(Cint),
+                                          _stream())
     _check(st, "lrqmm_gemm_static")
     return (D, Cint) if want_cint else D
 
@@ -361,33 +349,14 @@ def lrqmm_gemm(Aq, amaxA, BqT, amaxB, bits: int, factors_a=None, factors_b=None,
                workspace: Workspace | None = None, C=None):
     """C = deq(Aq . Bq) + compensation; factors_a = (U, Sig, Vt), factors_b = (W, Gam, Zt) or None."""
     import torch
-    _dev(Aq, torch.int8, "Aq")
-    _dev(BqT, torch.int8, "BqT")
-    _dev(amaxA, torch.float32, "amaxA")
-    _dev(amaxB, torch.float32, "amaxB")
-    M, K = Aq.shape
-    N, K2 = BqT.shape
-    if K != K2:
-        raise ValueError("Aq is M x K and BqT is N x K")
-    rank = 0
-    U = Sig = Vt = W = Gam = Zt = None
-    if factors_a is not None:
-        U, Sig, Vt = factors_a
-        W, Gam, Zt = factors_b
-        for n, t in (("U", U), ("Sig", Sig), ("Vt", Vt), ("W", W), ("Gam", Gam), ("Zt", Zt)):
-            _dev(t, torch.float32, n)
-        rank = Sig.numel()
-        if tuple(U.shape) != (M, rank) or tuple(Vt.shape) != (rank, K) or tuple(W.shape) != (K, rank) \
-                or tuple(Zt.shape) != (rank, N) or Gam.numel() != rank:
-            raise ValueError("factor shapes")
+    M, N, K, rank, f, Cint = _gemm_args(Aq, amaxA, BqT, amaxB, factors_a, factors_b, want_cint)
     if C is None:
         C = torch.empty((M, N), dtype=torch.float32, device=Aq.device)
-    Cint = torch.empty((M, N), dtype=torch.int32, device=Aq.device) if want_cint else None
     if workspace is None:
         workspace = Workspace.for_problem(M, N, K, rank, 0)
     st = load_library().lrqmm_gemm(M, N, K, bits, rank, _ptr(Aq), _ptr(amaxA), _ptr(BqT), _ptr(amaxB),
-                                   _ptr(U), _ptr(Sig), _ptr(Vt), _ptr(W), _ptr(Gam), _ptr(Zt), _ptr(C),
-                                   _ptr(Cint), ctypes.c_void_p(workspace.ptr), workspace.nbytes, _stream())
+                                   *map(_ptr, f), _ptr(C), _ptr(Cint), ctypes.c_void_p(workspace.ptr),
+                                   workspace.nbytes, _stream())
     _check(st, "lrqmm_gemm")
     return (C, Cint) if want_cint else C
 
