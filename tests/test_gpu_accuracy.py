@@ -19,8 +19,12 @@ from test_oracle_lrqmm import _tables
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("kind", ["uniform01", "normal", "poisson"])
-@pytest.mark.parametrize("bits", [4, 8, 3, 5])
+# the six distributions of Tables 3-4 at 4 and 8 bits; the widths 3 and 5 of Table 5 on three of them
+TABLE_CASES = [(k, b) for k in ("uniform01", "normal", "poisson", "uniform_pm1", "exponential", "chisquare") for b in (4, 8)] + \
+              [(k, b) for k in ("uniform01", "normal", "poisson") for b in (3, 5)]
+
+
+@pytest.mark.parametrize("kind,bits", TABLE_CASES)
 def test_table_setting_matches_oracle(kind, bits):
     from paper_2409_18772_amd import accuracy
     n, r = 2000, 10
@@ -52,3 +56,47 @@ def test_direct_quant_column_of_the_printed_tables():
             got = accuracy.measure(A, B, bits, 0)
             say(kind, bits, got["err_direct_quant"], "printed", t[kind][key])
             assert t[kind][key] / band < got["err_direct_quant"] < t[kind][key] * band
+
+
+def _oracle_errors(A, B, bits, rank):
+    res = o.lrqmm(A, B, bits, rank, 0, 1, seed=1, per_tensor=True, want_cint=False)
+    exact = o.exact_product(A, B)
+    return o.rel_err(exact, res["C"]), o.rel_err(exact, res["C0"]), tol_for(res) * np.linalg.norm(res["C"]) / np.linalg.norm(exact)
+
+
+def test_rank_sweep_matches_oracle_and_decreases():
+    """Error against the approximate rank (Evaluation, Fig. 3, first panel; size 200, uniform(0,1), 8 bits): every
+    point of the GPU sweep against the oracle's value at that rank, and the trend the figure shows -- the error
+    falls as the rank grows, and rank 1 alone (the mean of the residual) gives most of the gain."""
+    from paper_2409_18772_amd import accuracy
+    recs = list(accuracy.sweep_rank(200, 0, 1))
+    assert [r["rank"] for r in recs] == [1, 2, 5, 10, 20, 40, 80]
+    A = wl.random_matrix("uniform01", 200, 200, seed=0)
+    B = wl.random_matrix("uniform01", 200, 200, seed=1)
+    for r in recs:
+        e_lr, e_dq, tol = _oracle_errors(A, B, 8, r["rank"])
+        say("rank", r["rank"], "gpu", r["err_lrqmm"], "oracle", e_lr, "tol", tol)
+        assert abs(r["err_lrqmm"] - e_lr) <= tol
+        assert abs(r["err_direct_quant"] - e_dq) <= 1e-6
+    errs = [r["err_lrqmm"] for r in recs]
+    assert all(b < a for a, b in zip(errs, errs[1:]))
+    assert recs[0]["gain"] > 20.0
+
+
+def test_size_sweep_matches_oracle_and_scales():
+    """Error against the matrix size at rank 10 (Fig. 3, second panel): GPU against oracle at sizes 200, 500 and
+    1000, and over the whole sweep the error falls like size^(-1/2) (the i.i.d. part of the residual that a fixed
+    rank cannot capture averages out over the reduction length): err * sqrt(size) constant to 25 %."""
+    from paper_2409_18772_amd import accuracy
+    recs = list(accuracy.sweep_size(10, 0, 1))
+    assert [r["size"] for r in recs] == [200, 500, 1000, 2000, 4000]
+    for r in recs[:3]:
+        n = r["size"]
+        A = wl.random_matrix("uniform01", n, n, seed=0)
+        B = wl.random_matrix("uniform01", n, n, seed=1)
+        e_lr, e_dq, tol = _oracle_errors(A, B, 8, 10)
+        say("size", n, "gpu", r["err_lrqmm"], "oracle", e_lr, "tol", tol)
+        assert abs(r["err_lrqmm"] - e_lr) <= tol
+    scaled = [r["err_lrqmm"] * np.sqrt(r["size"]) for r in recs]
+    say("err * sqrt(size):", scaled)
+    assert max(scaled) / min(scaled) < 1.25
