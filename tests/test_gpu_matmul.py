@@ -135,16 +135,35 @@ def test_full_size_sampled_rows(name):
         assert e_dq / e_lr >= 10.0        # the headline claim on the outlier workload
 
 
-def test_resnet_conv_shape_sampled_rows():
+@pytest.mark.parametrize("oversample,power_iters", [(0, 0), (8, 1)])
+def test_resnet_conv_shape_sampled_rows(oversample, power_iters):
+    """The conv-shaped workload at full size (100352 x 64 x 576), with the configured sketch (no oversampling, no
+    power iteration) and with the alternative setting p = 8, q = 1."""
+    import paper_2409_18772_amd as L
     w = wl.CONFIGS["c5_resnet50_conv_int4_r8"]
     A, B = wl.make_inputs(w)
-    say("matmul full", w.name)
-    C = _run_gpu(w, A, B)
+    say("matmul full", w.name, "p", oversample, "q", power_iters)
+    C = to_np(L.lrqmm_matmul(to_dev(A), to_dev(B), w.bits, w.rank, oversample, power_iters, seed=w.sketch_seed))
     rows = np.random.default_rng(6).choice(w.M, size=512, replace=False)
-    ref = o.lrqmm(A, B, w.bits, w.rank, w.oversample, w.power_iters, seed=w.sketch_seed, row_sample=rows,
+    ref = o.lrqmm(A, B, w.bits, w.rank, oversample, power_iters, seed=w.sketch_seed, row_sample=rows,
                   want_cint=False)
-    assert rel_fro(ref["C"], C[rows]) < TOL
-    check_elementwise(C[rows], ref, w.rank, rows, what=w.name)
+    d = rel_fro(ref["C"], C[rows])
+    say(w.name, "gpu vs oracle", d, "tol", tol_for(ref))
+    if (oversample, power_iters) == (0, 0):
+        assert d < tol_for(ref)
+        check_elementwise(C[rows], ref, w.rank, rows, what=w.name)
+        return
+    # With p = 8, q = 1 the cut at r = 8 falls between two singular values of R_A that agree to 0.13 %
+    # (test_rsvd_truncation_between_nearly_equal_singular_values in test_gpu_rsvd_gemm.py): the rank-8 part is
+    # then fixed only to ~2e-4 of its norm at float32 resolution, and C inherits that through the compensation.
+    # What is unique is compared tightly -- the error against the exact product, which must equal the
+    # oracle's -- and the distance itself against the factorization's own tolerance carried to C.
+    exact = o.exact_product(A[rows], B)
+    e_gpu, e_ref = o.rel_err(exact, C[rows]), o.rel_err(exact, ref["C"])
+    comp = np.linalg.norm(ref["C"] - ref["C0"]) / np.linalg.norm(ref["C"])
+    say(w.name, "err vs exact: gpu", e_gpu, "oracle", e_ref, "compensation / C", comp)
+    assert abs(e_gpu - e_ref) <= 1e-4 * e_ref
+    assert d < tol_for(ref) + 2 * 2e-4 * comp
 
 
 # Rows of C checked against the oracle at 16384^3.  The 64 x 64 grid of 256 x 256 tiles is dealt to the 8 XCDs as

@@ -69,6 +69,41 @@ def test_rsvd_against_oracle(rows, cols, axis, bits, rank, p, q, kind):
     assert np.array_equal(to_np(S2), S) and np.array_equal(to_np(U2), U) and np.array_equal(to_np(Vt2), Vt)
 
 
+def test_rsvd_truncation_between_nearly_equal_singular_values():
+    """A case in which the rank-r truncation is not determined at float32 resolution: the residual of the tall
+    conv-shaped operand (100352 x 576, ReLU inputs) with l = 16, one power iteration, truncated to r = 8.  The
+    power iteration packs the captured bulk singular values together (44.06 and 44.00 at positions 8 and 9:
+    sigma_r / (sigma_r - sigma_r+1) = 778), so the singular vectors on the two sides of the cut mix under a
+    perturbation of the projected matrix of a few 1e-6 -- what float32 accumulation over 10^5 rows leaves --
+    by a few 1e-3, and U S V^T moves by about 2e-4 of its norm although every singular value stands to 1e-7.
+    Both truncations are equally good rank-8 approximations.  So the comparison is on what is unique -- the
+    singular values, the orthonormality of the factors, and the approximation error |R - U S V^T|_F, which
+    must equal the oracle's to 1e-6 -- and the distance itself is only held to the perturbation estimate
+    gap factor x 1e-5 relative to the part of U S V^T at the cut."""
+    import paper_2409_18772_amd as L
+    w = wl.CONFIGS["c5_resnet50_conv_int4_r8"]
+    X, _ = wl.make_inputs(w)
+    rank, p, q = 8, 8, 1
+    amax, s, codes, R = _residual_parts(X, o.ROWWISE, w.bits)
+    om = o.gaussian_sketch(w.sketch_seed, 0, X.shape[1], rank + p)
+    Q = o.range_finder(R, om, q)
+    spectrum = np.linalg.svd(Q.T @ R, compute_uv=False)
+    gap = spectrum[rank - 1] / (spectrum[rank - 1] - spectrum[rank])
+    U0, S0, Vt0 = o.rsvd(R, rank, om, q)
+    U, S, Vt = L.lrqmm_rsvd(to_dev(X), to_dev(amax), 0, w.bits, rank, p, q, seed=w.sketch_seed)
+    U, S, Vt = (to_np(t).astype(np.float64) for t in (U, S, Vt))
+    Rr0, Rr = (U0 * S0) @ Vt0, (U * S) @ Vt
+    e0, e1 = np.linalg.norm(R - Rr0), np.linalg.norm(R - Rr)
+    d = rel_fro(Rr0, Rr)
+    say("gap factor", gap, "sigma rel", np.max(np.abs(S - S0) / S0), "U S Vt distance", d, "approximation error",
+        e1, "oracle", e0)
+    assert gap > 100                                    # the case is what it is meant to be
+    assert np.allclose(S, S0, rtol=2e-5, atol=0)
+    assert np.max(np.abs(U.T @ U - np.eye(rank))) < 2e-5 and np.max(np.abs(Vt @ Vt.T - np.eye(rank))) < 2e-5
+    assert abs(e1 - e0) <= 1e-6 * e0
+    assert d <= gap * 1e-5 * S0[rank - 1] / np.linalg.norm(S0)
+
+
 def test_rsvd_zero_residual_and_errors():
     import torch
     import paper_2409_18772_amd as L
