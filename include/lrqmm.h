@@ -294,8 +294,9 @@ LRQMM_API int lrqmm_residual_matmul(int M, int N, int K, int bits, int terms, in
  * synchronisation), writes the per-stage mean duration in milliseconds to
  * stage_ms[LRQMM_PROF_STAGES] (host pointer) and the number of calls averaged to
  * *ncalls (host pointer), then resets the call counter.  Not thread safe.
- *   stage 0 quantize A   stage 1 RSVD of R_A     (library's second stream, concurrent with 2-3)
- *   stage 2 quantize B   stage 3 RSVD of R_B     (caller's stream)
+ *   stage 0 quantize A   stage 1 RSVD of R_A     (stages 0-1 and 2-3 run concurrently: the larger
+ *   stage 2 quantize B   stage 3 RSVD of R_B      operand's on the caller's stream, the other's on
+ *                                                 the library's second stream)
  *   stage 4 compensation panels
  *   stage 5 int8 GEMM kernel with fused epilogue, or -- when the integer product ran early,
  *           see lrqmm_matmul -- the dequantizing rank-2r update kernel alone
