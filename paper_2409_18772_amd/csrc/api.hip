@@ -277,7 +277,7 @@ static int rsvd_plan(LaunchList& ops, const float* X, int ldx, const float* amax
                      int round_mode, int rank, int oversample, int power_iters, uint64_t seed,
                      const float* omega_or_null, float* U, float* Sigma, float* Vt, void* workspace,
                      size_t workspace_bytes, hipStream_t st, int precision, size_t* svd_index = nullptr,
-                     bool prepared = false, int8_t* fused_codes = nullptr) {
+                     bool prepared = false, int8_t* fused_codes = nullptr, float* row_amax_out = nullptr) {
     if (rows < 0 || cols < 0 || rank < 1 || oversample < 0 || power_iters < 0 || ldx < cols) return LRQMM_ERR_INVALID_ARG;
     if (!dims_ok(rows, cols)) return LRQMM_ERR_UNSUPPORTED;
     if (!precision_ok(precision)) return LRQMM_ERR_INVALID_ARG;
@@ -299,7 +299,8 @@ static int rsvd_plan(LaunchList& ops, const float* X, int ldx, const float* amax
     const int nscale = axis == LRQMM_AXIS_ROW ? rows : cols;
     if (prepared) {
         // the caller has already filled the sketch (w.Wc) on this stream, and either the step vectors (w.lam, w.s)
-        // too or -- with fused_codes -- only the group maxima: the first pass then quantizes as well
+        // too or -- with fused_codes -- only the group maxima: the first pass then quantizes as well; with
+        // row_amax_out not even those: the first pass reads the operand once for maxima, codes and Y
     } else if (omega_or_null) {
         ops.push_back([=] { return launch_scales(amax, nscale, pad_to(nscale, 4), q.qmaxf, w.lam, w.s, st); });
         ops.push_back([=] { return launch_pad_copy(omega_or_null, cols, ell, LP, w.Wc, st); });
@@ -324,7 +325,12 @@ static int rsvd_plan(LaunchList& ops, const float* X, int ldx, const float* amax
         ops.push_back([=] { return launch_resid_mul_t(X, ldx, rows, cols, axis, w.lam, w.s, q, w.Yr, LP, pt, w.partial, st, pl); });
     };
     // Y = R Omega (with fused_codes: the same launch also writes the codes and the step vectors)
-    if (fused_codes)
+    if (fused_codes && row_amax_out)
+        ops.push_back([=] {
+            return launch_quant_sketch_rows(X, ldx, rows, cols, q, w.Wc, LP, w.partial, row_amax_out, w.lam, w.s,
+                                            fused_codes, st);
+        });
+    else if (fused_codes)
         ops.push_back([=] {
             return launch_quant_sketch(X, ldx, rows, cols, axis, amax, q, w.Wc, LP, pn, w.partial, w.lam, w.s, fused_codes,
                                        st, planes);
@@ -620,10 +626,15 @@ int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int
         if (carve_rsvd(ra, M, K, LRQMM_AXIS_ROW, LPm, rank, &wa) > w.subA_bytes) return LRQMM_ERR_WORKSPACE;
         if (carve_rsvd(rb, K, N, LRQMM_AXIS_COL, LPm, rank, &wb) > w.subB_bytes) return LRQMM_ERR_WORKSPACE;
     }
-    const bool fuse_a = rank > 0 && K > 0 && quant_sketch_fusable(A, lda, M, K, LPm, plan_pass_n(M, K), w.Aq);
+    // Short rows of A (an im2col'd convolution: K = 576) stay in registers: maxima, codes and Y from a single read.
+    const bool onepass_a = rank > 0 && K > 0 && !per_tensor && planes_subspace(precision) == 3 &&
+                           plan_pass_n(M, K).splits == 1 && quant_sketch_rows_usable(A, lda, M, K, LPm, w.Aq);
+    const bool fuse_a = !onepass_a && rank > 0 && K > 0 && quant_sketch_fusable(A, lda, M, K, LPm, plan_pass_n(M, K), w.Aq);
     const bool fuse_b = rank > 0 && K > 0 && quant_sketch_fusable(B, ldb, K, N, LPm, plan_pass_n(K, N), w.BqT);
     opsA.push_back([=] { prof_mark(slot, 0, ast); return LRQMM_OK; });
-    if (fuse_a) {
+    if (onepass_a) {
+        opsA.push_back([=] { return launch_fill_sketch(seed, LRQMM_AXIS_ROW, K, rank + oversample, LPm, wa.Wc, ast); });
+    } else if (fuse_a) {
         opsA.push_back([=] { return launch_fill_sketch(seed, LRQMM_AXIS_ROW, K, rank + oversample, LPm, wa.Wc, ast); });
         opsA.push_back([=] { return launch_absmax_rows(A, lda, M, K, qp, per_tensor, w.amaxA, ast); });
     } else if (K > 0) opsA.push_back([=] { return lrqmm_quantize_ex(A, lda, M, K, LRQMM_AXIS_ROW, bits, round_mode, scale_mode, w.Aq, w.amaxA, ast); });
@@ -631,8 +642,8 @@ int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int
     opsA.push_back([=] { prof_mark(slot, 1, ast); return LRQMM_OK; });
     if (rank > 0)
         LRQ_TRY(rsvd_plan(opsA, A, lda, w.amaxA, M, K, LRQMM_AXIS_ROW, bits, round_mode, rank, oversample, power_iters,
-                          seed, nullptr, w.U, w.Sig, w.Vt, w.subA, w.subA_bytes, ast, precision, &svdA, fuse_a,
-                          fuse_a ? w.Aq : nullptr));
+                          seed, nullptr, w.U, w.Sig, w.Vt, w.subA, w.subA_bytes, ast, precision, &svdA,
+                          fuse_a || onepass_a, fuse_a || onepass_a ? w.Aq : nullptr, onepass_a ? w.amaxA : nullptr));
     opsA.push_back([=] { prof_mark(slot, 2, ast); return LRQMM_OK; });
     opsB.push_back([=] { prof_mark(slot, 3, bst); return LRQMM_OK; });
     // B's first kernel fills the sketch and clears the column maxima (they are formed with atomic maxima) in one

@@ -155,6 +155,134 @@ __global__ __launch_bounds__(256) void resid_mul_n_kernel(
             if (orow0 + v < rows) out[(size_t)(orow0 + v) * LP + 16 * nt + r] = acc[nt][v];
 }
 
+template <int ROUND_MODE>
+__device__ __forceinline__ float quant_code_residual(float x, float lam, float s, const QuantParams& q, float& code) {
+    const float t = x * lam;
+    const float c = ROUND_MODE == 0 ? floorf(t) : rintf(t);
+    code = fminf(fmaxf(c, q.lo), q.hi);
+    return fmaf(-code, s, x);
+}
+
+// ---------------------------------------------------------------------------
+// Row quantization (Eq. (quantA), one scale per row of A) and the sketch product Y = R.Omega (Algorithm 1, the
+// sample matrix) from ONE read of the operand, for short rows (cols <= 640, a multiple of 16) and sketches
+// padded to 16 columns.  A tile is 32 rows: two groups of 16 rows, each shared by four waves that take a
+// quarter of the columns each (NJQ blocks of 16), so a lane keeps 4 NJQ values of one tile in registers between
+// the row maximum and the codes, and has room for the next tile's values as well: workgroups are persistent,
+// take a contiguous run of tiles, and load tile i+1 while tile i is quantized and multiplied.  The row maxima
+// and the four partial products of a row group are exchanged through LDS (two barriers per tile; the partial
+// products are added in the order of the quarters, so the result does not depend on the launch).  The sketch
+// sits in LDS for the life of the workgroup, 64 floats per line of four rows, each line rotated by 16 (line mod
+// 4) floats so that the four lane groups of a matrix-core operand read four different bank groups.
+// amax, lam_out, s_out and the codes carry the bits the separate quantization kernel writes.
+// ---------------------------------------------------------------------------
+template <int NJQ>
+__global__ __launch_bounds__(512, 4) void quant_sketch_rows_kernel(
+    const float* __restrict__ X, int ldx, int rows, int cols, QuantParams q, const float* __restrict__ W,
+    float* __restrict__ Y, float* __restrict__ amax, float* __restrict__ lam_out, float* __restrict__ s_out,
+    int8_t* __restrict__ codes) {
+    extern __shared__ __align__(16) float wsm[];       // cols x 16 floats, rotated lines
+    __shared__ float smax[2][4][16];
+    __shared__ float4 yx[8][64];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int r = lane & 15, g = lane >> 4;
+    const int rg = wave >> 2, kq = wave & 3;
+    const int nj = cols >> 4, njq = (nj + 3) >> 2;      // 16-column blocks in all, per quarter (njq <= NJQ)
+    const int kbeg = min(cols, kq * njq * 16), kend = min(cols, kbeg + njq * 16);
+    // The wave's NJQ blocks start at kbase, moved down where the quarter would run past the row's end, so that
+    // every block lies inside the row and block jq sits at the constant offset 16 jq; blocks outside
+    // [kbeg, kend) belong to another wave (or to none) and are skipped.
+    const int kbase = min(kbeg, cols - 16 * NJQ);
+    const int ntiles = (rows + 31) >> 5;
+    const int t0 = (int)((long long)blockIdx.x * ntiles / gridDim.x);
+    const int t1 = (int)((long long)(blockIdx.x + 1) * ntiles / gridDim.x);
+    if (t0 >= t1) return;                                // uniform
+    for (int e = threadIdx.x; e < cols * 4; e += 512) {
+        const int k = e >> 2, n4 = (e & 3) * 4, line = k >> 2;
+        const float4 v = *reinterpret_cast<const float4*>(W + (size_t)k * 16 + n4);
+        *reinterpret_cast<float4*>(wsm + line * 64 + (((k & 3) * 16 + n4 + 16 * (line & 3)) & 63)) = v;
+    }
+    // No guard on the values: rows past the end (they read row 0) only reach their own maxima, codes and output
+    // rows, none of which is stored.
+    auto load_tile = [&](float4 (&x)[NJQ], int tile) {
+        const int row = tile * 32 + rg * 16 + r;
+        const float* xp = X + (size_t)(row < rows ? row : 0) * ldx + 4 * g + kbase;
+#pragma unroll
+        for (int jq = 0; jq < NJQ; ++jq) x[jq] = *reinterpret_cast<const float4*>(xp + 16 * jq);
+    };
+    auto process = [&](const float4 (&x)[NJQ], int tile) {
+        const int row = tile * 32 + rg * 16 + r;
+        const bool row_ok = row < rows;
+        float m = 0.f;
+#pragma unroll
+        for (int jq = 0; jq < NJQ; ++jq)
+            if (kbase + 16 * jq >= kbeg && kbase + 16 * jq < kend)           // uniform over the wave
+                m = fmaxf(fmaxf(m, fabsf(x[jq].x)), fmaxf(fabsf(x[jq].y), fmaxf(fabsf(x[jq].z), fabsf(x[jq].w))));
+        m = fmaxf(m, __shfl_xor(m, 16, 64));     // the four lanes of a row
+        m = fmaxf(m, __shfl_xor(m, 32, 64));
+        if (g == 0) smax[rg][kq][r] = m;
+        __syncthreads();        // the quarters' maxima (and, for the first tile, the sketch) are in LDS
+        m = fmaxf(fmaxf(smax[rg][0][r], smax[rg][1][r]), fmaxf(smax[rg][2][r], smax[rg][3][r]));
+        float lam_r, s_r;
+        make_scales(m, q.qmaxf, lam_r, s_r);
+        if (row_ok && g == 0 && kq == 0) {
+            amax[row] = m;
+            lam_out[row] = lam_r;
+            s_out[row] = s_r;
+        }
+        v4f acc = (v4f){0.f, 0.f, 0.f, 0.f};
+        int8_t* cp = codes + (size_t)(row_ok ? row : 0) * cols + 4 * g + kbase;
+        // sketch rows k + 4g + t of block k: line (k >> 2) + g, whose rotation is 16 g (k is a multiple of 16)
+        const float* wline0 = wsm + ((kbase >> 2) + g) * 64;
+        auto quarter = [&](auto mode) {          // one uniform branch on the rounding mode per tile
+            constexpr int RM = decltype(mode)::value;
+#pragma unroll
+            for (int jq = 0; jq < NJQ; ++jq) {
+                const int k = kbase + 16 * jq;
+                if (k < kbeg || k >= kend) continue;         // uniform over the wave
+                float res[4], c0, c1, c2, c3;
+                res[0] = quant_code_residual<RM>(x[jq].x, lam_r, s_r, q, c0);
+                res[1] = quant_code_residual<RM>(x[jq].y, lam_r, s_r, q, c1);
+                res[2] = quant_code_residual<RM>(x[jq].z, lam_r, s_r, q, c2);
+                res[3] = quant_code_residual<RM>(x[jq].w, lam_r, s_r, q, c3);
+                const int i0 = (int)c0, i1 = (int)c1, i2 = (int)c2, i3 = (int)c3;
+                const uint32_t pk = (uint32_t)(i0 & 0xff) | ((uint32_t)(i1 & 0xff) << 8) |
+                                    ((uint32_t)(i2 & 0xff) << 16) | ((uint32_t)(i3 & 0xff) << 24);
+                if (row_ok) *reinterpret_cast<uint32_t*>(cp + 16 * jq) = pk;
+                const float* wline = wline0 + 4 * jq * 64;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) acc = mfma16(res[t], wline[(16 * t + r + 16 * g) & 63], acc);
+                // one block at a time: hoisting every block's residuals above the matrix instructions would
+                // cost four registers per block, and the second register set needs them
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        if (q.round_mode == 0) quarter(std::integral_constant<int, 0>{});
+        else quarter(std::integral_constant<int, 1>{});
+        yx[wave][lane] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        __syncthreads();        // the four partial products of each row group are in LDS
+        // wave kq adds element kq of its row group's accumulators (output row 4g + kq, column r)
+        const float* yp = reinterpret_cast<const float*>(&yx[rg * 4][lane]) + kq;
+        float sum = yp[0];
+        sum += yp[64 * 4];
+        sum += yp[2 * 64 * 4];
+        sum += yp[3 * 64 * 4];
+        const int orow = tile * 32 + rg * 16 + 4 * g + kq;
+        if (orow < rows) Y[(size_t)orow * 16 + r] = sum;
+    };
+    float4 xa[NJQ], xb[NJQ];
+    int tile = t0;
+    load_tile(xa, tile);
+    while (true) {          // two tiles per round: the register sets swap roles
+        load_tile(xb, min(tile + 1, t1 - 1));
+        process(xa, tile);
+        if (++tile >= t1) break;
+        load_tile(xa, min(tile + 1, t1 - 1));
+        process(xb, tile);
+        if (++tile >= t1) break;
+    }
+}
+
 // ---------------------------------------------------------------------------
 // The same product on the bf16 matrix cores.  A float32 value is the exact sum of three
 // bfloat16 planes (8 + 8 + 8 significant bits: round to nearest, subtract, repeat), and the
@@ -251,14 +379,6 @@ struct WStageBf16 {
 };
 
 // residual x - code s and the code itself (the arithmetic of quant_code / quant_residual_m)
-template <int ROUND_MODE>
-__device__ __forceinline__ float quant_code_residual(float x, float lam, float s, const QuantParams& q, float& code) {
-    const float t = x * lam;
-    const float c = ROUND_MODE == 0 ? floorf(t) : rintf(t);
-    code = fminf(fmaxf(c, q.lo), q.hi);
-    return fmaf(-code, s, x);
-}
-
 // FULLK: the vector path with cols and the split length multiples of the chunk depth, so no
 // load in the loop needs a guard along the reduction (rows past the end read row 0 and are not stored).
 template <int NT, int AXIS, bool VEC, bool FULLK = false, int PL = 3, bool QOUT = false>
@@ -1074,6 +1194,40 @@ int launch_quant_sketch(const float* X, int ldx, int rows, int cols, int axis, c
     }
 #undef LRQ_QS_PL
 #undef LRQ_QS
+    LRQ_CHECK_LAUNCH();
+    return LRQMM_OK;
+}
+
+bool quant_sketch_rows_usable(const float* X, int ldx, int rows, int cols, int LP, const int8_t* codes) {
+    return rows > 0 && LP == 16 && cols >= 16 && cols % 16 == 0 && cols <= 640 && ldx % 4 == 0 && aligned16(X) &&
+           ((uintptr_t)codes & 3) == 0;
+}
+
+int launch_quant_sketch_rows(const float* X, int ldx, int rows, int cols, QuantParams q, const float* W, int LP,
+                             float* Y, float* amax, float* lam_out, float* s_out, int8_t* codes, hipStream_t st) {
+    if (!quant_sketch_rows_usable(X, ldx, rows, cols, LP, codes)) return LRQMM_ERR_UNSUPPORTED;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        return LRQMM_ERR_HIP;
+    // persistent workgroups, two per compute unit (registers and LDS allow that many), each with a run of tiles
+    dim3 grid(min(ceil_div(rows, 32), 2 * cus));
+    const size_t lds = (size_t)cols * 16 * sizeof(float);
+#define LRQ_QSR(NJQV) hipLaunchKernelGGL((quant_sketch_rows_kernel<NJQV>), grid, dim3(512), lds, st, X, ldx, rows, cols, q, W, Y, amax, lam_out, s_out, codes)
+    switch (ceil_div(cols / 16, 4)) {
+        case 1: LRQ_QSR(1); break;
+        case 2: LRQ_QSR(2); break;
+        case 3: LRQ_QSR(3); break;
+        case 4: LRQ_QSR(4); break;
+        case 5: LRQ_QSR(5); break;
+        case 6: LRQ_QSR(6); break;
+        case 7: LRQ_QSR(7); break;
+        case 8: LRQ_QSR(8); break;
+        case 9: LRQ_QSR(9); break;
+        case 10: LRQ_QSR(10); break;
+        default: return LRQMM_ERR_UNSUPPORTED;
+    }
+#undef LRQ_QSR
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }

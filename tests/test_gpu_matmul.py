@@ -73,6 +73,47 @@ def test_scaled_configs_full_output(name, M, N, K):
     check_elementwise(C, ref, w.rank, what=w.name)
 
 
+SHORT_ROWS = [
+    # M, N, K, rank, oversample, power_iters: K a multiple of 16 up to 640 (A's rows are kept in registers), ragged M,
+    # K / 16 a multiple of 4 and not (the four waves of a row group then take unequal shares)
+    (130, 70, 96, 4, 4, 1),
+    (1000, 64, 576, 8, 0, 0),
+    (257, 40, 640, 12, 4, 2),
+    (64, 33, 400, 12, 8, 0),
+    (500, 80, 272, 16, 8, 1),
+    (90, 48, 16, 4, 0, 0),
+    (2100, 24, 208, 3, 2, 1),
+    (33, 40, 336, 16, 0, 0),
+]
+
+
+@pytest.mark.parametrize("mode", [o.FLOOR, o.NEAREST])
+@pytest.mark.parametrize("M,N,K,r,p,q", SHORT_ROWS)
+def test_short_rows_of_a_single_read(M, N, K, r, p, q, mode):
+    """A with short rows and a sketch of at most 16 columns: row maxima, codes and the sketch product come from
+    one read of A (the fourth and fifth shape have wider sketches and take the separate kernels).  Checked against
+    the oracle, and against the same call on a copy of A whose row stride (K + 1) rules that kernel out, so that
+    the separate quantization and sketch kernels run: the two differ only in the order in which the sketch
+    product is summed."""
+    import torch
+    import paper_2409_18772_amd as L
+    A = wl.random_matrix("relu_normal", M, K, seed=51)
+    B = wl.random_matrix("normal", K, N, seed=52)
+    say("short rows", M, N, K, "rank", r, "p", p, "q", q, "mode", mode)
+    dA, dB = to_dev(A), to_dev(B)
+    C = to_np(L.lrqmm_matmul(dA, dB, 4, r, p, q, seed=9, round_mode=mode))
+    ref = o.lrqmm(A, B, 4, r, p, q, seed=9, round_mode=mode)
+    d = rel_fro(ref["C"], C)
+    say("gpu vs oracle", d, "tol", tol_for(ref))
+    assert d < tol_for(ref)
+    check_elementwise(C, ref, r, what=f"short rows {M}x{N}x{K}")
+    wide = torch.zeros((M, K + 1), dtype=torch.float32, device="cuda")
+    wide[:, :K] = dA
+    D = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    L.lrqmm_matmul_ex(wide[:, :K], dB, D, 4, r, p, q, seed=9, round_mode=mode)
+    assert rel_fro(C, to_np(D)) < tol_for(ref)
+
+
 def test_rank_zero_is_direct_quant_and_modes():
     import paper_2409_18772_amd as L
     A = wl.random_matrix("normal", 150, 200, seed=1)
