@@ -166,111 +166,125 @@ __device__ __forceinline__ float quant_code_residual(float x, float lam, float s
 // ---------------------------------------------------------------------------
 // Row quantization (Eq. (quantA), one scale per row of A) and the sketch product Y = R.Omega (Algorithm 1, the
 // sample matrix) from ONE read of the operand, for short rows (cols <= 640, a multiple of 16) and sketches
-// padded to 16 columns.  A tile is 32 rows: two groups of 16 rows, each shared by four waves that take a
-// quarter of the columns each (NJQ blocks of 16), so a lane keeps 4 NJQ values of one tile in registers between
-// the row maximum and the codes, and has room for the next tile's values as well: workgroups are persistent,
-// take a contiguous run of tiles, and load tile i+1 while tile i is quantized and multiplied.  The row maxima
-// and the four partial products of a row group are exchanged through LDS (two barriers per tile; the partial
-// products are added in the order of the quarters, so the result does not depend on the launch).  The sketch
-// sits in LDS for the life of the workgroup, 64 floats per line of four rows, each line rotated by 16 (line mod
-// 4) floats so that the four lane groups of a matrix-core operand read four different bank groups.
+// padded to 16 columns.  A tile is 16 rows; workgroups of 8 waves are persistent, take a contiguous run of
+// tiles, and load tile i+1 into a second register set while tile i is worked on.
+//   * Wave w reads rows 2w and 2w+1 of the tile, adjacent lanes adjacent 16-byte pieces (NV float4 per lane), so
+//     global loads and the code stores are fully coalesced and a row's maximum is a reduction inside one wave.
+//   * The residuals go to LDS as a 16-row tile (row stride = 4 mod 64 floats: the 64 lanes of a matrix-core operand
+//     read 64 different banks).  For the product the waves split the reduction: wave w always takes the same
+//     columns, so its sketch operands stay in registers (4 NV values) for the life of the workgroup.
+//   * The eight partial products of a tile meet in LDS and are added in the order of the waves, so the result
+//     does not depend on the launch.  Two barriers per tile.
 // amax, lam_out, s_out and the codes carry the bits the separate quantization kernel writes.
 // ---------------------------------------------------------------------------
-template <int NJQ>
-__global__ __launch_bounds__(512, 4) void quant_sketch_rows_kernel(
+#ifndef LRQ_QSR_WGS
+#define LRQ_QSR_WGS 2      // resident workgroups per compute unit the kernel is built and launched for
+#endif
+template <int NV>
+__global__ __launch_bounds__(512, 2 * LRQ_QSR_WGS) void quant_sketch_rows_kernel(
     const float* __restrict__ X, int ldx, int rows, int cols, QuantParams q, const float* __restrict__ W,
     float* __restrict__ Y, float* __restrict__ amax, float* __restrict__ lam_out, float* __restrict__ s_out,
     int8_t* __restrict__ codes) {
-    extern __shared__ __align__(16) float wsm[];       // cols x 16 floats, rotated lines
-    __shared__ float smax[2][4][16];
-    __shared__ float4 yx[8][64];
+    constexpr int NS = 4 * NV;                           // matrix-core steps (of 4 columns) per wave, at most
+    extern __shared__ __align__(16) float rt[];          // residual tile: 16 rows of ldr floats
+    __shared__ float pacc[8][256];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r = lane & 15, g = lane >> 4;
-    const int rg = wave >> 2, kq = wave & 3;
-    const int nj = cols >> 4, njq = (nj + 3) >> 2;      // 16-column blocks in all, per quarter (njq <= NJQ)
-    const int kbeg = min(cols, kq * njq * 16), kend = min(cols, kbeg + njq * 16);
-    // The wave's NJQ blocks start at kbase, moved down where the quarter would run past the row's end, so that
-    // every block lies inside the row and block jq sits at the constant offset 16 jq; blocks outside
-    // [kbeg, kend) belong to another wave (or to none) and are skipped.
-    const int kbase = min(kbeg, cols - 16 * NJQ);
-    const int ntiles = (rows + 31) >> 5;
+    const int cpr = cols >> 2;                           // 16-byte pieces, and steps, per row
+    const int ldr = cols + ((68 - (cols & 63)) & 63);
+    const int spw = (cpr + 7) >> 3;                      // steps per wave (spw <= NS)
+    const int s0 = min(cpr, wave * spw), s1 = min(cpr, s0 + spw);
+    const int ntiles = (rows + 15) >> 4;
     const int t0 = (int)((long long)blockIdx.x * ntiles / gridDim.x);
     const int t1 = (int)((long long)(blockIdx.x + 1) * ntiles / gridDim.x);
     if (t0 >= t1) return;                                // uniform
-    for (int e = threadIdx.x; e < cols * 4; e += 512) {
-        const int k = e >> 2, n4 = (e & 3) * 4, line = k >> 2;
-        const float4 v = *reinterpret_cast<const float4*>(W + (size_t)k * 16 + n4);
-        *reinterpret_cast<float4*>(wsm + line * 64 + (((k & 3) * 16 + n4 + 16 * (line & 3)) & 63)) = v;
+    float wreg[NS];      // B operands: Omega[4 s + g][r] for the wave's steps
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+        const float v = W[(size_t)(4 * min(s0 + i, cpr - 1) + g) * 16 + r];
+        wreg[i] = s0 + i < s1 ? v : 0.f;
     }
-    // No guard on the values: rows past the end (they read row 0) only reach their own maxima, codes and output
-    // rows, none of which is stored.
-    auto load_tile = [&](float4 (&x)[NJQ], int tile) {
-        const int row = tile * 32 + rg * 16 + r;
-        const float* xp = X + (size_t)(row < rows ? row : 0) * ldx + 4 * g + kbase;
-#pragma unroll
-        for (int jq = 0; jq < NJQ; ++jq) x[jq] = *reinterpret_cast<const float4*>(xp + 16 * jq);
+    // piece u of a lane: number lane + 64 u of the wave's two rows
+    auto piece = [&](int u, int& rl, int& cc) {
+        const int c = lane + 64 * u;
+        rl = c >= cpr ? 1 : 0;
+        cc = c - (rl ? cpr : 0);
+        return c < 2 * cpr;
     };
-    auto process = [&](const float4 (&x)[NJQ], int tile) {
-        const int row = tile * 32 + rg * 16 + r;
-        const bool row_ok = row < rows;
-        float m = 0.f;
+    // No guard on the values: rows past the end read row 0 and only reach their own maxima, codes and output
+    // rows, none of which is stored; pieces past the two rows read piece 0 and are not used.
+    auto load_tile = [&](float4 (&x)[NV], int tile) {
+        const int row0 = tile * 16 + 2 * wave;
+        const float* p0 = X + (size_t)(row0 < rows ? row0 : 0) * ldx;
+        const float* p1 = X + (size_t)(row0 + 1 < rows ? row0 + 1 : 0) * ldx;
 #pragma unroll
-        for (int jq = 0; jq < NJQ; ++jq)
-            if (kbase + 16 * jq >= kbeg && kbase + 16 * jq < kend)           // uniform over the wave
-                m = fmaxf(fmaxf(m, fabsf(x[jq].x)), fmaxf(fabsf(x[jq].y), fmaxf(fabsf(x[jq].z), fabsf(x[jq].w))));
-        m = fmaxf(m, __shfl_xor(m, 16, 64));     // the four lanes of a row
-        m = fmaxf(m, __shfl_xor(m, 32, 64));
-        if (g == 0) smax[rg][kq][r] = m;
-        __syncthreads();        // the quarters' maxima (and, for the first tile, the sketch) are in LDS
-        m = fmaxf(fmaxf(smax[rg][0][r], smax[rg][1][r]), fmaxf(smax[rg][2][r], smax[rg][3][r]));
-        float lam_r, s_r;
-        make_scales(m, q.qmaxf, lam_r, s_r);
-        if (row_ok && g == 0 && kq == 0) {
-            amax[row] = m;
-            lam_out[row] = lam_r;
-            s_out[row] = s_r;
+        for (int u = 0; u < NV; ++u) {
+            int rl, cc;
+            const bool valid = piece(u, rl, cc);
+            x[u] = *reinterpret_cast<const float4*>((rl ? p1 : p0) + 4 * (valid ? cc : 0));
         }
-        v4f acc = (v4f){0.f, 0.f, 0.f, 0.f};
-        int8_t* cp = codes + (size_t)(row_ok ? row : 0) * cols + 4 * g + kbase;
-        // sketch rows k + 4g + t of block k: line (k >> 2) + g, whose rotation is 16 g (k is a multiple of 16)
-        const float* wline0 = wsm + ((kbase >> 2) + g) * 64;
-        auto quarter = [&](auto mode) {          // one uniform branch on the rounding mode per tile
+    };
+    auto process = [&](const float4 (&x)[NV], int tile) {
+        const int row0 = tile * 16 + 2 * wave;
+        float m0 = 0.f, m1 = 0.f;
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            int rl, cc;
+            const bool valid = piece(u, rl, cc);
+            const float mm = fmaxf(fmaxf(fabsf(x[u].x), fabsf(x[u].y)), fmaxf(fabsf(x[u].z), fabsf(x[u].w)));
+            if (valid && rl == 0) m0 = fmaxf(m0, mm);
+            if (valid && rl == 1) m1 = fmaxf(m1, mm);
+        }
+        m0 = wave_max(m0);
+        m1 = wave_max(m1);
+        float lam0, sc0, lam1, sc1;
+        make_scales(m0, q.qmaxf, lam0, sc0);
+        make_scales(m1, q.qmaxf, lam1, sc1);
+        if (lane < 2 && row0 + lane < rows) {
+            amax[row0 + lane] = lane ? m1 : m0;
+            lam_out[row0 + lane] = lane ? lam1 : lam0;
+            s_out[row0 + lane] = lane ? sc1 : sc0;
+        }
+        auto quantize = [&](auto mode) {         // one uniform branch on the rounding mode per tile
             constexpr int RM = decltype(mode)::value;
 #pragma unroll
-            for (int jq = 0; jq < NJQ; ++jq) {
-                const int k = kbase + 16 * jq;
-                if (k < kbeg || k >= kend) continue;         // uniform over the wave
-                float res[4], c0, c1, c2, c3;
-                res[0] = quant_code_residual<RM>(x[jq].x, lam_r, s_r, q, c0);
-                res[1] = quant_code_residual<RM>(x[jq].y, lam_r, s_r, q, c1);
-                res[2] = quant_code_residual<RM>(x[jq].z, lam_r, s_r, q, c2);
-                res[3] = quant_code_residual<RM>(x[jq].w, lam_r, s_r, q, c3);
+            for (int u = 0; u < NV; ++u) {
+                int rl, cc;
+                if (!piece(u, rl, cc)) continue;
+                const float lam_r = rl ? lam1 : lam0, s_r = rl ? sc1 : sc0;
+                float c0, c1, c2, c3;
+                float4 res;
+                res.x = quant_code_residual<RM>(x[u].x, lam_r, s_r, q, c0);
+                res.y = quant_code_residual<RM>(x[u].y, lam_r, s_r, q, c1);
+                res.z = quant_code_residual<RM>(x[u].z, lam_r, s_r, q, c2);
+                res.w = quant_code_residual<RM>(x[u].w, lam_r, s_r, q, c3);
                 const int i0 = (int)c0, i1 = (int)c1, i2 = (int)c2, i3 = (int)c3;
                 const uint32_t pk = (uint32_t)(i0 & 0xff) | ((uint32_t)(i1 & 0xff) << 8) |
                                     ((uint32_t)(i2 & 0xff) << 16) | ((uint32_t)(i3 & 0xff) << 24);
-                if (row_ok) *reinterpret_cast<uint32_t*>(cp + 16 * jq) = pk;
-                const float* wline = wline0 + 4 * jq * 64;
-#pragma unroll
-                for (int t = 0; t < 4; ++t) acc = mfma16(res[t], wline[(16 * t + r + 16 * g) & 63], acc);
-                // one block at a time: hoisting every block's residuals above the matrix instructions would
-                // cost four registers per block, and the second register set needs them
-                __builtin_amdgcn_sched_barrier(0);
+                if (row0 + rl < rows) *reinterpret_cast<uint32_t*>(codes + (size_t)(row0 + rl) * cols + 4 * cc) = pk;
+                *reinterpret_cast<float4*>(rt + (2 * wave + rl) * ldr + 4 * cc) = res;
             }
         };
-        if (q.round_mode == 0) quarter(std::integral_constant<int, 0>{});
-        else quarter(std::integral_constant<int, 1>{});
-        yx[wave][lane] = make_float4(acc[0], acc[1], acc[2], acc[3]);
-        __syncthreads();        // the four partial products of each row group are in LDS
-        // wave kq adds element kq of its row group's accumulators (output row 4g + kq, column r)
-        const float* yp = reinterpret_cast<const float*>(&yx[rg * 4][lane]) + kq;
-        float sum = yp[0];
-        sum += yp[64 * 4];
-        sum += yp[2 * 64 * 4];
-        sum += yp[3 * 64 * 4];
-        const int orow = tile * 32 + rg * 16 + 4 * g + kq;
-        if (orow < rows) Y[(size_t)orow * 16 + r] = sum;
+        if (q.round_mode == 0) quantize(std::integral_constant<int, 0>{});
+        else quantize(std::integral_constant<int, 1>{});
+        __syncthreads();        // the tile's residuals are in LDS; the last tile's partial products have been read
+        v4f acc = (v4f){0.f, 0.f, 0.f, 0.f};
+        const float* ap = rt + r * ldr + 4 * s0 + g;
+#pragma unroll
+        for (int i = 0; i < NS; ++i)
+            if (s0 + i < s1) acc = mfma16(ap[4 * i], wreg[i], acc);      // the same for all lanes of a wave
+#pragma unroll
+        for (int v = 0; v < 4; ++v) pacc[wave][(4 * g + v) * 16 + r] = acc[v];
+        __syncthreads();        // the eight partial products are in LDS; the residual tile has been read
+        if (threadIdx.x < 256) {
+            float sum = pacc[0][threadIdx.x];
+#pragma unroll
+            for (int w = 1; w < 8; ++w) sum += pacc[w][threadIdx.x];
+            const int orow = tile * 16 + (threadIdx.x >> 4);
+            if (orow < rows) Y[(size_t)orow * 16 + (threadIdx.x & 15)] = sum;
+        }
     };
-    float4 xa[NJQ], xb[NJQ];
+    float4 xa[NV], xb[NV];
     int tile = t0;
     load_tile(xa, tile);
     while (true) {          // two tiles per round: the register sets swap roles
@@ -1210,21 +1224,16 @@ int launch_quant_sketch_rows(const float* X, int ldx, int rows, int cols, QuantP
     if (hipGetDevice(&dev) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
         return LRQMM_ERR_HIP;
-    // persistent workgroups, two per compute unit (registers and LDS allow that many), each with a run of tiles
-    dim3 grid(min(ceil_div(rows, 32), 2 * cus));
-    const size_t lds = (size_t)cols * 16 * sizeof(float);
-#define LRQ_QSR(NJQV) hipLaunchKernelGGL((quant_sketch_rows_kernel<NJQV>), grid, dim3(512), lds, st, X, ldx, rows, cols, q, W, Y, amax, lam_out, s_out, codes)
-    switch (ceil_div(cols / 16, 4)) {
+    // persistent workgroups, two per compute unit (registers allow that many), each with a run of 16-row tiles
+    dim3 grid(min(ceil_div(rows, 16), LRQ_QSR_WGS * cus));
+    const size_t lds = (size_t)16 * (cols + ((68 - (cols & 63)) & 63)) * sizeof(float);
+#define LRQ_QSR(NVV) hipLaunchKernelGGL((quant_sketch_rows_kernel<NVV>), grid, dim3(512), lds, st, X, ldx, rows, cols, q, W, Y, amax, lam_out, s_out, codes)
+    switch (ceil_div(cols, 128)) {
         case 1: LRQ_QSR(1); break;
         case 2: LRQ_QSR(2); break;
         case 3: LRQ_QSR(3); break;
         case 4: LRQ_QSR(4); break;
         case 5: LRQ_QSR(5); break;
-        case 6: LRQ_QSR(6); break;
-        case 7: LRQ_QSR(7); break;
-        case 8: LRQ_QSR(8); break;
-        case 9: LRQ_QSR(9); break;
-        case 10: LRQ_QSR(10); break;
         default: return LRQMM_ERR_UNSUPPORTED;
     }
 #undef LRQ_QSR

@@ -82,7 +82,7 @@ SHORT_ROWS = [
     (64, 33, 400, 12, 8, 0),
     (500, 80, 272, 16, 8, 1),
     (90, 48, 16, 4, 0, 0),
-    (2100, 24, 208, 3, 2, 1),
+    (2100, 24, 208, 5, 0, 1),
     (33, 40, 336, 16, 0, 0),
 ]
 
