@@ -702,33 +702,34 @@ struct CodesShape {
 };
 
 // PL: planes of the factor that enter (3: float32 accuracy; 2: relative error 2^-16; 1: plain bfloat16 factor).
-template <int NT, int PL = 3>
+// MT: 16-row tiles per wave (a wave owns 16 MT rows, a workgroup 64 MT).
+template <int NT, int PL = 3, int MT = 4>
 __global__ __launch_bounds__(256, 1) void codes_mul_bf16_kernel(CodesJobBf16 j0, CodesJobBf16 j1, int K, int Kp) {
     using S = CodesShape<NT, PL>;
     constexpr int RP = S::RP, KB = S::KB, LDK = S::LDK, NC = S::NC;
     __shared__ __align__(16) uint16_t bs[PL * RP * LDK];
     const CodesJobBf16 job = blockIdx.z == 0 ? j0 : j1;
-    if ((int)blockIdx.x * 256 >= job.rows || (int)blockIdx.y >= job.splits) return;
+    if ((int)blockIdx.x * 64 * MT >= job.rows || (int)blockIdx.y >= job.splits) return;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int li = lane & 15, kq = lane >> 4;
-    const int r0 = blockIdx.x * 256 + wave * 64;
+    const int r0 = blockIdx.x * 64 * MT + wave * 16 * MT;
     const int kb = blockIdx.y * job.chunk, ke = min(K, kb + job.chunk);
-    const int8_t* ap[4];
+    const int8_t* ap[MT];
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) ap[mt] = job.Cq + (size_t)min(r0 + 16 * mt + li, job.rows - 1) * K;
-    v4f acc[4][NT];
+    for (int mt = 0; mt < MT; ++mt) ap[mt] = job.Cq + (size_t)min(r0 + 16 * mt + li, job.rows - 1) * K;
+    v4f acc[MT][NT];
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
+    for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (v4f){0.f, 0.f, 0.f, 0.f};
     for (int ks = kb; ks < ke; ks += KB) {
         // codes of the whole slab; rows past the end re-read the last row (never stored), and
         // codes past K meet zero planes, so clamped addresses need no mask
-        uint4 ca[4][NC];
+        uint4 ca[MT][NC];
 #pragma unroll
         for (int c = 0; c < NC; ++c)            // issued in the order of use: the first chunk's products can start
 #pragma unroll                                  // while the later chunks are still on their way
-            for (int mt = 0; mt < 4; ++mt)
+            for (int mt = 0; mt < MT; ++mt)
                 ca[mt][c] = *reinterpret_cast<const uint4*>(ap[mt] + min(ks + 64 * c + 16 * kq, K - 16));
         if (ks > kb) __syncthreads();       // previous slab no longer read
         for (int p0 = threadIdx.x; p0 < S::PIECES; p0 += 256 * S::BATCH) {
@@ -756,9 +757,9 @@ __global__ __launch_bounds__(256, 1) void codes_mul_bf16_kernel(CodesJobBf16 j0,
             if (ks + 64 * c < ke) {             // uniform
 #pragma unroll
                 for (int sidx = 0; sidx < 2; ++sidx) {
-                    v8bf af[4];
+                    v8bf af[MT];
 #pragma unroll
-                    for (int mt = 0; mt < 4; ++mt)
+                    for (int mt = 0; mt < MT; ++mt)
                         af[mt] = sidx == 0 ? codes_to_bf16(ca[mt][c].x, ca[mt][c].y)
                                            : codes_to_bf16(ca[mt][c].z, ca[mt][c].w);
 #pragma unroll
@@ -769,7 +770,7 @@ __global__ __launch_bounds__(256, 1) void codes_mul_bf16_kernel(CodesJobBf16 j0,
                             b.u = *reinterpret_cast<const uint4*>(
                                 &bs[(pl * RP + 16 * nt + li) * LDK + 64 * c + 16 * kq + 8 * sidx]);
 #pragma unroll
-                            for (int mt = 0; mt < 4; ++mt)
+                            for (int mt = 0; mt < MT; ++mt)
                                 acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[mt], b.v, acc[mt][nt], 0, 0, 0);
                         }
                 }
@@ -778,7 +779,7 @@ __global__ __launch_bounds__(256, 1) void codes_mul_bf16_kernel(CodesJobBf16 j0,
     }
     float* out = job.partial + (size_t)blockIdx.y * job.rows * RP;
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
+    for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
@@ -786,6 +787,64 @@ __global__ __launch_bounds__(256, 1) void codes_mul_bf16_kernel(CodesJobBf16 j0,
                 const int row = r0 + 16 * mt + 4 * kq + v;
                 if (row < job.rows) out[(size_t)row * RP + 16 * nt + li] = acc[mt][nt][v];
             }
+}
+
+// The same product for short rows (K <= 640) and factors of at most 16 columns: all of Bp fits in LDS (PL planes
+// x 16 rows x (Kp + 8) bfloat16), so workgroups are persistent -- two of eight waves per CU, the planes copied once --
+// and after the one barrier behind that copy the waves are on their own: a wave takes the 16-row tiles w, w + W,
+// w + 2W, ... (W waves in the grid) and loads a tile's codes at once (NC 16-byte loads per lane, the whole row);
+// the sixteen waves of a CU are at different points of that cycle, which keeps loads in flight while others
+// compute.  blockIdx.z selects the job as above.
+template <int PL, int NC>
+__global__ __launch_bounds__(512, 4) void codes_mul_rows_kernel(CodesJobBf16 j0, CodesJobBf16 j1, int K, int Kp) {
+    extern __shared__ __align__(16) uint16_t bsr[];       // [PL][16][Kp + 8]
+    const CodesJobBf16 job = blockIdx.z == 0 ? j0 : j1;
+    const int ntiles = (job.rows + 15) >> 4;
+    if ((int)blockIdx.x * 8 >= ntiles) return;            // no tile for any wave of this workgroup
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int li = lane & 15, kq = lane >> 4;
+    const int LDK = Kp + 8, ppr = Kp >> 3;
+    for (int p = threadIdx.x; p < PL * 16 * ppr; p += 512) {
+        const int rowp = p / ppr, seg = p - rowp * ppr;
+        *reinterpret_cast<uint4*>(&bsr[rowp * LDK + 8 * seg]) =
+            *reinterpret_cast<const uint4*>(job.Bp + (size_t)rowp * Kp + 8 * seg);
+    }
+    __syncthreads();
+    const int nwaves = gridDim.x * 8;
+    // codes past K meet zero planes and rows past the end re-read the last row (never stored): clamped
+    // addresses, no masks
+    auto load_tile = [&](uint4 (&ca)[NC], int tile) {
+        const int8_t* ap = job.Cq + (size_t)min(tile * 16 + li, job.rows - 1) * K;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) ca[c] = *reinterpret_cast<const uint4*>(ap + min(64 * c + 16 * kq, K - 16));
+    };
+    auto process = [&](const uint4 (&ca)[NC], int tile) {
+        v4f acc = (v4f){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            if (64 * c >= Kp) continue;             // the planes end at Kp (uniform)
+#pragma unroll
+            for (int sidx = 0; sidx < 2; ++sidx) {
+                const v8bf af = sidx == 0 ? codes_to_bf16(ca[c].x, ca[c].y) : codes_to_bf16(ca[c].z, ca[c].w);
+#pragma unroll
+                for (int pl = 0; pl < PL; ++pl) {
+                    union { uint4 u; v8bf v; } b;
+                    b.u = *reinterpret_cast<const uint4*>(&bsr[(pl * 16 + li) * LDK + 64 * c + 16 * kq + 8 * sidx]);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, b.v, acc, 0, 0, 0);
+                }
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int row = tile * 16 + 4 * kq + v;
+            if (row < job.rows) job.partial[(size_t)row * 16 + li] = acc[v];
+        }
+    };
+    uint4 x[NC];
+    for (int tile = blockIdx.x * 8 + wave; tile < ntiles; tile += nwaves) {
+        load_tile(x, tile);
+        process(x, tile);
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -1258,6 +1317,24 @@ int launch_codes_mul_n2(const int8_t* codesA, int rowsA, const float* WA, const 
     if (fast) {
         CodesJobBf16 j0 = {codesA, WA3, partialA, rowsA, planA.chunk, planA.splits};
         CodesJobBf16 j1 = {codesB, WB3, partialB, rowsB, planB.chunk, planB.splits};
+        // short rows, one tile of factor columns, no split of the reduction: the persistent kernel
+        const size_t lds_rows = (size_t)planes * 16 * (Kp + 8) * sizeof(uint16_t);
+        if (LP == 16 && K <= 640 && planA.splits == 1 && planB.splits == 1 && lds_rows <= 64 * 1024) {
+            int dev = 0, cus = 0;
+            if (hipGetDevice(&dev) != hipSuccess ||
+                hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+                return LRQMM_ERR_HIP;
+            dim3 g2(min(ceil_div(ceil_div(max(rowsA, rowsB), 16), 8), 2 * cus), 1, 2);
+            const int nc = ceil_div(K, 64);
+#define LRQ_CMR(PLV, NCV) hipLaunchKernelGGL((codes_mul_rows_kernel<PLV, NCV>), g2, dim3(512), lds_rows, st, j0, j1, K, Kp)
+#define LRQ_CMR_NC(PLV) do { if (nc <= 2) LRQ_CMR(PLV, 2); else if (nc <= 4) LRQ_CMR(PLV, 4); else if (nc <= 6) LRQ_CMR(PLV, 6); \
+            else if (nc <= 8) LRQ_CMR(PLV, 8); else LRQ_CMR(PLV, 10); } while (0)
+            if (planes == 2) LRQ_CMR_NC(2); else if (planes == 1) LRQ_CMR_NC(1); else LRQ_CMR_NC(3);
+#undef LRQ_CMR_NC
+#undef LRQ_CMR
+            LRQ_CHECK_LAUNCH();
+            return LRQMM_OK;
+        }
         dim3 grid(ceil_div(max(rowsA, rowsB), 256), max(planA.splits, planB.splits), 2);
         if (planes == 2) { NT_SWITCH(LP / 16, hipLaunchKernelGGL((codes_mul_bf16_kernel<NT_, 2>), grid, dim3(256), 0, st, j0, j1, K, Kp)); }
         else if (planes == 1) { NT_SWITCH(LP / 16, hipLaunchKernelGGL((codes_mul_bf16_kernel<NT_, 1>), grid, dim3(256), 0, st, j0, j1, K, Kp)); }
