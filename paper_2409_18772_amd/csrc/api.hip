@@ -48,7 +48,9 @@ size_t carve_rsvd(Arena& a, int rows, int cols, int axis, int LP, int rank, Rsvd
                                                   : (size_t)pt.splits * cols);
     // (the block count is not monotone in the row count -- 4096 rows make 64 blocks of 64, 4100 rows 33 of 128 --
     // so take the larger of the two uses, Gram of a rows x LP and of a cols x LP factor)
-    const int nb = gram_blocks(rows, LP) > gram_blocks(cols, LP) ? gram_blocks(rows, LP) : gram_blocks(cols, LP);
+    // (and the one-read quantization kernel for row-quantized operands leaves one partial per workgroup)
+    int nb = gram_blocks(rows, LP) > gram_blocks(cols, LP) ? gram_blocks(rows, LP) : gram_blocks(cols, LP);
+    if (axis == LRQMM_AXIS_ROW && LP == 16 && quant_sketch_rows_blocks(rows) > nb) nb = quant_sketch_rows_blocks(rows);
     RsvdWs t;
     t.lam = a.take<float>(npad);
     t.s = a.take<float>(npad);
@@ -325,19 +327,23 @@ static int rsvd_plan(LaunchList& ops, const float* X, int ldx, const float* amax
         ops.push_back([=] { return launch_resid_mul_t(X, ldx, rows, cols, axis, w.lam, w.s, q, w.Yr, LP, pt, w.partial, st, pl); });
     };
     // Y = R Omega (with fused_codes: the same launch also writes the codes and the step vectors)
-    if (fused_codes && row_amax_out)
+    if (fused_codes && row_amax_out) {
+        // one read of X: maxima, codes, Y (straight into its place) and the Gram partials of Y
         ops.push_back([=] {
-            return launch_quant_sketch_rows(X, ldx, rows, cols, q, w.Wc, LP, w.partial, row_amax_out, w.lam, w.s,
+            return launch_quant_sketch_rows(X, ldx, rows, cols, q, w.Wc, LP, w.Yr, w.gpart, row_amax_out, w.lam, w.s,
                                             fused_codes, st);
         });
-    else if (fused_codes)
+        ops.push_back([=] { return launch_gram_sum(w.gpart, quant_sketch_rows_blocks(rows), LP, w.gram, st); });
+        ops.push_back([=] { return launch_chol_inverse(w.gram, ell, LP, w.T, st); });
+        ops.push_back([=] { return launch_apply(w.Yr, rows, LP, w.T, LP, LP, w.Yr, LP, 0, st); });
+    } else if (fused_codes)
         ops.push_back([=] {
             return launch_quant_sketch(X, ldx, rows, cols, axis, amax, q, w.Wc, LP, pn, w.partial, w.lam, w.s, fused_codes,
                                        st, planes);
         });
     else
         pass_n();
-    orth(pn.splits, rows, w.Yr);
+    if (!(fused_codes && row_amax_out)) orth(pn.splits, rows, w.Yr);
     for (int it = 0; it < power_iters; ++it) {
         // Z = orth(R^T Q); Q = orth(R Z)
         pass_t(planes);

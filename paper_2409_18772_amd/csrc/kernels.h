@@ -73,13 +73,18 @@ int launch_quant_sketch(const float* X, int ldx, int rows, int cols, int axis, c
                         const float* W, int LP, PassPlan plan, float* partial, float* lam_out, float* s_out,
                         int8_t* codes, hipStream_t st, int planes = 3);
 // Row quantization and the sketch product from one read, for operands quantized by rows whose rows are short
-// (cols <= 640, a multiple of 16) and sketches padded to 16 columns: writes the row maxima amax[rows], the step
-// vectors, the codes (rows x cols) and Y = R.W (rows x 16, a single partial).  Maxima, steps and codes carry the
-// bits of launch_quantize_rows; Y is the float32 matrix-core product of launch_resid_mul_n with the reduction cut
-// into four parts that are added in a fixed order.  Otherwise LRQMM_ERR_UNSUPPORTED and nothing is launched.
+// (cols <= 576, a multiple of 16) and sketches padded to 16 columns: writes the row maxima amax[rows], the step
+// vectors, the codes (rows x cols), Y = R.W (rows x 16) and gpart[quant_sketch_rows_blocks(rows)][16][16], the
+// float64 Gram matrices of the workgroups' rows of Y (to be added by launch_gram_sum).  Maxima, steps and codes
+// carry the bits of launch_quantize_rows; Y is the float32 matrix-core product of launch_resid_mul_n with the
+// reduction cut into eight parts that are added in a fixed order.  Otherwise LRQMM_ERR_UNSUPPORTED and nothing is
+// launched.
+#define LRQ_QSR_MAX_BLOCKS 512
 bool quant_sketch_rows_usable(const float* X, int ldx, int rows, int cols, int LP, const int8_t* codes);
+int quant_sketch_rows_blocks(int rows);
 int launch_quant_sketch_rows(const float* X, int ldx, int rows, int cols, QuantParams q, const float* W, int LP,
-                             float* Y, float* amax, float* lam_out, float* s_out, int8_t* codes, hipStream_t st);
+                             float* Y, double* gpart, float* amax, float* lam_out, float* s_out, int8_t* codes,
+                             hipStream_t st);
 // partial[s][cols][LP] = R[chunk s, :]^T . W[chunk s, :]    (W is rows x LP)
 int launch_resid_mul_t(const float* X, int ldx, int rows, int cols, int axis, const float* lam,
                        const float* s, QuantParams q, const float* W, int LP, PassPlan plan,

@@ -167,6 +167,31 @@ __global__ __launch_bounds__(64) void gram_sum_kernel(const double* __restrict__
     gram[idx] = acc;
 }
 
+// The same sum for more than GRAM_BATCH partials (a tall operand with a narrow sketch): a thread of the kernel
+// above would go through several batches, one memory latency each.  Here eight threads share an entry -- thread
+// (part, e) adds the partials [part per, (part + 1) per) in order, per = ceil(nb / 8) -- and the eight sums are
+// added in the order of the parts.  Lanes 8 part + e of a wave: the loads of a part are 8 adjacent entries.
+__global__ __launch_bounds__(64) void gram_sum_parts_kernel(const double* __restrict__ gpart, int nb, int entries,
+                                                            double* __restrict__ gram) {
+    const int e = threadIdx.x & 7, part = threadIdx.x >> 3;
+    const int idx = min((int)blockIdx.x * 8 + e, entries - 1);      // (past the end: the last entry again, not stored)
+    const int per = (nb + 7) >> 3;
+    const int b_begin = min(nb, part * per), b_end = min(nb, b_begin + per);
+    const double* src = gpart + idx;
+    double acc = 0.0;
+    for (int b0 = b_begin; b0 < b_end; b0 += GRAM_BATCH) {
+        double v[GRAM_BATCH];
+#pragma unroll
+        for (int blk = 0; blk < GRAM_BATCH; ++blk) v[blk] = src[(size_t)min(b0 + blk, nb - 1) * entries];
+#pragma unroll
+        for (int blk = 0; blk < GRAM_BATCH; ++blk) acc += (b0 + blk < b_end) ? v[blk] : 0.0;
+    }
+    double sum = __shfl(acc, e, 64);
+#pragma unroll
+    for (int p = 1; p < 8; ++p) sum += __shfl(acc, 8 * p + e, 64);
+    if (part == 0 && (int)blockIdx.x * 8 + e < entries) gram[idx] = sum;
+}
+
 // Cholesky-QR factor T = L^-T (upper triangular, Q = Y T) of the Gram matrix G = L L^T, by
 // symmetric elimination of the augmented matrix [G | I]: step j subtracts
 // (M[i][j] / d_j) * (row j) from every row i > j, d_j the pivot M[j][j].  The left half is then
@@ -685,7 +710,10 @@ int launch_reduce_gram(const float* partial, int splits, int n, int LP, const fl
 }
 
 int launch_gram_sum(const double* gpart, int nb, int LP, double* gram, hipStream_t st) {
-    hipLaunchKernelGGL(gram_sum_kernel, dim3(ceil_div(LP * LP, 64)), dim3(64), 0, st, gpart, nb, LP * LP, gram);
+    if (nb > GRAM_BATCH)    // several batches per entry: eight threads share an entry
+        hipLaunchKernelGGL(gram_sum_parts_kernel, dim3(ceil_div(LP * LP, 8)), dim3(64), 0, st, gpart, nb, LP * LP, gram);
+    else
+        hipLaunchKernelGGL(gram_sum_kernel, dim3(ceil_div(LP * LP, 64)), dim3(64), 0, st, gpart, nb, LP * LP, gram);
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }

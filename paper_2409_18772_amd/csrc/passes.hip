@@ -165,7 +165,7 @@ __device__ __forceinline__ float quant_code_residual(float x, float lam, float s
 
 // ---------------------------------------------------------------------------
 // Row quantization (Eq. (quantA), one scale per row of A) and the sketch product Y = R.Omega (Algorithm 1, the
-// sample matrix) from ONE read of the operand, for short rows (cols <= 640, a multiple of 16) and sketches
+// sample matrix) from ONE read of the operand, for short rows (cols <= 576, a multiple of 16) and sketches
 // padded to 16 columns.  A tile is 16 rows; workgroups of 8 waves are persistent, take a contiguous run of
 // tiles, and load tile i+1 into a second register set while tile i is worked on.
 //   * Wave w reads rows 2w and 2w+1 of the tile, adjacent lanes adjacent 16-byte pieces (NV float4 per lane), so
@@ -177,22 +177,31 @@ __device__ __forceinline__ float quant_code_residual(float x, float lam, float s
 //     does not depend on the launch.  Two barriers per tile.
 // amax, lam_out, s_out and the codes carry the bits the separate quantization kernel writes.
 // ---------------------------------------------------------------------------
-#ifndef LRQ_QSR_WGS
-#define LRQ_QSR_WGS 2      // resident workgroups per compute unit the kernel is built and launched for
-#endif
-template <int NV>
-__global__ __launch_bounds__(512, 2 * LRQ_QSR_WGS) void quant_sketch_rows_kernel(
+template <int NS>     // matrix-core steps (of 4 columns) per wave: ceil(cols / 32)
+__global__ __launch_bounds__(512, 4) void quant_sketch_rows_kernel(
     const float* __restrict__ X, int ldx, int rows, int cols, QuantParams q, const float* __restrict__ W,
-    float* __restrict__ Y, float* __restrict__ amax, float* __restrict__ lam_out, float* __restrict__ s_out,
-    int8_t* __restrict__ codes) {
-    constexpr int NS = 4 * NV;                           // matrix-core steps (of 4 columns) per wave, at most
+    float* __restrict__ Y, double* __restrict__ gpart, float* __restrict__ amax, float* __restrict__ lam_out,
+    float* __restrict__ s_out, int8_t* __restrict__ codes) {
+    constexpr int NV = (NS + 3) / 4;                     // 16-byte pieces per lane: ceil(cols / 128)
     extern __shared__ __align__(16) float rt[];          // residual tile: 16 rows of ldr floats
     __shared__ float pacc[8][256];
+    __shared__ float yt[16][17];                         // the last finished tile of Y (rows past the end: zeros)
+    __shared__ double gl[256];                           // the workgroup's Y^T Y so far, entry (t / 16, t % 16) by thread t
+    if (threadIdx.x < 256) gl[threadIdx.x] = 0.0;        // (kept in LDS: no register lives across the tile loop for it)
+    auto gram_tile = [&] {
+        if (threadIdx.x < 256) {
+            const int ga = threadIdx.x >> 4, gb = threadIdx.x & 15;
+            double gacc = gl[threadIdx.x];
+#pragma unroll
+            for (int rr = 0; rr < 16; ++rr) gacc = fma((double)yt[rr][ga], (double)yt[rr][gb], gacc);
+            gl[threadIdx.x] = gacc;
+        }
+    };
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r = lane & 15, g = lane >> 4;
     const int cpr = cols >> 2;                           // 16-byte pieces, and steps, per row
     const int ldr = cols + ((68 - (cols & 63)) & 63);
-    const int spw = (cpr + 7) >> 3;                      // steps per wave (spw <= NS)
+    const int spw = (cpr + 7) >> 3;                      // steps per wave (= NS)
     const int s0 = min(cpr, wave * spw), s1 = min(cpr, s0 + spw);
     const int ntiles = (rows + 15) >> 4;
     const int t0 = (int)((long long)blockIdx.x * ntiles / gridDim.x);
@@ -268,6 +277,7 @@ __global__ __launch_bounds__(512, 2 * LRQ_QSR_WGS) void quant_sketch_rows_kernel
         if (q.round_mode == 0) quantize(std::integral_constant<int, 0>{});
         else quantize(std::integral_constant<int, 1>{});
         __syncthreads();        // the tile's residuals are in LDS; the last tile's partial products have been read
+        if (tile > t0) gram_tile();     // the previous tile of Y is in LDS too
         v4f acc = (v4f){0.f, 0.f, 0.f, 0.f};
         const float* ap = rt + r * ldr + 4 * s0 + g;
 #pragma unroll
@@ -282,6 +292,7 @@ __global__ __launch_bounds__(512, 2 * LRQ_QSR_WGS) void quant_sketch_rows_kernel
             for (int w = 1; w < 8; ++w) sum += pacc[w][threadIdx.x];
             const int orow = tile * 16 + (threadIdx.x >> 4);
             if (orow < rows) Y[(size_t)orow * 16 + (threadIdx.x & 15)] = sum;
+            yt[threadIdx.x >> 4][threadIdx.x & 15] = orow < rows ? sum : 0.f;
         }
     };
     float4 xa[NV], xb[NV];
@@ -295,6 +306,9 @@ __global__ __launch_bounds__(512, 2 * LRQ_QSR_WGS) void quant_sketch_rows_kernel
         process(xb, tile);
         if (++tile >= t1) break;
     }
+    __syncthreads();
+    gram_tile();
+    if (threadIdx.x < 256) gpart[(size_t)blockIdx.x * 256 + threadIdx.x] = gl[threadIdx.x];
 }
 
 // ---------------------------------------------------------------------------
@@ -1272,27 +1286,25 @@ int launch_quant_sketch(const float* X, int ldx, int rows, int cols, int axis, c
 }
 
 bool quant_sketch_rows_usable(const float* X, int ldx, int rows, int cols, int LP, const int8_t* codes) {
-    return rows > 0 && LP == 16 && cols >= 16 && cols % 16 == 0 && cols <= 640 && ldx % 4 == 0 && aligned16(X) &&
+    // (rows of up to 576 columns: beyond that the two register sets of a tile no longer fit 128 registers)
+    return rows > 0 && LP == 16 && cols >= 16 && cols % 16 == 0 && cols <= 576 && ldx % 4 == 0 && aligned16(X) &&
            ((uintptr_t)codes & 3) == 0;
 }
 
+int quant_sketch_rows_blocks(int rows) { return min(ceil_div(rows, 16), LRQ_QSR_MAX_BLOCKS); }
+
 int launch_quant_sketch_rows(const float* X, int ldx, int rows, int cols, QuantParams q, const float* W, int LP,
-                             float* Y, float* amax, float* lam_out, float* s_out, int8_t* codes, hipStream_t st) {
+                             float* Y, double* gpart, float* amax, float* lam_out, float* s_out, int8_t* codes,
+                             hipStream_t st) {
     if (!quant_sketch_rows_usable(X, ldx, rows, cols, LP, codes)) return LRQMM_ERR_UNSUPPORTED;
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-        return LRQMM_ERR_HIP;
-    // persistent workgroups, two per compute unit (registers allow that many), each with a run of 16-row tiles
-    dim3 grid(min(ceil_div(rows, 16), LRQ_QSR_WGS * cus));
+    // persistent workgroups, each with a run of 16-row tiles; their number does not depend on the device, so
+    // neither does the order in which the Gram matrix is summed (two per compute unit on a 256-CU chip)
+    dim3 grid(quant_sketch_rows_blocks(rows));
     const size_t lds = (size_t)16 * (cols + ((68 - (cols & 63)) & 63)) * sizeof(float);
-#define LRQ_QSR(NVV) hipLaunchKernelGGL((quant_sketch_rows_kernel<NVV>), grid, dim3(512), lds, st, X, ldx, rows, cols, q, W, Y, amax, lam_out, s_out, codes)
-    switch (ceil_div(cols, 128)) {
-        case 1: LRQ_QSR(1); break;
-        case 2: LRQ_QSR(2); break;
-        case 3: LRQ_QSR(3); break;
-        case 4: LRQ_QSR(4); break;
-        case 5: LRQ_QSR(5); break;
+#define LRQ_QSR(NSV) case NSV: hipLaunchKernelGGL((quant_sketch_rows_kernel<NSV>), grid, dim3(512), lds, st, X, ldx, rows, cols, q, W, Y, gpart, amax, lam_out, s_out, codes); break
+    switch (ceil_div(cols, 32)) {
+        LRQ_QSR(1); LRQ_QSR(2); LRQ_QSR(3); LRQ_QSR(4); LRQ_QSR(5); LRQ_QSR(6); LRQ_QSR(7); LRQ_QSR(8); LRQ_QSR(9); LRQ_QSR(10);
+        LRQ_QSR(11); LRQ_QSR(12); LRQ_QSR(13); LRQ_QSR(14); LRQ_QSR(15); LRQ_QSR(16); LRQ_QSR(17); LRQ_QSR(18);
         default: return LRQMM_ERR_UNSUPPORTED;
     }
 #undef LRQ_QSR

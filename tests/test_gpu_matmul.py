@@ -74,7 +74,7 @@ def test_scaled_configs_full_output(name, M, N, K):
 
 
 SHORT_ROWS = [
-    # M, N, K, rank, oversample, power_iters: K a multiple of 16 up to 640 (A's rows are kept in registers), ragged M,
+    # M, N, K, rank, oversample, power_iters: K a multiple of 16 up to 576 (A's rows are kept in registers), ragged M,
     # K / 16 a multiple of 4 and not (the four waves of a row group then take unequal shares)
     (130, 70, 96, 4, 4, 1),
     (1000, 64, 576, 8, 0, 0),
@@ -84,6 +84,7 @@ SHORT_ROWS = [
     (90, 48, 16, 4, 0, 0),
     (2100, 24, 208, 5, 0, 1),
     (33, 40, 336, 16, 0, 0),
+    (700, 64, 544, 8, 8, 1),
 ]
 
 
@@ -91,7 +92,8 @@ SHORT_ROWS = [
 @pytest.mark.parametrize("M,N,K,r,p,q", SHORT_ROWS)
 def test_short_rows_of_a_single_read(M, N, K, r, p, q, mode):
     """A with short rows and a sketch of at most 16 columns: row maxima, codes and the sketch product come from
-    one read of A (the fourth and fifth shape have wider sketches and take the separate kernels).  Checked against
+    one read of A (the third, fourth and fifth shape have longer rows or wider sketches and take the separate
+    kernels).  Checked against
     the oracle, and against the same call on a copy of A whose row stride (K + 1) rules that kernel out, so that
     the separate quantization and sketch kernels run: the two differ only in the order in which the sketch
     product is summed."""
