@@ -193,15 +193,19 @@ def main():
     # Quantization + factorization of one operand as one streaming job.  Algorithmic bytes: one read for the
     # group maxima, one per residual product (the first of them also writes the codes), 4 B per element each,
     # plus 1 B per element of codes.  (Shapes off the guard-free kernels read B once more: maxima, codes,
-    # products.)  With rank 0 only the maxima and the codes remain.
+    # products.)  With rank 0 only the maxima and the codes remain.  Short rows of A (K <= 576, a sketch of at most
+    # 16 columns) are the one case that gets by with fewer reads than this count: maxima, codes and the first
+    # product come from a single read there ("reads_performed").
+    one_read_a = (w.rank > 0 and w.K % 16 == 0 and 16 <= w.K <= 576 and w.rank + w.oversample <= 16)
     for op, elems in (("a", w.M * w.K), ("b", w.K * w.N)):
         n_reads = (1 + passes) if w.rank > 0 else (1 if op == "a" else 2)
         job_ms = stages["quantize_" + op] + stages["rsvd_" + op]
         gbs = (4.0 * n_reads + 1.0) * elems / (job_ms * 1e-3) / 1e9
         stage_info["rsvd_" + op].update(passes=passes)
         stage_info["quantize_and_factor_" + op] = {
-            "ms": round(job_ms, 4), "operand_reads": n_reads, "algorithmic_GBs": round(gbs, 1),
-            "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
+            "ms": round(job_ms, 4), "operand_reads": n_reads,
+            "reads_performed": n_reads - 1 if (op == "a" and one_read_a) else n_reads,
+            "algorithmic_GBs": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
     stage_info[gemm_key].update(TOPs=round(achieved, 1), frac_int8_mfma=round(achieved / PEAK_INT8_TOPS, 4))
     # which roof bounds the product: its algorithmic bytes (codes read once, 4-byte results written once, panels)
     # against its operations; below peak_ops / peak_bytes operations per byte the kernel is bound by memory

@@ -633,8 +633,9 @@ int lrqmm_matmul_ex(int M, int N, int K, int bits, int rank, int oversample, int
         if (carve_rsvd(rb, K, N, LRQMM_AXIS_COL, LPm, rank, &wb) > w.subB_bytes) return LRQMM_ERR_WORKSPACE;
     }
     // Short rows of A (an im2col'd convolution: K = 576) stay in registers: maxima, codes and Y from a single read.
-    const bool onepass_a = rank > 0 && K > 0 && !per_tensor && planes_subspace(precision) == 3 &&
-                           plan_pass_n(M, K).splits == 1 && quant_sketch_rows_usable(A, lda, M, K, LPm, w.Aq);
+    // (in every precision mode: this pass then runs in float32, which the reduced modes allow)
+    const bool onepass_a = rank > 0 && K > 0 && !per_tensor && plan_pass_n(M, K).splits == 1 &&
+                           quant_sketch_rows_usable(A, lda, M, K, LPm, w.Aq);
     const bool fuse_a = !onepass_a && rank > 0 && K > 0 && quant_sketch_fusable(A, lda, M, K, LPm, plan_pass_n(M, K), w.Aq);
     const bool fuse_b = rank > 0 && K > 0 && quant_sketch_fusable(B, ldb, K, N, LPm, plan_pass_n(K, N), w.BqT);
     opsA.push_back([=] { prof_mark(slot, 0, ast); return LRQMM_OK; });
