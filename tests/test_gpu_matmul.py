@@ -85,6 +85,7 @@ SHORT_ROWS = [
     (2100, 24, 208, 5, 0, 1),
     (33, 40, 336, 16, 0, 0),
     (700, 64, 544, 8, 8, 1),
+    (20, 24, 64, 4, 0, 0),
 ]
 
 
@@ -114,6 +115,12 @@ def test_short_rows_of_a_single_read(M, N, K, r, p, q, mode):
     D = torch.empty((M, N), dtype=torch.float32, device="cuda")
     L.lrqmm_matmul_ex(wide[:, :K], dB, D, 4, r, p, q, seed=9, round_mode=mode)
     assert rel_fro(C, to_np(D)) < tol_for(ref)
+    # a row stride the one-read kernel accepts (K + 4): the same kernel on a window, the same bits
+    wide4 = torch.zeros((M, K + 4), dtype=torch.float32, device="cuda")
+    wide4[:, :K] = dA
+    D4 = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    L.lrqmm_matmul_ex(wide4[:, :K], dB, D4, 4, r, p, q, seed=9, round_mode=mode)
+    assert np.array_equal(C, to_np(D4))
 
 
 def test_rank_zero_is_direct_quant_and_modes():
