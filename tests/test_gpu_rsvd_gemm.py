@@ -43,6 +43,9 @@ RSVD_CASES = [
     # a tall operand with a narrow sketch: more than 64 Gram workgroups, summed in several batches
     (20000, 64, o.ROWWISE, 4, 8, 0, 1, "relu_normal"),
     (64, 20000, o.COLWISE, 4, 8, 0, 1, "normal"),
+    # the same with a sketch of 32 padded columns (71 partials of 1024 entries)
+    (9000, 200, o.ROWWISE, 4, 20, 8, 1, "normal"),
+    (200, 9000, o.COLWISE, 4, 20, 8, 1, "relu_normal"),
 ]
 
 
