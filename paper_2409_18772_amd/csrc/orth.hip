@@ -12,6 +12,13 @@
 // zero residual) are dropped: the corresponding columns of Q are zero.
 #include "kernels.h"
 
+// The kernels of this file are short links of a dependent chain and share the chip with the other operand's
+// streaming passes or with the integer product, whose waves keep every SIMD busy.  Their waves ask for the
+// highest issue priority on their SIMD (a property of the wave, set by an instruction of the kernel itself: the
+// streams all stay at the default priority).  Measured: 4096^3, l = 40: 0.509 -> 0.494 ms per step; 16384^3,
+// l = 80: 10.04 -> 9.97 ms.
+__device__ __forceinline__ void raise_wave_priority() { __builtin_amdgcn_s_setprio(3); }
+
 #define GB_TILE 64        // rows of Y staged per LDS tile in the Gram kernel
 #define GRAM_BATCH 64         // Gram partials that gram_sum_kernel adds per batch of loads
 #define GRAM_MIN_ROWS 64
@@ -40,6 +47,7 @@ __global__ __launch_bounds__(256) void reduce_gram_kernel(const float* __restric
                                                           float* __restrict__ Y,
                                                           double* __restrict__ gpart) {
     constexpr int LP = NT * 16;
+    raise_wave_priority();
     constexpr int ld = LP + 1;
     constexpr int Q4 = LP / 4;      // float4 groups per row
     __shared__ float tile[GB_TILE * ld];
@@ -154,6 +162,7 @@ __global__ __launch_bounds__(256) void reduce_gram_kernel(const float* __restric
 __global__ __launch_bounds__(64) void gram_sum_kernel(const double* __restrict__ gpart, int nb, int entries,
                                                       double* __restrict__ gram) {
     const int idx = blockIdx.x * 64 + threadIdx.x;
+    raise_wave_priority();
     if (idx >= entries) return;
     const double* src = gpart + idx;
     double acc = 0.0;
@@ -174,6 +183,7 @@ __global__ __launch_bounds__(64) void gram_sum_kernel(const double* __restrict__
 __global__ __launch_bounds__(64) void gram_sum_parts_kernel(const double* __restrict__ gpart, int nb, int entries,
                                                             double* __restrict__ gram) {
     const int e = threadIdx.x & 7, part = threadIdx.x >> 3;
+    raise_wave_priority();
     const int idx = min((int)blockIdx.x * 8 + e, entries - 1);      // (past the end: the last entry again, not stored)
     const int per = (nb + 7) >> 3;
     const int b_begin = min(nb, part * per), b_end = min(nb, b_begin + per);
@@ -234,6 +244,7 @@ template <int NT>
 __global__ __launch_bounds__(CholShape<NT>::THREADS) void chol_inverse_kernel(const double* __restrict__ gram, int ell,
                                                                      double* __restrict__ T) {
     using S = CholShape<NT>;
+    raise_wave_priority();
     constexpr int LP = S::LP, KR = S::KR, KC = S::KC, NTI = S::NTI;
     static_assert(NTI % 2 == 0, "pairs of pivots stay inside one register row");
     __shared__ double rowb[2][2][2 * LP];
@@ -367,6 +378,7 @@ struct ApplyJob {
 template <int NT>
 __global__ __launch_bounds__(64) void apply_kernel(ApplyJob j0, ApplyJob j1, int nb0) {
     constexpr int LP = NT * 16;
+    raise_wave_priority();
     constexpr int KQ = LP / 4;
     const bool first = (int)blockIdx.x < nb0;
     const ApplyJob job = first ? j0 : j1;
@@ -497,6 +509,7 @@ __global__ __launch_bounds__(SVD_THREADS) void small_svd_kernel(const double* __
                                                                 double* __restrict__ Ur,
                                                                 double* __restrict__ Mv) {
     __shared__ __align__(16) double pool[SVD_POOL];
+    raise_wave_priority();
     __shared__ __align__(16) double2 rot[2][MAXL / 2];      // (c, s) per slot, two generations
     __shared__ int order[MAXL];
     __shared__ int finished;
