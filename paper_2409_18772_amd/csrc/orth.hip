@@ -20,7 +20,7 @@
 __device__ __forceinline__ void raise_wave_priority() { __builtin_amdgcn_s_setprio(3); }
 
 #define GB_TILE 64        // rows of Y staged per LDS tile in the Gram kernel
-#define GRAM_BATCH 64         // Gram partials that gram_sum_kernel adds per batch of loads
+#define GRAM_BATCH 64         // Gram partials per batch of loads when there are more than 64 of them
 #define GRAM_MIN_ROWS 64
 #define MAXL LRQMM_MAX_SKETCH
 
@@ -154,47 +154,31 @@ __global__ __launch_bounds__(256) void reduce_gram_kernel(const float* __restric
     }
 }
 
-// Gram matrix = the nb block partials summed in fixed order, one thread per entry, GRAM_BATCH partials per
-// batch of loads.  The partials were written by other workgroups (other XCDs), so every load is a
-// long-latency miss: a thread issues all loads of a batch before the first add, without branches (a
-// clamped index re-reads the last partial, whose value is then masked), and the entries are
-// spread over many small workgroups because one compute unit alone is load-bandwidth bound.
-__global__ __launch_bounds__(64) void gram_sum_kernel(const double* __restrict__ gpart, int nb, int entries,
-                                                      double* __restrict__ gram) {
-    const int idx = blockIdx.x * 64 + threadIdx.x;
-    raise_wave_priority();
-    if (idx >= entries) return;
-    const double* src = gpart + idx;
-    double acc = 0.0;
-    for (int b0 = 0; b0 < nb; b0 += GRAM_BATCH) {
-        double v[GRAM_BATCH];
-#pragma unroll
-        for (int blk = 0; blk < GRAM_BATCH; ++blk) v[blk] = src[(size_t)min(b0 + blk, nb - 1) * entries];
-#pragma unroll
-        for (int blk = 0; blk < GRAM_BATCH; ++blk) acc += (b0 + blk < nb) ? v[blk] : 0.0;
-    }
-    gram[idx] = acc;
-}
-
-// The same sum for more than GRAM_BATCH partials (a tall operand with a narrow sketch): a thread of the kernel
-// above would go through several batches, one memory latency each.  Here eight threads share an entry -- thread
-// (part, e) adds the partials [part per, (part + 1) per) in order, per = ceil(nb / 8) -- and the eight sums are
+// Gram matrix = the nb block partials summed by eight threads per entry: thread (part, e) adds the partials
+// [part per, (part + 1) per) in order, per = ceil(nb / 8), BATCH loads in flight at a time, and the eight sums are
 // added in the order of the parts.  Lanes 8 part + e of a wave: the loads of a part are 8 adjacent entries.
+// BATCH = 8 for up to 64 partials: one batch, and few enough registers (under 64) for the waves to start beside
+// two resident workgroups of the other operand's pass kernels, which leave about 80 registers per lane free on
+// a SIMD -- a kernel with one thread per entry and 64 partials in 128 registers waited for a pass workgroup to
+// drain first (16384^3: 58-121 us on average against 4 us alone; the partials were written by other workgroups on
+// other XCDs, so every load is a long-latency miss and all loads of a batch are issued before the first add).  BATCH = 64 beyond that (tall
+// operands with narrow sketches: several hundred partials).
+template <int BATCH>
 __global__ __launch_bounds__(64) void gram_sum_parts_kernel(const double* __restrict__ gpart, int nb, int entries,
                                                             double* __restrict__ gram) {
-    const int e = threadIdx.x & 7, part = threadIdx.x >> 3;
     raise_wave_priority();
+    const int e = threadIdx.x & 7, part = threadIdx.x >> 3;
     const int idx = min((int)blockIdx.x * 8 + e, entries - 1);      // (past the end: the last entry again, not stored)
     const int per = (nb + 7) >> 3;
     const int b_begin = min(nb, part * per), b_end = min(nb, b_begin + per);
     const double* src = gpart + idx;
     double acc = 0.0;
-    for (int b0 = b_begin; b0 < b_end; b0 += GRAM_BATCH) {
-        double v[GRAM_BATCH];
+    for (int b0 = b_begin; b0 < b_end; b0 += BATCH) {
+        double v[BATCH];
 #pragma unroll
-        for (int blk = 0; blk < GRAM_BATCH; ++blk) v[blk] = src[(size_t)min(b0 + blk, nb - 1) * entries];
+        for (int blk = 0; blk < BATCH; ++blk) v[blk] = src[(size_t)min(b0 + blk, nb - 1) * entries];
 #pragma unroll
-        for (int blk = 0; blk < GRAM_BATCH; ++blk) acc += (b0 + blk < b_end) ? v[blk] : 0.0;
+        for (int blk = 0; blk < BATCH; ++blk) acc += (b0 + blk < b_end) ? v[blk] : 0.0;
     }
     double sum = __shfl(acc, e, 64);
 #pragma unroll
@@ -723,10 +707,10 @@ int launch_reduce_gram(const float* partial, int splits, int n, int LP, const fl
 }
 
 int launch_gram_sum(const double* gpart, int nb, int LP, double* gram, hipStream_t st) {
-    if (nb > GRAM_BATCH)    // several batches per entry: eight threads share an entry
-        hipLaunchKernelGGL(gram_sum_parts_kernel, dim3(ceil_div(LP * LP, 8)), dim3(64), 0, st, gpart, nb, LP * LP, gram);
+    if (nb > GRAM_BATCH)
+        hipLaunchKernelGGL(gram_sum_parts_kernel<GRAM_BATCH>, dim3(ceil_div(LP * LP, 8)), dim3(64), 0, st, gpart, nb, LP * LP, gram);
     else
-        hipLaunchKernelGGL(gram_sum_kernel, dim3(ceil_div(LP * LP, 64)), dim3(64), 0, st, gpart, nb, LP * LP, gram);
+        hipLaunchKernelGGL(gram_sum_parts_kernel<8>, dim3(ceil_div(LP * LP, 8)), dim3(64), 0, st, gpart, nb, LP * LP, gram);
     LRQ_CHECK_LAUNCH();
     return LRQMM_OK;
 }
