@@ -175,6 +175,9 @@ __device__ __forceinline__ float quant_code_residual(float x, float lam, float s
 //     columns, so its sketch operands stay in registers (4 NV values) for the life of the workgroup.
 //   * The eight partial products of a tile meet in LDS and are added in the order of the waves, so the result
 //     does not depend on the launch.  Two barriers per tile.
+//   * A finished 16 x 16 tile of Y stays in LDS until the next barrier, where threads 0-255 add its Y^T Y to the
+//     workgroup's float64 Gram matrix (also in LDS); at the end each workgroup leaves gpart[block][16][16], which
+//     is what the orthonormalization needs next: no separate pass over Y forms it.
 // amax, lam_out, s_out and the codes carry the bits the separate quantization kernel writes.
 // ---------------------------------------------------------------------------
 template <int NS>     // matrix-core steps (of 4 columns) per wave: ceil(cols / 32)
