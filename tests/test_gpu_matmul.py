@@ -445,22 +445,23 @@ def test_largest_config_properties():
     assert e_lr * 10.0 < e_dq
 
 
-@pytest.mark.parametrize("shape", [(4096, 2048, 512), (300, 200, 260)])
+@pytest.mark.parametrize("shape", [(4096, 2048, 512, 28, 4, 1), (300, 200, 260, 28, 4, 1), (3000, 64, 576, 8, 0, 0)])
 def test_call_can_be_captured_in_a_graph(shape):
     """The call only enqueues kernels and event waits (its clears are fill kernels), so it may be recorded
     into a HIP graph, side streams included; every replay must reproduce the eager result, with eager work
     and synchronizations between the replays.  The first shape takes the three-stream schedule (sketch of 32
-    columns on the large-tile kernel)."""
+    columns on the large-tile kernel), the third the persistent kernels for short rows of A (their launchers
+    ask the runtime for the device's CU count, which a capture has to tolerate)."""
     import torch
     import paper_2409_18772_amd as L
-    M, N, K = shape
+    M, N, K, r, p, q = shape
     A = to_dev(wl.random_matrix("normal", M, K, seed=31))
     B = to_dev(wl.random_matrix("normal", K, N, seed=32))
-    ws = L.Workspace.for_problem(M, N, K, 28, 4)
+    ws = L.Workspace.for_problem(M, N, K, r, p)
     C = torch.empty((M, N), dtype=torch.float32, device="cuda")
 
     def step():
-        L.lrqmm_matmul(A, B, 4, 28, 4, 1, seed=7, workspace=ws, C=C)
+        L.lrqmm_matmul(A, B, 4, r, p, q, seed=7, workspace=ws, C=C)
 
     step()
     torch.cuda.synchronize()
